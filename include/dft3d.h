@@ -1,0 +1,156 @@
+/*
+ * dft3d -- 3-D complex DFT on a tensor-product grid as mode-wise dense contractions,
+ *          for one AMD MI355X (gfx950).  C ABI; no C++ or torch types cross this boundary.
+ *
+ * Two formulations of the same transform (paper, Section III):
+ *   KDFT  every tensor mode is contracted with an N x N Vandermonde matrix (Eq. 10 / Eq. 11);
+ *         a nonuniform axis only changes the matrix.
+ *   FFT   per axis a split N = A*B (Eq. 13 with P = B): an A-point transform over the slow
+ *         sub-index (Eq. 16), a twiddle factor, a B-point transform over the fast sub-index
+ *         (the "phase adjustment" of Eq. 15 factored into a diagonal and a matrix product),
+ *         and a re-ordering so the result is in natural order.
+ *
+ * Data layout.  Tensors are nx x ny x nz, C order (z fastest), complex64 stored as interleaved
+ * (re, im) floats -- the memory of a contiguous numpy/torch complex64 array.  `in`, `out` and
+ * the workspace are DEVICE pointers owned by the caller, 16-byte aligned, non-overlapping.
+ * Coordinate arrays are HOST pointers, copied during plan creation.
+ *
+ * Conventions.  FORWARD uses exp(-2 pi i ...) and is unscaled (Eq. 1, Eq. 12).  BACKWARD uses
+ * exp(+2 pi i ...) and multiplies by 1/(nx ny nz), so BACKWARD(FORWARD(x)) = x on uniform axes;
+ * it is not offered for nonuniform axes (there the inverse is a linear solve, Section III-A).
+ * A nonuniform axis has matrix entries M[k, n] = exp(-2 pi i k c[n]), k = 0..N-1, with c[n] the
+ * sample coordinate in cycles (period 1).
+ *
+ * Errors.  Every call returns a status; nothing throws or aborts across the boundary.
+ * dft3d_last_error() returns a thread-local, human-readable message for the last failure.
+ * Execution calls only enqueue work on the given HIP stream and never synchronise; calls that
+ * use one plan must be ordered on a stream because they share the plan's workspace.
+ */
+#ifndef DFT3D_H
+#define DFT3D_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dft3d_plan_s* dft3d_plan;
+
+typedef enum {
+    DFT3D_OK = 0,
+    DFT3D_ERR_INVALID_ARG = 1,
+    DFT3D_ERR_UNSUPPORTED = 2,
+    DFT3D_ERR_ALLOC = 3,
+    DFT3D_ERR_HIP = 4
+} dft3d_status;
+
+typedef enum { DFT3D_KDFT = 0, DFT3D_FFT = 1 } dft3d_formulation;
+
+/* value = sign of the exponent */
+typedef enum { DFT3D_FORWARD = -1, DFT3D_BACKWARD = 1 } dft3d_direction;
+
+/* plan flags */
+#define DFT3D_FLAG_CLOBBER_INPUT 1u /* exec may overwrite `in`; then no workspace is needed */
+#define DFT3D_FLAG_UNFUSED 2u       /* FFT: run the twiddle and the re-ordering as separate
+                                       kernels instead of fusing them into the contractions */
+
+/*
+ * Plan creation (Eq. 3 / Eq. 12 matrices, Eq. 13 split).  Generates the per-axis matrices
+ * (and, for FFT, the stage matrices and twiddle tables) in fp64 on the host, rounds them once
+ * to fp32 and uploads them; this call allocates device memory and synchronises.
+ *   plan      receives the handle, or NULL on failure
+ *   nx,ny,nz  axis lengths, each >= 1
+ *   f         DFT3D_KDFT or DFT3D_FFT
+ *   cx,cy,cz  NULL for a uniform axis, else HOST array of n? doubles (sample coordinates in
+ *             cycles).  FFT requires all three NULL (Section III-B: uniform sampling).
+ * dft3d_plan_create_ex additionally takes
+ *   split     NULL, or three first-stage lengths A (0 = choose); A must divide the axis length.
+ *             Default: A = 2^floor(log2(N)/2) for powers of two, else the divisor pair closest
+ *             to sqrt(N) with A <= B.  (512 -> 16*32, 2048 -> 32*64.)
+ *   flags     DFT3D_FLAG_* bits
+ * Errors: INVALID_ARG (NULL plan pointer, size < 1, bad split, unknown formulation),
+ * UNSUPPORTED (FFT with coordinates), ALLOC / HIP (device allocation or copy failed).
+ */
+dft3d_status dft3d_plan_create(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
+                               dft3d_formulation f, const double* cx, const double* cy,
+                               const double* cz);
+dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
+                                  dft3d_formulation f, const double* cx, const double* cy,
+                                  const double* cz, const int64_t* split, uint32_t flags);
+
+/* Frees the plan and the device memory it owns (not the workspace).  NULL is accepted. */
+dft3d_status dft3d_plan_destroy(dft3d_plan plan);
+
+/* Bytes of caller-provided device workspace dft3d_exec needs: 0 with CLOBBER_INPUT, else the
+ * size of one tensor (8 * nx*ny*nz).  The step calls below need none. */
+size_t dft3d_plan_workspace_bytes(dft3d_plan plan);
+
+/* Hands the plan a DEVICE buffer of at least dft3d_plan_workspace_bytes bytes.  The caller
+ * keeps ownership and must keep it alive while exec calls are in flight. */
+dft3d_status dft3d_plan_set_workspace(dft3d_plan plan, void* dev, size_t bytes);
+
+/* First-stage / second-stage lengths chosen for an axis (0, 1 or 2) of an FFT plan. */
+dft3d_status dft3d_plan_get_split(dft3d_plan plan, int axis, int64_t* A, int64_t* B);
+
+/*
+ * The whole transform (Eq. 10): out = transform(in).  Out of place: in != out, and neither may
+ * overlap the workspace.  `in` is left intact unless the plan has CLOBBER_INPUT.
+ * direction: DFT3D_FORWARD or DFT3D_BACKWARD.  stream: a hipStream_t passed as void* (NULL =
+ * the null stream).  Errors: INVALID_ARG (NULL / misaligned / aliased pointers, bad direction,
+ * workspace missing or too small), UNSUPPORTED (BACKWARD on a nonuniform plan), HIP (launch).
+ */
+dft3d_status dft3d_exec(dft3d_plan plan, const void* in, void* out, int direction,
+                        void* stream);
+
+/* ---- single steps of the path; each is one kernel launch, out of place, same layout ------- */
+
+/* KDFT, one mode product (Eq. 2 along `axis` of the tensor; steps of Eq. 11):
+ *   out[.., k, ..] = sum_n M_axis[k, n] in[.., n, ..].   axis = 0, 1 or 2.
+ * BACKWARD conjugates the matrix and scales by 1/N_axis.  Valid on KDFT plans. */
+dft3d_status dft3d_mode_contract(dft3d_plan plan, int axis, const void* in, void* out,
+                                 int direction, void* stream);
+
+/* FFT, first stage on `axis` (Eq. 16, then the twiddle if fuse_twiddle != 0):
+ *   out[k_a*B + beta] = T * sum_l exp(-+2 pi i k_a l / A) in[B*l + beta],
+ *   T = exp(-+2 pi i beta k_a / N) if fuse_twiddle else 1.  Valid on FFT plans. */
+dft3d_status dft3d_fft_first_stage(dft3d_plan plan, int axis, const void* in, void* out,
+                                   int direction, int fuse_twiddle, void* stream);
+
+/* FFT, the twiddle alone (the diagonal part of Eq. 15's phase adjustment):
+ *   out[k_a*B + beta] = exp(-+2 pi i beta k_a / N) in[k_a*B + beta].  Memory-bound pass. */
+dft3d_status dft3d_fft_phase(dft3d_plan plan, int axis, const void* in, void* out,
+                             int direction, void* stream);
+
+/* FFT, second stage on `axis` (the matrix part of Eq. 15's phase adjustment):
+ *   W[k_a, k_b] = sum_beta exp(-+2 pi i k_b beta / B) in[k_a*B + beta]
+ * stored at slot k_a*B + k_b, or, if reorder != 0, in natural order at k_a + A*k_b.
+ * BACKWARD also scales by 1/N_axis. */
+dft3d_status dft3d_fft_second_stage(dft3d_plan plan, int axis, const void* in, void* out,
+                                    int direction, int reorder, void* stream);
+
+/* FFT, the re-ordering alone (Section IV, in-order transform): for every axis whose bit is set
+ * in axes_mask (bit 0 = x, 1 = y, 2 = z), out[k_a + A*k_b] = in[k_a*B + k_b].  Pure data
+ * movement through LDS; memory-bound pass. */
+dft3d_status dft3d_fft_reorder(dft3d_plan plan, int axes_mask, const void* in, void* out,
+                               void* stream);
+
+/* ---- host-side generator, exposed so its rounding can be tested without a GPU -------------- */
+
+/* Writes the n x n transform matrix of one axis as the library rounds it (fp64 evaluation with
+ * exact argument reduction, one rounding to fp32): re[k*n + j], im[k*n + j] = M[k, j].
+ * coords: NULL (uniform) or HOST array of n doubles.  HOST output arrays of n*n floats. */
+dft3d_status dft3d_generate_matrix(int64_t n, const double* coords, int direction, float* re,
+                                   float* im);
+
+/* Writes the A x B twiddle table T[k_a*B + beta] = exp(-+2 pi i beta k_a / (A*B)) to HOST arrays. */
+dft3d_status dft3d_generate_twiddle(int64_t A, int64_t B, int direction, float* re, float* im);
+
+const char* dft3d_status_string(dft3d_status s);
+const char* dft3d_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DFT3D_H */

@@ -1,0 +1,9 @@
+"""dft3d for MI355X: thin Python binding over the C-ABI library (see include/dft3d.h).
+
+Importing this package does not load the shared library; the first call does, and fails
+loudly if it has not been built (there is no CPU fallback).
+"""
+from .binding import (  # noqa: F401
+    BACKWARD, FFT, FLAG_CLOBBER_INPUT, FLAG_UNFUSED, FORWARD, KDFT, Dft3dError, Plan,
+    generate_matrix, generate_twiddle, library_path, load_library,
+)

@@ -1,0 +1,242 @@
+"""ctypes binding of libdft3d.so.  Argument marshalling only: every step runs in the library.
+
+Tensors are torch complex64 CUDA(HIP) tensors, contiguous, shape (nx, ny, nz); the binding
+passes ``data_ptr()`` and the current torch stream's handle.  torch is used for device memory
+and streams only.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+from . import build as _build
+
+KDFT = 0
+FFT = 1
+FORWARD = -1
+BACKWARD = 1
+FLAG_CLOBBER_INPUT = 1
+FLAG_UNFUSED = 2
+
+EXPORTS = [
+    "dft3d_plan_create", "dft3d_plan_create_ex", "dft3d_plan_destroy",
+    "dft3d_plan_workspace_bytes", "dft3d_plan_set_workspace", "dft3d_plan_get_split",
+    "dft3d_exec", "dft3d_mode_contract", "dft3d_fft_first_stage", "dft3d_fft_phase",
+    "dft3d_fft_second_stage", "dft3d_fft_reorder", "dft3d_generate_matrix",
+    "dft3d_generate_twiddle", "dft3d_status_string", "dft3d_last_error",
+]
+
+_lib = None
+
+
+class Dft3dError(RuntimeError):
+    def __init__(self, status: int, name: str, message: str):
+        super().__init__(f"{name}: {message}")
+        self.status = status
+        self.status_name = name
+
+
+def library_path() -> str:
+    return _build.lib_path()
+
+
+def load_library():
+    """Load libdft3d.so (built beforehand by build.build()); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} has not been built; run `python -m paper_2002_03260_amd.build` "
+            "(or __graft_entry__.build()) first -- there is no fallback path")
+    lib = ctypes.CDLL(path)
+    vp, i64, ci, u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32
+    lib.dft3d_plan_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, vp, vp, vp]
+    lib.dft3d_plan_create_ex.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, vp, vp, vp, vp, u32]
+    lib.dft3d_plan_destroy.argtypes = [vp]
+    lib.dft3d_plan_workspace_bytes.argtypes = [vp]
+    lib.dft3d_plan_workspace_bytes.restype = ctypes.c_size_t
+    lib.dft3d_plan_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
+    lib.dft3d_plan_get_split.argtypes = [vp, ci, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.dft3d_exec.argtypes = [vp, vp, vp, ci, vp]
+    lib.dft3d_mode_contract.argtypes = [vp, ci, vp, vp, ci, vp]
+    lib.dft3d_fft_first_stage.argtypes = [vp, ci, vp, vp, ci, ci, vp]
+    lib.dft3d_fft_phase.argtypes = [vp, ci, vp, vp, ci, vp]
+    lib.dft3d_fft_second_stage.argtypes = [vp, ci, vp, vp, ci, ci, vp]
+    lib.dft3d_fft_reorder.argtypes = [vp, ci, vp, vp, vp]
+    lib.dft3d_generate_matrix.argtypes = [i64, vp, ci, vp, vp]
+    lib.dft3d_generate_twiddle.argtypes = [i64, i64, ci, vp, vp]
+    for name in EXPORTS:
+        fn = getattr(lib, name)
+        if name in ("dft3d_status_string", "dft3d_last_error"):
+            fn.restype = ctypes.c_char_p
+        elif name != "dft3d_plan_workspace_bytes":
+            fn.restype = ctypes.c_int
+    lib.dft3d_status_string.argtypes = [ci]
+    lib.dft3d_last_error.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        lib = load_library()
+        raise Dft3dError(status, lib.dft3d_status_string(status).decode(),
+                         lib.dft3d_last_error().decode())
+
+
+def _host_coords(c, n):
+    if c is None:
+        return None
+    a = np.ascontiguousarray(c, dtype=np.float64)
+    if a.shape != (n,):
+        raise ValueError(f"coordinate array must have shape ({n},)")
+    return a
+
+
+def _np_ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def generate_matrix(n: int, coords=None, direction: int = FORWARD) -> np.ndarray:
+    """The n x n axis matrix exactly as the library rounds it (host call, complex64)."""
+    c = _host_coords(coords, n)
+    re = np.empty((n, n), np.float32)
+    im = np.empty((n, n), np.float32)
+    _check(load_library().dft3d_generate_matrix(n, _np_ptr(c), direction, _np_ptr(re), _np_ptr(im)))
+    return (re + 1j * im).astype(np.complex64)
+
+
+def generate_twiddle(A: int, B: int, direction: int = FORWARD) -> np.ndarray:
+    """The A x B twiddle table T[k_a, beta] as the library rounds it (host call, complex64)."""
+    re = np.empty((A, B), np.float32)
+    im = np.empty((A, B), np.float32)
+    _check(load_library().dft3d_generate_twiddle(A, B, direction, _np_ptr(re), _np_ptr(im)))
+    return (re + 1j * im).astype(np.complex64)
+
+
+def _stream_handle(stream) -> Optional[int]:
+    import torch
+
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+class Plan:
+    """Owns one dft3d_plan.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, shape: Sequence[int], formulation: int = KDFT, coords=(None, None, None),
+                 split: Optional[Sequence[int]] = None, flags: int = 0):
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        self.shape = tuple(int(s) for s in shape)
+        if len(self.shape) != 3:
+            raise ValueError("shape must have three entries")
+        self.formulation = formulation
+        self.flags = flags
+        cs = [_host_coords(c, n) for c, n in zip(coords, self.shape)]
+        sp = None
+        if split is not None:
+            sp = (ctypes.c_int64 * 3)(*[int(s) for s in split])
+        _check(self._lib.dft3d_plan_create_ex(ctypes.byref(self._h), *self.shape, formulation,
+                                              _np_ptr(cs[0]), _np_ptr(cs[1]), _np_ptr(cs[2]),
+                                              ctypes.cast(sp, ctypes.c_void_p) if sp else None,
+                                              flags))
+        self._workspace = None
+
+    # -- lifetime ---------------------------------------------------------------------------
+    def destroy(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            self._lib.dft3d_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+        self._workspace = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.destroy()
+
+    # -- workspace --------------------------------------------------------------------------
+    def workspace_bytes(self) -> int:
+        return int(self._lib.dft3d_plan_workspace_bytes(self._h))
+
+    def set_workspace(self, tensor):
+        """Give the plan a torch CUDA tensor as workspace (kept alive by this object)."""
+        nbytes = 0 if tensor is None else tensor.numel() * tensor.element_size()
+        ptr = None if tensor is None else ctypes.c_void_p(tensor.data_ptr())
+        _check(self._lib.dft3d_plan_set_workspace(self._h, ptr, nbytes))
+        self._workspace = tensor
+
+    def ensure_workspace(self, device="cuda"):
+        import torch
+
+        need = self.workspace_bytes()
+        if need and self._workspace is None:
+            self.set_workspace(torch.empty(need // 8, dtype=torch.complex64, device=device))
+
+    def split(self, axis: int):
+        a, b = ctypes.c_int64(), ctypes.c_int64()
+        _check(self._lib.dft3d_plan_get_split(self._h, axis, ctypes.byref(a), ctypes.byref(b)))
+        return int(a.value), int(b.value)
+
+    # -- execution --------------------------------------------------------------------------
+    def _tensors(self, x, out):
+        import torch
+
+        if x.dtype != torch.complex64 or not x.is_cuda or not x.is_contiguous():
+            raise ValueError("input must be a contiguous complex64 CUDA tensor")
+        if tuple(x.shape) != self.shape:
+            raise ValueError(f"input shape {tuple(x.shape)} does not match plan {self.shape}")
+        if out is None:
+            out = torch.empty_like(x)
+        elif (out.dtype != torch.complex64 or not out.is_cuda or not out.is_contiguous()
+              or tuple(out.shape) != self.shape):
+            raise ValueError("output must be a contiguous complex64 CUDA tensor of the plan's shape")
+        return ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(out.data_ptr()), out
+
+    def exec(self, x, out=None, direction: int = FORWARD, stream=None):
+        xi, oi, out = self._tensors(x, out)
+        if not (self.flags & FLAG_CLOBBER_INPUT):
+            self.ensure_workspace(x.device)
+        _check(self._lib.dft3d_exec(self._h, xi, oi, direction, _stream_handle(stream)))
+        return out
+
+    def mode_contract(self, axis, x, out=None, direction: int = FORWARD, stream=None):
+        xi, oi, out = self._tensors(x, out)
+        _check(self._lib.dft3d_mode_contract(self._h, axis, xi, oi, direction, _stream_handle(stream)))
+        return out
+
+    def fft_first_stage(self, axis, x, out=None, direction: int = FORWARD, fuse_twiddle: bool = True,
+                        stream=None):
+        xi, oi, out = self._tensors(x, out)
+        _check(self._lib.dft3d_fft_first_stage(self._h, axis, xi, oi, direction,
+                                               1 if fuse_twiddle else 0, _stream_handle(stream)))
+        return out
+
+    def fft_phase(self, axis, x, out=None, direction: int = FORWARD, stream=None):
+        xi, oi, out = self._tensors(x, out)
+        _check(self._lib.dft3d_fft_phase(self._h, axis, xi, oi, direction, _stream_handle(stream)))
+        return out
+
+    def fft_second_stage(self, axis, x, out=None, direction: int = FORWARD, reorder: bool = False,
+                         stream=None):
+        xi, oi, out = self._tensors(x, out)
+        _check(self._lib.dft3d_fft_second_stage(self._h, axis, xi, oi, direction,
+                                                1 if reorder else 0, _stream_handle(stream)))
+        return out
+
+    def fft_reorder(self, axes_mask, x, out=None, stream=None):
+        xi, oi, out = self._tensors(x, out)
+        _check(self._lib.dft3d_fft_reorder(self._h, axes_mask, xi, oi, _stream_handle(stream)))
+        return out

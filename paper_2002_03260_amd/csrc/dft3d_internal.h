@@ -1,0 +1,75 @@
+// Internal declarations shared by the host side (plan, generator) and the HIP kernels of the
+// dft3d library.  Not part of the public boundary (include/dft3d.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "dft3d.h"
+
+namespace dft3d {
+
+// ---- device matrices --------------------------------------------------------------------
+// A K x N complex matrix M is kept on the device as two fp32 planes stored TRANSPOSED,
+// plane[n * ld + k] = Re/Im M[k, n], zero-padded to `rows` x `ld` with ld a multiple of
+// kPlaneLdAlign and rows a multiple of kPlaneRowAlign, so kernels stage tiles of it without
+// bounds checks.  (Lanes of an MFMA operand walk k at fixed n: unit stride in this layout.)
+constexpr int kPlaneLdAlign = 128;
+constexpr int kPlaneRowAlign = 64;
+
+struct DeviceMatrix {
+    float* re = nullptr;
+    float* im = nullptr;
+    int K = 0;     // output length (rows of M)
+    int N = 0;     // contracted length (columns of M)
+    int ld = 0;    // padded K
+    int rows = 0;  // padded N
+};
+
+// ---- one mode contraction ---------------------------------------------------------------
+// in  viewed as [O][N][I] (contiguous),  out element (o, k, i) at
+//   (o / Olo) * sYohi + (o % Olo) * sYolo + k * sYk + i
+// out = scale * tw * sum_n M[k, n] in[o, n, i], with M conjugated if conj != 0 and
+// tw = Tw[k * twB + i / twInner] if Tw != nullptr else 1.
+struct ContractArgs {
+    const float2* X;
+    float2* Y;
+    DeviceMatrix M;
+    int64_t O;
+    int64_t I;
+    int64_t Olo, sYohi, sYolo, sYk;
+    const float2* Tw;
+    int twB;
+    int64_t twInner;
+    float scale;
+    int conj;
+};
+
+hipError_t launch_contract(const ContractArgs& a, hipStream_t stream);
+
+// ---- twiddle (phase) multiply -------------------------------------------------------------
+// Tensor viewed as [outer][A][B][inner]; out = in * Tw[k_a * B + beta] (conjugated if conj).
+hipError_t launch_phase(const float2* in, float2* out, int64_t outer, int A, int B, int64_t inner,
+                        const float2* Tw, int conj, hipStream_t stream);
+
+// ---- sub-index swap (in-order re-ordering) ------------------------------------------------
+// For each axis j with swap[j] != 0, the element at slot ka*B[j] + kb moves to ka + A[j]*kb.
+struct ReorderArgs {
+    const float2* in;
+    float2* out;
+    int n[3];
+    int A[3];
+    int B[3];
+    int swap[3];
+};
+hipError_t launch_reorder(const ReorderArgs& a, hipStream_t stream);
+
+// ---- host generator -----------------------------------------------------------------------
+// exp(sign * 2 pi i * t) for t = p/q reduced exactly (uniform) or a real number of turns.
+void unit_root_ratio(int64_t p, int64_t q, int sign, double* re, double* im);
+void unit_root_turns(double t, int sign, double* re, double* im);
+
+void set_error(const char* fmt, ...);
+
+}  // namespace dft3d

@@ -1,0 +1,588 @@
+// Host side of the dft3d C ABI: plan creation (split choice, matrix generation and upload),
+// argument validation and the sequencing of kernel launches for dft3d_exec and the step calls.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "dft3d_internal.h"
+
+namespace dft3d {
+
+namespace {
+thread_local char g_error[512] = "";
+}
+
+void set_error(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+}
+
+namespace {
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+void free_matrix(DeviceMatrix& m)
+{
+    if (m.re) (void)hipFree(m.re);
+    m = DeviceMatrix{};
+}
+
+// Upload a K x N complex matrix given as row-major host planes into the padded, transposed
+// device layout.  re and im share one allocation.
+dft3d_status upload_matrix(const std::vector<float>& re, const std::vector<float>& im, int K, int N,
+                           DeviceMatrix* out)
+{
+    DeviceMatrix m;
+    m.K = K;
+    m.N = N;
+    m.ld = round_up(K, kPlaneLdAlign);
+    m.rows = round_up(N, kPlaneRowAlign);
+    const size_t plane = (size_t)m.ld * m.rows;
+    std::vector<float> host(2 * plane, 0.0f);
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n) {
+            host[(size_t)n * m.ld + k] = re[(size_t)k * N + n];
+            host[plane + (size_t)n * m.ld + k] = im[(size_t)k * N + n];
+        }
+    float* dev = nullptr;
+    hipError_t e = hipMalloc((void**)&dev, 2 * plane * sizeof(float));
+    if (e != hipSuccess) {
+        set_error("hipMalloc of a %d x %d matrix failed: %s", K, N, hipGetErrorString(e));
+        return DFT3D_ERR_ALLOC;
+    }
+    e = hipMemcpy(dev, host.data(), 2 * plane * sizeof(float), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(dev);
+        set_error("upload of a %d x %d matrix failed: %s", K, N, hipGetErrorString(e));
+        return DFT3D_ERR_HIP;
+    }
+    m.re = dev;
+    m.im = dev + plane;
+    *out = m;
+    return DFT3D_OK;
+}
+
+dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out)
+{
+    std::vector<float> re((size_t)n * n), im((size_t)n * n);
+    dft3d_status s = dft3d_generate_matrix(n, coords, DFT3D_FORWARD, re.data(), im.data());
+    if (s != DFT3D_OK) return s;
+    return upload_matrix(re, im, (int)n, (int)n, out);
+}
+
+// Default first-stage length: 2^floor(log2(N)/2) for powers of two, else the divisor pair
+// closest to sqrt(N) with A <= B.
+int64_t default_split(int64_t n)
+{
+    if ((n & (n - 1)) == 0) {
+        int lg = 0;
+        while ((int64_t(1) << (lg + 1)) <= n) ++lg;
+        return int64_t(1) << (lg / 2);
+    }
+    int64_t best = 1;
+    for (int64_t a = 1; a * a <= n; ++a)
+        if (n % a == 0) best = a;
+    return best;
+}
+
+}  // namespace
+}  // namespace dft3d
+
+using namespace dft3d;
+
+struct dft3d_plan_s {
+    int64_t n[3] = {0, 0, 0};
+    dft3d_formulation form = DFT3D_KDFT;
+    uint32_t flags = 0;
+    bool nonuniform[3] = {false, false, false};
+
+    // KDFT: forward matrix per axis; axes with equal length and no coordinates share storage
+    DeviceMatrix M[3];
+    int M_owner[3] = {0, 1, 2};
+
+    // FFT: per axis first/second-stage matrices and twiddle table (shared between equal axes)
+    int64_t A[3] = {1, 1, 1}, B[3] = {1, 1, 1};
+    DeviceMatrix FA[3], FB[3];
+    float2* Tw[3] = {nullptr, nullptr, nullptr};
+    int F_owner[3] = {0, 1, 2};
+
+    void* workspace = nullptr;
+    size_t workspace_bytes = 0;
+
+    int64_t elements() const { return n[0] * n[1] * n[2]; }
+    int64_t inner(int axis) const { return axis == 0 ? n[1] * n[2] : (axis == 1 ? n[2] : 1); }
+    int64_t outer(int axis) const { return axis == 0 ? 1 : (axis == 1 ? n[0] : n[0] * n[1]); }
+};
+
+namespace {
+
+bool valid_direction(int d) { return d == DFT3D_FORWARD || d == DFT3D_BACKWARD; }
+
+dft3d_status check_buffers(const dft3d_plan_s* p, const void* in, void* out, const char* who)
+{
+    if (!p) { set_error("%s: plan is NULL", who); return DFT3D_ERR_INVALID_ARG; }
+    if (!in || !out) { set_error("%s: NULL tensor pointer", who); return DFT3D_ERR_INVALID_ARG; }
+    if (((uintptr_t)in & 15) || ((uintptr_t)out & 15)) {
+        set_error("%s: tensor pointers must be 16-byte aligned", who);
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    const uintptr_t bytes = (uintptr_t)p->elements() * 8;
+    const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
+    if (a < b + bytes && b < a + bytes) {
+        set_error("%s: in and out overlap (the transform is out of place)", who);
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    return DFT3D_OK;
+}
+
+dft3d_status hip_status(hipError_t e, const char* who)
+{
+    if (e == hipSuccess) return DFT3D_OK;
+    set_error("%s: kernel launch failed: %s", who, hipGetErrorString(e));
+    return DFT3D_ERR_HIP;
+}
+
+// out[.., k, ..] = sum_n M[k,n] in[.., n, ..] along `axis`, natural layout.
+hipError_t run_mode(const dft3d_plan_s* p, int axis, const float2* in, float2* out, int conj,
+                    float scale, hipStream_t st)
+{
+    ContractArgs a{};
+    a.X = in;
+    a.Y = out;
+    a.M = p->M[axis];
+    a.O = p->outer(axis);
+    a.I = p->inner(axis);
+    a.Olo = 1;
+    a.sYohi = (int64_t)a.M.K * a.I;
+    a.sYolo = 0;
+    a.sYk = a.I;
+    a.Tw = nullptr;
+    a.twB = 1;
+    a.twInner = 1;
+    a.scale = scale;
+    a.conj = conj;
+    return launch_contract(a, st);
+}
+
+// FFT first stage on `axis`: view [outer][A][B*inner], contract the A index.
+hipError_t run_first_stage(const dft3d_plan_s* p, int axis, const float2* in, float2* out, int conj,
+                           int fuse_twiddle, hipStream_t st)
+{
+    ContractArgs a{};
+    a.X = in;
+    a.Y = out;
+    a.M = p->FA[axis];
+    a.O = p->outer(axis);
+    a.I = p->B[axis] * p->inner(axis);
+    a.Olo = 1;
+    a.sYohi = (int64_t)a.M.K * a.I;
+    a.sYolo = 0;
+    a.sYk = a.I;
+    a.Tw = fuse_twiddle ? p->Tw[axis] : nullptr;
+    a.twB = (int)p->B[axis];
+    a.twInner = p->inner(axis);
+    a.scale = 1.0f;
+    a.conj = conj;
+    return launch_contract(a, st);
+}
+
+// FFT second stage on `axis`: view [outer*A][B][inner], contract the B index; with reorder the
+// result (k_a, k_b) lands at natural position k_a + A*k_b of the axis.
+hipError_t run_second_stage(const dft3d_plan_s* p, int axis, const float2* in, float2* out, int conj,
+                            float scale, int reorder, hipStream_t st)
+{
+    const int64_t A = p->A[axis], B = p->B[axis], inner = p->inner(axis);
+    ContractArgs a{};
+    a.X = in;
+    a.Y = out;
+    a.M = p->FB[axis];
+    a.O = p->outer(axis) * A;
+    a.I = inner;
+    a.Olo = A;
+    a.sYohi = A * B * inner;
+    if (reorder) {
+        a.sYolo = inner;        // k_a is the fast sub-index
+        a.sYk = A * inner;      // k_b the slow one
+    } else {
+        a.sYolo = B * inner;
+        a.sYk = inner;
+    }
+    a.Tw = nullptr;
+    a.twB = 1;
+    a.twInner = 1;
+    a.scale = scale;
+    a.conj = conj;
+    return launch_contract(a, st);
+}
+
+hipError_t run_reorder(const dft3d_plan_s* p, int mask, const float2* in, float2* out, hipStream_t st)
+{
+    ReorderArgs r{};
+    r.in = in;
+    r.out = out;
+    for (int j = 0; j < 3; ++j) {
+        r.n[j] = (int)p->n[j];
+        r.A[j] = (int)p->A[j];
+        r.B[j] = (int)p->B[j];
+        r.swap[j] = (mask >> j) & 1;
+    }
+    return launch_reorder(r, st);
+}
+
+float axis_scale(const dft3d_plan_s* p, int axis, int direction)
+{
+    return direction == DFT3D_BACKWARD ? (float)(1.0 / (double)p->n[axis]) : 1.0f;
+}
+
+dft3d_status require_uniform_for_backward(const dft3d_plan_s* p, int direction, const char* who)
+{
+    if (direction == DFT3D_BACKWARD && (p->nonuniform[0] || p->nonuniform[1] || p->nonuniform[2])) {
+        set_error("%s: BACKWARD is not defined for a plan with nonuniform axes", who);
+        return DFT3D_ERR_UNSUPPORTED;
+    }
+    return DFT3D_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dft3d_status_string(dft3d_status s)
+{
+    switch (s) {
+        case DFT3D_OK: return "DFT3D_OK";
+        case DFT3D_ERR_INVALID_ARG: return "DFT3D_ERR_INVALID_ARG";
+        case DFT3D_ERR_UNSUPPORTED: return "DFT3D_ERR_UNSUPPORTED";
+        case DFT3D_ERR_ALLOC: return "DFT3D_ERR_ALLOC";
+        case DFT3D_ERR_HIP: return "DFT3D_ERR_HIP";
+    }
+    return "DFT3D_ERR_UNKNOWN";
+}
+
+const char* dft3d_last_error(void) { return g_error; }
+
+dft3d_status dft3d_plan_create(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
+                               dft3d_formulation f, const double* cx, const double* cy,
+                               const double* cz)
+{
+    return dft3d_plan_create_ex(plan, nx, ny, nz, f, cx, cy, cz, nullptr, 0);
+}
+
+dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
+                                  dft3d_formulation f, const double* cx, const double* cy,
+                                  const double* cz, const int64_t* split, uint32_t flags)
+{
+    if (!plan) { set_error("plan_create: plan pointer is NULL"); return DFT3D_ERR_INVALID_ARG; }
+    *plan = nullptr;
+    const int64_t n[3] = {nx, ny, nz};
+    const double* c[3] = {cx, cy, cz};
+    for (int j = 0; j < 3; ++j)
+        if (n[j] < 1 || n[j] > (int64_t(1) << 24)) {
+            set_error("plan_create: axis %d has length %lld (must be 1..2^24)", j, (long long)n[j]);
+            return DFT3D_ERR_INVALID_ARG;
+        }
+    if (f != DFT3D_KDFT && f != DFT3D_FFT) {
+        set_error("plan_create: unknown formulation %d", (int)f);
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    if (flags & ~(DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_UNFUSED)) {
+        set_error("plan_create: unknown flag bits 0x%x", flags);
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    if (f == DFT3D_FFT && (cx || cy || cz)) {
+        set_error("plan_create: the FFT formulation requires uniform sampling on every axis");
+        return DFT3D_ERR_UNSUPPORTED;
+    }
+    // inner / outer extents are handled as 32-bit quantities inside the kernels
+    if (ny * nz >= (int64_t(1) << 31) || nx * ny >= (int64_t(1) << 31)) {
+        set_error("plan_create: ny*nz and nx*ny must be below 2^31");
+        return DFT3D_ERR_UNSUPPORTED;
+    }
+
+    dft3d_plan_s* p = new (std::nothrow) dft3d_plan_s();
+    if (!p) { set_error("plan_create: out of host memory"); return DFT3D_ERR_ALLOC; }
+    p->form = f;
+    p->flags = flags;
+    for (int j = 0; j < 3; ++j) {
+        p->n[j] = n[j];
+        p->nonuniform[j] = c[j] != nullptr;
+    }
+
+    dft3d_status s = DFT3D_OK;
+    if (f == DFT3D_KDFT) {
+        for (int j = 0; j < 3 && s == DFT3D_OK; ++j) {
+            p->M_owner[j] = j;
+            for (int i = 0; i < j; ++i)
+                if (!c[j] && !c[i] && n[i] == n[j]) { p->M_owner[j] = i; break; }
+            if (p->M_owner[j] == j) s = make_axis_matrix(n[j], c[j], &p->M[j]);
+            else p->M[j] = p->M[p->M_owner[j]];
+        }
+    } else {
+        for (int j = 0; j < 3 && s == DFT3D_OK; ++j) {
+            int64_t A = (split && split[j] > 0) ? split[j] : default_split(n[j]);
+            if (A < 1 || n[j] % A != 0) {
+                set_error("plan_create: split %lld does not divide axis length %lld", (long long)A,
+                          (long long)n[j]);
+                s = DFT3D_ERR_INVALID_ARG;
+                break;
+            }
+            p->A[j] = A;
+            p->B[j] = n[j] / A;
+            p->F_owner[j] = j;
+            for (int i = 0; i < j; ++i)
+                if (n[i] == n[j] && p->A[i] == A) { p->F_owner[j] = i; break; }
+            if (p->F_owner[j] != j) {
+                const int i = p->F_owner[j];
+                p->FA[j] = p->FA[i];
+                p->FB[j] = p->FB[i];
+                p->Tw[j] = p->Tw[i];
+                continue;
+            }
+            s = make_axis_matrix(p->A[j], nullptr, &p->FA[j]);
+            if (s == DFT3D_OK) s = make_axis_matrix(p->B[j], nullptr, &p->FB[j]);
+            if (s != DFT3D_OK) break;
+            const size_t cnt = (size_t)(p->A[j] * p->B[j]);
+            std::vector<float> tr(cnt), ti(cnt);
+            s = dft3d_generate_twiddle(p->A[j], p->B[j], DFT3D_FORWARD, tr.data(), ti.data());
+            if (s != DFT3D_OK) break;
+            std::vector<float2> tw(cnt);
+            for (size_t e = 0; e < cnt; ++e) tw[e] = make_float2(tr[e], ti[e]);
+            hipError_t e = hipMalloc((void**)&p->Tw[j], cnt * sizeof(float2));
+            if (e != hipSuccess) {
+                set_error("plan_create: hipMalloc of a twiddle table failed: %s", hipGetErrorString(e));
+                s = DFT3D_ERR_ALLOC;
+                break;
+            }
+            e = hipMemcpy(p->Tw[j], tw.data(), cnt * sizeof(float2), hipMemcpyHostToDevice);
+            if (e != hipSuccess) {
+                set_error("plan_create: twiddle upload failed: %s", hipGetErrorString(e));
+                s = DFT3D_ERR_HIP;
+                break;
+            }
+        }
+    }
+    if (s != DFT3D_OK) {
+        dft3d_plan_destroy(p);
+        return s;
+    }
+    *plan = p;
+    return DFT3D_OK;
+}
+
+dft3d_status dft3d_plan_destroy(dft3d_plan p)
+{
+    if (!p) return DFT3D_OK;
+    for (int j = 0; j < 3; ++j) {
+        if (p->form == DFT3D_KDFT) {
+            if (p->M_owner[j] == j) free_matrix(p->M[j]);
+        } else if (p->F_owner[j] == j) {
+            free_matrix(p->FA[j]);
+            free_matrix(p->FB[j]);
+            if (p->Tw[j]) (void)hipFree(p->Tw[j]);
+        }
+    }
+    delete p;
+    return DFT3D_OK;
+}
+
+size_t dft3d_plan_workspace_bytes(dft3d_plan p)
+{
+    if (!p) return 0;
+    if (p->flags & DFT3D_FLAG_CLOBBER_INPUT) return 0;
+    return (size_t)p->elements() * 8;
+}
+
+dft3d_status dft3d_plan_set_workspace(dft3d_plan p, void* dev, size_t bytes)
+{
+    if (!p) { set_error("set_workspace: plan is NULL"); return DFT3D_ERR_INVALID_ARG; }
+    if (dev && ((uintptr_t)dev & 15)) {
+        set_error("set_workspace: workspace must be 16-byte aligned");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    if (dev && bytes < dft3d_plan_workspace_bytes(p)) {
+        set_error("set_workspace: %zu bytes given, %zu needed", bytes, dft3d_plan_workspace_bytes(p));
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    p->workspace = dev;
+    p->workspace_bytes = dev ? bytes : 0;
+    return DFT3D_OK;
+}
+
+dft3d_status dft3d_plan_get_split(dft3d_plan p, int axis, int64_t* A, int64_t* B)
+{
+    if (!p || axis < 0 || axis > 2 || !A || !B) {
+        set_error("get_split: invalid argument");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    if (p->form != DFT3D_FFT) {
+        set_error("get_split: not an FFT plan");
+        return DFT3D_ERR_UNSUPPORTED;
+    }
+    *A = p->A[axis];
+    *B = p->B[axis];
+    return DFT3D_OK;
+}
+
+dft3d_status dft3d_mode_contract(dft3d_plan p, int axis, const void* in, void* out, int direction,
+                                 void* stream)
+{
+    dft3d_status s = check_buffers(p, in, out, "mode_contract");
+    if (s != DFT3D_OK) return s;
+    if (axis < 0 || axis > 2 || !valid_direction(direction)) {
+        set_error("mode_contract: bad axis or direction");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    if (p->form != DFT3D_KDFT) { set_error("mode_contract: not a KDFT plan"); return DFT3D_ERR_UNSUPPORTED; }
+    if (direction == DFT3D_BACKWARD && p->nonuniform[axis]) {
+        set_error("mode_contract: BACKWARD is not defined for a nonuniform axis");
+        return DFT3D_ERR_UNSUPPORTED;
+    }
+    return hip_status(run_mode(p, axis, (const float2*)in, (float2*)out, direction == DFT3D_BACKWARD,
+                               axis_scale(p, axis, direction), (hipStream_t)stream),
+                      "mode_contract");
+}
+
+dft3d_status dft3d_fft_first_stage(dft3d_plan p, int axis, const void* in, void* out, int direction,
+                                   int fuse_twiddle, void* stream)
+{
+    dft3d_status s = check_buffers(p, in, out, "fft_first_stage");
+    if (s != DFT3D_OK) return s;
+    if (axis < 0 || axis > 2 || !valid_direction(direction)) {
+        set_error("fft_first_stage: bad axis or direction");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    if (p->form != DFT3D_FFT) { set_error("fft_first_stage: not an FFT plan"); return DFT3D_ERR_UNSUPPORTED; }
+    return hip_status(run_first_stage(p, axis, (const float2*)in, (float2*)out,
+                                      direction == DFT3D_BACKWARD, fuse_twiddle, (hipStream_t)stream),
+                      "fft_first_stage");
+}
+
+dft3d_status dft3d_fft_phase(dft3d_plan p, int axis, const void* in, void* out, int direction,
+                             void* stream)
+{
+    dft3d_status s = check_buffers(p, in, out, "fft_phase");
+    if (s != DFT3D_OK) return s;
+    if (axis < 0 || axis > 2 || !valid_direction(direction)) {
+        set_error("fft_phase: bad axis or direction");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    if (p->form != DFT3D_FFT) { set_error("fft_phase: not an FFT plan"); return DFT3D_ERR_UNSUPPORTED; }
+    return hip_status(launch_phase((const float2*)in, (float2*)out, p->outer(axis), (int)p->A[axis],
+                                   (int)p->B[axis], p->inner(axis), p->Tw[axis],
+                                   direction == DFT3D_BACKWARD, (hipStream_t)stream),
+                      "fft_phase");
+}
+
+dft3d_status dft3d_fft_second_stage(dft3d_plan p, int axis, const void* in, void* out, int direction,
+                                    int reorder, void* stream)
+{
+    dft3d_status s = check_buffers(p, in, out, "fft_second_stage");
+    if (s != DFT3D_OK) return s;
+    if (axis < 0 || axis > 2 || !valid_direction(direction)) {
+        set_error("fft_second_stage: bad axis or direction");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    if (p->form != DFT3D_FFT) { set_error("fft_second_stage: not an FFT plan"); return DFT3D_ERR_UNSUPPORTED; }
+    return hip_status(run_second_stage(p, axis, (const float2*)in, (float2*)out,
+                                       direction == DFT3D_BACKWARD, axis_scale(p, axis, direction),
+                                       reorder, (hipStream_t)stream),
+                      "fft_second_stage");
+}
+
+dft3d_status dft3d_fft_reorder(dft3d_plan p, int axes_mask, const void* in, void* out, void* stream)
+{
+    dft3d_status s = check_buffers(p, in, out, "fft_reorder");
+    if (s != DFT3D_OK) return s;
+    if (axes_mask < 0 || axes_mask > 7) { set_error("fft_reorder: bad axes mask"); return DFT3D_ERR_INVALID_ARG; }
+    if (p->form != DFT3D_FFT) { set_error("fft_reorder: not an FFT plan"); return DFT3D_ERR_UNSUPPORTED; }
+    return hip_status(run_reorder(p, axes_mask, (const float2*)in, (float2*)out, (hipStream_t)stream),
+                      "fft_reorder");
+}
+
+dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, void* stream)
+{
+    dft3d_status s = check_buffers(p, in, out, "exec");
+    if (s != DFT3D_OK) return s;
+    if (!valid_direction(direction)) { set_error("exec: bad direction"); return DFT3D_ERR_INVALID_ARG; }
+    s = require_uniform_for_backward(p, direction, "exec");
+    if (s != DFT3D_OK) return s;
+
+    const bool clobber = (p->flags & DFT3D_FLAG_CLOBBER_INPUT) != 0;
+    float2* other = nullptr;     // the ping-pong partner of `out`
+    if (clobber) {
+        other = (float2*)const_cast<void*>(in);
+    } else {
+        const size_t need = dft3d_plan_workspace_bytes(p);
+        if (!p->workspace || p->workspace_bytes < need) {
+            set_error("exec: a workspace of %zu bytes must be set first", need);
+            return DFT3D_ERR_INVALID_ARG;
+        }
+        const uintptr_t w = (uintptr_t)p->workspace, bytes = (uintptr_t)need;
+        const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
+        if ((w < a + bytes && a < w + bytes) || (w < b + bytes && b < w + bytes)) {
+            set_error("exec: the workspace overlaps in or out");
+            return DFT3D_ERR_INVALID_ARG;
+        }
+        other = (float2*)p->workspace;
+    }
+
+    hipStream_t st = (hipStream_t)stream;
+    const int conj = direction == DFT3D_BACKWARD;
+    const bool unfused = (p->flags & DFT3D_FLAG_UNFUSED) != 0;
+
+    // The passes ping-pong between `out` and `other`; the pass count is odd so that, starting
+    // with in -> out, the last pass also lands in `out`.
+    //   KDFT: modes z, y, x (3 passes).
+    //   FFT : per axis z, y, x: first stage (+twiddle), second stage; the x and y re-orderings
+    //         are folded into the second-stage stores (they only change row addresses), the z
+    //         re-ordering is one transposing pass at the end (7 passes).
+    //   FFT unfused: per axis first stage, twiddle pass, second stage; one re-ordering pass of
+    //         all three axes at the end (10 passes -> starts with in -> other).
+    int npass = 3;
+    if (p->form == DFT3D_FFT) npass = unfused ? 10 : 7;
+    if (clobber && (npass % 2 == 0)) {
+        set_error("exec: CLOBBER_INPUT cannot be combined with this pass structure");
+        return DFT3D_ERR_UNSUPPORTED;
+    }
+    const float2* src = (const float2*)in;
+    float2* dst = (npass % 2 == 1) ? (float2*)out : other;
+    auto advance = [&]() {
+        src = dst;
+        dst = (dst == (float2*)out) ? other : (float2*)out;
+    };
+
+    hipError_t e = hipSuccess;
+    if (p->form == DFT3D_KDFT) {
+        for (int axis = 2; axis >= 0 && e == hipSuccess; --axis) {
+            e = run_mode(p, axis, src, dst, conj, axis_scale(p, axis, direction), st);
+            advance();
+        }
+    } else {
+        for (int axis = 2; axis >= 0 && e == hipSuccess; --axis) {
+            e = run_first_stage(p, axis, src, dst, conj, unfused ? 0 : 1, st);
+            advance();
+            if (unfused && e == hipSuccess) {
+                e = launch_phase(src, dst, p->outer(axis), (int)p->A[axis], (int)p->B[axis],
+                                 p->inner(axis), p->Tw[axis], conj, st);
+                advance();
+            }
+            if (e != hipSuccess) break;
+            const int fold = (!unfused && axis != 2) ? 1 : 0;
+            e = run_second_stage(p, axis, src, dst, conj, axis_scale(p, axis, direction), fold, st);
+            advance();
+        }
+        if (e == hipSuccess) {
+            e = run_reorder(p, unfused ? 7 : 4, src, dst, st);
+            advance();
+        }
+    }
+    return hip_status(e, "exec");
+}
+
+}  // extern "C"

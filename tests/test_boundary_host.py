@@ -1,0 +1,117 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header declares, its host
+generator rounds like the fp64 oracle says it should, and argument errors come back as status
+codes.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2002_03260_amd as dft
+from paper_2002_03260_amd import binding
+from oracle import dft3d_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2002_03260_amd import build
+
+    if build.is_stale():
+        build.build()
+    return dft.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dft3d.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dft3d_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = declared_symbols()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def ulp32(x):
+    return np.spacing(np.abs(x).astype(np.float32)).astype(np.float64)
+
+
+@pytest.mark.parametrize("n,nonuniform", [(2, False), (4, False), (8, False), (30, False), (37, False),
+                                          (256, False), (2048, False), (128, True), (45, True)])
+def test_generated_matrix_is_oracle_matrix_rounded_once(lib, n, nonuniform):
+    c = np.sort(np.random.default_rng(n).random(n)) if nonuniform else None
+    M = dft.generate_matrix(n, c)
+    O = orc.dft_matrix(n, c)
+    for part in (np.real, np.imag):
+        err = np.abs(part(M).astype(np.float64) - part(O))
+        # one rounding to fp32 of a value computed to ~1e-16 (k*c carries ~k*1e-16 for nonuniform)
+        assert np.all(err <= 0.5 * ulp32(part(O)) + 1e-12)
+    Mb = dft.generate_matrix(n, c, dft.BACKWARD)
+    assert np.array_equal(Mb, M.conj())
+
+
+@pytest.mark.parametrize("n", [4, 8, 16, 64, 12, 20])
+def test_quarter_turn_entries_are_exact(lib, n):
+    M = dft.generate_matrix(n)
+    k, j = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    r = (k * j) % n
+    for q, val in ((0, 1), (1, -1j), (2, -1), (3, 1j)):
+        if (q * n) % 4:
+            continue
+        mask = r == q * n // 4
+        assert np.all(M[mask] == np.complex64(val))
+    assert np.all(np.abs(np.abs(M.astype(np.complex128)) - 1) < 1e-7)
+
+
+def test_uniform_coordinates_reproduce_uniform_matrix_bitwise(lib):
+    for n in (8, 64, 512):
+        assert np.array_equal(dft.generate_matrix(n, np.arange(n) / n), dft.generate_matrix(n))
+
+
+def test_twiddle_table(lib):
+    for A, B in ((16, 32), (32, 64), (3, 5), (1, 7), (7, 1)):
+        T = dft.generate_twiddle(A, B)
+        want = np.exp(-2j * np.pi * ((np.outer(np.arange(A), np.arange(B)) % (A * B)) / (A * B)))
+        assert np.max(np.abs(T - want)) < 6.1e-8
+        assert np.array_equal(dft.generate_twiddle(A, B, dft.BACKWARD), T.conj())
+        assert np.all(T[0, :] == 1) and np.all(T[:, 0] == 1)
+
+
+def test_argument_errors_are_status_codes(lib):
+    h = ctypes.c_void_p()
+    st = lib.dft3d_plan_create(ctypes.byref(h), 0, 4, 4, dft.KDFT, None, None, None)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_INVALID_ARG" and not h
+    assert b"axis 0" in lib.dft3d_last_error()
+    st = lib.dft3d_plan_create(None, 4, 4, 4, dft.KDFT, None, None, None)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_INVALID_ARG"
+    st = lib.dft3d_plan_create(ctypes.byref(h), 4, 4, 4, 7, None, None, None)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_INVALID_ARG"
+    c = (ctypes.c_double * 4)(0.0, 0.1, 0.2, 0.3)
+    st = lib.dft3d_plan_create(ctypes.byref(h), 4, 4, 4, dft.FFT, ctypes.cast(c, ctypes.c_void_p), None, None)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_UNSUPPORTED" and not h
+    st = lib.dft3d_plan_create_ex(ctypes.byref(h), 4, 4, 4, dft.KDFT, None, None, None, None, 0x80)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_INVALID_ARG"
+    # NULL plans
+    assert lib.dft3d_plan_destroy(None) == 0
+    assert lib.dft3d_plan_workspace_bytes(None) == 0
+    st = lib.dft3d_exec(None, None, None, dft.FORWARD, None)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_INVALID_ARG"
+    st = lib.dft3d_generate_matrix(0, None, dft.FORWARD, None, None)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_INVALID_ARG"
+    assert lib.dft3d_status_string(99) == b"DFT3D_ERR_UNKNOWN"
+
+
+def test_plan_creation_without_a_gpu_fails_loudly(lib):
+    import torch
+
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(dft.Dft3dError) as ei:
+        dft.Plan((8, 8, 8), dft.KDFT)
+    assert ei.value.status_name in ("DFT3D_ERR_ALLOC", "DFT3D_ERR_HIP")

@@ -1,0 +1,273 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle.
+
+Bar (relative L2 error in fp64, complex64 arithmetic on the GPU): <= 2e-5 for every transform
+and every single step; bit-exact where all arithmetic is exact in fp32 (N in {2, 4} with small
+Gaussian-integer inputs).  The maximum element-wise error is printed for the record.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import dft3d_workloads as wl
+from oracle import dft3d_oracle as orc
+from oracle import fft_formulation as ff
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-5
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def rel_l2(got, want):
+    got = np.asarray(got, dtype=np.complex128)
+    d = np.linalg.norm((got - want).ravel())
+    return d / max(np.linalg.norm(want.ravel()), 1e-300)
+
+
+def report(name, got, want):
+    got = np.asarray(got, dtype=np.complex128)
+    r = rel_l2(got, want)
+    m = np.max(np.abs(got - want))
+    say(f"[parity] {name}: relL2={r:.3e} max|err|={m:.3e} max|ref|={np.max(np.abs(want)):.3e}")
+    return r
+
+
+@pytest.fixture(scope="module")
+def dft(gpu_device):
+    import paper_2002_03260_amd as d
+
+    d.load_library()
+    return d
+
+
+def to_dev(x):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda")
+
+
+def to_host(t):
+    import torch
+
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+# ------------------------------------------------------------------------------------ KDFT
+KDFT_SHAPES = [(4, 4, 4), (5, 7, 3), (1, 1, 9), (9, 1, 1), (17, 33, 20), (32, 32, 32),
+               (64, 48, 80), (130, 20, 258), (24, 200, 36)]
+
+
+@pytest.mark.parametrize("shape", KDFT_SHAPES)
+def test_kdft_uniform_matches_oracle(dft, shape):
+    say(f"case kdft uniform {shape}")
+    x = wl.draw_complex(shape, "normal", 1000 + sum(shape))
+    want = orc.dft3d(x)
+    with dft.Plan(shape, dft.KDFT) as p:
+        got = to_host(p.exec(to_dev(x)))
+    assert report(f"kdft {shape}", got, want) <= TOL
+
+
+@pytest.mark.parametrize("shape", [(6, 10, 12), (40, 33, 70), (128, 16, 32)])
+def test_kdft_nonuniform_matches_oracle(dft, shape):
+    say(f"case kdft nonuniform {shape}")
+    x = wl.draw_complex(shape, "uniform", 2000 + sum(shape))
+    rng = np.random.default_rng(5)
+    coords = (np.sort(rng.random(shape[0])), None, np.sort(rng.random(shape[2])))
+    want = orc.dft3d(x, coords)
+    with dft.Plan(shape, dft.KDFT, coords=coords) as p:
+        got = to_host(p.exec(to_dev(x)))
+    assert report(f"kdft nonuniform {shape}", got, want) <= TOL
+
+
+@pytest.mark.parametrize("axis", [0, 1, 2])
+@pytest.mark.parametrize("shape", [(20, 36, 28), (128, 130, 64), (3, 5, 260)])
+def test_single_mode_contraction(dft, shape, axis):
+    say(f"case mode_contract {shape} axis {axis}")
+    x = wl.draw_complex(shape, "normal", 3000 + axis)
+    M = orc.dft_matrix(shape[axis])
+    want = orc.mode_contract(M, x, axis)
+    with dft.Plan(shape, dft.KDFT) as p:
+        got = to_host(p.mode_contract(axis, to_dev(x)))
+        assert report(f"mode {axis} {shape}", got, want) <= TOL
+        # backward: conjugate matrix, scaled by 1/N
+        wantb = orc.mode_contract(orc.dft_matrix(shape[axis], sign=orc.BACKWARD), x, axis) / shape[axis]
+        gotb = to_host(p.mode_contract(axis, to_dev(x), direction=dft.BACKWARD))
+        assert report(f"mode {axis} {shape} backward", gotb, wantb) <= TOL
+
+
+def test_kdft_backward_and_roundtrip(dft):
+    shape = (32, 48, 64)
+    say(f"case kdft backward {shape}")
+    x = wl.draw_complex(shape, "normal", 77)
+    with dft.Plan(shape, dft.KDFT) as p:
+        xd = to_dev(x)
+        X = p.exec(xd)
+        got = to_host(p.exec(xd, direction=dft.BACKWARD))
+        assert report("kdft backward", got, orc.dft3d(x, sign=orc.BACKWARD)) <= TOL
+        back = to_host(p.exec(X, direction=dft.BACKWARD))
+        assert report("kdft roundtrip", back, x.astype(np.complex128)) <= TOL
+
+
+def test_kdft_clobber_input(dft):
+    shape = (16, 24, 40)
+    x = wl.draw_complex(shape, "normal", 78)
+    with dft.Plan(shape, dft.KDFT, flags=dft.FLAG_CLOBBER_INPUT) as p:
+        assert p.workspace_bytes() == 0
+        got = to_host(p.exec(to_dev(x)))
+    assert report("kdft clobber", got, orc.dft3d(x)) <= TOL
+
+
+@pytest.mark.parametrize("shape", [(2, 2, 2), (4, 4, 4), (2, 4, 2), (4, 2, 4)])
+def test_exact_arithmetic_is_bitwise(dft, shape):
+    # every matrix entry is 0 / +-1 and the inputs are small integers: fp32 is exact
+    say(f"case exact {shape}")
+    x = wl.gaussian_integers(shape, 31)
+    want = orc.dft3d(x)
+    assert np.array_equal(want, np.round(want))
+    with dft.Plan(shape, dft.KDFT) as p:
+        got = to_host(p.exec(to_dev(x)))
+    assert np.array_equal(got.astype(np.complex128), np.round(want))
+    with dft.Plan(shape, dft.FFT) as p:
+        got = to_host(p.exec(to_dev(x)))
+    assert np.array_equal(got.astype(np.complex128), np.round(want))
+
+
+def test_generated_matrix_on_device_equals_host_generator(dft):
+    # contracting the identity along an axis returns the matrix the device holds
+    n = 48
+    shape = (n, 1, n)
+    x = np.zeros(shape, np.complex64)
+    x[np.arange(n), 0, np.arange(n)] = 1            # x[a, 0, c] = delta(a, c)
+    rng = np.random.default_rng(3)
+    c = np.sort(rng.random(n))
+    with dft.Plan(shape, dft.KDFT, coords=(c, None, None)) as p:
+        got = to_host(p.mode_contract(0, to_dev(x)))[:, 0, :]     # got[k, c] = M[k, c]
+    assert np.array_equal(got, dft.generate_matrix(n, c))
+
+
+# ------------------------------------------------------------------------------------ FFT steps
+FFT_CASES = [((16, 16, 16), None), ((8, 12, 30), (2, 3, 5)), ((64, 32, 128), None),
+             ((36, 20, 48), (6, 4, 8)), ((32, 32, 512), (4, 8, 16)), ((6, 5, 7), (3, 1, 7))]
+
+
+@pytest.mark.parametrize("shape,split", FFT_CASES)
+def test_fft_steps_match_oracle_steps(dft, shape, split):
+    say(f"case fft steps {shape} split {split}")
+    x = wl.draw_complex(shape, "normal", 4000 + sum(shape))
+    xd = to_dev(x)
+    with dft.Plan(shape, dft.FFT, split=split) as p:
+        for axis in range(3):
+            A, B = p.split(axis)
+            assert A * B == shape[axis]
+            say(f"  axis {axis}: A={A} B={B}")
+            loc = ff.local_transform(x, axis, A, B)
+            got = to_host(p.fft_first_stage(axis, xd, fuse_twiddle=False))
+            assert report(f"f1 no-twiddle axis {axis}", got, loc) <= TOL
+            z = ff.first_stage(x, axis, A, B)
+            got = to_host(p.fft_first_stage(axis, xd, fuse_twiddle=True))
+            assert report(f"f1 axis {axis}", got, z) <= TOL
+            got = to_host(p.fft_phase(axis, xd))
+            assert report(f"phase axis {axis}", got, ff.twiddle(x, axis, A, B)) <= TOL
+            w = ff.second_stage(x, axis, A, B)
+            got = to_host(p.fft_second_stage(axis, xd, reorder=False))
+            assert report(f"f2 axis {axis}", got, w) <= TOL
+            got = to_host(p.fft_second_stage(axis, xd, reorder=True))
+            assert report(f"f2+reorder axis {axis}", got, ff.reorder(w, axis, A, B)) <= TOL
+            # pure data movement: exact
+            got = to_host(p.fft_reorder(1 << axis, xd))
+            assert np.array_equal(got, ff.reorder(x, axis, A, B).astype(np.complex64))
+        want = x.astype(np.complex128)
+        for axis in range(3):
+            A, B = p.split(axis)
+            want = ff.reorder(want, axis, A, B)
+        assert np.array_equal(to_host(p.fft_reorder(7, xd)), want.astype(np.complex64))
+
+
+@pytest.mark.parametrize("shape,split", FFT_CASES + [((64, 64, 64), None), ((128, 16, 256), None)])
+@pytest.mark.parametrize("flags", [0, 2])
+def test_fft_exec_matches_oracle(dft, shape, split, flags):
+    say(f"case fft exec {shape} split {split} flags {flags}")
+    x = wl.draw_complex(shape, "normal", 5000 + sum(shape))
+    want = orc.dft3d(x)
+    with dft.Plan(shape, dft.FFT, split=split, flags=flags) as p:
+        xd = to_dev(x)
+        got = to_host(p.exec(xd))
+        assert report(f"fft exec {shape}", got, want) <= TOL
+        assert np.array_equal(to_host(xd), x), "input must be left intact"
+        gotb = to_host(p.exec(xd, direction=dft.BACKWARD))
+        assert report(f"fft exec backward {shape}", gotb, orc.dft3d(x, sign=orc.BACKWARD)) <= TOL
+
+
+def test_kdft_and_fft_agree(dft):
+    import torch
+
+    shape = (64, 128, 256)
+    x = wl.draw_complex(shape, "normal", 6000)
+    xd = to_dev(x)
+    with dft.Plan(shape, dft.KDFT) as pk, dft.Plan(shape, dft.FFT) as pf:
+        a = pk.exec(xd)
+        b = pf.exec(xd)
+        torch.cuda.synchronize()
+        r = (torch.linalg.vector_norm((a - b).to(torch.complex128)) /
+             torch.linalg.vector_norm(a.to(torch.complex128))).item()
+    say(f"[parity] kdft vs fft {shape}: relL2={r:.3e}")
+    assert r <= 2 * TOL
+
+
+# ------------------------------------------------------------------------------------ the named configurations
+def test_cfg1_kdft_32(dft):
+    w = wl.WORKLOADS["cfg1"]
+    x = wl.make_input(w)
+    with dft.Plan(w.shape, dft.KDFT) as p:
+        got = to_host(p.exec(to_dev(x)))
+    assert report(w.name, got, orc.dft3d(x)) <= TOL
+
+
+def test_cfg4_kdft_nonuniform_128(dft):
+    w = wl.WORKLOADS["cfg4"]
+    x = wl.make_input(w)
+    coords = wl.make_coords(w)
+    with dft.Plan(w.shape, dft.KDFT, coords=coords) as p:
+        got = to_host(p.exec(to_dev(x)))
+    assert report(w.name, got, orc.dft3d(x, coords)) <= TOL
+
+
+def test_cfg2_kdft_256(dft):
+    w = wl.WORKLOADS["cfg2"]
+    say(f"case {w.name}")
+    x = wl.make_input(w)
+    with dft.Plan(w.shape, dft.KDFT) as p:
+        got = to_host(p.exec(to_dev(x)))
+    say("  gpu done, running oracle")
+    assert report(w.name, got, orc.dft3d(x)) <= TOL
+
+
+# ------------------------------------------------------------------------------------ boundary behaviour on the device
+def test_exec_argument_errors(dft):
+    import torch
+
+    shape = (8, 8, 8)
+    x = to_dev(wl.draw_complex(shape, "normal", 1))
+    with dft.Plan(shape, dft.KDFT) as p:
+        with pytest.raises(dft.Dft3dError) as ei:      # no workspace set
+            p._lib.dft3d_exec  # noqa: B018
+            from paper_2002_03260_amd.binding import _check
+            import ctypes
+            _check(p._lib.dft3d_exec(p._h, ctypes.c_void_p(x.data_ptr()),
+                                     ctypes.c_void_p(torch.empty_like(x).data_ptr()), dft.FORWARD, None))
+        assert ei.value.status_name == "DFT3D_ERR_INVALID_ARG"
+        with pytest.raises(dft.Dft3dError):            # in place
+            p.exec(x, out=x)
+        with pytest.raises(dft.Dft3dError):            # bad direction
+            p.exec(x, direction=0)
+    rng = np.random.default_rng(0)
+    with dft.Plan(shape, dft.KDFT, coords=(np.sort(rng.random(8)), None, None)) as p:
+        with pytest.raises(dft.Dft3dError) as ei:
+            p.exec(x, direction=dft.BACKWARD)
+        assert ei.value.status_name == "DFT3D_ERR_UNSUPPORTED"
