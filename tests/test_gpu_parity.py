@@ -129,7 +129,8 @@ def test_exact_arithmetic_is_bitwise(dft, shape):
     say(f"case exact {shape}")
     x = wl.gaussian_integers(shape, 31)
     want = orc.dft3d(x)
-    assert np.array_equal(want, np.round(want))
+    # the oracle's own entries carry ~1e-16 (libm cos(pi/2) is not 0): exact result = nearest integer
+    assert np.max(np.abs(want - np.round(want))) < 1e-12
     with dft.Plan(shape, dft.KDFT) as p:
         got = to_host(p.exec(to_dev(x)))
     assert np.array_equal(got.astype(np.complex128), np.round(want))
