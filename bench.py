@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the dft3d hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+
+One "step" is one whole transform (dft3d_exec: every kernel of the path) of one seeded
+synthetic tensor that is already resident in HBM.  The default workload is the 256^3 KDFT
+configuration the headline metric is quoted on.  Prints ONE JSON line with the throughput in
+effective GFLOP/s (5 E log2 E convention), the roofline of the dominant kernel measured with
+HIP events recorded by the library on the exec stream inside the timed region, and the CPU
+oracle timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F32_TFLOPS = 157.3      # 256 CU x 256 flop/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); None until measured for a workload.
+MEASURED_TRAFFIC = {}
+
+
+def effective_flop(E: int) -> float:
+    return 5.0 * E * math.log2(E)
+
+
+def cpu_baseline(w, wl, budget_macs: float = 3.0e10):
+    """Time the fp64 oracle on the host cores; full transform if small, else per-mode slabs."""
+    import numpy as np
+    from oracle import dft3d_oracle as orc
+
+    n1, n2, n3 = w.shape
+    E = w.elements
+    total_macs = E * (n1 + n2 + n3)
+    coords = wl.make_coords(w)
+    if total_macs <= budget_macs:
+        x = wl.make_input(w)
+        t0 = time.perf_counter()
+        orc.dft3d(x, coords)
+        t = time.perf_counter() - t0
+        sample = f"full {n1}x{n2}x{n3} transform, 1 run"
+    else:
+        # same sums on slabs of the tensor, one mode at a time, extrapolated linearly in the
+        # number of independent rows (each mode's cost is exactly proportional to it)
+        per_mode = budget_macs / 3
+        rng_in = wl.draw_complex if E <= (1 << 30) else None
+        t = 0.0
+        parts = []
+        for axis, n in enumerate(w.shape):
+            other = E // n
+            rows = max(1, min(other, int(per_mode / (n * n))))   # independent 1-D transforms
+            # build a sample tensor whose `axis` has full length and the rest holds `rows` lines
+            if axis == 0:
+                shape = (n, 1, rows)
+            elif axis == 1:
+                shape = (1, n, rows)
+            else:
+                shape = (1, rows, n)
+            xs = wl.draw_complex(shape, w.dist, w.seed + 17 * axis).astype(np.complex128)
+            M = orc.dft_matrix(n, coords[axis])
+            t0 = time.perf_counter()
+            orc.mode_contract(M, xs, axis)
+            dt = time.perf_counter() - t0
+            t += dt * (other / rows)
+            parts.append(f"mode {axis}: {rows} of {other} lines")
+        sample = "per-mode direct sums on line samples, extrapolated: " + "; ".join(parts)
+    return {
+        "value": effective_flop(E) / t / 1e9,
+        "unit": "GFLOP/s (5*E*log2(E))",
+        "seconds_full_transform": t,
+        "cores": orc.num_threads(),
+        "kind": "oracle",
+        "sample": sample,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="cfg2",
+                    help="cfg1..cfg4, cfg5-kdft or cfg5-fft (default cfg2 = KDFT 256^3)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (one MI355X holds the whole "
+              "problem); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import dft3d_workloads as wl
+    import paper_2002_03260_amd as dft
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dft.load_library()
+    torch.cuda.set_device(0)
+
+    name = args.workload
+    form_override = None
+    if name.startswith("cfg5"):
+        form_override = dft.FFT if name.endswith("fft") else dft.KDFT
+        w = wl.WORKLOADS["cfg5"]
+    else:
+        w = wl.WORKLOADS[name]
+    form = form_override if form_override is not None else w.formulation
+    big = w.elements > (1 << 30)
+    steps = args.steps if args.steps is not None else (3 if (big and form == dft.KDFT) else 20)
+    warmup = args.warmup if args.warmup is not None else (1 if big else 3)
+
+    coords = wl.make_coords(w)
+    split = [a for a, _ in w.splits] if (form == dft.FFT and w.splits) else None
+    flags = dft.FLAG_CLOBBER_INPUT if big else 0
+    plan = dft.Plan(w.shape, form, coords=coords, split=split, flags=flags)
+    x = wl.make_input_device(w) if big else torch.from_numpy(wl.make_input(w)).to("cuda")
+    out = torch.empty_like(x)
+    plan.ensure_workspace()
+    stream = torch.cuda.current_stream()
+
+    for _ in range(warmup):
+        plan.exec(x, out, stream=stream)
+    torch.cuda.synchronize()
+
+    plan.enable_profiling(steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        plan.exec(x, out, stream=stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    E = w.elements
+    value = effective_flop(E) / (ms_per_step * 1e-3) / 1e9
+
+    # per-pass kernel durations from the events the library recorded inside the timed region
+    per_exec = [plan.read_profile(i) for i in range(steps)]
+    npass = len(per_exec[0])
+    pass_ms = [sum(p[i] for p in per_exec) / steps for i in range(npass)]
+
+    if form == dft.KDFT:
+        pass_names = ["mode_z(contiguous)", "mode_y(strided)", "mode_x(strided)"]
+        # the strided contraction kernel runs two of the three passes: the dominant kernel
+        dom = [1, 2]
+        dom_ms = sum(pass_ms[i] for i in dom) / len(dom)
+        n_dom = sum(w.shape[2 - i] for i in dom) / len(dom)       # contracted length of those passes
+        flops = 8.0 * n_dom * E                                     # 4 real products per complex MAC
+        roofline = {
+            "bound": "mfma", "kernel": "k_contract_s (strided mode contraction, fp32 MFMA)",
+            "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_F32_TFLOPS,
+            "unit": "TFLOP/s", "avg_launch_ms": dom_ms,
+            "flop_per_launch": flops,
+        }
+    else:
+        pass_names = ["z_stage1+twiddle", "z_stage2", "y_stage1+twiddle", "y_stage2+reorder",
+                      "x_stage1+twiddle", "x_stage2+reorder", "z_reorder"]
+        dom = max(range(npass), key=lambda i: pass_ms[i])
+        dom_ms = pass_ms[dom]
+        nbytes = 16.0 * E
+        roofline = {
+            "bound": "hbm", "kernel": pass_names[dom] if dom < len(pass_names) else f"pass{dom}",
+            "achieved": nbytes / (dom_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "avg_launch_ms": dom_ms, "bytes_per_launch": nbytes,
+        }
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline["traffic"] = MEASURED_TRAFFIC.get(name)
+    roofline["passes_ms"] = {(pass_names[i] if i < len(pass_names) else f"pass{i}"): round(pass_ms[i], 5)
+                             for i in range(npass)}
+
+    result = {
+        "metric": "dft3d_effective_gflops",
+        "value": value,
+        "unit": "GFLOP/s (5*E*log2(E), E = total points)",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": w.name + ("" if form_override is None else ("_fft" if form == dft.FFT else "_kdft")),
+            "formulation": "FFT" if form == dft.FFT else "KDFT",
+            "shape": list(w.shape), "input": f"complex64, iid {w.dist}, seed {w.seed}",
+            "nonuniform": w.nonuniform,
+            "split": [list(s) for s in w.splits] if (form == dft.FFT and w.splits) else None,
+        },
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, wl)
+    plan.destroy()
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

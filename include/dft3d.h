@@ -104,6 +104,19 @@ dft3d_status dft3d_plan_get_split(dft3d_plan plan, int axis, int64_t* A, int64_t
 dft3d_status dft3d_exec(dft3d_plan plan, const void* in, void* out, int direction,
                         void* stream);
 
+/*
+ * Per-pass timing of dft3d_exec (measurement aid; the analogue of the per-operation breakdown
+ * the paper reads from its profiler in Section V).  After enable_profiling(plan, max_execs)
+ * the next max_execs calls of dft3d_exec record a HIP event before and after every kernel on
+ * the exec stream (no synchronisation is added).  read_profile, called after the caller has
+ * synchronised the stream, returns the milliseconds of each pass of exec number exec_index
+ * (0-based since enabling): ms must hold DFT3D_MAX_PASSES floats, *npass receives the count.
+ * enable_profiling(plan, 0) switches it off and frees the events.
+ */
+#define DFT3D_MAX_PASSES 16
+dft3d_status dft3d_plan_enable_profiling(dft3d_plan plan, int max_execs);
+dft3d_status dft3d_plan_read_profile(dft3d_plan plan, int exec_index, float* ms, int* npass);
+
 /* ---- single steps of the path; each is one kernel launch, out of place, same layout ------- */
 
 /* KDFT, one mode product (Eq. 2 along `axis` of the tensor; steps of Eq. 11):

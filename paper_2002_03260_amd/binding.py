@@ -24,7 +24,7 @@ FLAG_UNFUSED = 2
 EXPORTS = [
     "dft3d_plan_create", "dft3d_plan_create_ex", "dft3d_plan_destroy",
     "dft3d_plan_workspace_bytes", "dft3d_plan_set_workspace", "dft3d_plan_get_split",
-    "dft3d_exec", "dft3d_mode_contract", "dft3d_fft_first_stage", "dft3d_fft_phase",
+    "dft3d_exec", "dft3d_plan_enable_profiling", "dft3d_plan_read_profile", "dft3d_mode_contract", "dft3d_fft_first_stage", "dft3d_fft_phase",
     "dft3d_fft_second_stage", "dft3d_fft_reorder", "dft3d_generate_matrix",
     "dft3d_generate_twiddle", "dft3d_status_string", "dft3d_last_error",
 ]
@@ -63,6 +63,8 @@ def load_library():
     lib.dft3d_plan_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
     lib.dft3d_plan_get_split.argtypes = [vp, ci, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     lib.dft3d_exec.argtypes = [vp, vp, vp, ci, vp]
+    lib.dft3d_plan_enable_profiling.argtypes = [vp, ci]
+    lib.dft3d_plan_read_profile.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ci)]
     lib.dft3d_mode_contract.argtypes = [vp, ci, vp, vp, ci, vp]
     lib.dft3d_fft_first_stage.argtypes = [vp, ci, vp, vp, ci, ci, vp]
     lib.dft3d_fft_phase.argtypes = [vp, ci, vp, vp, ci, vp]
@@ -189,6 +191,17 @@ class Plan:
         a, b = ctypes.c_int64(), ctypes.c_int64()
         _check(self._lib.dft3d_plan_get_split(self._h, axis, ctypes.byref(a), ctypes.byref(b)))
         return int(a.value), int(b.value)
+
+    # -- per-pass timing -------------------------------------------------------------------
+    def enable_profiling(self, max_execs: int):
+        _check(self._lib.dft3d_plan_enable_profiling(self._h, int(max_execs)))
+
+    def read_profile(self, exec_index: int):
+        """Milliseconds of each kernel of exec number ``exec_index`` (stream must be synchronised)."""
+        ms = (ctypes.c_float * 16)()
+        n = ctypes.c_int()
+        _check(self._lib.dft3d_plan_read_profile(self._h, int(exec_index), ms, ctypes.byref(n)))
+        return [float(ms[i]) for i in range(n.value)]
 
     # -- execution --------------------------------------------------------------------------
     def _tensors(self, x, out):

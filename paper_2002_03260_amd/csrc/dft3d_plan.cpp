@@ -115,6 +115,12 @@ struct dft3d_plan_s {
     void* workspace = nullptr;
     size_t workspace_bytes = 0;
 
+    // optional per-pass event timing of exec
+    std::vector<hipEvent_t> prof_events;   // [exec][pass][begin,end]
+    std::vector<int> prof_npass;           // passes recorded per exec
+    int prof_capacity = 0;
+    int prof_next = 0;
+
     int64_t elements() const { return n[0] * n[1] * n[2]; }
     int64_t inner(int axis) const { return axis == 0 ? n[1] * n[2] : (axis == 1 ? n[2] : 1); }
     int64_t outer(int axis) const { return axis == 0 ? 1 : (axis == 1 ? n[0] : n[0] * n[1]); }
@@ -375,9 +381,58 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
     return DFT3D_OK;
 }
 
+dft3d_status dft3d_plan_enable_profiling(dft3d_plan p, int max_execs)
+{
+    if (!p || max_execs < 0 || max_execs > 4096) {
+        set_error("enable_profiling: invalid argument");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    for (hipEvent_t ev : p->prof_events) (void)hipEventDestroy(ev);
+    p->prof_events.clear();
+    p->prof_npass.assign((size_t)max_execs, 0);
+    p->prof_capacity = 0;
+    p->prof_next = 0;
+    const size_t count = (size_t)max_execs * DFT3D_MAX_PASSES * 2;
+    p->prof_events.reserve(count);
+    for (size_t i = 0; i < count; ++i) {
+        hipEvent_t ev;
+        hipError_t e = hipEventCreate(&ev);
+        if (e != hipSuccess) {
+            set_error("enable_profiling: hipEventCreate failed: %s", hipGetErrorString(e));
+            for (hipEvent_t x : p->prof_events) (void)hipEventDestroy(x);
+            p->prof_events.clear();
+            return DFT3D_ERR_HIP;
+        }
+        p->prof_events.push_back(ev);
+    }
+    p->prof_capacity = max_execs;
+    return DFT3D_OK;
+}
+
+dft3d_status dft3d_plan_read_profile(dft3d_plan p, int exec_index, float* ms, int* npass)
+{
+    if (!p || !ms || !npass || exec_index < 0 || exec_index >= p->prof_next) {
+        set_error("read_profile: invalid argument or exec not recorded");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    const int np = p->prof_npass[(size_t)exec_index];
+    for (int i = 0; i < np; ++i) {
+        const size_t base = ((size_t)exec_index * DFT3D_MAX_PASSES + i) * 2;
+        hipError_t e = hipEventElapsedTime(&ms[i], p->prof_events[base], p->prof_events[base + 1]);
+        if (e != hipSuccess) {
+            set_error("read_profile: hipEventElapsedTime failed: %s (stream not synchronised?)",
+                      hipGetErrorString(e));
+            return DFT3D_ERR_HIP;
+        }
+    }
+    *npass = np;
+    return DFT3D_OK;
+}
+
 dft3d_status dft3d_plan_destroy(dft3d_plan p)
 {
     if (!p) return DFT3D_OK;
+    for (hipEvent_t ev : p->prof_events) (void)hipEventDestroy(ev);
     for (int j = 0; j < 3; ++j) {
         if (p->form == DFT3D_KDFT) {
             if (p->M_owner[j] == j) free_matrix(p->M[j]);
@@ -552,7 +607,16 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
     }
     const float2* src = (const float2*)in;
     float2* dst = (npass % 2 == 1) ? (float2*)out : other;
+    const int prof_slot = (p->prof_next < p->prof_capacity) ? p->prof_next++ : -1;
+    int pass = 0;
+    auto mark = [&](int which) {   // event before (0) / after (1) the current pass
+        if (prof_slot < 0 || pass >= DFT3D_MAX_PASSES) return;
+        (void)hipEventRecord(p->prof_events[((size_t)prof_slot * DFT3D_MAX_PASSES + pass) * 2 + which], st);
+    };
     auto advance = [&]() {
+        mark(1);
+        ++pass;
+        if (prof_slot >= 0) p->prof_npass[(size_t)prof_slot] = pass < DFT3D_MAX_PASSES ? pass : DFT3D_MAX_PASSES;
         src = dst;
         dst = (dst == (float2*)out) ? other : (float2*)out;
     };
@@ -560,24 +624,29 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
     hipError_t e = hipSuccess;
     if (p->form == DFT3D_KDFT) {
         for (int axis = 2; axis >= 0 && e == hipSuccess; --axis) {
+            mark(0);
             e = run_mode(p, axis, src, dst, conj, axis_scale(p, axis, direction), st);
             advance();
         }
     } else {
         for (int axis = 2; axis >= 0 && e == hipSuccess; --axis) {
+            mark(0);
             e = run_first_stage(p, axis, src, dst, conj, unfused ? 0 : 1, st);
             advance();
             if (unfused && e == hipSuccess) {
+                mark(0);
                 e = launch_phase(src, dst, p->outer(axis), (int)p->A[axis], (int)p->B[axis],
                                  p->inner(axis), p->Tw[axis], conj, st);
                 advance();
             }
             if (e != hipSuccess) break;
             const int fold = (!unfused && axis != 2) ? 1 : 0;
+            mark(0);
             e = run_second_stage(p, axis, src, dst, conj, axis_scale(p, axis, direction), fold, st);
             advance();
         }
         if (e == hipSuccess) {
+            mark(0);
             e = run_reorder(p, unfused ? 7 : 4, src, dst, st);
             advance();
         }
