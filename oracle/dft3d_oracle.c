@@ -18,8 +18,8 @@
  *     c[n] the sample coordinate in cycles (period 1);
  *   - tensors are C-ordered, last index fastest, complex numbers stored as (re, im) pairs.
  *
- * Everything is accumulated in plain fp64 in the order the sums are written.  No blocking,
- * no FFT, no BLAS.  OpenMP only splits independent output elements across threads.
+ * Everything is accumulated in plain fp64 in the order the sums are written.  No FFT, no BLAS,
+ * no re-association of any sum.  OpenMP only splits independent output elements across threads.
  */
 #include <math.h>
 #include <stdint.h>
@@ -78,27 +78,45 @@ void oracle_dft_matrix(int64_t K, int64_t N, const int64_t* ks, const double* co
 /*
  * One mode product (Eq. 2 applied along one index of a tensor, the building block of Eq. 5
  * and Eq. 11):   out[o, k, i] = sum_n M[k, n] * in[o, n, i]
- * in  is O x N x I, out is O x K x I, M is K x N; all complex fp64, row-major, interleaved.
+ * in  is O x N x I, out is O x K x I, M is K x N; complex, row-major, interleaved; M and out
+ * are fp64, in is fp64 (oracle_mode_contract) or fp32 promoted exactly (oracle_mode_contract_f32).
+ * Each output is one sum taken in the order n = 0..N-1.  Threads only split independent
+ * outputs: (o, k) pairs and, inside one pair, ranges of i.
  */
+#define ORACLE_IBLOCK 2048
+#define ORACLE_MODE_CONTRACT_BODY(IN_T)                                                      \
+    int64_t OK = O * K;                                                                       \
+    int64_t nib = (I + ORACLE_IBLOCK - 1) / ORACLE_IBLOCK;                                    \
+    _Pragma("omp parallel for collapse(2) schedule(static)")                                  \
+    for (int64_t ok = 0; ok < OK; ++ok) {                                                     \
+        for (int64_t ib = 0; ib < nib; ++ib) {                                                \
+            int64_t o = ok / K, k = ok % K;                                                   \
+            int64_t i0 = ib * ORACLE_IBLOCK;                                                  \
+            int64_t i1 = i0 + ORACLE_IBLOCK < I ? i0 + ORACLE_IBLOCK : I;                     \
+            double* dst = out + 2 * ((o * K + k) * I);                                        \
+            for (int64_t i = i0; i < i1; ++i) { dst[2 * i] = 0.0; dst[2 * i + 1] = 0.0; }     \
+            for (int64_t n = 0; n < N; ++n) {                                                 \
+                double mr = M[2 * (k * N + n)], mi = M[2 * (k * N + n) + 1];                  \
+                const IN_T* src = in + 2 * ((o * N + n) * I);                                 \
+                for (int64_t i = i0; i < i1; ++i) {                                           \
+                    double xr = (double)src[2 * i], xi = (double)src[2 * i + 1];              \
+                    dst[2 * i]     += mr * xr - mi * xi;                                      \
+                    dst[2 * i + 1] += mr * xi + mi * xr;                                      \
+                }                                                                             \
+            }                                                                                 \
+        }                                                                                     \
+    }
+
 void oracle_mode_contract(int64_t O, int64_t N, int64_t I, int64_t K, const double* M,
                           const double* in, double* out)
 {
-    int64_t OK = O * K;
-#pragma omp parallel for schedule(static)
-    for (int64_t ok = 0; ok < OK; ++ok) {
-        int64_t o = ok / K, k = ok % K;
-        double* dst = out + 2 * ((o * K + k) * I);
-        for (int64_t i = 0; i < I; ++i) { dst[2 * i] = 0.0; dst[2 * i + 1] = 0.0; }
-        for (int64_t n = 0; n < N; ++n) {
-            double mr = M[2 * (k * N + n)], mi = M[2 * (k * N + n) + 1];
-            const double* src = in + 2 * ((o * N + n) * I);
-            for (int64_t i = 0; i < I; ++i) {
-                double xr = src[2 * i], xi = src[2 * i + 1];
-                dst[2 * i]     += mr * xr - mi * xi;
-                dst[2 * i + 1] += mr * xi + mi * xr;
-            }
-        }
-    }
+    ORACLE_MODE_CONTRACT_BODY(double)
+}
+
+void oracle_mode_contract_f32(int64_t O, int64_t N, int64_t I, int64_t K, const double* M,
+                              const float* in, double* out)
+{
+    ORACLE_MODE_CONTRACT_BODY(float)
 }
 
 /*

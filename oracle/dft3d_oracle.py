@@ -11,6 +11,7 @@ The functions mirror the C file:
 * :func:`dft3d_brute`      -- the literal triple sum of Eq. 10 (tiny inputs; pins ``dft3d``)
 * :func:`dft3d_sampled`    -- selected output slabs of a large transform (same sums, only the
   requested output frequencies along the first axis are evaluated)
+* :func:`dft3d_pencils`    -- selected output pencils along the first axis, likewise
 """
 from __future__ import annotations
 
@@ -50,6 +51,8 @@ def _load():
         lib.oracle_dft_matrix.restype = None
         lib.oracle_mode_contract.argtypes = [i64, i64, i64, i64, dp, dp, dp]
         lib.oracle_mode_contract.restype = None
+        lib.oracle_mode_contract_f32.argtypes = [i64, i64, i64, i64, dp, fp, dp]
+        lib.oracle_mode_contract_f32.restype = None
         lib.oracle_dft3d.argtypes = [i64, i64, i64, fp, dp, dp, dp, dp, ip, ip]
         lib.oracle_dft3d.restype = ctypes.c_int
         lib.oracle_dft3d_brute.argtypes = [i64, i64, i64, fp, dp, dp, dp, dp, ip]
@@ -89,9 +92,13 @@ def dft_matrix(n: int, coords=None, sign: int = FORWARD, ks=None) -> np.ndarray:
 
 
 def mode_contract(M: np.ndarray, x: np.ndarray, axis: int) -> np.ndarray:
-    """``out[..., k, ...] = sum_n M[k, n] x[..., n, ...]`` along ``axis`` in fp64."""
+    """``out[..., k, ...] = sum_n M[k, n] x[..., n, ...]`` along ``axis`` in fp64.
+
+    A complex64 ``x`` is promoted element by element inside the C loop (exactly), anything
+    else is converted to complex128 first."""
     M = np.ascontiguousarray(M, dtype=np.complex128)
-    x = np.ascontiguousarray(x, dtype=np.complex128)
+    f32 = isinstance(x, np.ndarray) and x.dtype == np.complex64
+    x = np.ascontiguousarray(x) if f32 else np.ascontiguousarray(x, dtype=np.complex128)
     axis = axis % x.ndim
     K, N = M.shape
     if x.shape[axis] != N:
@@ -99,7 +106,8 @@ def mode_contract(M: np.ndarray, x: np.ndarray, axis: int) -> np.ndarray:
     O = int(np.prod(x.shape[:axis], dtype=np.int64))
     I = int(np.prod(x.shape[axis + 1:], dtype=np.int64))
     out = np.empty(x.shape[:axis] + (K,) + x.shape[axis + 1:], dtype=np.complex128)
-    _load().oracle_mode_contract(O, N, I, K, _ptr(M), _ptr(x), _ptr(out))
+    fn = _load().oracle_mode_contract_f32 if f32 else _load().oracle_mode_contract
+    fn(O, N, I, K, _ptr(M), _ptr(x), _ptr(out))
     return out
 
 
@@ -159,3 +167,17 @@ def dft3d_sampled(x: np.ndarray, k1s, coords=(None, None, None), sign: int = FOR
         acc += mode_contract(M1[:, a0:a1], np.asarray(x[a0:a1]), axis=0)
     y = mode_contract(dft_matrix(n2, coords[1], sign), acc, axis=1)
     return mode_contract(dft_matrix(n3, coords[2], sign), y, axis=2)
+
+
+def dft3d_pencils(x: np.ndarray, k2s, k3s, coords=(None, None, None), sign: int = FORWARD) -> np.ndarray:
+    """Output pencils ``X[:, k2, k3]`` for every pair in ``k2s`` x ``k3s``: shape (n1, len(k2s), len(k3s)).
+
+    Modes 3 and 2 are taken with the matching matrix rows only, mode 1 in full.  Unscaled."""
+    if x.ndim != 3 or x.dtype != np.complex64:
+        raise ValueError("oracle input must be a 3-D complex64 array")
+    n1, n2, n3 = x.shape
+    M3 = dft_matrix(n3, coords[2], sign, ks=np.asarray(k3s, dtype=np.int64))
+    M2 = dft_matrix(n2, coords[1], sign, ks=np.asarray(k2s, dtype=np.int64))
+    y = mode_contract(M3, x, axis=2)             # (n1, n2, |k3s|)
+    y = mode_contract(M2, y, axis=1)             # (n1, |k2s|, |k3s|)
+    return mode_contract(dft_matrix(n1, coords[0], sign), y, axis=0)

@@ -267,6 +267,23 @@ def test_sampled_slabs_equal_full():
     assert rel_l2(got, full[ks]) < 1e-14
 
 
+def test_pencils_equal_full():
+    shape = (9, 6, 7)
+    x = rand_c64(shape, 14)
+    rng = np.random.default_rng(4)
+    coords = (None, np.sort(rng.random(6)), np.sort(rng.random(7)))
+    full = orc.dft3d(x, coords)
+    k2s, k3s = [5, 0], [3, 6, 1]
+    got = orc.dft3d_pencils(x, k2s, k3s, coords)
+    assert rel_l2(got, full[:, k2s][:, :, k3s]) < 1e-14
+
+
+def test_mode_contract_complex64_input_is_promoted_exactly():
+    x = rand_c64((4, 3000, 2), 15)
+    M = orc.dft_matrix(3000, ks=[1, 7])
+    assert np.array_equal(orc.mode_contract(M, x, 1), orc.mode_contract(M, x.astype(np.complex128), 1))
+
+
 # --------------------------------------------------------------------------- FFT formulation (Eq. 12-16)
 @pytest.mark.parametrize("N,A,B", [(8, 2, 4), (8, 4, 2), (16, 4, 4), (15, 3, 5), (15, 5, 3),
                                    (32, 4, 8), (12, 1, 12), (12, 12, 1)])
