@@ -22,6 +22,7 @@ namespace dft3d {
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;  // 4 wavefronts per workgroup
 
@@ -46,27 +47,60 @@ __device__ __forceinline__ int64_t out_offset(const ContractArgs& a, int64_t o)
 }
 
 // ------------------------------------------------------------------------------------------
+// Mode contraction on fp32 MFMA.  Two kernels share one software pipeline:
+//
+//   prologue : chunk 0 global -> registers -> LDS[0]; barrier
+//   chunk c  : request chunk c+1 from global memory into registers; MFMAs on LDS[c&1]
+//              (operands of k-step s+1 are read from LDS while the MFMAs of k-step s issue);
+//              then registers -> LDS[(c+1)&1]; barrier
+//
+// so a global load always has one full chunk of MFMA work to land, and there is one barrier
+// per chunk.  MASKED = false is the fast path for shapes that are whole multiples of the tile:
+// no bounds logic at all.  MASKED = true clamps addresses and selects zeros (branch-free).
+// EV = complex numbers per global load of the data tile (2 -> 16-byte loads).
+// ------------------------------------------------------------------------------------------
+template <int EV> struct CVec;
+template <> struct CVec<1> { typedef f32x2 type; };   // native vectors: they stay in registers
+template <> struct CVec<2> { typedef f32x4 type; };
+
+template <int EV>
+__device__ __forceinline__ typename CVec<EV>::type cvec_zero();
+template <> __device__ __forceinline__ f32x2 cvec_zero<1>() { return f32x2{0.f, 0.f}; }
+template <> __device__ __forceinline__ f32x4 cvec_zero<2>() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
+
+// store one or two complex numbers to an LDS location that is only 8-byte aligned
+__device__ __forceinline__ void store_cvec(float2* dst, f32x2 v)
+{
+    *reinterpret_cast<f32x2*>(dst) = v;
+}
+__device__ __forceinline__ void store_cvec(float2* dst, f32x4 v)
+{
+    *reinterpret_cast<f32x2*>(dst) = f32x2{v.x, v.y};
+    *reinterpret_cast<f32x2*>(dst + 1) = f32x2{v.z, v.w};
+}
+
 // Strided-mode contraction.  Workgroup tile: TM output rows (k) x TN columns (i) of one o.
 // Waves tile it as (TM/WM) x (TN/WN); each wave owns WM x WN complex outputs.
-// ------------------------------------------------------------------------------------------
-template <int TM, int TN, int WM, int WN, int KC, int NBUF, int MINW>
+template <int TM, int TN, int WM, int WN, int KC, int EV, bool MASKED, int MINW>
 __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, int tilesK,
                                                                int64_t tilesI, int64_t total)
 {
+    typedef typename CVec<EV>::type xvec;
     constexpr int NWN = TN / WN;
     static_assert((TM / WM) * NWN == 4, "four waves per workgroup");
-    constexpr int BM = WM / 16, BN = WN / 16;
-    constexpr int XP = TN + 4;    // row pitch of the data tile in float2 (keeps rows n, n+1 off the same banks)
-    constexpr int VP = TM + 16;   // row pitch of a matrix plane in floats
-    constexpr int XL = KC * TN / kThreads;            // float2 loads per thread per chunk
-    constexpr int VL = KC * TM / 4 / kThreads;        // float4 loads per thread per plane per chunk
-    constexpr int VLn = VL > 0 ? VL : 1;
-    static_assert(XL >= 1 && (KC * TN) % kThreads == 0, "data tile must split evenly");
-    static_assert((KC * TM / 4) % kThreads == 0 || KC * TM / 4 < kThreads, "matrix tile split");
+    static_assert(!MASKED || EV == 1, "the masked path loads single elements");
+    constexpr int BM = WM / 16, BN = WN / 16, KS = KC / 4;
+    constexpr int XP = TN + 16;   // float2 pitch: rows n, n+1 land 32 banks apart (b64 reads conflict-free)
+    constexpr int VP = TM + 16;   // float pitch: rows n..n+3 land 16 banks apart
+    constexpr int TPR = TN / EV;                  // threads per tile row
+    static_assert(kThreads % TPR == 0, "row must divide the workgroup");
+    constexpr int XRPP = kThreads / TPR;          // rows per pass
+    static_assert(KC % XRPP == 0, "KC must be a multiple of the rows per pass");
+    constexpr int XL = KC / XRPP;                 // loads per thread per chunk
 
-    __shared__ __align__(16) float2 Xs[NBUF][KC][XP];
-    __shared__ __align__(16) float Vr[NBUF][KC][VP];
-    __shared__ __align__(16) float Vi[NBUF][KC][VP];
+    __shared__ __align__(16) float2 Xs[2][KC][XP];
+    __shared__ __align__(16) float Vr[2][KC][VP];
+    __shared__ __align__(16) float Vi[2][KC][VP];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -89,49 +123,53 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     const int64_t I = a.I;
     const float2* __restrict__ Xo = a.X + o * (int64_t)N * I;
 
-    // per-thread load coordinates
-    constexpr int XRPP = kThreads / TN > 0 ? kThreads / TN : 1;  // rows per pass (TN <= 256)
-    static_assert(TN <= kThreads, "TN <= 256");
-    const int xc = tid % TN;
-    const int xr = tid / TN;
-    const bool xcol_ok = (i0 + xc) < I;
+    const int xc = (tid % TPR) * EV;
+    const int xr = tid / TPR;
+    const bool xcol_ok = !MASKED || (i0 + xc) < I;
+    const int64_t xcol = MASKED ? ((i0 + xc) < I ? (i0 + xc) : (I - 1)) : (i0 + xc);
 
-    float2 xreg[XL];
-    float4 vrreg[VLn], vireg[VLn];
+    constexpr int VV = KC * TM / 4;               // float4 per matrix plane per chunk
+    constexpr int VL = (VV + kThreads - 1) / kThreads;
+    xvec xreg[XL];
+    f32x4 vrreg[VL], vireg[VL];
 
     auto gload = [&](int n0) {
 #pragma unroll
-        for (int j = 0; j < XL; ++j) {
-            int n = n0 + xr + j * XRPP;
-            float2 v = make_float2(0.f, 0.f);
-            if (xcol_ok && n < N) v = Xo[(int64_t)n * I + i0 + xc];
-            xreg[j] = v;
+        for (int j = 0; j < VL; ++j) {
+            const int f = tid + j * kThreads;
+            if (VV % kThreads == 0 || f < VV) {
+                const int r = f / (TM / 4), c4 = f % (TM / 4);
+                const int64_t off = (int64_t)(n0 + r) * a.M.ld + k0 + c4 * 4;
+                vrreg[j] = *reinterpret_cast<const f32x4*>(a.M.re + off);
+                vireg[j] = *reinterpret_cast<const f32x4*>(a.M.im + off);
+            }
         }
 #pragma unroll
-        for (int j = 0; j < VLn; ++j) {
-            int f = tid + j * kThreads;            // float4 index inside the KC x TM/4 tile
-            if (VL > 0 || f < KC * TM / 4) {
-                int r = f / (TM / 4), c4 = f % (TM / 4);
-                const int64_t off = (int64_t)(n0 + r) * a.M.ld + k0 + c4 * 4;
-                vrreg[j] = *reinterpret_cast<const float4*>(a.M.re + off);
-                vireg[j] = *reinterpret_cast<const float4*>(a.M.im + off);
+        for (int j = 0; j < XL; ++j) {
+            const int n = n0 + xr + j * XRPP;
+            if (MASKED) {
+                const int nn = n < N ? n : N - 1;
+                xvec v = *reinterpret_cast<const xvec*>(Xo + (int64_t)nn * I + xcol);
+                xreg[j] = (xcol_ok && n < N) ? v : cvec_zero<EV>();
+            } else {
+                xreg[j] = *reinterpret_cast<const xvec*>(Xo + (int64_t)n * I + xcol);
             }
         }
     };
+    const float vsign = a.conj ? -1.0f : 1.0f;
     auto lstore = [&](int buf) {
 #pragma unroll
-        for (int j = 0; j < XL; ++j) Xs[buf][xr + j * XRPP][xc] = xreg[j];
-#pragma unroll
-        for (int j = 0; j < VLn; ++j) {
-            int f = tid + j * kThreads;
-            if (VL > 0 || f < KC * TM / 4) {
-                int r = f / (TM / 4), c4 = f % (TM / 4);
-                float4 vi = vireg[j];
-                if (a.conj) { vi.x = -vi.x; vi.y = -vi.y; vi.z = -vi.z; vi.w = -vi.w; }
-                *reinterpret_cast<float4*>(&Vr[buf][r][c4 * 4]) = vrreg[j];
-                *reinterpret_cast<float4*>(&Vi[buf][r][c4 * 4]) = vi;
+        for (int j = 0; j < VL; ++j) {
+            const int f = tid + j * kThreads;
+            if (VV % kThreads == 0 || f < VV) {
+                const int r = f / (TM / 4), c4 = f % (TM / 4);
+                *reinterpret_cast<f32x4*>(&Vr[buf][r][c4 * 4]) = vrreg[j];
+                *reinterpret_cast<f32x4*>(&Vi[buf][r][c4 * 4]) = vireg[j] * vsign;
             }
         }
+#pragma unroll
+        for (int j = 0; j < XL; ++j)
+            *reinterpret_cast<xvec*>(&Xs[buf][xr + j * XRPP][xc]) = xreg[j];
     };
 
     f32x4 accr[BM][BN], acci[BM][BN];
@@ -149,46 +187,53 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     __syncthreads();
 
     for (int c = 0; c < nchunks; ++c) {
-        const int buf = (NBUF == 2) ? (c & 1) : 0;
+        const int buf = c & 1;
         const bool more = (c + 1) < nchunks;
-        if (more) gload((c + 1) * KC);
-
-#pragma unroll
-        for (int s = 0; s < KC / 4; ++s) {
+        if (more) gload((c + 1) * KC);      // lands while this chunk's MFMAs run
+        float ar[2][BM], ai[2][BM];
+        f32x2 bx[2][BN];
+        auto read_operands = [&](int slot, int s) {
             const int n = 4 * s + lq;
-            float ar[BM], ai[BM], an[BM], br[BN], bi[BN];
 #pragma unroll
             for (int bm = 0; bm < BM; ++bm) {
-                ar[bm] = Vr[buf][n][wm0 + bm * 16 + l16];
-                ai[bm] = Vi[buf][n][wm0 + bm * 16 + l16];
-                an[bm] = -ai[bm];
+                ar[slot][bm] = Vr[buf][n][wm0 + bm * 16 + l16];
+                ai[slot][bm] = Vi[buf][n][wm0 + bm * 16 + l16];
             }
 #pragma unroll
-            for (int bn = 0; bn < BN; ++bn) {
-                float2 x = Xs[buf][n][wn0 + bn * 16 + l16];
-                br[bn] = x.x;
-                bi[bn] = x.y;
-            }
+            for (int bn = 0; bn < BN; ++bn)
+                bx[slot][bn] = *reinterpret_cast<const f32x2*>(&Xs[buf][n][wn0 + bn * 16 + l16]);
+        };
+        read_operands(0, 0);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const int cur = s & 1;
+            if (s + 1 < KS) read_operands(cur ^ 1, s + 1);
+            float an[BM];
+#pragma unroll
+            for (int bm = 0; bm < BM; ++bm) an[bm] = -ai[cur][bm];
 #pragma unroll
             for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn) accr[bm][bn] = mfma16(ar[bm], br[bn], accr[bm][bn]);
+                for (int bn = 0; bn < BN; ++bn)
+                    accr[bm][bn] = mfma16(ar[cur][bm], bx[cur][bn].x, accr[bm][bn]);
 #pragma unroll
             for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn) acci[bm][bn] = mfma16(ar[bm], bi[bn], acci[bm][bn]);
+                for (int bn = 0; bn < BN; ++bn)
+                    acci[bm][bn] = mfma16(ar[cur][bm], bx[cur][bn].y, acci[bm][bn]);
 #pragma unroll
             for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn) accr[bm][bn] = mfma16(an[bm], bi[bn], accr[bm][bn]);
+                for (int bn = 0; bn < BN; ++bn)
+                    accr[bm][bn] = mfma16(an[bm], bx[cur][bn].y, accr[bm][bn]);
 #pragma unroll
             for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn) acci[bm][bn] = mfma16(ai[bm], br[bn], acci[bm][bn]);
+                for (int bn = 0; bn < BN; ++bn)
+                    acci[bm][bn] = mfma16(ai[cur][bm], bx[cur][bn].x, acci[bm][bn]);
         }
-
-        if (NBUF == 1) __syncthreads();
-        if (more) lstore((NBUF == 2) ? (buf ^ 1) : 0);
+        __builtin_amdgcn_sched_barrier(0);  // keep the LDS refill (and its wait) behind the MFMAs
+        if (more) lstore(buf ^ 1);
         __syncthreads();
     }
 
@@ -198,14 +243,14 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
 #pragma unroll
     for (int bn = 0; bn < BN; ++bn) {
         const int64_t col = i0 + wn0 + bn * 16 + l16;
-        if (col >= I) continue;
+        if (MASKED && col >= I) continue;
         const int64_t beta = a.Tw ? (col / a.twInner) : 0;
 #pragma unroll
         for (int bm = 0; bm < BM; ++bm) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int k = k0 + wm0 + bm * 16 + 4 * lq + v;
-                if (k >= K) continue;
+                if (MASKED && k >= K) continue;
                 float yr = accr[bm][bn][v] * a.scale;
                 float yi = acci[bm][bn][v] * a.scale;
                 if (a.Tw) {
@@ -222,28 +267,28 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     }
 }
 
-// ------------------------------------------------------------------------------------------
 // Contiguous-mode contraction (I == 1): out[o, k] = sum_n in[o, n] M[k, n].
 // Workgroup tile: TO rows (o) x TK columns (k).  The data tile is the MFMA A operand.
-// ------------------------------------------------------------------------------------------
-template <int TO, int TK, int WO, int WK, int KC, int NBUF, int MINW>
+template <int TO, int TK, int WO, int WK, int KC, int EV, bool MASKED, int MINW>
 __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, int tilesK,
                                                                int64_t tilesO, int64_t total)
 {
+    typedef typename CVec<EV>::type xvec;
     constexpr int NWK = TK / WK;
     static_assert((TO / WO) * NWK == 4, "four waves per workgroup");
-    constexpr int BM = WO / 16, BN = WK / 16;
+    static_assert(!MASKED || EV == 1, "the masked path loads single elements");
+    constexpr int BM = WO / 16, BN = WK / 16, KS = KC / 4;
     constexpr int XP = KC + 1;    // odd pitch (in float2): lanes walking o hit distinct banks
     constexpr int VP = TK + 16;
-    constexpr int XL = TO * KC / kThreads;
-    constexpr int VL = KC * TK / 4 / kThreads;
-    constexpr int VLn = VL > 0 ? VL : 1;
-    static_assert(XL >= 1 && (TO * KC) % kThreads == 0, "data tile must split evenly");
-    static_assert(kThreads % KC == 0, "KC divides 256");
+    constexpr int TPR = KC / EV;                  // threads per data row
+    static_assert(kThreads % TPR == 0, "row must divide the workgroup");
+    constexpr int XRPP = kThreads / TPR;          // rows per pass
+    static_assert(TO % XRPP == 0, "TO must be a multiple of the rows per pass");
+    constexpr int XL = TO / XRPP;
 
-    __shared__ __align__(16) float2 Xs[NBUF][TO][XP];
-    __shared__ __align__(16) float Vr[NBUF][KC][VP];
-    __shared__ __align__(16) float Vi[NBUF][KC][VP];
+    __shared__ __align__(16) float2 Xs[2][TO][XP];
+    __shared__ __align__(16) float Vr[2][KC][VP];
+    __shared__ __align__(16) float Vi[2][KC][VP];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -262,46 +307,54 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
     const int N = a.M.N;
     const int64_t O = a.O;
 
-    constexpr int XRPP = kThreads / KC;   // rows per pass
-    const int xc = tid % KC;
-    const int xr = tid / KC;
+    const int xc = (tid % TPR) * EV;
+    const int xr = tid / TPR;
 
-    float2 xreg[XL];
-    float4 vrreg[VLn], vireg[VLn];
+    constexpr int VV = KC * TK / 4;
+    constexpr int VL = (VV + kThreads - 1) / kThreads;
+    xvec xreg[XL];
+    f32x4 vrreg[VL], vireg[VL];
 
     auto gload = [&](int n0) {
 #pragma unroll
-        for (int j = 0; j < XL; ++j) {
-            int64_t orow = o0 + xr + j * XRPP;
-            int n = n0 + xc;
-            float2 v = make_float2(0.f, 0.f);
-            if (orow < O && n < N) v = a.X[orow * N + n];
-            xreg[j] = v;
+        for (int j = 0; j < VL; ++j) {
+            const int f = tid + j * kThreads;
+            if (VV % kThreads == 0 || f < VV) {
+                const int r = f / (TK / 4), c4 = f % (TK / 4);
+                const int64_t off = (int64_t)(n0 + r) * a.M.ld + k0 + c4 * 4;
+                vrreg[j] = *reinterpret_cast<const f32x4*>(a.M.re + off);
+                vireg[j] = *reinterpret_cast<const f32x4*>(a.M.im + off);
+            }
         }
 #pragma unroll
-        for (int j = 0; j < VLn; ++j) {
-            int f = tid + j * kThreads;
-            if (VL > 0 || f < KC * TK / 4) {
-                int r = f / (TK / 4), c4 = f % (TK / 4);
-                const int64_t off = (int64_t)(n0 + r) * a.M.ld + k0 + c4 * 4;
-                vrreg[j] = *reinterpret_cast<const float4*>(a.M.re + off);
-                vireg[j] = *reinterpret_cast<const float4*>(a.M.im + off);
+        for (int j = 0; j < XL; ++j) {
+            const int64_t orow = o0 + xr + j * XRPP;
+            const int n = n0 + xc;
+            if (MASKED) {
+                const int64_t oo = orow < O ? orow : O - 1;
+                const int nn = n < N ? n : N - 1;
+                xvec v = *reinterpret_cast<const xvec*>(a.X + oo * N + nn);
+                xreg[j] = (orow < O && n < N) ? v : cvec_zero<EV>();
+            } else {
+                xreg[j] = *reinterpret_cast<const xvec*>(a.X + orow * N + n);
             }
         }
     };
+    const float vsign = a.conj ? -1.0f : 1.0f;
     auto lstore = [&](int buf) {
 #pragma unroll
-        for (int j = 0; j < XL; ++j) Xs[buf][xr + j * XRPP][xc] = xreg[j];
-#pragma unroll
-        for (int j = 0; j < VLn; ++j) {
-            int f = tid + j * kThreads;
-            if (VL > 0 || f < KC * TK / 4) {
-                int r = f / (TK / 4), c4 = f % (TK / 4);
-                float4 vi = vireg[j];
-                if (a.conj) { vi.x = -vi.x; vi.y = -vi.y; vi.z = -vi.z; vi.w = -vi.w; }
-                *reinterpret_cast<float4*>(&Vr[buf][r][c4 * 4]) = vrreg[j];
-                *reinterpret_cast<float4*>(&Vi[buf][r][c4 * 4]) = vi;
+        for (int j = 0; j < VL; ++j) {
+            const int f = tid + j * kThreads;
+            if (VV % kThreads == 0 || f < VV) {
+                const int r = f / (TK / 4), c4 = f % (TK / 4);
+                *reinterpret_cast<f32x4*>(&Vr[buf][r][c4 * 4]) = vrreg[j];
+                *reinterpret_cast<f32x4*>(&Vi[buf][r][c4 * 4]) = vireg[j] * vsign;
             }
+        }
+#pragma unroll
+        for (int j = 0; j < XL; ++j) {
+            float2* dst = &Xs[buf][xr + j * XRPP][xc];     // odd pitch: 8-byte aligned only
+            store_cvec(dst, xreg[j]);
         }
     };
 
@@ -320,46 +373,53 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
     __syncthreads();
 
     for (int c = 0; c < nchunks; ++c) {
-        const int buf = (NBUF == 2) ? (c & 1) : 0;
+        const int buf = c & 1;
         const bool more = (c + 1) < nchunks;
-        if (more) gload((c + 1) * KC);
-
-#pragma unroll
-        for (int s = 0; s < KC / 4; ++s) {
+        if (more) gload((c + 1) * KC);      // lands while this chunk's MFMAs run
+        f32x2 ax[2][BM];
+        float br[2][BN], bi[2][BN];
+        auto read_operands = [&](int slot, int s) {
             const int n = 4 * s + lq;
-            float ar[BM], ai[BM], br[BN], bi[BN], bn_[BN];
 #pragma unroll
-            for (int bm = 0; bm < BM; ++bm) {
-                float2 x = Xs[buf][wo0 + bm * 16 + l16][n];
-                ar[bm] = x.x;
-                ai[bm] = x.y;
-            }
+            for (int bm = 0; bm < BM; ++bm)
+                ax[slot][bm] = *reinterpret_cast<const f32x2*>(&Xs[buf][wo0 + bm * 16 + l16][n]);
 #pragma unroll
             for (int bn = 0; bn < BN; ++bn) {
-                br[bn] = Vr[buf][n][wk0 + bn * 16 + l16];
-                bi[bn] = Vi[buf][n][wk0 + bn * 16 + l16];
-                bn_[bn] = -bi[bn];
+                br[slot][bn] = Vr[buf][n][wk0 + bn * 16 + l16];
+                bi[slot][bn] = Vi[buf][n][wk0 + bn * 16 + l16];
             }
+        };
+        read_operands(0, 0);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const int cur = s & 1;
+            if (s + 1 < KS) read_operands(cur ^ 1, s + 1);
+            float bneg[BN];
+#pragma unroll
+            for (int bn = 0; bn < BN; ++bn) bneg[bn] = -bi[cur][bn];
 #pragma unroll
             for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn) accr[bm][bn] = mfma16(ar[bm], br[bn], accr[bm][bn]);
+                for (int bn = 0; bn < BN; ++bn)
+                    accr[bm][bn] = mfma16(ax[cur][bm].x, br[cur][bn], accr[bm][bn]);
 #pragma unroll
             for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn) acci[bm][bn] = mfma16(ar[bm], bi[bn], acci[bm][bn]);
+                for (int bn = 0; bn < BN; ++bn)
+                    acci[bm][bn] = mfma16(ax[cur][bm].x, bi[cur][bn], acci[bm][bn]);
 #pragma unroll
             for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn) accr[bm][bn] = mfma16(ai[bm], bn_[bn], accr[bm][bn]);
+                for (int bn = 0; bn < BN; ++bn)
+                    accr[bm][bn] = mfma16(ax[cur][bm].y, bneg[bn], accr[bm][bn]);
 #pragma unroll
             for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn) acci[bm][bn] = mfma16(ai[bm], br[bn], acci[bm][bn]);
+                for (int bn = 0; bn < BN; ++bn)
+                    acci[bm][bn] = mfma16(ax[cur][bm].y, br[cur][bn], acci[bm][bn]);
         }
-
-        if (NBUF == 1) __syncthreads();
-        if (more) lstore((NBUF == 2) ? (buf ^ 1) : 0);
+        __builtin_amdgcn_sched_barrier(0);  // keep the LDS refill (and its wait) behind the MFMAs
+        if (more) lstore(buf ^ 1);
         __syncthreads();
     }
 
@@ -367,13 +427,13 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
 #pragma unroll
     for (int bn = 0; bn < BN; ++bn) {
         const int k = k0 + wk0 + bn * 16 + l16;
-        if (k >= K) continue;
+        if (MASKED && k >= K) continue;
 #pragma unroll
         for (int bm = 0; bm < BM; ++bm) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int64_t orow = o0 + wo0 + bm * 16 + 4 * lq + v;
-                if (orow >= O) continue;
+                if (MASKED && orow >= O) continue;
                 float yr = accr[bm][bn][v] * a.scale;
                 float yi = acci[bm][bn][v] * a.scale;
                 if (a.Tw) {   // I == 1 means beta == 0
@@ -496,45 +556,53 @@ hipError_t launch_tiles(KernelT kernel, const ContractArgs& a, int tilesK, int64
 
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Picks a tile configuration for one contraction and launches it.  S<...>/C<...> name the
+// template arguments (tile, wave tile, chunk); each is instantiated in a fast (whole tiles,
+// 16-byte loads) and a masked (any shape) version.
+template <int TM, int TN, int WM, int WN, int KC>
+hipError_t launch_s(const ContractArgs& a, hipStream_t stream)
+{
+    const int K = a.M.K, N = a.M.N;
+    const int tk = (int)cdiv(K, TM);
+    const int64_t ti = cdiv(a.I, TN);
+    const int64_t total = (int64_t)tk * ti * a.O;
+    const bool whole = (K % TM == 0) && (N % KC == 0) && (a.I % TN == 0);
+    if (whole)
+        return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, 2, false, 2>, a, tk, ti, total, stream);
+    return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, 1, true, 2>, a, tk, ti, total, stream);
+}
+
+template <int TO, int TK, int WO, int WK, int KC>
+hipError_t launch_c(const ContractArgs& a, hipStream_t stream)
+{
+    const int K = a.M.K, N = a.M.N;
+    const int tk = (int)cdiv(K, TK);
+    const int64_t to = cdiv(a.O, TO);
+    const int64_t total = (int64_t)tk * to;
+    const bool whole = (K % TK == 0) && (N % KC == 0) && (a.O % TO == 0);
+    if (whole)
+        return launch_tiles(k_contract_c<TO, TK, WO, WK, KC, 2, false, 2>, a, tk, to, total, stream);
+    return launch_tiles(k_contract_c<TO, TK, WO, WK, KC, 1, true, 2>, a, tk, to, total, stream);
+}
+
 }  // namespace
 
 hipError_t launch_contract(const ContractArgs& a, hipStream_t stream)
 {
     const int K = a.M.K, N = a.M.N;
     if (a.O <= 0 || a.I <= 0 || K <= 0 || N <= 0) return hipSuccess;
+    constexpr int64_t kFillTiles = 512;   // two workgroups on each of the 256 CUs
     if (a.I == 1) {
-        // contiguous contraction
-        if (N <= 32 && K <= 32) {
-            const int tk = 1;
-            const int64_t to = cdiv(a.O, 128);
-            return launch_tiles(k_contract_c<128, 32, 32, 32, 32, 1, 2>, a, tk, to, tk * to, stream);
-        }
-        if (N <= 64 && K <= 64) {
-            const int tk = 1;
-            const int64_t to = cdiv(a.O, 128);
-            return launch_tiles(k_contract_c<128, 64, 32, 64, 16, 2, 2>, a, tk, to, tk * to, stream);
-        }
-        const int tk = (int)cdiv(K, 128);
-        const int64_t to = cdiv(a.O, 128);
-        return launch_tiles(k_contract_c<128, 128, 64, 64, 16, 2, 2>, a, tk, to, tk * to, stream);
+        if (N <= 32 && K <= 32) return launch_c<128, 32, 32, 32, 16>(a, stream);
+        if (N <= 64 && K <= 64) return launch_c<128, 64, 32, 64, 16>(a, stream);
+        if (cdiv(K, 128) * cdiv(a.O, 128) < kFillTiles) return launch_c<64, 64, 32, 32, 16>(a, stream);
+        return launch_c<128, 128, 64, 64, 16>(a, stream);
     }
-    // strided contraction
-    if (K <= 16 && N <= 16) {
-        const int64_t ti = cdiv(a.I, 256);
-        return launch_tiles(k_contract_s<16, 256, 16, 64, 16, 1, 2>, a, 1, ti, ti * a.O, stream);
-    }
-    if (K <= 32 && N <= 32) {
-        const int64_t ti = cdiv(a.I, 128);
-        return launch_tiles(k_contract_s<32, 128, 32, 32, 32, 1, 2>, a, 1, ti, ti * a.O, stream);
-    }
-    if (K <= 64 && N <= 64) {
-        const int64_t ti = cdiv(a.I, 128);
-        return launch_tiles(k_contract_s<64, 128, 64, 32, 16, 2, 2>, a, 1, ti, ti * a.O, stream);
-    }
-    const int tk = (int)cdiv(K, 128);
-    const int64_t ti = cdiv(a.I, 128);
-    return launch_tiles(k_contract_s<128, 128, 64, 64, 16, 2, 2>, a, tk, ti, (int64_t)tk * ti * a.O,
-                        stream);
+    if (K <= 16 && N <= 16) return launch_s<16, 256, 16, 64, 16>(a, stream);
+    if (K <= 32 && N <= 32) return launch_s<32, 128, 32, 32, 16>(a, stream);
+    if (K <= 64 && N <= 64) return launch_s<64, 128, 64, 32, 16>(a, stream);
+    if (cdiv(K, 128) * cdiv(a.I, 128) * a.O < kFillTiles) return launch_s<64, 64, 32, 32, 16>(a, stream);
+    return launch_s<128, 128, 64, 64, 16>(a, stream);
 }
 
 hipError_t launch_phase(const float2* in, float2* out, int64_t outer, int A, int B, int64_t inner,
