@@ -93,6 +93,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2",
                     help="cfg1..cfg4, cfg5-kdft or cfg5-fft (default cfg2 = KDFT 256^3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused", action="store_true",
+                    help="FFT: run the twiddle and the re-ordering as separate memory-bound kernels")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -126,6 +128,8 @@ def main() -> int:
     coords = wl.make_coords(w)
     split = [a for a, _ in w.splits] if (form == dft.FFT and w.splits) else None
     flags = dft.FLAG_CLOBBER_INPUT if big else 0
+    if args.unfused and form == dft.FFT:
+        flags = dft.FLAG_UNFUSED     # 10 passes: needs the separate workspace
     plan = dft.Plan(w.shape, form, coords=coords, split=split, flags=flags)
     x = wl.make_input_device(w) if big else torch.from_numpy(wl.make_input(w)).to("cuda")
     out = torch.empty_like(x)
@@ -169,6 +173,8 @@ def main() -> int:
     else:
         pass_names = ["z_stage1+twiddle", "z_stage2", "y_stage1+twiddle", "y_stage2+reorder",
                       "x_stage1+twiddle", "x_stage2+reorder", "z_reorder"]
+        if args.unfused:
+            pass_names = [f"{ax}_{st}" for ax in "zyx" for st in ("stage1", "phase", "stage2")] + ["reorder_xyz"]
         dom = max(range(npass), key=lambda i: pass_ms[i])
         dom_ms = pass_ms[dom]
         nbytes = 16.0 * E

@@ -81,7 +81,9 @@ __device__ __forceinline__ void store_cvec(float2* dst, f32x4 v)
 
 // Strided-mode contraction.  Workgroup tile: TM output rows (k) x TN columns (i) of one o.
 // Waves tile it as (TM/WM) x (TN/WN); each wave owns WM x WN complex outputs.
-template <int TM, int TN, int WM, int WN, int KC, int EV, bool MASKED, int MINW>
+// In the masked version the columns of ALL o are flattened into one index (col = o*I + i), so a
+// narrow inner extent (I < TN) still fills the tile; every thread decodes its own (o, i).
+template <int TM, int TN, int WM, int WN, int KC, int NB, int EV, bool MASKED, int MINW>
 __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, int tilesK,
                                                                int64_t tilesI, int64_t total)
 {
@@ -98,9 +100,9 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     static_assert(KC % XRPP == 0, "KC must be a multiple of the rows per pass");
     constexpr int XL = KC / XRPP;                 // loads per thread per chunk
 
-    __shared__ __align__(16) float2 Xs[2][KC][XP];
-    __shared__ __align__(16) float Vr[2][KC][VP];
-    __shared__ __align__(16) float Vi[2][KC][VP];
+    __shared__ __align__(16) float2 Xs[NB][KC][XP];
+    __shared__ __align__(16) float Vr[NB][KC][VP];
+    __shared__ __align__(16) float Vi[NB][KC][VP];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -110,23 +112,33 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     const int l16 = lane & 15;
     const int lq = lane >> 4;
 
-    // logical tile: k-tile fastest, then column tile, then o
+    // logical tile: k-tile fastest, then column tile (fast path: of one o; masked: of the
+    // flattened (o, i) index)
     int64_t t = xcd_remap((int64_t)blockIdx.x, total);
     const int kt = (int)(t % tilesK);
     t /= tilesK;
-    const int64_t it = t % tilesI;
-    const int64_t o = t / tilesI;
     const int k0 = kt * TM;
-    const int64_t i0 = it * TN;
 
     const int N = a.M.N;
     const int64_t I = a.I;
-    const float2* __restrict__ Xo = a.X + o * (int64_t)N * I;
-
     const int xc = (tid % TPR) * EV;
     const int xr = tid / TPR;
-    const bool xcol_ok = !MASKED || (i0 + xc) < I;
-    const int64_t xcol = MASKED ? ((i0 + xc) < I ? (i0 + xc) : (I - 1)) : (i0 + xc);
+
+    int64_t tile_o = 0, c0 = 0;       // fast path: the tile's o and first column; masked: first flat column
+    bool xcol_ok = true;
+    const float2* __restrict__ Xo;    // this thread's column in row n = 0
+    if (MASKED) {
+        c0 = t * TN;
+        const int64_t cg = c0 + xc;
+        xcol_ok = cg < a.O * I;
+        const int64_t cc = xcol_ok ? cg : 0;
+        const int64_t o = cc / I;
+        Xo = a.X + o * (int64_t)N * I + (cc - o * I);
+    } else {
+        tile_o = t / tilesI;
+        c0 = (t % tilesI) * TN;
+        Xo = a.X + tile_o * (int64_t)N * I + c0 + xc;
+    }
 
     constexpr int VV = KC * TM / 4;               // float4 per matrix plane per chunk
     constexpr int VL = (VV + kThreads - 1) / kThreads;
@@ -149,10 +161,10 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
             const int n = n0 + xr + j * XRPP;
             if (MASKED) {
                 const int nn = n < N ? n : N - 1;
-                xvec v = *reinterpret_cast<const xvec*>(Xo + (int64_t)nn * I + xcol);
+                xvec v = *reinterpret_cast<const xvec*>(Xo + (int64_t)nn * I);
                 xreg[j] = (xcol_ok && n < N) ? v : cvec_zero<EV>();
             } else {
-                xreg[j] = *reinterpret_cast<const xvec*>(Xo + (int64_t)n * I + xcol);
+                xreg[j] = *reinterpret_cast<const xvec*>(Xo + (int64_t)n * I);
             }
         }
     };
@@ -187,7 +199,7 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     __syncthreads();
 
     for (int c = 0; c < nchunks; ++c) {
-        const int buf = c & 1;
+        const int buf = (NB == 2) ? (c & 1) : 0;
         const bool more = (c + 1) < nchunks;
         if (more) gload((c + 1) * KC);      // lands while this chunk's MFMAs run
         float ar[2][BM], ai[2][BM];
@@ -233,17 +245,22 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
                     acci[bm][bn] = mfma16(ai[cur][bm], bx[cur][bn].x, acci[bm][bn]);
         }
         __builtin_amdgcn_sched_barrier(0);  // keep the LDS refill (and its wait) behind the MFMAs
-        if (more) lstore(buf ^ 1);
+        if (NB == 1) __syncthreads();       // single buffer: everyone must be done reading it
+        if (more) lstore((NB == 2) ? (buf ^ 1) : 0);
         __syncthreads();
     }
 
     // epilogue: scale, optional twiddle, store (16 consecutive columns per quarter-wave)
     const int K = a.M.K;
-    float2* __restrict__ Yo = a.Y + out_offset(a, o);
 #pragma unroll
     for (int bn = 0; bn < BN; ++bn) {
-        const int64_t col = i0 + wn0 + bn * 16 + l16;
-        if (MASKED && col >= I) continue;
+        int64_t o = tile_o, col = c0 + wn0 + bn * 16 + l16;
+        if (MASKED) {
+            if (col >= a.O * I) continue;
+            o = col / I;
+            col -= o * I;
+        }
+        float2* __restrict__ Yo = a.Y + out_offset(a, o);
         const int64_t beta = a.Tw ? (col / a.twInner) : 0;
 #pragma unroll
         for (int bm = 0; bm < BM; ++bm) {
@@ -451,43 +468,54 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
 }
 
 // ------------------------------------------------------------------------------------------
-// Twiddle multiply: tensor [outer][A][B][inner], out = in * Tw[ka*B + beta].  Each thread moves
-// EV consecutive complex numbers (16 bytes when EV == 2).
+// Twiddle multiply (memory-bound).  The tensor [outer][A][B][inner] is walked as a matrix whose
+// twiddle depends on the row only (inner > 1: rows = outer*A*B, columns = inner, factor
+// Tw[row % (A*B)]) or on the column only (inner == 1: rows = outer, columns = A*B, factor
+// Tw[col]); either way the per-element index arithmetic is 32-bit.  One workgroup owns whole
+// rows in turn; each thread moves EV complex numbers per access (EV = 2 -> 16 bytes).
 // ------------------------------------------------------------------------------------------
-template <int EV>
+template <int EV, bool BY_ROW>
 __global__ __launch_bounds__(kThreads) void k_phase(const float2* __restrict__ in,
-                                                    float2* __restrict__ out, int64_t nvec,
-                                                    int AB, int64_t inner,
+                                                    float2* __restrict__ out, int64_t rows,
+                                                    int cols, int AB,
                                                     const float2* __restrict__ Tw, int conj)
 {
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x; v < nvec; v += stride) {
-        const int64_t e = v * EV;
-        // slot along the split axis = (e / inner) % (A*B); the table is indexed by it directly
-        if (EV == 2) {
-            float4 x = *reinterpret_cast<const float4*>(in + e);
-            float2 w0 = Tw[(e / inner) % AB];
-            float2 w1 = Tw[((e + 1) / inner) % AB];
-            if (conj) { w0.y = -w0.y; w1.y = -w1.y; }
-            float4 y;
-            y.x = x.x * w0.x - x.y * w0.y;
-            y.y = x.x * w0.y + x.y * w0.x;
-            y.z = x.z * w1.x - x.w * w1.y;
-            y.w = x.z * w1.y + x.w * w1.x;
-            *reinterpret_cast<float4*>(out + e) = y;
-        } else {
-            float2 x = in[e];
-            float2 w = Tw[(e / inner) % AB];
-            if (conj) w.y = -w.y;
-            out[e] = make_float2(x.x * w.x - x.y * w.y, x.x * w.y + x.y * w.x);
+    typedef typename CVec<EV>::type xvec;
+    const float s = conj ? -1.0f : 1.0f;
+    for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
+        const float2* __restrict__ src = in + r * cols;
+        float2* __restrict__ dst = out + r * cols;
+        float2 wr = make_float2(1.f, 0.f);
+        if (BY_ROW) {
+            wr = Tw[(int)(r % AB)];
+            wr.y *= s;
+        }
+        for (int c = threadIdx.x * EV; c < cols; c += kThreads * EV) {
+            xvec x = *reinterpret_cast<const xvec*>(src + c);
+            xvec y;
+#pragma unroll
+            for (int e = 0; e < EV; ++e) {
+                float2 w = wr;
+                if (!BY_ROW) {
+                    w = Tw[c + e];
+                    w.y *= s;
+                }
+                y[2 * e] = x[2 * e] * w.x - x[2 * e + 1] * w.y;
+                y[2 * e + 1] = x[2 * e] * w.y + x[2 * e + 1] * w.x;
+            }
+            *reinterpret_cast<xvec*>(dst + c) = y;
         }
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// Re-ordering.  One workgroup moves whole rows (the fastest axis) at a time: a row is read
-// contiguously, optionally transposed [A][B] -> [B][A] through LDS, and written contiguously
-// to the row whose (x, y) indices have their sub-indices swapped.
+// Re-ordering.  The swap of the x and y sub-indices only changes which output row an input row
+// goes to; the swap of the z sub-indices is a transposition [A][B] -> [B][A] inside each
+// contiguous row, done through LDS.  A workgroup takes a batch of G consecutive input rows
+// (G * nz contiguous complex numbers), reads them with EV-wide accesses, and writes every row
+// contiguously.  In LDS the element at slot s = ka*B + kb of batch row g sits at
+// g*(nz + A) + s + ka: one padding element per B-row, so the transposed read walks ka with the
+// odd stride B + 1 and consecutive lanes hit distinct banks.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ int swap_slot(int s, int A, int B)
 {
@@ -495,32 +523,55 @@ __device__ __forceinline__ int swap_slot(int s, int A, int B)
     return (s / B) + A * (s % B);
 }
 
-constexpr int kReorderMaxRow = 8192;   // complex elements of one row that fit the LDS buffer
-constexpr int kReorderPad = 264;       // room for one padding element per [B]-row of the row
-
-__global__ __launch_bounds__(kThreads) void k_reorder_rows(ReorderArgs a, int64_t nrows)
+template <int CAP, int EV>
+__global__ __launch_bounds__(kThreads) void k_reorder_rows(ReorderArgs a, int64_t nrows, int G)
 {
-    __shared__ float2 row[kReorderMaxRow + kReorderPad];
+    typedef typename CVec<EV>::type xvec;
+    __shared__ __align__(16) float2 buf[CAP];
     const int nz = a.n[2];
     const int A = a.A[2], B = a.B[2];
-    for (int64_t r = blockIdx.x; r < nrows; r += gridDim.x) {
-        int ix = (int)(r / a.n[1]);
-        int iy = (int)(r % a.n[1]);
-        int ox = a.swap[0] ? swap_slot(ix, a.A[0], a.B[0]) : ix;
-        int oy = a.swap[1] ? swap_slot(iy, a.A[1], a.B[1]) : iy;
-        const float2* __restrict__ src = a.in + r * (int64_t)nz;
-        float2* __restrict__ dst = a.out + ((int64_t)ox * a.n[1] + oy) * (int64_t)nz;
+    const int pitch = nz + A;
+    const int64_t nbatches = (nrows + G - 1) / G;
+    for (int64_t b = blockIdx.x; b < nbatches; b += gridDim.x) {
+        const int64_t r0 = b * G;
+        const int g_here = (int)((nrows - r0) < G ? (nrows - r0) : G);
+        const int count = g_here * nz;
+        const float2* __restrict__ src = a.in + r0 * (int64_t)nz;
         if (!a.swap[2]) {
-            for (int z = threadIdx.x; z < nz; z += kThreads) dst[z] = src[z];
+            // rows keep their content: copy each to its permuted place
+            for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
+                const int g = e / nz, z = e - g * nz;
+                const int64_t r = r0 + g;
+                const int ix = (int)(r / a.n[1]), iy = (int)(r % a.n[1]);
+                const int ox = a.swap[0] ? swap_slot(ix, a.A[0], a.B[0]) : ix;
+                const int oy = a.swap[1] ? swap_slot(iy, a.A[1], a.B[1]) : iy;
+                *reinterpret_cast<xvec*>(a.out + ((int64_t)ox * a.n[1] + oy) * (int64_t)nz + z) =
+                    *reinterpret_cast<const xvec*>(src + e);
+            }
             continue;
         }
-        // stage: element at slot s = ka*B + kb is kept at s + ka (one float2 of padding per
-        // row of B) so the transposed read below walks ka with an odd stride in LDS
-        for (int s = threadIdx.x; s < nz; s += kThreads) row[s + s / B] = src[s];
+        for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
+            const xvec v = *reinterpret_cast<const xvec*>(src + e);
+            const int g = e / nz, s = e - g * nz;
+            store_cvec(&buf[g * pitch + s + s / B], v);   // s and s+1 share a B-row (B even when EV == 2)
+        }
         __syncthreads();
-        for (int k = threadIdx.x; k < nz; k += kThreads) {
-            int kb = k / A, ka = k % A;           // natural index k = ka + A*kb
-            dst[k] = row[ka * (B + 1) + kb];
+        for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
+            const int g = e / nz, k = e - g * nz;          // natural index k = ka + A*kb
+            const int kb = k / A, ka = k - kb * A;
+            const float2* p = &buf[g * pitch + ka * (B + 1) + kb];
+            xvec v;
+#pragma unroll
+            for (int q = 0; q < EV; ++q) {                 // k+1 is the next ka (A even when EV == 2)
+                const float2 t = p[q * (B + 1)];
+                v[2 * q] = t.x;
+                v[2 * q + 1] = t.y;
+            }
+            const int64_t r = r0 + g;
+            const int ix = (int)(r / a.n[1]), iy = (int)(r % a.n[1]);
+            const int ox = a.swap[0] ? swap_slot(ix, a.A[0], a.B[0]) : ix;
+            const int oy = a.swap[1] ? swap_slot(iy, a.A[1], a.B[1]) : iy;
+            *reinterpret_cast<xvec*>(a.out + ((int64_t)ox * a.n[1] + oy) * (int64_t)nz + k) = v;
         }
         __syncthreads();
     }
@@ -559,17 +610,20 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // Picks a tile configuration for one contraction and launches it.  S<...>/C<...> name the
 // template arguments (tile, wave tile, chunk); each is instantiated in a fast (whole tiles,
 // 16-byte loads) and a masked (any shape) version.
-template <int TM, int TN, int WM, int WN, int KC>
+template <int TM, int TN, int WM, int WN, int KC, int NB>
 hipError_t launch_s(const ContractArgs& a, hipStream_t stream)
 {
     const int K = a.M.K, N = a.M.N;
     const int tk = (int)cdiv(K, TM);
-    const int64_t ti = cdiv(a.I, TN);
-    const int64_t total = (int64_t)tk * ti * a.O;
     const bool whole = (K % TM == 0) && (N % KC == 0) && (a.I % TN == 0);
-    if (whole)
-        return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, 2, false, 2>, a, tk, ti, total, stream);
-    return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, 1, true, 2>, a, tk, ti, total, stream);
+    if (whole) {
+        const int64_t ti = a.I / TN;
+        const int64_t total = (int64_t)tk * ti * a.O;
+        return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, NB, 2, false, 2>, a, tk, ti, total, stream);
+    }
+    // masked: column tiles run over the flattened (o, i) index
+    const int64_t tc = cdiv(a.O * a.I, TN);
+    return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, NB, 1, true, 2>, a, tk, tc, (int64_t)tk * tc, stream);
 }
 
 template <int TO, int TK, int WO, int WK, int KC>
@@ -598,11 +652,11 @@ hipError_t launch_contract(const ContractArgs& a, hipStream_t stream)
         if (cdiv(K, 128) * cdiv(a.O, 128) < kFillTiles) return launch_c<64, 64, 32, 32, 16>(a, stream);
         return launch_c<128, 128, 64, 64, 16>(a, stream);
     }
-    if (K <= 16 && N <= 16) return launch_s<16, 256, 16, 64, 16>(a, stream);
-    if (K <= 32 && N <= 32) return launch_s<32, 128, 32, 32, 16>(a, stream);
-    if (K <= 64 && N <= 64) return launch_s<64, 128, 64, 32, 16>(a, stream);
-    if (cdiv(K, 128) * cdiv(a.I, 128) * a.O < kFillTiles) return launch_s<64, 64, 32, 32, 16>(a, stream);
-    return launch_s<128, 128, 64, 64, 16>(a, stream);
+    if (K <= 16 && N <= 16) return launch_s<16, 256, 16, 64, 16, 1>(a, stream);
+    if (K <= 32 && N <= 32) return launch_s<32, 128, 32, 32, 32, 1>(a, stream);
+    if (K <= 64 && N <= 64) return launch_s<64, 128, 64, 32, 16, 2>(a, stream);
+    if (cdiv(K, 128) * cdiv(a.I, 128) * a.O < kFillTiles) return launch_s<64, 64, 32, 32, 16, 2>(a, stream);
+    return launch_s<128, 128, 64, 64, 16, 2>(a, stream);
 }
 
 hipError_t launch_phase(const float2* in, float2* out, int64_t outer, int A, int B, int64_t inner,
@@ -610,36 +664,55 @@ hipError_t launch_phase(const float2* in, float2* out, int64_t outer, int A, int
 {
     const int64_t total = outer * A * B * inner;
     if (total <= 0) return hipSuccess;
-    const bool vec2 = (total % 2 == 0);
-    const int64_t nvec = vec2 ? total / 2 : total;
-    int64_t blocks = cdiv(nvec, kThreads);
-    if (blocks > 256 * 32) blocks = 256 * 32;
-    if (vec2)
-        hipLaunchKernelGGL(k_phase<2>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, in, out,
-                           nvec, A * B, inner, Tw, conj);
-    else
-        hipLaunchKernelGGL(k_phase<1>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, in, out,
-                           nvec, A * B, inner, Tw, conj);
+    const int AB = A * B;
+    const bool by_row = inner > 1;
+    const int64_t rows = by_row ? outer * AB : outer;
+    const int cols = by_row ? (int)inner : AB;
+    int64_t blocks = rows < 256 * 16 ? rows : 256 * 16;
+    const dim3 grid((unsigned)blocks), block(kThreads);
+    const bool vec2 = (cols % 2 == 0);
+    if (by_row) {
+        if (vec2) hipLaunchKernelGGL((k_phase<2, true>), grid, block, 0, stream, in, out, rows, cols, AB, Tw, conj);
+        else hipLaunchKernelGGL((k_phase<1, true>), grid, block, 0, stream, in, out, rows, cols, AB, Tw, conj);
+    } else {
+        if (vec2) hipLaunchKernelGGL((k_phase<2, false>), grid, block, 0, stream, in, out, rows, cols, AB, Tw, conj);
+        else hipLaunchKernelGGL((k_phase<1, false>), grid, block, 0, stream, in, out, rows, cols, AB, Tw, conj);
+    }
     return hipGetLastError();
 }
+
+namespace {
+template <int CAP>
+hipError_t launch_reorder_rows(const ReorderArgs& a, int64_t nrows, hipStream_t stream)
+{
+    const int nz = a.n[2];
+    const int pitch = nz + a.A[2];
+    int G = CAP / pitch;
+    if (G < 1) G = 1;
+    // keep at least ~8 batches per CU in the grid
+    while (G > 1 && (nrows + G - 1) / G < 256 * 8) G /= 2;
+    const int64_t nbatches = (nrows + G - 1) / G;
+    const int64_t blocks = nbatches < 256 * 16 ? nbatches : 256 * 16;
+    const bool vec2 = (nz % 2 == 0) && (!a.swap[2] || (a.A[2] % 2 == 0 && a.B[2] % 2 == 0));
+    if (vec2)
+        hipLaunchKernelGGL((k_reorder_rows<CAP, 2>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a, nrows, G);
+    else
+        hipLaunchKernelGGL((k_reorder_rows<CAP, 1>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a, nrows, G);
+    return hipGetLastError();
+}
+}  // namespace
 
 hipError_t launch_reorder(const ReorderArgs& a, hipStream_t stream)
 {
     const int64_t nrows = (int64_t)a.n[0] * a.n[1];
     const int64_t total = nrows * a.n[2];
     if (total <= 0) return hipSuccess;
-    // the staged row takes n[2] + A[2] slots when the fastest axis is transposed
-    const bool fits = a.n[2] <= kReorderMaxRow && (!a.swap[2] || a.A[2] <= kReorderPad);
-    if (fits) {
-        int64_t blocks = nrows < 256 * 16 ? nrows : 256 * 16;
-        hipLaunchKernelGGL(k_reorder_rows, dim3((unsigned)blocks), dim3(kThreads), 0, stream, a,
-                           nrows);
-    } else {
-        int64_t blocks = cdiv(total, kThreads);
-        if (blocks > 256 * 32) blocks = 256 * 32;
-        hipLaunchKernelGGL(k_reorder_gather, dim3((unsigned)blocks), dim3(kThreads), 0, stream, a,
-                           total);
-    }
+    const int need = a.n[2] + a.A[2];      // LDS slots of one staged row
+    if (need <= 2304) return launch_reorder_rows<2304>(a, nrows, stream);      // 18 KiB: 8 workgroups per CU
+    if (need <= 8448) return launch_reorder_rows<8448>(a, nrows, stream);      // 66 KiB: 2 per CU
+    int64_t blocks = cdiv(total, kThreads);
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(k_reorder_gather, dim3((unsigned)blocks), dim3(kThreads), 0, stream, a, total);
     return hipGetLastError();
 }
 
