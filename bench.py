@@ -175,6 +175,8 @@ def main() -> int:
                       "x_stage1+twiddle", "x_stage2+reorder", "z_reorder"]
         if args.unfused:
             pass_names = [f"{ax}_{st}" for ax in "zyx" for st in ("stage1", "phase", "stage2")] + ["reorder_xyz"]
+        elif npass == 5:
+            pass_names = ["z_fused_axis"] + pass_names[2:6]
         dom = max(range(npass), key=lambda i: pass_ms[i])
         dom_ms = pass_ms[dom]
         nbytes = 16.0 * E

@@ -143,11 +143,24 @@ dft3d_status dft3d_fft_phase(dft3d_plan plan, int axis, const void* in, void* ou
 dft3d_status dft3d_fft_second_stage(dft3d_plan plan, int axis, const void* in, void* out,
                                     int direction, int reorder, void* stream);
 
+/* FFT, one whole axis in a single fused kernel: first stage, twiddle, second stage and natural
+ * order (Eq. 13 - Eq. 16 for that axis), one read and one write of the tensor.  Offered for
+ * axis 2 (z) with splits 16x16, 16x32, 32x32, 32x64, 64x64; UNSUPPORTED otherwise.  dft3d_exec
+ * uses it whenever it applies (unless the plan has DFT3D_FLAG_UNFUSED). */
+dft3d_status dft3d_fft_axis(dft3d_plan plan, int axis, const void* in, void* out, int direction,
+                            void* stream);
+
 /* FFT, the re-ordering alone (Section IV, in-order transform): for every axis whose bit is set
  * in axes_mask (bit 0 = x, 1 = y, 2 = z), out[k_a + A*k_b] = in[k_a*B + k_b].  Pure data
  * movement through LDS; memory-bound pass. */
 dft3d_status dft3d_fft_reorder(dft3d_plan plan, int axes_mask, const void* in, void* out,
                                void* stream);
+
+/* Plain device-to-device copy of `bytes` (multiple of 16) with the library's own copy kernel:
+ * the achievable-HBM-bandwidth reference for the memory-bound passes and the calibration
+ * kernel for hardware byte counters (its traffic is exactly 2*bytes).  variant selects the
+ * launch shape (0 = default).  in/out: DEVICE, 16-byte aligned, non-overlapping. */
+dft3d_status dft3d_device_copy(const void* in, void* out, size_t bytes, int variant, void* stream);
 
 /* ---- host-side generator, exposed so its rounding can be tested without a GPU -------------- */
 

@@ -25,7 +25,7 @@ EXPORTS = [
     "dft3d_plan_create", "dft3d_plan_create_ex", "dft3d_plan_destroy",
     "dft3d_plan_workspace_bytes", "dft3d_plan_set_workspace", "dft3d_plan_get_split",
     "dft3d_exec", "dft3d_plan_enable_profiling", "dft3d_plan_read_profile", "dft3d_mode_contract", "dft3d_fft_first_stage", "dft3d_fft_phase",
-    "dft3d_fft_second_stage", "dft3d_fft_reorder", "dft3d_generate_matrix",
+    "dft3d_fft_second_stage", "dft3d_fft_axis", "dft3d_fft_reorder", "dft3d_device_copy", "dft3d_generate_matrix",
     "dft3d_generate_twiddle", "dft3d_status_string", "dft3d_last_error",
 ]
 
@@ -69,7 +69,9 @@ def load_library():
     lib.dft3d_fft_first_stage.argtypes = [vp, ci, vp, vp, ci, ci, vp]
     lib.dft3d_fft_phase.argtypes = [vp, ci, vp, vp, ci, vp]
     lib.dft3d_fft_second_stage.argtypes = [vp, ci, vp, vp, ci, ci, vp]
+    lib.dft3d_fft_axis.argtypes = [vp, ci, vp, vp, ci, vp]
     lib.dft3d_fft_reorder.argtypes = [vp, ci, vp, vp, vp]
+    lib.dft3d_device_copy.argtypes = [vp, vp, ctypes.c_size_t, ci, vp]
     lib.dft3d_generate_matrix.argtypes = [i64, vp, ci, vp, vp]
     lib.dft3d_generate_twiddle.argtypes = [i64, i64, ci, vp, vp]
     for name in EXPORTS:
@@ -126,6 +128,16 @@ def _stream_handle(stream) -> Optional[int]:
 
     s = torch.cuda.current_stream() if stream is None else stream
     return ctypes.c_void_p(s.cuda_stream)
+
+
+def device_copy(src, dst, variant: int = 0, stream=None):
+    """Copy one contiguous CUDA tensor into another of the same byte size with the library's copy kernel."""
+    nbytes = src.numel() * src.element_size()
+    if nbytes != dst.numel() * dst.element_size():
+        raise ValueError("size mismatch")
+    _check(load_library().dft3d_device_copy(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()),
+                                            nbytes, variant, _stream_handle(stream)))
+    return dst
 
 
 class Plan:
@@ -247,6 +259,11 @@ class Plan:
         xi, oi, out = self._tensors(x, out)
         _check(self._lib.dft3d_fft_second_stage(self._h, axis, xi, oi, direction,
                                                 1 if reorder else 0, _stream_handle(stream)))
+        return out
+
+    def fft_axis(self, axis, x, out=None, direction: int = FORWARD, stream=None):
+        xi, oi, out = self._tensors(x, out)
+        _check(self._lib.dft3d_fft_axis(self._h, axis, xi, oi, direction, _stream_handle(stream)))
         return out
 
     def fft_reorder(self, axes_mask, x, out=None, stream=None):

@@ -65,6 +65,19 @@ struct ReorderArgs {
 };
 hipError_t launch_reorder(const ReorderArgs& a, hipStream_t stream);
 
+// ---- fused contiguous-axis FFT-formulation pass ---------------------------------------------
+// One launch = first stage + twiddle + second stage + in-order placement of the z axis of a
+// tensor with `nrows` rows of A*B complex numbers.  Available for a fixed set of (A, B).
+bool fft_z_supported(int A, int B);
+hipError_t launch_fft_z(const float2* in, float2* out, int64_t nrows, int A, int B,
+                        const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
+                        int conj, hipStream_t stream);
+
+// ---- plain copy (bandwidth reference / counter calibration) -------------------------------
+// variant: units digit = accesses in flight per thread (1, 2, else 4); tens digit t > 0 caps the
+// grid at 256*t workgroups (grid-stride), 0 launches one chunk per workgroup.
+hipError_t launch_copy(const void* in, void* out, size_t bytes, int variant, hipStream_t stream);
+
 // ---- host generator -----------------------------------------------------------------------
 // exp(sign * 2 pi i * t) for t = p/q reduced exactly (uniform) or a real number of turns.
 void unit_root_ratio(int64_t p, int64_t q, int sign, double* re, double* im);

@@ -41,6 +41,19 @@ __device__ __forceinline__ int64_t xcd_remap(int64_t wg, int64_t total)
     return (wg % kXcds) * (total / kXcds) + wg / kXcds;
 }
 
+// HIP limits a grid dimension to fewer than 2^32 threads; big launches fold the workgroup index
+// into (x, y).
+__device__ __forceinline__ int64_t linear_block_id()
+{
+    return (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+}
+inline dim3 grid_for(int64_t blocks)
+{
+    const int64_t kMaxX = 1 << 22;
+    if (blocks <= kMaxX) return dim3((unsigned)blocks);
+    return dim3((unsigned)kMaxX, (unsigned)((blocks + kMaxX - 1) / kMaxX));
+}
+
 __device__ __forceinline__ int64_t out_offset(const ContractArgs& a, int64_t o)
 {
     return (o / a.Olo) * a.sYohi + (o % a.Olo) * a.sYolo;
@@ -114,7 +127,9 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
 
     // logical tile: k-tile fastest, then column tile (fast path: of one o; masked: of the
     // flattened (o, i) index)
-    int64_t t = xcd_remap((int64_t)blockIdx.x, total);
+    int64_t t = linear_block_id();
+    if (t >= total) return;
+    t = xcd_remap(t, total);
     const int kt = (int)(t % tilesK);
     t /= tilesK;
     const int k0 = kt * TM;
@@ -261,7 +276,7 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
             col -= o * I;
         }
         float2* __restrict__ Yo = a.Y + out_offset(a, o);
-        const int64_t beta = a.Tw ? (col / a.twInner) : 0;
+        const int beta = a.Tw ? (int)((uint32_t)col / (uint32_t)a.twInner) : 0;   // col < I < 2^31
 #pragma unroll
         for (int bm = 0; bm < BM; ++bm) {
 #pragma unroll
@@ -315,7 +330,9 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
     const int l16 = lane & 15;
     const int lq = lane >> 4;
 
-    int64_t t = xcd_remap((int64_t)blockIdx.x, total);
+    int64_t t = linear_block_id();
+    if (t >= total) return;
+    t = xcd_remap(t, total);
     const int kt = (int)(t % tilesK);
     const int64_t ot = t / tilesK;
     const int k0 = kt * TK;
@@ -468,44 +485,243 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
 }
 
 // ------------------------------------------------------------------------------------------
+// Fused FFT-formulation pass for the contiguous axis: first stage, twiddle, second stage and the
+// in-order placement of one axis in a single read and a single write of the tensor.
+//
+// A workgroup keeps both stage matrices in LDS and walks over tiles of R complete rows
+// (R*A*B contiguous complex numbers).  Per tile:
+//   1. registers -> xs[row][l][beta]              (the next tile's global loads are issued here,
+//                                                  so they land during the MFMA work below)
+//   2. stage 1 (data = MFMA B operand): Z[k_a][(row,beta)] = sum_l FA[k_a][l] xs[row][l][beta],
+//      times the twiddle T[k_a][beta], written to zs[(row,k_a)][beta]
+//   3. stage 2 (data = MFMA A operand): W[(row,k_a)][k_b] = sum_beta zs[(row,k_a)][beta] FB[k_b][beta],
+//      written to os[row][k_b][k_a], i.e. at the natural position k_a + A*k_b of the row
+//   4. os -> global, contiguous 16-byte stores.
+// LDS pitches: xs rows (l) are B+16 apart so the two l-rows a half-wave reads sit 32 banks apart;
+// zs and os have odd pitches (B+1, A+1) so lanes that walk rows hit distinct banks.
+// ------------------------------------------------------------------------------------------
+template <int A, int B, int R, int NW>
+__global__ __launch_bounds__(NW * 64) void k_fft_z(const float2* __restrict__ X, float2* __restrict__ Y,
+                                                   int64_t nrows, DeviceMatrix FA, DeviceMatrix FB,
+                                                   const float2* __restrict__ Tw, float scale, int conj)
+{
+    constexpr int NT = NW * 64;
+    constexpr int N = A * B;
+    constexpr int XP = B + 16, ZP = B + 1, OP = A + 1, FAP = A + 16, FBP = B + 16;
+    constexpr int XS = R * A * XP, OS = R * B * OP;
+    constexpr int XOS = XS > OS ? XS : OS;
+    constexpr int TILE = R * N;                    // complex numbers per tile
+    static_assert(TILE % (2 * NT) == 0, "tile must split into 16-byte loads evenly");
+    constexpr int XL = TILE / (2 * NT);            // 16-byte loads per thread per tile
+    static_assert(A % 16 == 0 && B % 16 == 0, "stage lengths must be multiples of the MFMA block");
+
+    __shared__ __align__(16) float2 xos[XOS];      // xs, later reused as os
+    __shared__ __align__(16) float2 zs[R * A * ZP];
+    __shared__ __align__(16) float far[A * FAP], fai[A * FAP];
+    __shared__ __align__(16) float fbr[B * FBP], fbi[B * FBP];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int l16 = lane & 15;
+    const int lq = lane >> 4;
+    const float isign = conj ? -1.0f : 1.0f;
+
+    // stage matrices -> LDS (transposed planes [n][k], as stored on the device)
+    for (int e = tid; e < A * A; e += NT) {
+        const int n = e / A, k = e % A;
+        far[n * FAP + k] = FA.re[(int64_t)n * FA.ld + k];
+        fai[n * FAP + k] = FA.im[(int64_t)n * FA.ld + k] * isign;
+    }
+    for (int e = tid; e < B * B; e += NT) {
+        const int n = e / B, k = e % B;
+        fbr[n * FBP + k] = FB.re[(int64_t)n * FB.ld + k];
+        fbi[n * FBP + k] = FB.im[(int64_t)n * FB.ld + k] * isign;
+    }
+
+    const int64_t ntiles = (nrows + R - 1) / R;
+    const int64_t nwg = (int64_t)gridDim.x * gridDim.y;
+    f32x4 xreg[XL];
+    auto gload = [&](int64_t tile) {
+        const int64_t base = tile * TILE;
+        const int64_t limit = nrows * N;           // first element past the tensor
+#pragma unroll
+        for (int j = 0; j < XL; ++j) {
+            const int64_t e = base + 2 * (tid + j * NT);
+            xreg[j] = (e < limit) ? *reinterpret_cast<const f32x4*>(X + e) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+
+    int64_t tile = linear_block_id();
+    if (tile < ntiles) gload(tile);
+    for (; tile < ntiles; tile += nwg) {
+        // 1. registers -> xs
+#pragma unroll
+        for (int j = 0; j < XL; ++j) {
+            const int e = 2 * (tid + j * NT);
+            const int rl = e / B, beta = e % B;     // rl = row*A + l
+            *reinterpret_cast<f32x4*>(&xos[rl * XP + beta]) = xreg[j];
+        }
+        __syncthreads();
+        if (tile + nwg < ntiles) gload(tile + nwg);
+
+        // 2. stage 1: blocks over (row, k_a block, beta block)
+        constexpr int S1 = R * (A / 16) * (B / 16);
+        constexpr int U1 = (S1 % (2 * NW) == 0) ? 2 : 1;      // blocks in flight per wave
+        for (int b0 = wave * U1; b0 < S1; b0 += NW * U1) {
+            int bb[U1], bm[U1], row[U1];
+            float2 tw[U1][4];
+            f32x4 cr[U1], ci[U1];
+#pragma unroll
+            for (int u = 0; u < U1; ++u) {
+                const int b = b0 + u;
+                bb[u] = b % (B / 16);
+                bm[u] = (b / (B / 16)) % (A / 16);
+                row[u] = b / ((B / 16) * (A / 16));
+                cr[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                ci[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int v = 0; v < 4; ++v)      // requested now, needed after the MFMAs
+                    tw[u][v] = Tw[(bm[u] * 16 + 4 * lq + v) * B + bb[u] * 16 + l16];
+            }
+#pragma unroll
+            for (int s = 0; s < A / 4; ++s) {
+                const int l = 4 * s + lq;
+                float ar[U1], ai[U1];
+                f32x2 x[U1];
+#pragma unroll
+                for (int u = 0; u < U1; ++u) {
+                    ar[u] = far[l * FAP + bm[u] * 16 + l16];
+                    ai[u] = fai[l * FAP + bm[u] * 16 + l16];
+                    x[u] = *reinterpret_cast<const f32x2*>(&xos[(row[u] * A + l) * XP + bb[u] * 16 + l16]);
+                }
+#pragma unroll
+                for (int u = 0; u < U1; ++u) cr[u] = mfma16(ar[u], x[u].x, cr[u]);
+#pragma unroll
+                for (int u = 0; u < U1; ++u) ci[u] = mfma16(ar[u], x[u].y, ci[u]);
+#pragma unroll
+                for (int u = 0; u < U1; ++u) cr[u] = mfma16(-ai[u], x[u].y, cr[u]);
+#pragma unroll
+                for (int u = 0; u < U1; ++u) ci[u] = mfma16(ai[u], x[u].x, ci[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < U1; ++u) {
+                const int beta = bb[u] * 16 + l16;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int ka = bm[u] * 16 + 4 * lq + v;
+                    const float wx = tw[u][v].x, wy = tw[u][v].y * isign;
+                    zs[(row[u] * A + ka) * ZP + beta] =
+                        make_float2(cr[u][v] * wx - ci[u][v] * wy, cr[u][v] * wy + ci[u][v] * wx);
+                }
+            }
+        }
+        __syncthreads();
+
+        // 3. stage 2: blocks over ((row,k_a) block, k_b block); xs is dead, os takes its place
+        constexpr int S2 = (R * A / 16) * (B / 16);
+        constexpr int U2 = (S2 % (2 * NW) == 0) ? 2 : 1;
+        for (int b0 = wave * U2; b0 < S2; b0 += NW * U2) {
+            int bn[U2], bmz[U2];
+            f32x4 cr[U2], ci[U2];
+#pragma unroll
+            for (int u = 0; u < U2; ++u) {
+                bn[u] = (b0 + u) % (B / 16);
+                bmz[u] = (b0 + u) / (B / 16);
+                cr[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                ci[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int s = 0; s < B / 4; ++s) {
+                const int beta = 4 * s + lq;
+                f32x2 z[U2];
+                float br[U2], bi[U2];
+#pragma unroll
+                for (int u = 0; u < U2; ++u) {
+                    z[u] = *reinterpret_cast<const f32x2*>(&zs[(bmz[u] * 16 + l16) * ZP + beta]);
+                    br[u] = fbr[beta * FBP + bn[u] * 16 + l16];
+                    bi[u] = fbi[beta * FBP + bn[u] * 16 + l16];
+                }
+#pragma unroll
+                for (int u = 0; u < U2; ++u) cr[u] = mfma16(z[u].x, br[u], cr[u]);
+#pragma unroll
+                for (int u = 0; u < U2; ++u) ci[u] = mfma16(z[u].x, bi[u], ci[u]);
+#pragma unroll
+                for (int u = 0; u < U2; ++u) cr[u] = mfma16(z[u].y, -bi[u], cr[u]);
+#pragma unroll
+                for (int u = 0; u < U2; ++u) ci[u] = mfma16(z[u].y, br[u], ci[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < U2; ++u) {
+                const int kb = bn[u] * 16 + l16;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int m = bmz[u] * 16 + 4 * lq + v;         // (row, k_a)
+                    const int row = m / A, ka = m % A;
+                    xos[(row * B + kb) * OP + ka] = make_float2(cr[u][v] * scale, ci[u][v] * scale);
+                }
+            }
+        }
+        __syncthreads();
+
+        // 4. os -> global in natural order (k = k_a + A*k_b), two complex numbers per store
+        {
+            const int64_t base = tile * TILE;
+            const int64_t limit = nrows * N;
+#pragma unroll
+            for (int j = 0; j < XL; ++j) {
+                const int e = 2 * (tid + j * NT);
+                const int row = e / N, k = e % N;
+                const int kb = k / A, ka = k % A;          // k even, A even: k+1 is the next k_a
+                const float2 p0 = xos[(row * B + kb) * OP + ka];
+                const float2 p1 = xos[(row * B + kb) * OP + ka + 1];
+                if (base + e < limit)
+                    *reinterpret_cast<f32x4*>(Y + base + e) = f32x4{p0.x, p0.y, p1.x, p1.y};
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Twiddle multiply (memory-bound).  The tensor [outer][A][B][inner] is walked as a matrix whose
 // twiddle depends on the row only (inner > 1: rows = outer*A*B, columns = inner, factor
 // Tw[row % (A*B)]) or on the column only (inner == 1: rows = outer, columns = A*B, factor
-// Tw[col]); either way the per-element index arithmetic is 32-bit.  One workgroup owns whole
-// rows in turn; each thread moves EV complex numbers per access (EV = 2 -> 16 bytes).
+// Tw[col]); either way the per-element index arithmetic is 32-bit.  Each thread moves EV complex
+// numbers (EV = 2 -> 16 bytes) and each workgroup one 4 KiB chunk, launched in memory order --
+// the launch shape that gave the best plain-copy bandwidth on this chip.
 // ------------------------------------------------------------------------------------------
 template <int EV, bool BY_ROW>
 __global__ __launch_bounds__(kThreads) void k_phase(const float2* __restrict__ in,
                                                     float2* __restrict__ out, int64_t rows,
-                                                    int cols, int AB,
+                                                    int cols, int chunks_per_row, int AB,
                                                     const float2* __restrict__ Tw, int conj)
 {
     typedef typename CVec<EV>::type xvec;
+    // one workgroup = one chunk of kThreads*EV columns of one row, launched in memory order
+    const int64_t bid = linear_block_id();
+    const int64_t r = bid / chunks_per_row;
+    const int c = (int)(bid % chunks_per_row) * (kThreads * EV) + threadIdx.x * EV;
+    if (r >= rows || c >= cols) return;
     const float s = conj ? -1.0f : 1.0f;
-    for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
-        const float2* __restrict__ src = in + r * cols;
-        float2* __restrict__ dst = out + r * cols;
-        float2 wr = make_float2(1.f, 0.f);
-        if (BY_ROW) {
-            wr = Tw[(int)(r % AB)];
-            wr.y *= s;
-        }
-        for (int c = threadIdx.x * EV; c < cols; c += kThreads * EV) {
-            xvec x = *reinterpret_cast<const xvec*>(src + c);
-            xvec y;
-#pragma unroll
-            for (int e = 0; e < EV; ++e) {
-                float2 w = wr;
-                if (!BY_ROW) {
-                    w = Tw[c + e];
-                    w.y *= s;
-                }
-                y[2 * e] = x[2 * e] * w.x - x[2 * e + 1] * w.y;
-                y[2 * e + 1] = x[2 * e] * w.y + x[2 * e + 1] * w.x;
-            }
-            *reinterpret_cast<xvec*>(dst + c) = y;
-        }
+    const xvec x = *reinterpret_cast<const xvec*>(in + r * cols + c);
+    float2 wr = make_float2(1.f, 0.f);
+    if (BY_ROW) {
+        wr = Tw[(int)(r % AB)];
+        wr.y *= s;
     }
+    xvec y;
+#pragma unroll
+    for (int e = 0; e < EV; ++e) {
+        float2 w = wr;
+        if (!BY_ROW) {
+            w = Tw[c + e];
+            w.y *= s;
+        }
+        y[2 * e] = x[2 * e] * w.x - x[2 * e + 1] * w.y;
+        y[2 * e + 1] = x[2 * e] * w.y + x[2 * e + 1] * w.x;
+    }
+    *reinterpret_cast<xvec*>(out + r * cols + c) = y;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -531,9 +747,10 @@ __global__ __launch_bounds__(kThreads) void k_reorder_rows(ReorderArgs a, int64_
     const int nz = a.n[2];
     const int A = a.A[2], B = a.B[2];
     const int pitch = nz + A;
-    const int64_t nbatches = (nrows + G - 1) / G;
-    for (int64_t b = blockIdx.x; b < nbatches; b += gridDim.x) {
+    {
+        const int64_t b = linear_block_id();      // one batch per workgroup, launched in memory order
         const int64_t r0 = b * G;
+        if (r0 >= nrows) return;
         const int g_here = (int)((nrows - r0) < G ? (nrows - r0) : G);
         const int count = g_here * nz;
         const float2* __restrict__ src = a.in + r0 * (int64_t)nz;
@@ -548,7 +765,7 @@ __global__ __launch_bounds__(kThreads) void k_reorder_rows(ReorderArgs a, int64_
                 *reinterpret_cast<xvec*>(a.out + ((int64_t)ox * a.n[1] + oy) * (int64_t)nz + z) =
                     *reinterpret_cast<const xvec*>(src + e);
             }
-            continue;
+            return;
         }
         for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
             const xvec v = *reinterpret_cast<const xvec*>(src + e);
@@ -573,7 +790,6 @@ __global__ __launch_bounds__(kThreads) void k_reorder_rows(ReorderArgs a, int64_
             const int oy = a.swap[1] ? swap_slot(iy, a.A[1], a.B[1]) : iy;
             *reinterpret_cast<xvec*>(a.out + ((int64_t)ox * a.n[1] + oy) * (int64_t)nz + k) = v;
         }
-        __syncthreads();
     }
 }
 
@@ -599,9 +815,7 @@ hipError_t launch_tiles(KernelT kernel, const ContractArgs& a, int tilesK, int64
                         int64_t total, hipStream_t stream)
 {
     if (total <= 0) return hipSuccess;
-    if (total > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)total), dim3(kThreads), 0, stream, a, tilesK,
-                       tilesOther, total);
+    hipLaunchKernelGGL(kernel, grid_for(total), dim3(kThreads), 0, stream, a, tilesK, tilesOther, total);
     return hipGetLastError();
 }
 
@@ -659,6 +873,81 @@ hipError_t launch_contract(const ContractArgs& a, hipStream_t stream)
     return launch_s<128, 128, 64, 64, 16, 2>(a, stream);
 }
 
+namespace {
+// Plain copy, 16 bytes per lane, UNROLL independent accesses per thread: the achievable-bandwidth
+// reference for the memory-bound passes and the calibration kernel for the HBM byte counters.
+template <int UNROLL>
+__global__ __launch_bounds__(kThreads) void k_copy(const f32x4* __restrict__ in, f32x4* __restrict__ out,
+                                                   int64_t nvec)
+{
+    const int64_t chunk = (int64_t)kThreads * UNROLL;
+    const int64_t nblocks = (int64_t)gridDim.x * gridDim.y;
+    for (int64_t base = linear_block_id() * chunk; base < nvec; base += nblocks * chunk) {
+        f32x4 v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int64_t i = base + threadIdx.x + (int64_t)u * kThreads;
+            if (i < nvec) v[u] = in[i];
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int64_t i = base + threadIdx.x + (int64_t)u * kThreads;
+            if (i < nvec) out[i] = v[u];
+        }
+    }
+}
+}  // namespace
+
+namespace {
+template <int A, int B, int R, int NW, int WGS_PER_CU>
+hipError_t launch_fft_z_inst(const float2* in, float2* out, int64_t nrows, const DeviceMatrix& FA,
+                             const DeviceMatrix& FB, const float2* Tw, float scale, int conj,
+                             hipStream_t stream)
+{
+    const int64_t ntiles = cdiv(nrows, R);
+    const int64_t resident = 256 * WGS_PER_CU;             // persistent workgroups
+    const int64_t blocks = ntiles < resident ? ntiles : resident;
+    hipLaunchKernelGGL((k_fft_z<A, B, R, NW>), grid_for(blocks), dim3(NW * 64), 0, stream, in, out, nrows,
+                       FA, FB, Tw, scale, conj);
+    return hipGetLastError();
+}
+}  // namespace
+
+bool fft_z_supported(int A, int B)
+{
+    return (A == 16 && B == 16) || (A == 16 && B == 32) || (A == 32 && B == 32) ||
+           (A == 32 && B == 64) || (A == 64 && B == 64);
+}
+
+hipError_t launch_fft_z(const float2* in, float2* out, int64_t nrows, int A, int B,
+                        const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
+                        int conj, hipStream_t stream)
+{
+    if (nrows <= 0) return hipSuccess;
+    if (A == 16 && B == 16) return launch_fft_z_inst<16, 16, 8, 4, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (A == 16 && B == 32) return launch_fft_z_inst<16, 32, 4, 4, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (A == 32 && B == 32) return launch_fft_z_inst<32, 32, 2, 4, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (A == 32 && B == 64) return launch_fft_z_inst<32, 64, 2, 8, 1>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (A == 64 && B == 64) return launch_fft_z_inst<64, 64, 1, 8, 1>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_copy(const void* in, void* out, size_t bytes, int variant, hipStream_t stream)
+{
+    const int64_t nvec = (int64_t)(bytes / 16);
+    if (nvec <= 0) return hipSuccess;
+    const int unroll = (variant % 10 == 1) ? 1 : ((variant % 10 == 2) ? 2 : 4);
+    const int64_t chunk = (int64_t)kThreads * unroll;
+    int64_t blocks = cdiv(nvec, chunk);
+    const int cap = variant >= 10 ? 256 * (variant / 10) : 0;     // 0: one chunk per workgroup
+    if (cap > 0 && blocks > cap) blocks = cap;
+    const dim3 grid = grid_for(blocks), block(kThreads);
+    if (unroll == 1) hipLaunchKernelGGL(k_copy<1>, grid, block, 0, stream, (const f32x4*)in, (f32x4*)out, nvec);
+    else if (unroll == 2) hipLaunchKernelGGL(k_copy<2>, grid, block, 0, stream, (const f32x4*)in, (f32x4*)out, nvec);
+    else hipLaunchKernelGGL(k_copy<4>, grid, block, 0, stream, (const f32x4*)in, (f32x4*)out, nvec);
+    return hipGetLastError();
+}
+
 hipError_t launch_phase(const float2* in, float2* out, int64_t outer, int A, int B, int64_t inner,
                         const float2* Tw, int conj, hipStream_t stream)
 {
@@ -668,15 +957,17 @@ hipError_t launch_phase(const float2* in, float2* out, int64_t outer, int A, int
     const bool by_row = inner > 1;
     const int64_t rows = by_row ? outer * AB : outer;
     const int cols = by_row ? (int)inner : AB;
-    int64_t blocks = rows < 256 * 16 ? rows : 256 * 16;
-    const dim3 grid((unsigned)blocks), block(kThreads);
     const bool vec2 = (cols % 2 == 0);
+    const int per_wg = kThreads * (vec2 ? 2 : 1);
+    const int cpr = (int)cdiv(cols, per_wg);
+    const int64_t blocks = rows * cpr;
+    const dim3 grid = grid_for(blocks), block(kThreads);
     if (by_row) {
-        if (vec2) hipLaunchKernelGGL((k_phase<2, true>), grid, block, 0, stream, in, out, rows, cols, AB, Tw, conj);
-        else hipLaunchKernelGGL((k_phase<1, true>), grid, block, 0, stream, in, out, rows, cols, AB, Tw, conj);
+        if (vec2) hipLaunchKernelGGL((k_phase<2, true>), grid, block, 0, stream, in, out, rows, cols, cpr, AB, Tw, conj);
+        else hipLaunchKernelGGL((k_phase<1, true>), grid, block, 0, stream, in, out, rows, cols, cpr, AB, Tw, conj);
     } else {
-        if (vec2) hipLaunchKernelGGL((k_phase<2, false>), grid, block, 0, stream, in, out, rows, cols, AB, Tw, conj);
-        else hipLaunchKernelGGL((k_phase<1, false>), grid, block, 0, stream, in, out, rows, cols, AB, Tw, conj);
+        if (vec2) hipLaunchKernelGGL((k_phase<2, false>), grid, block, 0, stream, in, out, rows, cols, cpr, AB, Tw, conj);
+        else hipLaunchKernelGGL((k_phase<1, false>), grid, block, 0, stream, in, out, rows, cols, cpr, AB, Tw, conj);
     }
     return hipGetLastError();
 }
@@ -687,17 +978,16 @@ hipError_t launch_reorder_rows(const ReorderArgs& a, int64_t nrows, hipStream_t 
 {
     const int nz = a.n[2];
     const int pitch = nz + a.A[2];
-    int G = CAP / pitch;
+    // a batch of about 512 complex numbers (4 KiB, one 16-byte access per thread), whole rows
+    int G = 512 / nz;
+    if (G > CAP / pitch) G = CAP / pitch;
     if (G < 1) G = 1;
-    // keep at least ~8 batches per CU in the grid
-    while (G > 1 && (nrows + G - 1) / G < 256 * 8) G /= 2;
-    const int64_t nbatches = (nrows + G - 1) / G;
-    const int64_t blocks = nbatches < 256 * 16 ? nbatches : 256 * 16;
+    const int64_t blocks = (nrows + G - 1) / G;
     const bool vec2 = (nz % 2 == 0) && (!a.swap[2] || (a.A[2] % 2 == 0 && a.B[2] % 2 == 0));
     if (vec2)
-        hipLaunchKernelGGL((k_reorder_rows<CAP, 2>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a, nrows, G);
+        hipLaunchKernelGGL((k_reorder_rows<CAP, 2>), grid_for(blocks), dim3(kThreads), 0, stream, a, nrows, G);
     else
-        hipLaunchKernelGGL((k_reorder_rows<CAP, 1>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a, nrows, G);
+        hipLaunchKernelGGL((k_reorder_rows<CAP, 1>), grid_for(blocks), dim3(kThreads), 0, stream, a, nrows, G);
     return hipGetLastError();
 }
 }  // namespace

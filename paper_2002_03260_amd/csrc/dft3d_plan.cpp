@@ -227,6 +227,19 @@ hipError_t run_second_stage(const dft3d_plan_s* p, int axis, const float2* in, f
     return launch_contract(a, st);
 }
 
+// FFT, whole z axis in one fused kernel (both stages, twiddle, natural order).
+bool z_axis_fusable(const dft3d_plan_s* p)
+{
+    return p->form == DFT3D_FFT && fft_z_supported((int)p->A[2], (int)p->B[2]);
+}
+
+hipError_t run_fused_z(const dft3d_plan_s* p, const float2* in, float2* out, int conj, float scale,
+                       hipStream_t st)
+{
+    return launch_fft_z(in, out, p->n[0] * p->n[1], (int)p->A[2], (int)p->B[2], p->FA[2], p->FB[2],
+                        p->Tw[2], scale, conj, st);
+}
+
 hipError_t run_reorder(const dft3d_plan_s* p, int mask, const float2* in, float2* out, hipStream_t st)
 {
     ReorderArgs r{};
@@ -550,6 +563,26 @@ dft3d_status dft3d_fft_second_stage(dft3d_plan p, int axis, const void* in, void
                       "fft_second_stage");
 }
 
+dft3d_status dft3d_fft_axis(dft3d_plan p, int axis, const void* in, void* out, int direction,
+                            void* stream)
+{
+    dft3d_status s = check_buffers(p, in, out, "fft_axis");
+    if (s != DFT3D_OK) return s;
+    if (axis < 0 || axis > 2 || !valid_direction(direction)) {
+        set_error("fft_axis: bad axis or direction");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    if (p->form != DFT3D_FFT) { set_error("fft_axis: not an FFT plan"); return DFT3D_ERR_UNSUPPORTED; }
+    if (axis != 2 || !z_axis_fusable(p)) {
+        set_error("fft_axis: no fused kernel for axis %d with split %lld x %lld", axis,
+                  (long long)p->A[axis], (long long)p->B[axis]);
+        return DFT3D_ERR_UNSUPPORTED;
+    }
+    return hip_status(run_fused_z(p, (const float2*)in, (float2*)out, direction == DFT3D_BACKWARD,
+                                  axis_scale(p, axis, direction), (hipStream_t)stream),
+                      "fft_axis");
+}
+
 dft3d_status dft3d_fft_reorder(dft3d_plan p, int axes_mask, const void* in, void* out, void* stream)
 {
     dft3d_status s = check_buffers(p, in, out, "fft_reorder");
@@ -558,6 +591,20 @@ dft3d_status dft3d_fft_reorder(dft3d_plan p, int axes_mask, const void* in, void
     if (p->form != DFT3D_FFT) { set_error("fft_reorder: not an FFT plan"); return DFT3D_ERR_UNSUPPORTED; }
     return hip_status(run_reorder(p, axes_mask, (const float2*)in, (float2*)out, (hipStream_t)stream),
                       "fft_reorder");
+}
+
+dft3d_status dft3d_device_copy(const void* in, void* out, size_t bytes, int variant, void* stream)
+{
+    if (!in || !out || (bytes & 15) || ((uintptr_t)in & 15) || ((uintptr_t)out & 15) || variant < 0) {
+        set_error("device_copy: pointers and size must be 16-byte multiples, variant >= 0");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
+    if (a < b + bytes && b < a + bytes) {
+        set_error("device_copy: in and out overlap");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    return hip_status(launch_copy(in, out, bytes, variant, (hipStream_t)stream), "device_copy");
 }
 
 dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, void* stream)
@@ -594,13 +641,15 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
     // The passes ping-pong between `out` and `other`; the pass count is odd so that, starting
     // with in -> out, the last pass also lands in `out`.
     //   KDFT: modes z, y, x (3 passes).
-    //   FFT : per axis z, y, x: first stage (+twiddle), second stage; the x and y re-orderings
-    //         are folded into the second-stage stores (they only change row addresses), the z
-    //         re-ordering is one transposing pass at the end (7 passes).
+    //   FFT : z axis in one fused kernel when its split has one (else first stage, second stage
+    //         and a transposing re-ordering pass at the end); y and x: first stage (+twiddle),
+    //         second stage with the re-ordering folded into its stores (they only change row
+    //         addresses).  5 passes (7 without the fused z kernel).
     //   FFT unfused: per axis first stage, twiddle pass, second stage; one re-ordering pass of
     //         all three axes at the end (10 passes -> starts with in -> other).
+    const bool zfused = !unfused && z_axis_fusable(p);
     int npass = 3;
-    if (p->form == DFT3D_FFT) npass = unfused ? 10 : 7;
+    if (p->form == DFT3D_FFT) npass = unfused ? 10 : (zfused ? 5 : 7);
     if (clobber && (npass % 2 == 0)) {
         set_error("exec: CLOBBER_INPUT cannot be combined with this pass structure");
         return DFT3D_ERR_UNSUPPORTED;
@@ -630,6 +679,12 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
         }
     } else {
         for (int axis = 2; axis >= 0 && e == hipSuccess; --axis) {
+            if (axis == 2 && zfused) {
+                mark(0);
+                e = run_fused_z(p, src, dst, conj, axis_scale(p, axis, direction), st);
+                advance();
+                continue;
+            }
             mark(0);
             e = run_first_stage(p, axis, src, dst, conj, unfused ? 0 : 1, st);
             advance();
@@ -645,7 +700,7 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
             e = run_second_stage(p, axis, src, dst, conj, axis_scale(p, axis, direction), fold, st);
             advance();
         }
-        if (e == hipSuccess) {
+        if (e == hipSuccess && !zfused) {
             mark(0);
             e = run_reorder(p, unfused ? 7 : 4, src, dst, st);
             advance();

@@ -190,6 +190,27 @@ def test_fft_steps_match_oracle_steps(dft, shape, split):
         assert np.array_equal(to_host(p.fft_reorder(7, xd)), want.astype(np.complex64))
 
 
+@pytest.mark.parametrize("shape,split", [((5, 7, 256), None), ((16, 9, 512), None), ((3, 3, 1024), None),
+                                         ((2, 5, 2048), None), ((1, 3, 4096), None),
+                                         ((4, 4, 512), (2, 2, 16)), ((33, 1, 256), None)])
+def test_fft_fused_axis_kernel(dft, shape, split):
+    """The single-kernel z-axis pass equals first stage + twiddle + second stage + re-ordering."""
+    say(f"case fft fused axis {shape} split {split}")
+    x = wl.draw_complex(shape, "normal", 4500 + sum(shape))
+    xd = to_dev(x)
+    with dft.Plan(shape, dft.FFT, split=split) as p:
+        A, B = p.split(2)
+        want = ff.fft_axis(x, 2, A, B)
+        got = to_host(p.fft_axis(2, xd))
+        assert report(f"fused z axis {A}x{B}", got, want) <= TOL
+        assert rel_l2(got, np.fft.fft(x.astype(np.complex128), axis=2)) <= TOL
+        wantb = ff.fft_axis(x, 2, A, B, sign=ff.BACKWARD) / shape[2]
+        gotb = to_host(p.fft_axis(2, xd, direction=dft.BACKWARD))
+        assert report(f"fused z axis {A}x{B} backward", gotb, wantb) <= TOL
+        with pytest.raises(dft.Dft3dError):
+            p.fft_axis(0, xd)
+
+
 @pytest.mark.parametrize("shape,split", FFT_CASES + [((64, 64, 64), None), ((128, 16, 256), None)])
 @pytest.mark.parametrize("flags", [0, 2])
 def test_fft_exec_matches_oracle(dft, shape, split, flags):
