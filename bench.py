@@ -177,6 +177,8 @@ def main() -> int:
             pass_names = [f"{ax}_{st}" for ax in "zyx" for st in ("stage1", "phase", "stage2")] + ["reorder_xyz"]
         elif npass == 5:
             pass_names = ["z_fused_axis"] + pass_names[2:6]
+        elif npass == 3:
+            pass_names = ["z_fused_axis", "y_fused_axis", "x_fused_axis"]
         dom = max(range(npass), key=lambda i: pass_ms[i])
         dom_ms = pass_ms[dom]
         nbytes = 16.0 * E

@@ -73,6 +73,14 @@ hipError_t launch_fft_z(const float2* in, float2* out, int64_t nrows, int A, int
                         const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
                         int conj, hipStream_t stream);
 
+// ---- fused strided-axis FFT-formulation pass ------------------------------------------------
+// Tensor viewed as [O][A*B][I]; one launch = both stages, twiddle and natural order along the
+// middle index.  I must be a multiple of 16; available for a fixed set of (A, B).
+bool fft_s_supported(int A, int B, int64_t I);
+hipError_t launch_fft_s(const float2* in, float2* out, int64_t O, int64_t I, int A, int B,
+                        const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
+                        int conj, hipStream_t stream);
+
 // ---- plain copy (bandwidth reference / counter calibration) -------------------------------
 // variant: units digit = accesses in flight per thread (1, 2, else 4); tens digit t > 0 caps the
 // grid at 256*t workgroups (grid-stride), 0 launches one chunk per workgroup.

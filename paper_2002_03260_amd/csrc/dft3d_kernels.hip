@@ -501,7 +501,7 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
 // zs and os have odd pitches (B+1, A+1) so lanes that walk rows hit distinct banks.
 // ------------------------------------------------------------------------------------------
 template <int A, int B, int R, int NW>
-__global__ __launch_bounds__(NW * 64) void k_fft_z(const float2* __restrict__ X, float2* __restrict__ Y,
+__global__ __launch_bounds__(NW * 64, 2) void k_fft_z(const float2* __restrict__ X, float2* __restrict__ Y,
                                                    int64_t nrows, DeviceMatrix FA, DeviceMatrix FB,
                                                    const float2* __restrict__ Tw, float scale, int conj)
 {
@@ -678,6 +678,188 @@ __global__ __launch_bounds__(NW * 64) void k_fft_z(const float2* __restrict__ X,
                 if (base + e < limit)
                     *reinterpret_cast<f32x4*>(Y + base + e) = f32x4{p0.x, p0.y, p1.x, p1.y};
             }
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Fused FFT-formulation pass for a strided axis (x or y): the tensor is viewed as
+// [o][pos = 0..A*B-1][c = 0..I-1] with c contiguous; a workgroup tile is ALL positions of the axis
+// for 16 neighbouring columns (A*B rows of 128 bytes), kept in LDS as xs[pos][16].
+//   stage 1 (in place): for every beta,  Z[k_a][beta][c] = T[k_a][beta] sum_l FA[k_a][l] xs[l][beta][c]
+//   stage 2: for every k_a,  W[k_b][c] = sum_beta FB[k_b][beta] Z[k_a][beta][c], stored straight from
+//            the accumulators to row k_a + A*k_b of the output (natural order).
+// Both stages use the data as the MFMA B operand (lanes walk the 16 columns), so no transposition
+// is needed.  A wave owns whole beta (stage 1) or whole k_a (stage 2) groups, which makes the
+// in-place stage 1 free of cross-wave hazards.  Rows are XOR-swizzled (the lowest bit of beta is
+// flipped when l is odd) so the two rows a half-wave reads lie in different bank halves.
+// The next tile's global loads are issued before the MFMA work of the current one.
+// ------------------------------------------------------------------------------------------
+template <int A, int B, int NW>
+__global__ __launch_bounds__(NW * 64, 2) void k_fft_s(const float2* __restrict__ X, float2* __restrict__ Y,
+                                                   int64_t O, int64_t I, DeviceMatrix FA, DeviceMatrix FB,
+                                                   const float2* __restrict__ Tw, float scale, int conj)
+{
+    constexpr int NT = NW * 64;
+    constexpr int N = A * B;
+    constexpr int TC = 16;
+    // plane pitches that put the four rows a wave reads (l .. l+3) on four distinct 16-bank groups
+    constexpr int FAP = (A % 64 == 16 || A % 64 == 48) ? A : A + 16;
+    constexpr int FBP = (B % 64 == 16 || B % 64 == 48) ? B : B + 16;
+    constexpr int RPP = NT / 8;                    // tile rows fetched per pass (8 threads x 16 B per row)
+    static_assert(N % RPP == 0, "axis length must be a multiple of the rows per pass");
+    constexpr int XL = N / RPP;                    // 16-byte loads per thread per tile
+    static_assert(A % 16 == 0 && B % 16 == 0 && B % NW == 0 && A % NW == 0, "unsupported split");
+
+    __shared__ __align__(16) float2 xs[N * TC];
+    __shared__ __align__(16) float far[A * FAP], fai[A * FAP];
+    __shared__ __align__(16) float fbr[B * FBP], fbi[B * FBP];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int l16 = lane & 15;
+    const int lq = lane >> 4;
+    const float isign = conj ? -1.0f : 1.0f;
+
+    for (int e = tid; e < A * A; e += NT) {
+        const int n = e / A, k = e % A;
+        far[n * FAP + k] = FA.re[(int64_t)n * FA.ld + k];
+        fai[n * FAP + k] = FA.im[(int64_t)n * FA.ld + k] * isign;
+    }
+    for (int e = tid; e < B * B; e += NT) {
+        const int n = e / B, k = e % B;
+        fbr[n * FBP + k] = FB.re[(int64_t)n * FB.ld + k];
+        fbi[n * FBP + k] = FB.im[(int64_t)n * FB.ld + k] * isign;
+    }
+
+    auto phys = [](int pos) { return pos ^ ((pos / B) & 1); };
+
+    const int64_t ctiles = I / TC;                 // column tiles per o (I is a multiple of 16)
+    const int64_t ntiles = O * ctiles;
+    const int64_t nwg = (int64_t)gridDim.x * gridDim.y;
+    const int lrow = tid / 8, lcol = (tid % 8) * 2;
+
+    f32x4 xreg[XL];
+    auto tile_base = [&](int64_t tile) { return (tile / ctiles) * (int64_t)N * I + (tile % ctiles) * TC; };
+    auto gload = [&](int64_t tile) {
+        const float2* src = X + tile_base(tile) + (int64_t)lrow * I + lcol;
+#pragma unroll
+        for (int j = 0; j < XL; ++j)
+            xreg[j] = *reinterpret_cast<const f32x4*>(src + (int64_t)(j * RPP) * I);
+    };
+
+    int64_t tile = linear_block_id();
+    if (tile < ntiles) gload(tile);
+    for (; tile < ntiles; tile += nwg) {
+#pragma unroll
+        for (int j = 0; j < XL; ++j)
+            *reinterpret_cast<f32x4*>(&xs[phys(lrow + j * RPP) * TC + lcol]) = xreg[j];
+        __syncthreads();
+        if (tile + nwg < ntiles) gload(tile + nwg);
+
+        // stage 1, in place; two beta groups in flight per wave
+        constexpr int U1 = ((B / NW) % 2 == 0) ? 2 : 1;
+        constexpr int BMA = A / 16;
+        for (int g = 0; g < B / NW; g += U1) {
+            f32x4 cr[U1][BMA], ci[U1][BMA];
+            float2 tw[U1][BMA][4];
+            int beta[U1];
+#pragma unroll
+            for (int u = 0; u < U1; ++u) {
+                beta[u] = wave + (g + u) * NW;
+#pragma unroll
+                for (int bm = 0; bm < BMA; ++bm) {
+                    cr[u][bm] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    ci[u][bm] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) tw[u][bm][v] = Tw[(bm * 16 + 4 * lq + v) * B + beta[u]];
+                }
+            }
+#pragma unroll 4
+            for (int s = 0; s < A / 4; ++s) {
+                const int l = 4 * s + lq;
+                float ar[BMA], ai[BMA];
+                f32x2 x[U1];
+#pragma unroll
+                for (int bm = 0; bm < BMA; ++bm) {
+                    ar[bm] = far[l * FAP + bm * 16 + l16];
+                    ai[bm] = fai[l * FAP + bm * 16 + l16];
+                }
+#pragma unroll
+                for (int u = 0; u < U1; ++u)
+                    x[u] = *reinterpret_cast<const f32x2*>(&xs[phys(l * B + beta[u]) * TC + l16]);
+#pragma unroll
+                for (int u = 0; u < U1; ++u)
+#pragma unroll
+                    for (int bm = 0; bm < BMA; ++bm) cr[u][bm] = mfma16(ar[bm], x[u].x, cr[u][bm]);
+#pragma unroll
+                for (int u = 0; u < U1; ++u)
+#pragma unroll
+                    for (int bm = 0; bm < BMA; ++bm) ci[u][bm] = mfma16(ar[bm], x[u].y, ci[u][bm]);
+#pragma unroll
+                for (int u = 0; u < U1; ++u)
+#pragma unroll
+                    for (int bm = 0; bm < BMA; ++bm) cr[u][bm] = mfma16(-ai[bm], x[u].y, cr[u][bm]);
+#pragma unroll
+                for (int u = 0; u < U1; ++u)
+#pragma unroll
+                    for (int bm = 0; bm < BMA; ++bm) ci[u][bm] = mfma16(ai[bm], x[u].x, ci[u][bm]);
+            }
+#pragma unroll
+            for (int u = 0; u < U1; ++u)
+#pragma unroll
+                for (int bm = 0; bm < BMA; ++bm)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int ka = bm * 16 + 4 * lq + v;
+                        const float wx = tw[u][bm][v].x, wy = tw[u][bm][v].y * isign;
+                        const float zr = cr[u][bm][v] * wx - ci[u][bm][v] * wy;
+                        const float zi = cr[u][bm][v] * wy + ci[u][bm][v] * wx;
+                        *reinterpret_cast<f32x2*>(&xs[phys(ka * B + beta[u]) * TC + l16]) = f32x2{zr, zi};
+                    }
+        }
+        __syncthreads();
+
+        // stage 2: one k_a group at a time per wave, all k_b blocks of it in flight
+        constexpr int BMB = B / 16;
+        float2* dst = Y + tile_base(tile) + l16;
+        for (int g = 0; g < A / NW; ++g) {
+            const int ka = wave + g * NW;
+            f32x4 cr[BMB], ci[BMB];
+#pragma unroll
+            for (int bm = 0; bm < BMB; ++bm) {
+                cr[bm] = f32x4{0.f, 0.f, 0.f, 0.f};
+                ci[bm] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll 4
+            for (int s = 0; s < B / 4; ++s) {
+                const int beta = 4 * s + lq;
+                const f32x2 z = *reinterpret_cast<const f32x2*>(&xs[phys(ka * B + beta) * TC + l16]);
+                float ar[BMB], ai[BMB];
+#pragma unroll
+                for (int bm = 0; bm < BMB; ++bm) {
+                    ar[bm] = fbr[beta * FBP + bm * 16 + l16];
+                    ai[bm] = fbi[beta * FBP + bm * 16 + l16];
+                }
+#pragma unroll
+                for (int bm = 0; bm < BMB; ++bm) cr[bm] = mfma16(ar[bm], z.x, cr[bm]);
+#pragma unroll
+                for (int bm = 0; bm < BMB; ++bm) ci[bm] = mfma16(ar[bm], z.y, ci[bm]);
+#pragma unroll
+                for (int bm = 0; bm < BMB; ++bm) cr[bm] = mfma16(-ai[bm], z.y, cr[bm]);
+#pragma unroll
+                for (int bm = 0; bm < BMB; ++bm) ci[bm] = mfma16(ai[bm], z.x, ci[bm]);
+            }
+#pragma unroll
+            for (int bm = 0; bm < BMB; ++bm)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int kb = bm * 16 + 4 * lq + v;
+                    *reinterpret_cast<f32x2*>(dst + (int64_t)(ka + A * kb) * I) =
+                        f32x2{cr[bm][v] * scale, ci[bm][v] * scale};
+                }
         }
         __syncthreads();
     }
@@ -929,6 +1111,38 @@ hipError_t launch_fft_z(const float2* in, float2* out, int64_t nrows, int A, int
     if (A == 32 && B == 32) return launch_fft_z_inst<32, 32, 2, 4, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     if (A == 32 && B == 64) return launch_fft_z_inst<32, 64, 2, 8, 1>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     if (A == 64 && B == 64) return launch_fft_z_inst<64, 64, 1, 8, 1>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    return hipErrorInvalidValue;
+}
+
+namespace {
+template <int A, int B, int NW, int WGS_PER_CU>
+hipError_t launch_fft_s_inst(const float2* in, float2* out, int64_t O, int64_t I, const DeviceMatrix& FA,
+                             const DeviceMatrix& FB, const float2* Tw, float scale, int conj,
+                             hipStream_t stream)
+{
+    const int64_t ntiles = O * (I / 16);
+    const int64_t resident = 256 * WGS_PER_CU;
+    const int64_t blocks = ntiles < resident ? ntiles : resident;
+    hipLaunchKernelGGL((k_fft_s<A, B, NW>), grid_for(blocks), dim3(NW * 64), 0, stream, in, out, O, I, FA, FB,
+                       Tw, scale, conj);
+    return hipGetLastError();
+}
+}  // namespace
+
+bool fft_s_supported(int A, int B, int64_t I)
+{
+    if (I % 16 != 0) return false;
+    return (A == 16 && B == 16) || (A == 16 && B == 32) || (A == 32 && B == 32);
+}
+
+hipError_t launch_fft_s(const float2* in, float2* out, int64_t O, int64_t I, int A, int B,
+                        const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
+                        int conj, hipStream_t stream)
+{
+    if (O <= 0 || I <= 0) return hipSuccess;
+    if (A == 16 && B == 16) return launch_fft_s_inst<16, 16, 4, 2>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
+    if (A == 16 && B == 32) return launch_fft_s_inst<16, 32, 4, 2>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
+    if (A == 32 && B == 32) return launch_fft_s_inst<32, 32, 8, 1>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
     return hipErrorInvalidValue;
 }
 

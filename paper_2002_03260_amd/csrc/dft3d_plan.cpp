@@ -240,6 +240,20 @@ hipError_t run_fused_z(const dft3d_plan_s* p, const float2* in, float2* out, int
                         p->Tw[2], scale, conj, st);
 }
 
+// FFT, whole x or y axis in one fused kernel.
+bool strided_axis_fusable(const dft3d_plan_s* p, int axis)
+{
+    return p->form == DFT3D_FFT && axis != 2 &&
+           fft_s_supported((int)p->A[axis], (int)p->B[axis], p->inner(axis));
+}
+
+hipError_t run_fused_s(const dft3d_plan_s* p, int axis, const float2* in, float2* out, int conj,
+                       float scale, hipStream_t st)
+{
+    return launch_fft_s(in, out, p->outer(axis), p->inner(axis), (int)p->A[axis], (int)p->B[axis],
+                        p->FA[axis], p->FB[axis], p->Tw[axis], scale, conj, st);
+}
+
 hipError_t run_reorder(const dft3d_plan_s* p, int mask, const float2* in, float2* out, hipStream_t st)
 {
     ReorderArgs r{};
@@ -573,14 +587,17 @@ dft3d_status dft3d_fft_axis(dft3d_plan p, int axis, const void* in, void* out, i
         return DFT3D_ERR_INVALID_ARG;
     }
     if (p->form != DFT3D_FFT) { set_error("fft_axis: not an FFT plan"); return DFT3D_ERR_UNSUPPORTED; }
-    if (axis != 2 || !z_axis_fusable(p)) {
+    const bool ok = axis == 2 ? z_axis_fusable(p) : strided_axis_fusable(p, axis);
+    if (!ok) {
         set_error("fft_axis: no fused kernel for axis %d with split %lld x %lld", axis,
                   (long long)p->A[axis], (long long)p->B[axis]);
         return DFT3D_ERR_UNSUPPORTED;
     }
-    return hip_status(run_fused_z(p, (const float2*)in, (float2*)out, direction == DFT3D_BACKWARD,
-                                  axis_scale(p, axis, direction), (hipStream_t)stream),
-                      "fft_axis");
+    const int conj = direction == DFT3D_BACKWARD;
+    const float sc = axis_scale(p, axis, direction);
+    hipError_t e = axis == 2 ? run_fused_z(p, (const float2*)in, (float2*)out, conj, sc, (hipStream_t)stream)
+                             : run_fused_s(p, axis, (const float2*)in, (float2*)out, conj, sc, (hipStream_t)stream);
+    return hip_status(e, "fft_axis");
 }
 
 dft3d_status dft3d_fft_reorder(dft3d_plan p, int axes_mask, const void* in, void* out, void* stream)
@@ -641,18 +658,30 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
     // The passes ping-pong between `out` and `other`; the pass count is odd so that, starting
     // with in -> out, the last pass also lands in `out`.
     //   KDFT: modes z, y, x (3 passes).
-    //   FFT : z axis in one fused kernel when its split has one (else first stage, second stage
-    //         and a transposing re-ordering pass at the end); y and x: first stage (+twiddle),
-    //         second stage with the re-ordering folded into its stores (they only change row
-    //         addresses).  5 passes (7 without the fused z kernel).
+    //   FFT : every axis whose split has a fused kernel takes one pass (both stages, twiddle and
+    //         natural order).  Otherwise: z = first stage, second stage and a transposing
+    //         re-ordering pass at the end; y / x = first stage (+twiddle) and second stage with
+    //         the re-ordering folded into its stores (they only change row addresses).
+    //         3 passes when all axes fuse, 7 when none does.
     //   FFT unfused: per axis first stage, twiddle pass, second stage; one re-ordering pass of
     //         all three axes at the end (10 passes -> starts with in -> other).
     const bool zfused = !unfused && z_axis_fusable(p);
-    int npass = 3;
-    if (p->form == DFT3D_FFT) npass = unfused ? 10 : (zfused ? 5 : 7);
+    bool sfused[2] = {!unfused && strided_axis_fusable(p, 0), !unfused && strided_axis_fusable(p, 1)};
+    auto count_passes = [&]() {
+        if (p->form != DFT3D_FFT) return 3;
+        if (unfused) return 10;
+        return (zfused ? 1 : 3) + (sfused[0] ? 1 : 2) + (sfused[1] ? 1 : 2);
+    };
+    int npass = count_passes();
     if (clobber && (npass % 2 == 0)) {
-        set_error("exec: CLOBBER_INPUT cannot be combined with this pass structure");
-        return DFT3D_ERR_UNSUPPORTED;
+        // ping-ponging between in and out needs an odd pass count: split one fused strided axis
+        if (sfused[1]) sfused[1] = false;
+        else if (sfused[0]) sfused[0] = false;
+        npass = count_passes();
+        if (npass % 2 == 0) {
+            set_error("exec: CLOBBER_INPUT cannot be combined with this pass structure");
+            return DFT3D_ERR_UNSUPPORTED;
+        }
     }
     const float2* src = (const float2*)in;
     float2* dst = (npass % 2 == 1) ? (float2*)out : other;
@@ -682,6 +711,12 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
             if (axis == 2 && zfused) {
                 mark(0);
                 e = run_fused_z(p, src, dst, conj, axis_scale(p, axis, direction), st);
+                advance();
+                continue;
+            }
+            if (axis != 2 && sfused[axis]) {
+                mark(0);
+                e = run_fused_s(p, axis, src, dst, conj, axis_scale(p, axis, direction), st);
                 advance();
                 continue;
             }

@@ -208,10 +208,30 @@ def test_fft_fused_axis_kernel(dft, shape, split):
         gotb = to_host(p.fft_axis(2, xd, direction=dft.BACKWARD))
         assert report(f"fused z axis {A}x{B} backward", gotb, wantb) <= TOL
         with pytest.raises(dft.Dft3dError):
-            p.fft_axis(0, xd)
+            p.fft_axis(0, xd)       # axis length shape[0] has no fused kernel in these cases
 
 
-@pytest.mark.parametrize("shape,split", FFT_CASES + [((64, 64, 64), None), ((128, 16, 256), None)])
+@pytest.mark.parametrize("shape,split", [((256, 3, 16), None), ((2, 512, 48), None), ((1024, 1, 32), None),
+                                         ((3, 256, 160), None), ((512, 5, 16), (16, 1, 4))])
+def test_fft_fused_strided_axis_kernel(dft, shape, split):
+    """The single-kernel x / y pass equals first stage + twiddle + second stage + re-ordering."""
+    say(f"case fft fused strided axis {shape} split {split}")
+    x = wl.draw_complex(shape, "normal", 4600 + sum(shape))
+    xd = to_dev(x)
+    with dft.Plan(shape, dft.FFT, split=split) as p:
+        axis = 0 if shape[0] >= 256 else 1
+        A, B = p.split(axis)
+        want = ff.fft_axis(x, axis, A, B)
+        got = to_host(p.fft_axis(axis, xd))
+        assert report(f"fused axis {axis} {A}x{B}", got, want) <= TOL
+        assert rel_l2(got, np.fft.fft(x.astype(np.complex128), axis=axis)) <= TOL
+        wantb = ff.fft_axis(x, axis, A, B, sign=ff.BACKWARD) / shape[axis]
+        gotb = to_host(p.fft_axis(axis, xd, direction=dft.BACKWARD))
+        assert report(f"fused axis {axis} {A}x{B} backward", gotb, wantb) <= TOL
+
+
+@pytest.mark.parametrize("shape,split", FFT_CASES + [((64, 64, 64), None), ((128, 16, 256), None),
+                                                     ((256, 512, 256), None), ((256, 256, 24), None)])
 @pytest.mark.parametrize("flags", [0, 2])
 def test_fft_exec_matches_oracle(dft, shape, split, flags):
     say(f"case fft exec {shape} split {split} flags {flags}")
