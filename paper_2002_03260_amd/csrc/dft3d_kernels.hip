@@ -500,8 +500,8 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
 // LDS pitches: xs rows (l) are B+16 apart so the two l-rows a half-wave reads sit 32 banks apart;
 // zs and os have odd pitches (B+1, A+1) so lanes that walk rows hit distinct banks.
 // ------------------------------------------------------------------------------------------
-template <int A, int B, int R, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void k_fft_z(const float2* __restrict__ X, float2* __restrict__ Y,
+template <int A, int B, int R, int NW, int MINW>
+__global__ __launch_bounds__(NW * 64, MINW) void k_fft_z(const float2* __restrict__ X, float2* __restrict__ Y,
                                                    int64_t nrows, DeviceMatrix FA, DeviceMatrix FB,
                                                    const float2* __restrict__ Tw, float scale, int conj)
 {
@@ -696,8 +696,8 @@ __global__ __launch_bounds__(NW * 64, 2) void k_fft_z(const float2* __restrict__
 // flipped when l is odd) so the two rows a half-wave reads lie in different bank halves.
 // The next tile's global loads are issued before the MFMA work of the current one.
 // ------------------------------------------------------------------------------------------
-template <int A, int B, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void k_fft_s(const float2* __restrict__ X, float2* __restrict__ Y,
+template <int A, int B, int NW, int MINW>
+__global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restrict__ X, float2* __restrict__ Y,
                                                    int64_t O, int64_t I, DeviceMatrix FA, DeviceMatrix FB,
                                                    const float2* __restrict__ Tw, float scale, int conj)
 {
@@ -734,7 +734,18 @@ __global__ __launch_bounds__(NW * 64, 2) void k_fft_s(const float2* __restrict__
         fbi[n * FBP + k] = FB.im[(int64_t)n * FB.ld + k] * isign;
     }
 
-    auto phys = [](int pos) { return pos ^ ((pos / B) & 1); };
+    // Swizzled LDS row of position pos = hi*B + beta is hi*B + (beta ^ (hi & 1)).  Every access
+    // below is written as a per-lane base plus a compile-time offset so the addresses need no
+    // registers of their own:
+    //   stage-1 reads : hi = l = 4s + lq        -> bit = lq & 1, beta = wave + g*NW (parity = wave & 1)
+    //   stage-1 writes: hi = k_a = 16bm + 4lq+v -> bit = v & 1
+    //   stage-2 reads : hi = k_a = wave + g*NW  -> bit = wave & 1, beta = 4s + lq
+    static_assert(NW % 2 == 0, "an even number of waves keeps the parity of beta fixed per wave");
+    const int flip = (wave & 1) ? -1 : 1;                                   // beta ^ 1 == beta + flip
+    const int s1_rd = (lq * B + wave + ((lq & 1) ? flip : 0)) * TC + l16;   // + (g*NW + 4s*B)*TC
+    const int s1_wr_even = (4 * lq * B + wave) * TC + l16;                  // + ((16bm + v)*B + g*NW)*TC
+    const int s1_wr_odd = s1_wr_even + flip * TC;
+    const int s2_rd = (wave * B + (lq ^ (wave & 1))) * TC + l16;            // + (g*NW*B + 4s)*TC
 
     const int64_t ctiles = I / TC;                 // column tiles per o (I is a multiple of 16)
     const int64_t ntiles = O * ctiles;
@@ -753,15 +764,32 @@ __global__ __launch_bounds__(NW * 64, 2) void k_fft_s(const float2* __restrict__
     int64_t tile = linear_block_id();
     if (tile < ntiles) gload(tile);
     for (; tile < ntiles; tile += nwg) {
+        {
+            // rows lrow + j*RPP: the swizzle bit ((row / B) & 1) is a per-thread constant when RPP
+            // is a multiple of 2B, and known at compile time per j when RPP divides B
+            static_assert(RPP % B == 0 || B % RPP == 0, "rows per pass and B must nest");
+            const int base0 = lrow * TC + lcol;
+            const int rb = (RPP % B == 0) ? ((lrow / B) & 1) : 0;
 #pragma unroll
-        for (int j = 0; j < XL; ++j)
-            *reinterpret_cast<f32x4*>(&xs[phys(lrow + j * RPP) * TC + lcol]) = xreg[j];
+            for (int j = 0; j < XL; ++j) {
+                const int jb = (RPP % B == 0) ? ((j * (RPP / B)) & 1) : (((j * RPP) / B) & 1);
+                const int addr = (base0 ^ ((rb ^ jb) << 4)) + j * RPP * TC;
+                *reinterpret_cast<f32x4*>(&xs[addr]) = xreg[j];
+            }
+        }
         __syncthreads();
         if (tile + nwg < ntiles) gload(tile + nwg);
 
-        // stage 1, in place; two beta groups in flight per wave
-        constexpr int U1 = ((B / NW) % 2 == 0) ? 2 : 1;
+        // The twiddles do not change from tile to tile; keeping all of them in registers across
+        // the tile loop costs more than re-reading them from cache, so the table pointer is made
+        // opaque here and the loads stay inside the loop.
+        const float2* tw_tab = Tw;
+        asm volatile("" : "+s"(tw_tab));
+
+        // stage 1, in place; U1 beta groups in flight per wave
+        constexpr int U1 = ((B / NW) % 4 == 0) ? 4 : (((B / NW) % 2 == 0) ? 2 : 1);
         constexpr int BMA = A / 16;
+#pragma unroll
         for (int g = 0; g < B / NW; g += U1) {
             f32x4 cr[U1][BMA], ci[U1][BMA];
             float2 tw[U1][BMA][4];
@@ -774,7 +802,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_fft_s(const float2* __restrict__
                     cr[u][bm] = f32x4{0.f, 0.f, 0.f, 0.f};
                     ci[u][bm] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) tw[u][bm][v] = Tw[(bm * 16 + 4 * lq + v) * B + beta[u]];
+                    for (int v = 0; v < 4; ++v) tw[u][bm][v] = tw_tab[(bm * 16 + 4 * lq + v) * B + beta[u]];
                 }
             }
 #pragma unroll 4
@@ -789,7 +817,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_fft_s(const float2* __restrict__
                 }
 #pragma unroll
                 for (int u = 0; u < U1; ++u)
-                    x[u] = *reinterpret_cast<const f32x2*>(&xs[phys(l * B + beta[u]) * TC + l16]);
+                    x[u] = *reinterpret_cast<const f32x2*>(&xs[s1_rd + ((g + u) * NW + 4 * s * B) * TC]);
 #pragma unroll
                 for (int u = 0; u < U1; ++u)
 #pragma unroll
@@ -817,26 +845,33 @@ __global__ __launch_bounds__(NW * 64, 2) void k_fft_s(const float2* __restrict__
                         const float wx = tw[u][bm][v].x, wy = tw[u][bm][v].y * isign;
                         const float zr = cr[u][bm][v] * wx - ci[u][bm][v] * wy;
                         const float zi = cr[u][bm][v] * wy + ci[u][bm][v] * wx;
-                        *reinterpret_cast<f32x2*>(&xs[phys(ka * B + beta[u]) * TC + l16]) = f32x2{zr, zi};
+                        const int wr = ((v & 1) ? s1_wr_odd : s1_wr_even) + ((bm * 16 + v) * B + (g + u) * NW) * TC;
+                        *reinterpret_cast<f32x2*>(&xs[wr]) = f32x2{zr, zi};
                     }
         }
         __syncthreads();
 
-        // stage 2: one k_a group at a time per wave, all k_b blocks of it in flight
+        // stage 2: U2 k_a groups at a time per wave (they share the FB operands), all k_b blocks in flight
         constexpr int BMB = B / 16;
+        constexpr int U2 = ((A / NW) % 2 == 0 && BMB <= 2) ? 2 : 1;
         float2* dst = Y + tile_base(tile) + l16;
-        for (int g = 0; g < A / NW; ++g) {
-            const int ka = wave + g * NW;
-            f32x4 cr[BMB], ci[BMB];
 #pragma unroll
-            for (int bm = 0; bm < BMB; ++bm) {
-                cr[bm] = f32x4{0.f, 0.f, 0.f, 0.f};
-                ci[bm] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
+        for (int g = 0; g < A / NW; g += U2) {
+            f32x4 cr[U2][BMB], ci[U2][BMB];
+#pragma unroll
+            for (int u = 0; u < U2; ++u)
+#pragma unroll
+                for (int bm = 0; bm < BMB; ++bm) {
+                    cr[u][bm] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    ci[u][bm] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
 #pragma unroll 4
             for (int s = 0; s < B / 4; ++s) {
                 const int beta = 4 * s + lq;
-                const f32x2 z = *reinterpret_cast<const f32x2*>(&xs[phys(ka * B + beta) * TC + l16]);
+                f32x2 z[U2];
+#pragma unroll
+                for (int u = 0; u < U2; ++u)
+                    z[u] = *reinterpret_cast<const f32x2*>(&xs[s2_rd + ((g + u) * NW * B + 4 * s) * TC]);
                 float ar[BMB], ai[BMB];
 #pragma unroll
                 for (int bm = 0; bm < BMB; ++bm) {
@@ -844,22 +879,34 @@ __global__ __launch_bounds__(NW * 64, 2) void k_fft_s(const float2* __restrict__
                     ai[bm] = fbi[beta * FBP + bm * 16 + l16];
                 }
 #pragma unroll
-                for (int bm = 0; bm < BMB; ++bm) cr[bm] = mfma16(ar[bm], z.x, cr[bm]);
+                for (int u = 0; u < U2; ++u)
 #pragma unroll
-                for (int bm = 0; bm < BMB; ++bm) ci[bm] = mfma16(ar[bm], z.y, ci[bm]);
+                    for (int bm = 0; bm < BMB; ++bm) cr[u][bm] = mfma16(ar[bm], z[u].x, cr[u][bm]);
 #pragma unroll
-                for (int bm = 0; bm < BMB; ++bm) cr[bm] = mfma16(-ai[bm], z.y, cr[bm]);
+                for (int u = 0; u < U2; ++u)
 #pragma unroll
-                for (int bm = 0; bm < BMB; ++bm) ci[bm] = mfma16(ai[bm], z.x, ci[bm]);
+                    for (int bm = 0; bm < BMB; ++bm) ci[u][bm] = mfma16(ar[bm], z[u].y, ci[u][bm]);
+#pragma unroll
+                for (int u = 0; u < U2; ++u)
+#pragma unroll
+                    for (int bm = 0; bm < BMB; ++bm) cr[u][bm] = mfma16(-ai[bm], z[u].y, cr[u][bm]);
+#pragma unroll
+                for (int u = 0; u < U2; ++u)
+#pragma unroll
+                    for (int bm = 0; bm < BMB; ++bm) ci[u][bm] = mfma16(ai[bm], z[u].x, ci[u][bm]);
             }
 #pragma unroll
-            for (int bm = 0; bm < BMB; ++bm)
+            for (int u = 0; u < U2; ++u) {
+                const int ka = wave + (g + u) * NW;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int kb = bm * 16 + 4 * lq + v;
-                    *reinterpret_cast<f32x2*>(dst + (int64_t)(ka + A * kb) * I) =
-                        f32x2{cr[bm][v] * scale, ci[bm][v] * scale};
-                }
+                for (int bm = 0; bm < BMB; ++bm)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int kb = bm * 16 + 4 * lq + v;
+                        *reinterpret_cast<f32x2*>(dst + (int64_t)(ka + A * kb) * I) =
+                            f32x2{cr[u][bm][v] * scale, ci[u][bm][v] * scale};
+                    }
+            }
         }
         __syncthreads();
     }
@@ -1081,7 +1128,7 @@ __global__ __launch_bounds__(kThreads) void k_copy(const f32x4* __restrict__ in,
 }  // namespace
 
 namespace {
-template <int A, int B, int R, int NW, int WGS_PER_CU>
+template <int A, int B, int R, int NW, int MINW, int WGS_PER_CU>
 hipError_t launch_fft_z_inst(const float2* in, float2* out, int64_t nrows, const DeviceMatrix& FA,
                              const DeviceMatrix& FB, const float2* Tw, float scale, int conj,
                              hipStream_t stream)
@@ -1089,7 +1136,7 @@ hipError_t launch_fft_z_inst(const float2* in, float2* out, int64_t nrows, const
     const int64_t ntiles = cdiv(nrows, R);
     const int64_t resident = 256 * WGS_PER_CU;             // persistent workgroups
     const int64_t blocks = ntiles < resident ? ntiles : resident;
-    hipLaunchKernelGGL((k_fft_z<A, B, R, NW>), grid_for(blocks), dim3(NW * 64), 0, stream, in, out, nrows,
+    hipLaunchKernelGGL((k_fft_z<A, B, R, NW, MINW>), grid_for(blocks), dim3(NW * 64), 0, stream, in, out, nrows,
                        FA, FB, Tw, scale, conj);
     return hipGetLastError();
 }
@@ -1106,16 +1153,16 @@ hipError_t launch_fft_z(const float2* in, float2* out, int64_t nrows, int A, int
                         int conj, hipStream_t stream)
 {
     if (nrows <= 0) return hipSuccess;
-    if (A == 16 && B == 16) return launch_fft_z_inst<16, 16, 8, 4, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
-    if (A == 16 && B == 32) return launch_fft_z_inst<16, 32, 4, 4, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
-    if (A == 32 && B == 32) return launch_fft_z_inst<32, 32, 2, 4, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
-    if (A == 32 && B == 64) return launch_fft_z_inst<32, 64, 2, 8, 1>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
-    if (A == 64 && B == 64) return launch_fft_z_inst<64, 64, 1, 8, 1>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (A == 16 && B == 16) return launch_fft_z_inst<16, 16, 8, 4, 2, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (A == 16 && B == 32) return launch_fft_z_inst<16, 32, 4, 8, 4, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (A == 32 && B == 32) return launch_fft_z_inst<32, 32, 2, 4, 2, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (A == 32 && B == 64) return launch_fft_z_inst<32, 64, 2, 8, 2, 1>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (A == 64 && B == 64) return launch_fft_z_inst<64, 64, 1, 8, 2, 1>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     return hipErrorInvalidValue;
 }
 
 namespace {
-template <int A, int B, int NW, int WGS_PER_CU>
+template <int A, int B, int NW, int MINW, int WGS_PER_CU>
 hipError_t launch_fft_s_inst(const float2* in, float2* out, int64_t O, int64_t I, const DeviceMatrix& FA,
                              const DeviceMatrix& FB, const float2* Tw, float scale, int conj,
                              hipStream_t stream)
@@ -1123,7 +1170,7 @@ hipError_t launch_fft_s_inst(const float2* in, float2* out, int64_t O, int64_t I
     const int64_t ntiles = O * (I / 16);
     const int64_t resident = 256 * WGS_PER_CU;
     const int64_t blocks = ntiles < resident ? ntiles : resident;
-    hipLaunchKernelGGL((k_fft_s<A, B, NW>), grid_for(blocks), dim3(NW * 64), 0, stream, in, out, O, I, FA, FB,
+    hipLaunchKernelGGL((k_fft_s<A, B, NW, MINW>), grid_for(blocks), dim3(NW * 64), 0, stream, in, out, O, I, FA, FB,
                        Tw, scale, conj);
     return hipGetLastError();
 }
@@ -1140,9 +1187,9 @@ hipError_t launch_fft_s(const float2* in, float2* out, int64_t O, int64_t I, int
                         int conj, hipStream_t stream)
 {
     if (O <= 0 || I <= 0) return hipSuccess;
-    if (A == 16 && B == 16) return launch_fft_s_inst<16, 16, 4, 2>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
-    if (A == 16 && B == 32) return launch_fft_s_inst<16, 32, 4, 2>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
-    if (A == 32 && B == 32) return launch_fft_s_inst<32, 32, 8, 1>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
+    if (A == 16 && B == 16) return launch_fft_s_inst<16, 16, 4, 2, 2>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
+    if (A == 16 && B == 32) return launch_fft_s_inst<16, 32, 4, 2, 2>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
+    if (A == 32 && B == 32) return launch_fft_s_inst<32, 32, 8, 2, 1>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
     return hipErrorInvalidValue;
 }
 
