@@ -28,7 +28,10 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    "cfg2": 2.80e8,      # strided contraction: 2 * FETCH_SIZE + WRITE_SIZE (calibrated), bytes per launch
+    "cfg3": 2.148e9,     # fused axis kernel
+}
 
 
 def effective_flop(E: int) -> float:
@@ -91,7 +94,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="cfg2",
-                    help="cfg1..cfg4, cfg5-kdft or cfg5-fft (default cfg2 = KDFT 256^3)")
+                    help="cfg1..cfg4, cfg5-kdft, cfg5-fft, or copy (default cfg2 = KDFT 256^3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unfused", action="store_true",
                     help="FFT: run the twiddle and the re-ordering as separate memory-bound kernels")
@@ -114,6 +117,35 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     name = args.workload
+    if name == "copy":
+        # bandwidth reference / counter calibration: plain copy of a 1 GiB tensor (the size of one
+        # 512^3 complex64 tensor), traffic exactly 2 GiB per launch
+        steps = args.steps if args.steps is not None else 20
+        warmup = args.warmup if args.warmup is not None else 3
+        n = (1 << 30) // 8
+        a = torch.empty(n, dtype=torch.complex64, device="cuda").normal_()
+        b = torch.empty_like(a)
+        for _ in range(warmup):
+            dft.device_copy(a, b, 1)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        t0 = time.perf_counter()
+        ev[0].record()
+        for _ in range(steps):
+            dft.device_copy(a, b, 1)
+        ev[1].record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms = ev[0].elapsed_time(ev[1]) / steps
+        gbs = 2 * n * 8 / (ms * 1e-3) / 1e9
+        print(json.dumps({"metric": "device_copy_bandwidth", "value": gbs, "unit": "GB/s", "n_gpus": 1,
+                          "steps": steps, "warmup": warmup, "ms_per_step": (t1 - t0) * 1e3 / steps,
+                          "higher_is_better": True, "dtype": "u8", "data": "synthetic",
+                          "config": {"workload": "copy_1GiB"},
+                          "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                       "frac": gbs / PEAK_HBM_GBS, "avg_launch_ms": ms,
+                                       "bytes_per_launch": 2.0 * n * 8}}), flush=True)
+        return 0
     form_override = None
     if name.startswith("cfg5"):
         form_override = dft.FFT if name.endswith("fft") else dft.KDFT
