@@ -20,6 +20,7 @@ FORWARD = -1
 BACKWARD = 1
 FLAG_CLOBBER_INPUT = 1
 FLAG_UNFUSED = 2
+FLAG_3M = 4
 
 EXPORTS = [
     "dft3d_plan_create", "dft3d_plan_create_ex", "dft3d_plan_destroy",

@@ -44,6 +44,7 @@ struct ContractArgs {
     int64_t twInner;
     float scale;
     int conj;
+    int three_m;   // use the three-real-product complex scheme where a kernel for it exists
 };
 
 hipError_t launch_contract(const ContractArgs& a, hipStream_t stream);

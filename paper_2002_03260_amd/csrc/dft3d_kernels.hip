@@ -96,7 +96,7 @@ __device__ __forceinline__ void store_cvec(float2* dst, f32x4 v)
 // Waves tile it as (TM/WM) x (TN/WN); each wave owns WM x WN complex outputs.
 // In the masked version the columns of ALL o are flattened into one index (col = o*I + i), so a
 // narrow inner extent (I < TN) still fills the tile; every thread decodes its own (o, i).
-template <int TM, int TN, int WM, int WN, int KC, int NB, int EV, bool MASKED, int MINW>
+template <int TM, int TN, int WM, int WN, int KC, int NB, int EV, bool MASKED, int MINW, int SCHEME>
 __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, int tilesK,
                                                                int64_t tilesI, int64_t total)
 {
@@ -199,13 +199,18 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
             *reinterpret_cast<xvec*>(&Xs[buf][xr + j * XRPP][xc]) = xreg[j];
     };
 
-    f32x4 accr[BM][BN], acci[BM][BN];
+    // SCHEME 4: accr / acci hold Re / Im.  SCHEME 3 (three real products per complex one):
+    // accr = sum Vr*Xr, acci = sum Vi*Xi, acc3 = sum (Vr+Vi)*(Xr+Xi); Re = accr - acci,
+    // Im = acc3 - accr - acci.
+    constexpr int B3 = (SCHEME == 3) ? BN : 1, M3 = (SCHEME == 3) ? BM : 1;
+    f32x4 accr[BM][BN], acci[BM][BN], acc3[M3][B3];
 #pragma unroll
     for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
         for (int bn = 0; bn < BN; ++bn) {
             accr[bm][bn] = f32x4{0.f, 0.f, 0.f, 0.f};
             acci[bm][bn] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (SCHEME == 3) acc3[bm % M3][bn % B3] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
 
     const int nchunks = (N + KC - 1) / KC;
@@ -235,29 +240,52 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
         for (int s = 0; s < KS; ++s) {
             const int cur = s & 1;
             if (s + 1 < KS) read_operands(cur ^ 1, s + 1);
-            float an[BM];
+            if (SCHEME == 3) {
+                float as[BM], bs[BN];
 #pragma unroll
-            for (int bm = 0; bm < BM; ++bm) an[bm] = -ai[cur][bm];
+                for (int bm = 0; bm < BM; ++bm) as[bm] = ar[cur][bm] + ai[cur][bm];
 #pragma unroll
-            for (int bm = 0; bm < BM; ++bm)
+                for (int bn = 0; bn < BN; ++bn) bs[bn] = bx[cur][bn].x + bx[cur][bn].y;
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn)
-                    accr[bm][bn] = mfma16(ar[cur][bm], bx[cur][bn].x, accr[bm][bn]);
+                for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-            for (int bm = 0; bm < BM; ++bm)
+                    for (int bn = 0; bn < BN; ++bn)
+                        accr[bm][bn] = mfma16(ar[cur][bm], bx[cur][bn].x, accr[bm][bn]);
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn)
-                    acci[bm][bn] = mfma16(ar[cur][bm], bx[cur][bn].y, acci[bm][bn]);
+                for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-            for (int bm = 0; bm < BM; ++bm)
+                    for (int bn = 0; bn < BN; ++bn)
+                        acci[bm][bn] = mfma16(ai[cur][bm], bx[cur][bn].y, acci[bm][bn]);
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn)
-                    accr[bm][bn] = mfma16(an[bm], bx[cur][bn].y, accr[bm][bn]);
+                for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-            for (int bm = 0; bm < BM; ++bm)
+                    for (int bn = 0; bn < BN; ++bn)
+                        acc3[bm % M3][bn % B3] = mfma16(as[bm], bs[bn], acc3[bm % M3][bn % B3]);
+            } else {
+                float an[BM];
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn)
-                    acci[bm][bn] = mfma16(ai[cur][bm], bx[cur][bn].x, acci[bm][bn]);
+                for (int bm = 0; bm < BM; ++bm) an[bm] = -ai[cur][bm];
+#pragma unroll
+                for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+                    for (int bn = 0; bn < BN; ++bn)
+                        accr[bm][bn] = mfma16(ar[cur][bm], bx[cur][bn].x, accr[bm][bn]);
+#pragma unroll
+                for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+                    for (int bn = 0; bn < BN; ++bn)
+                        acci[bm][bn] = mfma16(ar[cur][bm], bx[cur][bn].y, acci[bm][bn]);
+#pragma unroll
+                for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+                    for (int bn = 0; bn < BN; ++bn)
+                        accr[bm][bn] = mfma16(an[bm], bx[cur][bn].y, accr[bm][bn]);
+#pragma unroll
+                for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+                    for (int bn = 0; bn < BN; ++bn)
+                        acci[bm][bn] = mfma16(ai[cur][bm], bx[cur][bn].x, acci[bm][bn]);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);  // keep the LDS refill (and its wait) behind the MFMAs
         if (NB == 1) __syncthreads();       // single buffer: everyone must be done reading it
@@ -283,8 +311,14 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
             for (int v = 0; v < 4; ++v) {
                 const int k = k0 + wm0 + bm * 16 + 4 * lq + v;
                 if (MASKED && k >= K) continue;
-                float yr = accr[bm][bn][v] * a.scale;
-                float yi = acci[bm][bn][v] * a.scale;
+                float yr, yi;
+                if (SCHEME == 3) {
+                    yr = (accr[bm][bn][v] - acci[bm][bn][v]) * a.scale;
+                    yi = (acc3[bm % M3][bn % B3][v] - accr[bm][bn][v] - acci[bm][bn][v]) * a.scale;
+                } else {
+                    yr = accr[bm][bn][v] * a.scale;
+                    yi = acci[bm][bn][v] * a.scale;
+                }
                 if (a.Tw) {
                     float2 w = a.Tw[(int64_t)k * a.twB + beta];
                     if (a.conj) w.y = -w.y;
@@ -301,7 +335,7 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
 
 // Contiguous-mode contraction (I == 1): out[o, k] = sum_n in[o, n] M[k, n].
 // Workgroup tile: TO rows (o) x TK columns (k).  The data tile is the MFMA A operand.
-template <int TO, int TK, int WO, int WK, int KC, int EV, bool MASKED, int MINW>
+template <int TO, int TK, int WO, int WK, int KC, int EV, bool MASKED, int MINW, int SCHEME>
 __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, int tilesK,
                                                                int64_t tilesO, int64_t total)
 {
@@ -392,13 +426,18 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
         }
     };
 
-    f32x4 accr[BM][BN], acci[BM][BN];
+    // SCHEME 4: accr / acci hold Re / Im.  SCHEME 3 (three real products per complex one):
+    // accr = sum Vr*Xr, acci = sum Vi*Xi, acc3 = sum (Vr+Vi)*(Xr+Xi); Re = accr - acci,
+    // Im = acc3 - accr - acci.
+    constexpr int B3 = (SCHEME == 3) ? BN : 1, M3 = (SCHEME == 3) ? BM : 1;
+    f32x4 accr[BM][BN], acci[BM][BN], acc3[M3][B3];
 #pragma unroll
     for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
         for (int bn = 0; bn < BN; ++bn) {
             accr[bm][bn] = f32x4{0.f, 0.f, 0.f, 0.f};
             acci[bm][bn] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (SCHEME == 3) acc3[bm % M3][bn % B3] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
 
     const int nchunks = (N + KC - 1) / KC;
@@ -428,29 +467,52 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
         for (int s = 0; s < KS; ++s) {
             const int cur = s & 1;
             if (s + 1 < KS) read_operands(cur ^ 1, s + 1);
-            float bneg[BN];
+            if (SCHEME == 3) {
+                float as[BM], bs[BN];
 #pragma unroll
-            for (int bn = 0; bn < BN; ++bn) bneg[bn] = -bi[cur][bn];
+                for (int bm = 0; bm < BM; ++bm) as[bm] = ax[cur][bm].x + ax[cur][bm].y;
 #pragma unroll
-            for (int bm = 0; bm < BM; ++bm)
+                for (int bn = 0; bn < BN; ++bn) bs[bn] = br[cur][bn] + bi[cur][bn];
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn)
-                    accr[bm][bn] = mfma16(ax[cur][bm].x, br[cur][bn], accr[bm][bn]);
+                for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-            for (int bm = 0; bm < BM; ++bm)
+                    for (int bn = 0; bn < BN; ++bn)
+                        accr[bm][bn] = mfma16(ax[cur][bm].x, br[cur][bn], accr[bm][bn]);
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn)
-                    acci[bm][bn] = mfma16(ax[cur][bm].x, bi[cur][bn], acci[bm][bn]);
+                for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-            for (int bm = 0; bm < BM; ++bm)
+                    for (int bn = 0; bn < BN; ++bn)
+                        acci[bm][bn] = mfma16(ax[cur][bm].y, bi[cur][bn], acci[bm][bn]);
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn)
-                    accr[bm][bn] = mfma16(ax[cur][bm].y, bneg[bn], accr[bm][bn]);
+                for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
-            for (int bm = 0; bm < BM; ++bm)
+                    for (int bn = 0; bn < BN; ++bn)
+                        acc3[bm % M3][bn % B3] = mfma16(as[bm], bs[bn], acc3[bm % M3][bn % B3]);
+            } else {
+                float bneg[BN];
 #pragma unroll
-                for (int bn = 0; bn < BN; ++bn)
-                    acci[bm][bn] = mfma16(ax[cur][bm].y, br[cur][bn], acci[bm][bn]);
+                for (int bn = 0; bn < BN; ++bn) bneg[bn] = -bi[cur][bn];
+#pragma unroll
+                for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+                    for (int bn = 0; bn < BN; ++bn)
+                        accr[bm][bn] = mfma16(ax[cur][bm].x, br[cur][bn], accr[bm][bn]);
+#pragma unroll
+                for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+                    for (int bn = 0; bn < BN; ++bn)
+                        acci[bm][bn] = mfma16(ax[cur][bm].x, bi[cur][bn], acci[bm][bn]);
+#pragma unroll
+                for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+                    for (int bn = 0; bn < BN; ++bn)
+                        accr[bm][bn] = mfma16(ax[cur][bm].y, bneg[bn], accr[bm][bn]);
+#pragma unroll
+                for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+                    for (int bn = 0; bn < BN; ++bn)
+                        acci[bm][bn] = mfma16(ax[cur][bm].y, br[cur][bn], acci[bm][bn]);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);  // keep the LDS refill (and its wait) behind the MFMAs
         if (more) lstore(buf ^ 1);
@@ -468,8 +530,14 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
             for (int v = 0; v < 4; ++v) {
                 const int64_t orow = o0 + wo0 + bm * 16 + 4 * lq + v;
                 if (MASKED && orow >= O) continue;
-                float yr = accr[bm][bn][v] * a.scale;
-                float yi = acci[bm][bn][v] * a.scale;
+                float yr, yi;
+                if (SCHEME == 3) {
+                    yr = (accr[bm][bn][v] - acci[bm][bn][v]) * a.scale;
+                    yi = (acc3[bm % M3][bn % B3][v] - accr[bm][bn][v] - acci[bm][bn][v]) * a.scale;
+                } else {
+                    yr = accr[bm][bn][v] * a.scale;
+                    yi = acci[bm][bn][v] * a.scale;
+                }
                 if (a.Tw) {   // I == 1 means beta == 0
                     float2 w = a.Tw[(int64_t)k * a.twB];
                     if (a.conj) w.y = -w.y;
@@ -1053,7 +1121,7 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // Picks a tile configuration for one contraction and launches it.  S<...>/C<...> name the
 // template arguments (tile, wave tile, chunk); each is instantiated in a fast (whole tiles,
 // 16-byte loads) and a masked (any shape) version.
-template <int TM, int TN, int WM, int WN, int KC, int NB>
+template <int TM, int TN, int WM, int WN, int KC, int NB, int SCHEME = 4>
 hipError_t launch_s(const ContractArgs& a, hipStream_t stream)
 {
     const int K = a.M.K, N = a.M.N;
@@ -1062,14 +1130,14 @@ hipError_t launch_s(const ContractArgs& a, hipStream_t stream)
     if (whole) {
         const int64_t ti = a.I / TN;
         const int64_t total = (int64_t)tk * ti * a.O;
-        return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, NB, 2, false, 2>, a, tk, ti, total, stream);
+        return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, NB, 2, false, 2, SCHEME>, a, tk, ti, total, stream);
     }
     // masked: column tiles run over the flattened (o, i) index
     const int64_t tc = cdiv(a.O * a.I, TN);
-    return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, NB, 1, true, 2>, a, tk, tc, (int64_t)tk * tc, stream);
+    return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, NB, 1, true, 2, SCHEME>, a, tk, tc, (int64_t)tk * tc, stream);
 }
 
-template <int TO, int TK, int WO, int WK, int KC>
+template <int TO, int TK, int WO, int WK, int KC, int SCHEME = 4>
 hipError_t launch_c(const ContractArgs& a, hipStream_t stream)
 {
     const int K = a.M.K, N = a.M.N;
@@ -1078,8 +1146,8 @@ hipError_t launch_c(const ContractArgs& a, hipStream_t stream)
     const int64_t total = (int64_t)tk * to;
     const bool whole = (K % TK == 0) && (N % KC == 0) && (a.O % TO == 0);
     if (whole)
-        return launch_tiles(k_contract_c<TO, TK, WO, WK, KC, 2, false, 2>, a, tk, to, total, stream);
-    return launch_tiles(k_contract_c<TO, TK, WO, WK, KC, 1, true, 2>, a, tk, to, total, stream);
+        return launch_tiles(k_contract_c<TO, TK, WO, WK, KC, 2, false, 2, SCHEME>, a, tk, to, total, stream);
+    return launch_tiles(k_contract_c<TO, TK, WO, WK, KC, 1, true, 2, SCHEME>, a, tk, to, total, stream);
 }
 
 }  // namespace
@@ -1093,12 +1161,14 @@ hipError_t launch_contract(const ContractArgs& a, hipStream_t stream)
         if (N <= 32 && K <= 32) return launch_c<128, 32, 32, 32, 16>(a, stream);
         if (N <= 64 && K <= 64) return launch_c<128, 64, 32, 64, 16>(a, stream);
         if (cdiv(K, 128) * cdiv(a.O, 128) < kFillTiles) return launch_c<64, 64, 32, 32, 16>(a, stream);
+        if (a.three_m) return launch_c<128, 64, 64, 32, 16, 3>(a, stream);
         return launch_c<128, 128, 64, 64, 16>(a, stream);
     }
     if (K <= 16 && N <= 16) return launch_s<16, 256, 16, 64, 16, 1>(a, stream);
     if (K <= 32 && N <= 32) return launch_s<32, 128, 32, 32, 32, 1>(a, stream);
     if (K <= 64 && N <= 64) return launch_s<64, 128, 64, 32, 16, 2>(a, stream);
     if (cdiv(K, 128) * cdiv(a.I, 128) * a.O < kFillTiles) return launch_s<64, 64, 32, 32, 16, 2>(a, stream);
+    if (a.three_m) return launch_s<128, 64, 64, 32, 16, 2, 3>(a, stream);
     return launch_s<128, 128, 64, 64, 16, 2>(a, stream);
 }
 

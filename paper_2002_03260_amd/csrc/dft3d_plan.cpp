@@ -173,6 +173,7 @@ hipError_t run_mode(const dft3d_plan_s* p, int axis, const float2* in, float2* o
     a.twInner = 1;
     a.scale = scale;
     a.conj = conj;
+    a.three_m = (p->flags & DFT3D_FLAG_3M) ? 1 : 0;
     return launch_contract(a, st);
 }
 
@@ -324,7 +325,7 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
         set_error("plan_create: unknown formulation %d", (int)f);
         return DFT3D_ERR_INVALID_ARG;
     }
-    if (flags & ~(DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_UNFUSED)) {
+    if (flags & ~(DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_UNFUSED | DFT3D_FLAG_3M)) {
         set_error("plan_create: unknown flag bits 0x%x", flags);
         return DFT3D_ERR_INVALID_ARG;
     }

@@ -114,6 +114,23 @@ def test_kdft_backward_and_roundtrip(dft):
         assert report("kdft roundtrip", back, x.astype(np.complex128)) <= TOL
 
 
+@pytest.mark.parametrize("shape", [(256, 256, 256), (300, 260, 270), (128, 512, 130)])
+def test_kdft_three_product_scheme(dft, shape):
+    """DFT3D_FLAG_3M: three real products per complex product; same tolerance as the default."""
+    say(f"case kdft 3M {shape}")
+    x = wl.draw_complex(shape, "normal", 2500 + sum(shape))
+    want = orc.dft3d(x)
+    with dft.Plan(shape, dft.KDFT, flags=dft.FLAG_3M) as p:
+        xd = to_dev(x)
+        got = to_host(p.exec(xd))
+        assert report(f"kdft 3M {shape}", got, want) <= TOL
+        gotb = to_host(p.exec(xd, direction=dft.BACKWARD))
+        assert report(f"kdft 3M backward {shape}", gotb, orc.dft3d(x, sign=orc.BACKWARD)) <= TOL
+    with dft.Plan(shape, dft.KDFT) as p:
+        ref4 = to_host(p.exec(to_dev(x)))
+        report(f"kdft 4M {shape} (for comparison)", ref4, want)
+
+
 def test_kdft_clobber_input(dft):
     shape = (16, 24, 40)
     x = wl.draw_complex(shape, "normal", 78)
