@@ -62,10 +62,10 @@ __device__ __forceinline__ int64_t out_offset(const ContractArgs& a, int64_t o)
 // ------------------------------------------------------------------------------------------
 // Mode contraction on fp32 MFMA.  Two kernels share one software pipeline:
 //
-//   prologue : chunk 0 global -> registers -> LDS[0]; barrier
-//   chunk c  : request chunk c+1 from global memory into registers; MFMAs on LDS[c&1]
-//              (operands of k-step s+1 are read from LDS while the MFMAs of k-step s issue);
-//              then registers -> LDS[(c+1)&1]; barrier
+//   prologue : chunk 0 global -> registers -> LDS[0]; chunk 1 global -> registers; barrier
+//   chunk c  : registers (chunk c+1) -> LDS[(c+1)&1]; request chunk c+2 from global memory into
+//              the same registers; MFMAs on LDS[c&1] (operands of k-step s+1 are read from LDS
+//              while the MFMAs of k-step s issue); barrier
 //
 // so a global load always has one full chunk of MFMA work to land, and there is one barrier
 // per chunk.  MASKED = false is the fast path for shapes that are whole multiples of the tile:
@@ -216,12 +216,20 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     const int nchunks = (N + KC - 1) / KC;
     gload(0);
     lstore(0);
+    if (NB == 2 && nchunks > 1) gload(KC);
     __syncthreads();
 
     for (int c = 0; c < nchunks; ++c) {
         const int buf = (NB == 2) ? (c & 1) : 0;
         const bool more = (c + 1) < nchunks;
-        if (more) gload((c + 1) * KC);      // lands while this chunk's MFMAs run
+        if (NB == 2) {
+            // chunk c+1 was requested one whole chunk ago: move it to the other LDS buffer now
+            // (nobody reads that buffer any more) and request chunk c+2; both overlap the MFMAs
+            if (more) lstore(buf ^ 1);
+            if (c + 2 < nchunks) gload((c + 2) * KC);
+        } else if (more) {
+            gload((c + 1) * KC);
+        }
         float ar[2][BM], ai[2][BM];
         f32x2 bx[2][BN];
         auto read_operands = [&](int slot, int s) {
@@ -287,9 +295,11 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
                         acci[bm][bn] = mfma16(ai[cur][bm], bx[cur][bn].x, acci[bm][bn]);
             }
         }
-        __builtin_amdgcn_sched_barrier(0);  // keep the LDS refill (and its wait) behind the MFMAs
-        if (NB == 1) __syncthreads();       // single buffer: everyone must be done reading it
-        if (more) lstore((NB == 2) ? (buf ^ 1) : 0);
+        if (NB == 1) {
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();                // single buffer: everyone must be done reading it
+            if (more) lstore(0);
+        }
         __syncthreads();
     }
 
@@ -443,12 +453,14 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
     const int nchunks = (N + KC - 1) / KC;
     gload(0);
     lstore(0);
+    if (nchunks > 1) gload(KC);
     __syncthreads();
 
     for (int c = 0; c < nchunks; ++c) {
         const int buf = c & 1;
         const bool more = (c + 1) < nchunks;
-        if (more) gload((c + 1) * KC);      // lands while this chunk's MFMAs run
+        if (more) lstore(buf ^ 1);          // chunk c+1, requested one whole chunk ago
+        if (c + 2 < nchunks) gload((c + 2) * KC);
         f32x2 ax[2][BM];
         float br[2][BN], bi[2][BN];
         auto read_operands = [&](int slot, int s) {
@@ -514,8 +526,6 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
                         acci[bm][bn] = mfma16(ax[cur][bm].y, br[cur][bn], acci[bm][bn]);
             }
         }
-        __builtin_amdgcn_sched_barrier(0);  // keep the LDS refill (and its wait) behind the MFMAs
-        if (more) lstore(buf ^ 1);
         __syncthreads();
     }
 
@@ -1168,7 +1178,7 @@ hipError_t launch_contract(const ContractArgs& a, hipStream_t stream)
     if (K <= 32 && N <= 32) return launch_s<32, 128, 32, 32, 32, 1>(a, stream);
     if (K <= 64 && N <= 64) return launch_s<64, 128, 64, 32, 16, 2>(a, stream);
     if (cdiv(K, 128) * cdiv(a.I, 128) * a.O < kFillTiles) return launch_s<64, 64, 32, 32, 16, 2>(a, stream);
-    if (a.three_m) return launch_s<128, 64, 64, 32, 16, 2, 3>(a, stream);
+    if (a.three_m) return launch_s<64, 128, 32, 64, 16, 2, 3>(a, stream);
     return launch_s<128, 128, 64, 64, 16, 2>(a, stream);
 }
 
