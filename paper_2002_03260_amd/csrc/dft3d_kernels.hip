@@ -1131,7 +1131,7 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // Picks a tile configuration for one contraction and launches it.  S<...>/C<...> name the
 // template arguments (tile, wave tile, chunk); each is instantiated in a fast (whole tiles,
 // 16-byte loads) and a masked (any shape) version.
-template <int TM, int TN, int WM, int WN, int KC, int NB, int SCHEME = 4>
+template <int TM, int TN, int WM, int WN, int KC, int NB, int SCHEME = 4, int MINW = 2>
 hipError_t launch_s(const ContractArgs& a, hipStream_t stream)
 {
     const int K = a.M.K, N = a.M.N;
@@ -1140,11 +1140,11 @@ hipError_t launch_s(const ContractArgs& a, hipStream_t stream)
     if (whole) {
         const int64_t ti = a.I / TN;
         const int64_t total = (int64_t)tk * ti * a.O;
-        return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, NB, 2, false, 2, SCHEME>, a, tk, ti, total, stream);
+        return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, NB, 2, false, MINW, SCHEME>, a, tk, ti, total, stream);
     }
     // masked: column tiles run over the flattened (o, i) index
     const int64_t tc = cdiv(a.O * a.I, TN);
-    return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, NB, 1, true, 2, SCHEME>, a, tk, tc, (int64_t)tk * tc, stream);
+    return launch_tiles(k_contract_s<TM, TN, WM, WN, KC, NB, 1, true, MINW, SCHEME>, a, tk, tc, (int64_t)tk * tc, stream);
 }
 
 template <int TO, int TK, int WO, int WK, int KC, int SCHEME = 4>
