@@ -83,6 +83,27 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
                                   dft3d_formulation f, const double* cx, const double* cy,
                                   const double* cz, const int64_t* split, uint32_t flags);
 
+/*
+ * Plan for the general form of Eq. 1 - Eq. 3: arbitrary evaluation points on the z-plane.
+ * Axis j of the output has k_j entries, X(z_j0..z_j,k-1), with the K x N Vandermonde matrix
+ * V_j[r, n] = z_jr^{-n} (Eq. 3); the transform is V_x (x) V_y (x) V_z applied to the nx x ny x nz
+ * input (Eq. 11), giving a kx x ky x kz output.  KDFT only, FORWARD only (the inverse is a
+ * linear solve, Section III-A).
+ *   zx,zy,zz  HOST arrays of 2*k? doubles, (re, im) of each point; points must be non-zero.  NULL =
+ *             that axis uses the N-th roots of unity (then k? must equal n?).
+ *   flags     0 or DFT3D_FLAG_3M
+ * exec needs a workspace of dft3d_plan_workspace_bytes = 8*(nx*ny*kz + nx*ky*kz) bytes (the two
+ * intermediates).  dft3d_mode_contract on such a plan reads a tensor whose axes after `axis`
+ * already have their output length and writes one whose `axis` has length k (order z, y, x).
+ * Errors: INVALID_ARG (sizes, a zero / non-finite point, an entry that overflows fp32).
+ */
+dft3d_status dft3d_plan_create_points(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
+                                      int64_t kx, int64_t ky, int64_t kz, const double* zx,
+                                      const double* zy, const double* zz, uint32_t flags);
+
+/* Output lengths of a plan (equal to the input lengths except for evaluation-point plans). */
+dft3d_status dft3d_plan_get_output_shape(dft3d_plan plan, int64_t* kx, int64_t* ky, int64_t* kz);
+
 /* Frees the plan and the device memory it owns (not the workspace).  NULL is accepted. */
 dft3d_status dft3d_plan_destroy(dft3d_plan plan);
 
@@ -173,6 +194,10 @@ dft3d_status dft3d_device_copy(const void* in, void* out, size_t bytes, int vari
  * coords: NULL (uniform) or HOST array of n doubles.  HOST output arrays of n*n floats. */
 dft3d_status dft3d_generate_matrix(int64_t n, const double* coords, int direction, float* re,
                                    float* im);
+
+/* Writes the k x n Vandermonde matrix V[r*n + j] = z_r^{-j} (Eq. 3) for k points given as HOST
+ * (re, im) pairs, as the library rounds it, to HOST arrays of k*n floats. */
+dft3d_status dft3d_generate_points_matrix(int64_t k, int64_t n, const double* z, float* re, float* im);
 
 /* Writes the A x B twiddle table T[k_a*B + beta] = exp(-+2 pi i beta k_a / (A*B)) to HOST arrays. */
 dft3d_status dft3d_generate_twiddle(int64_t A, int64_t B, int direction, float* re, float* im);

@@ -76,6 +76,30 @@ void oracle_dft_matrix(int64_t K, int64_t N, const int64_t* ks, const double* co
 }
 
 /*
+ * Vandermonde matrix of Eq. 3 for K arbitrary non-zero points z_r of the z-plane:
+ *   M[r, n] = z_r^{-n},  n = 0..N-1,
+ * built literally as the powers 1, w, w^2, ... of w = 1/z_r by repeated complex multiplication
+ * (error grows like n * 1e-16, far below fp32 resolution for the lengths used here).
+ * z: K (re, im) pairs.  M: K x N, row-major, interleaved doubles.
+ */
+void oracle_points_matrix(int64_t K, int64_t N, const double* z, double* M)
+{
+    for (int64_t r = 0; r < K; ++r) {
+        double zr = z[2 * r], zi = z[2 * r + 1];
+        double d = zr * zr + zi * zi;
+        double wr = zr / d, wi = -zi / d;           /* w = 1 / z */
+        double pr = 1.0, pi = 0.0;
+        for (int64_t n = 0; n < N; ++n) {
+            M[2 * (r * N + n)] = pr;
+            M[2 * (r * N + n) + 1] = pi;
+            double tr = pr * wr - pi * wi;
+            pi = pr * wi + pi * wr;
+            pr = tr;
+        }
+    }
+}
+
+/*
  * One mode product (Eq. 2 applied along one index of a tensor, the building block of Eq. 5
  * and Eq. 11):   out[o, k, i] = sum_n M[k, n] * in[o, n, i]
  * in  is O x N x I, out is O x K x I, M is K x N; complex, row-major, interleaved; M and out

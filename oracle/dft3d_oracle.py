@@ -6,6 +6,8 @@ this module.  It shares nothing with the HIP library and does not import it.
 The functions mirror the C file:
 
 * :func:`dft_matrix`       -- rows of the per-axis transform matrix (paper Eq. 3, Eq. 12)
+* :func:`points_matrix`    -- Vandermonde matrix of arbitrary evaluation points (paper Eq. 3 as written)
+* :func:`dft3d_points`     -- the transform at arbitrary per-axis evaluation points (Eq. 10 in general form)
 * :func:`mode_contract`    -- one mode product (paper Eq. 2 applied along a tensor index)
 * :func:`dft3d`            -- the 3-D transform one axis at a time (paper Eq. 10 / Eq. 11)
 * :func:`dft3d_brute`      -- the literal triple sum of Eq. 10 (tiny inputs; pins ``dft3d``)
@@ -49,6 +51,8 @@ def _load():
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_dft_matrix.argtypes = [i64, i64, ctypes.c_void_p, dp, ip, dp]
         lib.oracle_dft_matrix.restype = None
+        lib.oracle_points_matrix.argtypes = [i64, i64, dp, dp]
+        lib.oracle_points_matrix.restype = None
         lib.oracle_mode_contract.argtypes = [i64, i64, i64, i64, dp, dp, dp]
         lib.oracle_mode_contract.restype = None
         lib.oracle_mode_contract_f32.argtypes = [i64, i64, i64, i64, dp, fp, dp]
@@ -89,6 +93,30 @@ def dft_matrix(n: int, coords=None, sign: int = FORWARD, ks=None) -> np.ndarray:
     M = np.empty((K, n), dtype=np.complex128)
     _load().oracle_dft_matrix(K, n, _ptr(ksa), _ptr(c), int(sign), _ptr(M))
     return M
+
+
+def points_matrix(z, n: int) -> np.ndarray:
+    """K x n Vandermonde matrix ``M[r, j] = z_r**(-j)`` of paper Eq. 3 for arbitrary points ``z``."""
+    z = np.ascontiguousarray(z, dtype=np.complex128)
+    if z.ndim != 1 or np.any(z == 0):
+        raise ValueError("points must be a 1-D array of non-zero complex numbers")
+    M = np.empty((z.shape[0], n), dtype=np.complex128)
+    _load().oracle_points_matrix(z.shape[0], n, _ptr(z), _ptr(M))
+    return M
+
+
+def dft3d_points(x: np.ndarray, points) -> np.ndarray:
+    """General form of Eq. 10: X(z1_a, z2_b, z3_c) for per-axis evaluation points.
+
+    ``points[j]`` is a 1-D complex array of points for axis j, or None for the N-th roots of
+    unity.  Output shape (len(points[0]), len(points[1]), len(points[2]))."""
+    x = _check_input(x)
+    y = x
+    for axis in (2, 1, 0):
+        n = x.shape[axis]
+        M = dft_matrix(n) if points[axis] is None else points_matrix(points[axis], n)
+        y = mode_contract(M, y, axis)
+    return y
 
 
 def mode_contract(M: np.ndarray, x: np.ndarray, axis: int) -> np.ndarray:

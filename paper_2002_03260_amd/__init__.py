@@ -5,5 +5,5 @@ loudly if it has not been built (there is no CPU fallback).
 """
 from .binding import (  # noqa: F401
     BACKWARD, FFT, FLAG_3M, FLAG_CLOBBER_INPUT, FLAG_UNFUSED, FORWARD, KDFT, Dft3dError, Plan,
-    device_copy, generate_matrix, generate_twiddle, library_path, load_library,
+    device_copy, generate_matrix, generate_points_matrix, generate_twiddle, library_path, load_library,
 )

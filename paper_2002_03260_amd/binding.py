@@ -23,7 +23,8 @@ FLAG_UNFUSED = 2
 FLAG_3M = 4
 
 EXPORTS = [
-    "dft3d_plan_create", "dft3d_plan_create_ex", "dft3d_plan_destroy",
+    "dft3d_plan_create", "dft3d_plan_create_ex", "dft3d_plan_create_points",
+    "dft3d_plan_get_output_shape", "dft3d_generate_points_matrix", "dft3d_plan_destroy",
     "dft3d_plan_workspace_bytes", "dft3d_plan_set_workspace", "dft3d_plan_get_split",
     "dft3d_exec", "dft3d_plan_enable_profiling", "dft3d_plan_read_profile", "dft3d_mode_contract", "dft3d_fft_first_stage", "dft3d_fft_phase",
     "dft3d_fft_second_stage", "dft3d_fft_axis", "dft3d_fft_reorder", "dft3d_device_copy", "dft3d_generate_matrix",
@@ -58,6 +59,9 @@ def load_library():
     vp, i64, ci, u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32
     lib.dft3d_plan_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, vp, vp, vp]
     lib.dft3d_plan_create_ex.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, vp, vp, vp, vp, u32]
+    lib.dft3d_plan_create_points.argtypes = [ctypes.POINTER(vp), i64, i64, i64, i64, i64, i64, vp, vp, vp, u32]
+    lib.dft3d_plan_get_output_shape.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.dft3d_generate_points_matrix.argtypes = [i64, i64, vp, vp, vp]
     lib.dft3d_plan_destroy.argtypes = [vp]
     lib.dft3d_plan_workspace_bytes.argtypes = [vp]
     lib.dft3d_plan_workspace_bytes.restype = ctypes.c_size_t
@@ -116,6 +120,16 @@ def generate_matrix(n: int, coords=None, direction: int = FORWARD) -> np.ndarray
     return (re + 1j * im).astype(np.complex64)
 
 
+def generate_points_matrix(z, n: int) -> np.ndarray:
+    """The K x n Vandermonde matrix z_r**(-j) as the library rounds it (host call, complex64)."""
+    z = np.ascontiguousarray(z, dtype=np.complex128)
+    K = z.shape[0]
+    re = np.empty((K, n), np.float32)
+    im = np.empty((K, n), np.float32)
+    _check(load_library().dft3d_generate_points_matrix(K, n, _np_ptr(z), _np_ptr(re), _np_ptr(im)))
+    return (re + 1j * im).astype(np.complex64)
+
+
 def generate_twiddle(A: int, B: int, direction: int = FORWARD) -> np.ndarray:
     """The A x B twiddle table T[k_a, beta] as the library rounds it (host call, complex64)."""
     re = np.empty((A, B), np.float32)
@@ -145,7 +159,7 @@ class Plan:
     """Owns one dft3d_plan.  Methods mirror the C entry points one to one."""
 
     def __init__(self, shape: Sequence[int], formulation: int = KDFT, coords=(None, None, None),
-                 split: Optional[Sequence[int]] = None, flags: int = 0):
+                 split: Optional[Sequence[int]] = None, flags: int = 0, points=None):
         self._lib = load_library()
         self._h = ctypes.c_void_p()
         self.shape = tuple(int(s) for s in shape)
@@ -153,6 +167,16 @@ class Plan:
             raise ValueError("shape must have three entries")
         self.formulation = formulation
         self.flags = flags
+        self.out_shape = self.shape
+        self._workspace = None
+        if points is not None:
+            # general form of the transform: arbitrary evaluation points per axis (None = roots of unity)
+            zs = [None if z is None else np.ascontiguousarray(z, dtype=np.complex128) for z in points]
+            ks = [n if z is None else int(z.shape[0]) for z, n in zip(zs, self.shape)]
+            _check(self._lib.dft3d_plan_create_points(ctypes.byref(self._h), *self.shape, *ks,
+                                                      _np_ptr(zs[0]), _np_ptr(zs[1]), _np_ptr(zs[2]), flags))
+            self.out_shape = tuple(ks)
+            return
         cs = [_host_coords(c, n) for c, n in zip(coords, self.shape)]
         sp = None
         if split is not None:
@@ -161,7 +185,6 @@ class Plan:
                                               _np_ptr(cs[0]), _np_ptr(cs[1]), _np_ptr(cs[2]),
                                               ctypes.cast(sp, ctypes.c_void_p) if sp else None,
                                               flags))
-        self._workspace = None
 
     # -- lifetime ---------------------------------------------------------------------------
     def destroy(self):
@@ -217,29 +240,39 @@ class Plan:
         return [float(ms[i]) for i in range(n.value)]
 
     # -- execution --------------------------------------------------------------------------
-    def _tensors(self, x, out):
+    def _tensors(self, x, out, in_shape=None, out_shape=None):
         import torch
 
+        in_shape = self.shape if in_shape is None else in_shape
+        out_shape = self.out_shape if out_shape is None else out_shape
         if x.dtype != torch.complex64 or not x.is_cuda or not x.is_contiguous():
             raise ValueError("input must be a contiguous complex64 CUDA tensor")
-        if tuple(x.shape) != self.shape:
-            raise ValueError(f"input shape {tuple(x.shape)} does not match plan {self.shape}")
+        if tuple(x.shape) != tuple(in_shape):
+            raise ValueError(f"input shape {tuple(x.shape)} does not match {tuple(in_shape)}")
         if out is None:
-            out = torch.empty_like(x)
+            out = torch.empty(tuple(out_shape), dtype=torch.complex64, device=x.device)
         elif (out.dtype != torch.complex64 or not out.is_cuda or not out.is_contiguous()
-              or tuple(out.shape) != self.shape):
-            raise ValueError("output must be a contiguous complex64 CUDA tensor of the plan's shape")
+              or tuple(out.shape) != tuple(out_shape)):
+            raise ValueError(f"output must be a contiguous complex64 CUDA tensor of shape {tuple(out_shape)}")
         return ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(out.data_ptr()), out
+
+    def stage_shapes(self, axis):
+        """Shapes mode_contract reads and writes for ``axis`` (modes are applied z, y, x)."""
+        n, k = self.shape, self.out_shape
+        cur = [n[j] if j <= axis else k[j] for j in range(3)]
+        nxt = list(cur)
+        nxt[axis] = k[axis]
+        return tuple(cur), tuple(nxt)
 
     def exec(self, x, out=None, direction: int = FORWARD, stream=None):
         xi, oi, out = self._tensors(x, out)
-        if not (self.flags & FLAG_CLOBBER_INPUT):
+        if self.workspace_bytes():
             self.ensure_workspace(x.device)
         _check(self._lib.dft3d_exec(self._h, xi, oi, direction, _stream_handle(stream)))
         return out
 
     def mode_contract(self, axis, x, out=None, direction: int = FORWARD, stream=None):
-        xi, oi, out = self._tensors(x, out)
+        xi, oi, out = self._tensors(x, out, *self.stage_shapes(axis))
         _check(self._lib.dft3d_mode_contract(self._h, axis, xi, oi, direction, _stream_handle(stream)))
         return out
 

@@ -63,6 +63,8 @@ void unit_root_turns(double t, int sign, double* re, double* im)
 
 using namespace dft3d;
 
+static const double kTwoPiGen = 6.283185307179586476925286766559;
+
 extern "C" dft3d_status dft3d_generate_matrix(int64_t n, const double* coords, int direction,
                                               float* re, float* im)
 {
@@ -96,6 +98,40 @@ extern "C" dft3d_status dft3d_generate_twiddle(int64_t A, int64_t B, int directi
             unit_root_ratio(ka * b, A * B, direction, &cr, &ci);
             re[ka * B + b] = (float)cr;
             im[ka * B + b] = (float)ci;
+        }
+    }
+    return DFT3D_OK;
+}
+
+extern "C" dft3d_status dft3d_generate_points_matrix(int64_t k, int64_t n, const double* z, float* re,
+                                                     float* im)
+{
+    if (k < 1 || n < 1 || !z || !re || !im) {
+        set_error("dft3d_generate_points_matrix: invalid argument");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    // V[r, j] = z_r^{-j} = |z_r|^{-j} exp(-i j arg z_r): modulus by exp/log, phase through the
+    // exactly reduced fraction of a turn (so points on the unit circle keep unit modulus)
+    for (int64_t r = 0; r < k; ++r) {
+        const double zr = z[2 * r], zi = z[2 * r + 1];
+        const double mod = std::hypot(zr, zi);
+        if (!(mod > 0.0) || !std::isfinite(mod)) {
+            set_error("dft3d_generate_points_matrix: point %lld is zero or not finite", (long long)r);
+            return DFT3D_ERR_INVALID_ARG;
+        }
+        const double turns = std::atan2(zi, zr) / kTwoPiGen;
+        const double lnmod = (mod == 1.0) ? 0.0 : std::log(mod);
+        for (int64_t j = 0; j < n; ++j) {
+            double cr, ci;
+            unit_root_turns((double)j * turns, DFT3D_FORWARD, &cr, &ci);
+            const double m = (lnmod == 0.0) ? 1.0 : std::exp(-(double)j * lnmod);
+            const float fr = (float)(m * cr), fi = (float)(m * ci);
+            if (!std::isfinite(fr) || !std::isfinite(fi)) {
+                set_error("dft3d_generate_points_matrix: entry (%lld, %lld) overflows fp32", (long long)r, (long long)j);
+                return DFT3D_ERR_INVALID_ARG;
+            }
+            re[r * n + j] = fr;
+            im[r * n + j] = fi;
         }
     }
     return DFT3D_OK;

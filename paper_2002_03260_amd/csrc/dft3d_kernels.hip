@@ -919,8 +919,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
                 for (int bm = 0; bm < BMA; ++bm)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const int ka = bm * 16 + 4 * lq + v;
-                        const float wx = tw[u][bm][v].x, wy = tw[u][bm][v].y * isign;
+                        const float wx = tw[u][bm][v].x, wy = tw[u][bm][v].y * isign;   // k_a = 16bm + 4lq + v
                         const float zr = cr[u][bm][v] * wx - ci[u][bm][v] * wy;
                         const float zi = cr[u][bm][v] * wy + ci[u][bm][v] * wx;
                         const int wr = ((v & 1) ? s1_wr_odd : s1_wr_even) + ((bm * 16 + v) * B + (g + u) * NW) * TC;

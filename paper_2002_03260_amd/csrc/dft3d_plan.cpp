@@ -97,7 +97,9 @@ int64_t default_split(int64_t n)
 using namespace dft3d;
 
 struct dft3d_plan_s {
-    int64_t n[3] = {0, 0, 0};
+    int64_t n[3] = {0, 0, 0};      // input lengths
+    int64_t k[3] = {0, 0, 0};      // output lengths (== n except for evaluation-point plans)
+    bool points = false;           // created by dft3d_plan_create_points
     dft3d_formulation form = DFT3D_KDFT;
     uint32_t flags = 0;
     bool nonuniform[3] = {false, false, false};
@@ -122,15 +124,21 @@ struct dft3d_plan_s {
     int prof_next = 0;
 
     int64_t elements() const { return n[0] * n[1] * n[2]; }
-    int64_t inner(int axis) const { return axis == 0 ? n[1] * n[2] : (axis == 1 ? n[2] : 1); }
+    int64_t out_elements() const { return k[0] * k[1] * k[2]; }
+    // Modes are applied in the order z, y, x, so when `axis` is contracted the axes after it
+    // already have their output length and the axes before it still have their input length.
+    int64_t inner(int axis) const { return axis == 0 ? k[1] * k[2] : (axis == 1 ? k[2] : 1); }
     int64_t outer(int axis) const { return axis == 0 ? 1 : (axis == 1 ? n[0] : n[0] * n[1]); }
+    int64_t stage_in_elements(int axis) const { return outer(axis) * n[axis] * inner(axis); }
+    int64_t stage_out_elements(int axis) const { return outer(axis) * k[axis] * inner(axis); }
 };
 
 namespace {
 
 bool valid_direction(int d) { return d == DFT3D_FORWARD || d == DFT3D_BACKWARD; }
 
-dft3d_status check_buffers(const dft3d_plan_s* p, const void* in, void* out, const char* who)
+dft3d_status check_buffers(const dft3d_plan_s* p, const void* in, void* out, const char* who,
+                           int64_t in_elems = -1, int64_t out_elems = -1)
 {
     if (!p) { set_error("%s: plan is NULL", who); return DFT3D_ERR_INVALID_ARG; }
     if (!in || !out) { set_error("%s: NULL tensor pointer", who); return DFT3D_ERR_INVALID_ARG; }
@@ -138,9 +146,10 @@ dft3d_status check_buffers(const dft3d_plan_s* p, const void* in, void* out, con
         set_error("%s: tensor pointers must be 16-byte aligned", who);
         return DFT3D_ERR_INVALID_ARG;
     }
-    const uintptr_t bytes = (uintptr_t)p->elements() * 8;
+    const uintptr_t abytes = (uintptr_t)(in_elems >= 0 ? in_elems : p->elements()) * 8;
+    const uintptr_t bbytes = (uintptr_t)(out_elems >= 0 ? out_elems : p->out_elements()) * 8;
     const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
-    if (a < b + bytes && b < a + bytes) {
+    if (a < b + bbytes && b < a + abytes) {
         set_error("%s: in and out overlap (the transform is out of place)", who);
         return DFT3D_ERR_INVALID_ARG;
     }
@@ -276,7 +285,7 @@ float axis_scale(const dft3d_plan_s* p, int axis, int direction)
 
 dft3d_status require_uniform_for_backward(const dft3d_plan_s* p, int direction, const char* who)
 {
-    if (direction == DFT3D_BACKWARD && (p->nonuniform[0] || p->nonuniform[1] || p->nonuniform[2])) {
+    if (direction == DFT3D_BACKWARD && (p->points || p->nonuniform[0] || p->nonuniform[1] || p->nonuniform[2])) {
         set_error("%s: BACKWARD is not defined for a plan with nonuniform axes", who);
         return DFT3D_ERR_UNSUPPORTED;
     }
@@ -345,6 +354,7 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
     p->flags = flags;
     for (int j = 0; j < 3; ++j) {
         p->n[j] = n[j];
+        p->k[j] = n[j];
         p->nonuniform[j] = c[j] != nullptr;
     }
 
@@ -457,6 +467,66 @@ dft3d_status dft3d_plan_read_profile(dft3d_plan p, int exec_index, float* ms, in
     return DFT3D_OK;
 }
 
+dft3d_status dft3d_plan_create_points(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
+                                      int64_t kx, int64_t ky, int64_t kz, const double* zx,
+                                      const double* zy, const double* zz, uint32_t flags)
+{
+    if (!plan) { set_error("plan_create_points: plan pointer is NULL"); return DFT3D_ERR_INVALID_ARG; }
+    *plan = nullptr;
+    const int64_t n[3] = {nx, ny, nz}, k[3] = {kx, ky, kz};
+    const double* z[3] = {zx, zy, zz};
+    for (int j = 0; j < 3; ++j) {
+        if (n[j] < 1 || n[j] > (int64_t(1) << 24) || k[j] < 1 || k[j] > (int64_t(1) << 24)) {
+            set_error("plan_create_points: axis %d has lengths %lld -> %lld (must be 1..2^24)", j,
+                      (long long)n[j], (long long)k[j]);
+            return DFT3D_ERR_INVALID_ARG;
+        }
+        if (!z[j] && k[j] != n[j]) {
+            set_error("plan_create_points: axis %d has no points, so its output length must equal its input length", j);
+            return DFT3D_ERR_INVALID_ARG;
+        }
+    }
+    if (flags & ~DFT3D_FLAG_3M) {
+        set_error("plan_create_points: only DFT3D_FLAG_3M is accepted");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    if (ky * kz >= (int64_t(1) << 31) || nx * ny >= (int64_t(1) << 31)) {
+        set_error("plan_create_points: ky*kz and nx*ny must be below 2^31");
+        return DFT3D_ERR_UNSUPPORTED;
+    }
+    dft3d_plan_s* p = new (std::nothrow) dft3d_plan_s();
+    if (!p) { set_error("plan_create_points: out of host memory"); return DFT3D_ERR_ALLOC; }
+    p->form = DFT3D_KDFT;
+    p->flags = flags;
+    p->points = true;
+    dft3d_status s = DFT3D_OK;
+    for (int j = 0; j < 3 && s == DFT3D_OK; ++j) {
+        p->n[j] = n[j];
+        p->k[j] = k[j];
+        p->nonuniform[j] = z[j] != nullptr;
+        p->M_owner[j] = j;
+        std::vector<float> re((size_t)(k[j] * n[j])), im((size_t)(k[j] * n[j]));
+        s = z[j] ? dft3d_generate_points_matrix(k[j], n[j], z[j], re.data(), im.data())
+                 : dft3d_generate_matrix(n[j], nullptr, DFT3D_FORWARD, re.data(), im.data());
+        if (s == DFT3D_OK) s = upload_matrix(re, im, (int)k[j], (int)n[j], &p->M[j]);
+    }
+    if (s != DFT3D_OK) {
+        dft3d_plan_destroy(p);
+        return s;
+    }
+    *plan = p;
+    return DFT3D_OK;
+}
+
+dft3d_status dft3d_plan_get_output_shape(dft3d_plan p, int64_t* kx, int64_t* ky, int64_t* kz)
+{
+    if (!p || !kx || !ky || !kz) { set_error("get_output_shape: invalid argument"); return DFT3D_ERR_INVALID_ARG; }
+    *kx = p->k[0];
+    *ky = p->k[1];
+    *kz = p->k[2];
+    return DFT3D_OK;
+}
+
 dft3d_status dft3d_plan_destroy(dft3d_plan p)
 {
     if (!p) return DFT3D_OK;
@@ -477,6 +547,8 @@ dft3d_status dft3d_plan_destroy(dft3d_plan p)
 size_t dft3d_plan_workspace_bytes(dft3d_plan p)
 {
     if (!p) return 0;
+    if (p->points)   // two intermediates of different shapes: after mode z and after mode y
+        return (size_t)(p->stage_out_elements(2) + p->stage_out_elements(1)) * 8;
     if (p->flags & DFT3D_FLAG_CLOBBER_INPUT) return 0;
     return (size_t)p->elements() * 8;
 }
@@ -515,14 +587,15 @@ dft3d_status dft3d_plan_get_split(dft3d_plan p, int axis, int64_t* A, int64_t* B
 dft3d_status dft3d_mode_contract(dft3d_plan p, int axis, const void* in, void* out, int direction,
                                  void* stream)
 {
-    dft3d_status s = check_buffers(p, in, out, "mode_contract");
-    if (s != DFT3D_OK) return s;
-    if (axis < 0 || axis > 2 || !valid_direction(direction)) {
+    if (p && (axis < 0 || axis > 2 || !valid_direction(direction))) {
         set_error("mode_contract: bad axis or direction");
         return DFT3D_ERR_INVALID_ARG;
     }
+    dft3d_status s = check_buffers(p, in, out, "mode_contract", p ? p->stage_in_elements(axis) : -1,
+                                   p ? p->stage_out_elements(axis) : -1);
+    if (s != DFT3D_OK) return s;
     if (p->form != DFT3D_KDFT) { set_error("mode_contract: not a KDFT plan"); return DFT3D_ERR_UNSUPPORTED; }
-    if (direction == DFT3D_BACKWARD && p->nonuniform[axis]) {
+    if (direction == DFT3D_BACKWARD && (p->nonuniform[axis] || p->points)) {
         set_error("mode_contract: BACKWARD is not defined for a nonuniform axis");
         return DFT3D_ERR_UNSUPPORTED;
     }
@@ -632,6 +705,28 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
     if (!valid_direction(direction)) { set_error("exec: bad direction"); return DFT3D_ERR_INVALID_ARG; }
     s = require_uniform_for_backward(p, direction, "exec");
     if (s != DFT3D_OK) return s;
+
+    if (p->points) {
+        // in -> W1 (mode z) -> W2 (mode y) -> out (mode x); the two intermediates live in the workspace
+        const size_t need = dft3d_plan_workspace_bytes(p);
+        if (!p->workspace || p->workspace_bytes < need) {
+            set_error("exec: a workspace of %zu bytes must be set first", need);
+            return DFT3D_ERR_INVALID_ARG;
+        }
+        const uintptr_t w = (uintptr_t)p->workspace, a = (uintptr_t)in, b = (uintptr_t)out;
+        const uintptr_t abytes = (uintptr_t)p->elements() * 8, bbytes = (uintptr_t)p->out_elements() * 8;
+        if ((w < a + abytes && a < w + need) || (w < b + bbytes && b < w + need)) {
+            set_error("exec: the workspace overlaps in or out");
+            return DFT3D_ERR_INVALID_ARG;
+        }
+        float2* w1 = (float2*)p->workspace;
+        float2* w2 = w1 + p->stage_out_elements(2);
+        hipStream_t pst = (hipStream_t)stream;
+        hipError_t pe = run_mode(p, 2, (const float2*)in, w1, 0, 1.0f, pst);
+        if (pe == hipSuccess) pe = run_mode(p, 1, w1, w2, 0, 1.0f, pst);
+        if (pe == hipSuccess) pe = run_mode(p, 0, w2, (float2*)out, 0, 1.0f, pst);
+        return hip_status(pe, "exec");
+    }
 
     const bool clobber = (p->flags & DFT3D_FLAG_CLOBBER_INPUT) != 0;
     float2* other = nullptr;     // the ping-pong partner of `out`

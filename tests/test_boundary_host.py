@@ -74,6 +74,24 @@ def test_uniform_coordinates_reproduce_uniform_matrix_bitwise(lib):
         assert np.array_equal(dft.generate_matrix(n, np.arange(n) / n), dft.generate_matrix(n))
 
 
+def test_points_matrix_is_oracle_matrix_rounded_once(lib):
+    rng = np.random.default_rng(12)
+    for K, n in ((5, 9), (64, 64), (3, 300)):
+        z = (0.97 + 0.06 * rng.random(K)) * np.exp(2j * np.pi * rng.random(K))
+        M = dft.generate_points_matrix(z, n)
+        O = orc.points_matrix(z, n)
+        err = np.abs(M.astype(np.complex128) - O)
+        assert np.all(err <= 0.75 * ulp32(np.abs(O)) * np.sqrt(2) + 1e-10 * np.abs(O))
+    # points on the unit circle at the roots of unity reproduce the uniform matrix
+    n = 32
+    z = np.exp(2j * np.pi * np.arange(n) / n)
+    assert np.max(np.abs(dft.generate_points_matrix(z, n) - dft.generate_matrix(n))) < 1.3e-7
+    with pytest.raises(dft.Dft3dError):
+        dft.generate_points_matrix(np.array([0.0 + 0.0j]), 4)          # zero point
+    with pytest.raises(dft.Dft3dError):
+        dft.generate_points_matrix(np.array([1e-3 + 0.0j]), 64)        # overflows fp32
+
+
 def test_twiddle_table(lib):
     for A, B in ((16, 32), (32, 64), (3, 5), (1, 7), (7, 1)):
         T = dft.generate_twiddle(A, B)

@@ -131,6 +131,37 @@ def test_kdft_three_product_scheme(dft, shape):
         report(f"kdft 4M {shape} (for comparison)", ref4, want)
 
 
+@pytest.mark.parametrize("shape,ks", [((6, 10, 12), (4, 10, 20)), ((40, 33, 70), (33, 50, 70)),
+                                      ((128, 64, 96), (200, 64, 130))])
+def test_kdft_arbitrary_evaluation_points(dft, shape, ks):
+    """Eq. 1 - Eq. 3 as written: arbitrary points of the z-plane per axis, rectangular matrices."""
+    say(f"case kdft points {shape} -> {ks}")
+    x = wl.draw_complex(shape, "uniform", 2600 + sum(shape))
+    rng = np.random.default_rng(6)
+    pts = []
+    for n, k in zip(shape, ks):
+        # moduli close to 1 so z^-n stays well inside fp32 range over the whole axis
+        pts.append((1.0 + (rng.random(k) - 0.5) / n) * np.exp(2j * np.pi * rng.random(k)))
+    pts[1] = None if ks[1] == shape[1] else pts[1]
+    want = orc.dft3d_points(x, pts)
+    with dft.Plan(shape, dft.KDFT, points=pts) as p:
+        assert p.out_shape == tuple(ks)
+        xd = to_dev(x)
+        got = to_host(p.exec(xd))
+        assert got.shape == tuple(ks)
+        assert report(f"kdft points {shape}->{ks}", got, want) <= TOL
+        with pytest.raises(dft.Dft3dError):
+            p.exec(xd, direction=dft.BACKWARD)
+        # single modes, in exec order
+        y = x.astype(np.complex128)
+        yd = xd
+        for axis in (2, 1, 0):
+            M = orc.dft_matrix(shape[axis]) if pts[axis] is None else orc.points_matrix(pts[axis], shape[axis])
+            y = orc.mode_contract(M, y, axis)
+            yd = p.mode_contract(axis, yd)
+            assert report(f"points mode {axis}", to_host(yd), y) <= TOL
+
+
 def test_kdft_clobber_input(dft):
     shape = (16, 24, 40)
     x = wl.draw_complex(shape, "normal", 78)

@@ -255,6 +255,44 @@ def test_nonuniform_axis_is_not_transposed():
     assert np.allclose(X, [3.0, np.exp(-2j * np.pi * 0.125) + 2 * np.exp(-2j * np.pi * 0.5)])
 
 
+# --------------------------------------------------------------------------- arbitrary evaluation points (Eq. 1-3 as written)
+def test_points_matrix_is_polynomial_evaluation():
+    # X(z_k) = sum_n x_n z_k^{-n} is the polynomial with coefficients x_n evaluated at 1/z_k
+    rng = np.random.default_rng(8)
+    n, K = 11, 7
+    z = (0.8 + 0.4 * rng.random(K)) * np.exp(2j * np.pi * rng.random(K))      # off the unit circle
+    x = rng.standard_normal(n) + 1j * rng.standard_normal(n)
+    M = orc.points_matrix(z, n)
+    want = np.polyval(x[::-1], 1.0 / z)
+    assert np.allclose(M @ x, want, rtol=1e-12, atol=1e-12)
+    assert np.allclose(M[:, 0], 1.0)
+    assert np.allclose(M[:, 1:] / M[:, :-1], (1.0 / z)[:, None], rtol=1e-12)
+
+
+def test_points_on_roots_of_unity_reproduce_the_uniform_transform():
+    shape = (6, 8, 5)
+    x = rand_c64(shape, 19)
+    pts = tuple(np.exp(2j * np.pi * np.arange(n) / n) for n in shape)
+    assert rel_l2(orc.dft3d_points(x, pts), orc.dft3d(x)) < 1e-13
+    assert rel_l2(orc.dft3d_points(x, (None, pts[1], None)), orc.dft3d(x)) < 1e-13
+
+
+def test_points_rectangular_output_matches_brute_polynomial():
+    shape = (3, 4, 5)
+    rng = np.random.default_rng(9)
+    x = rand_c64(shape, 20)
+    pts = [0.9 * np.exp(2j * np.pi * rng.random(k)) for k in (2, 6, 4)]
+    X = orc.dft3d_points(x, pts)
+    assert X.shape == (2, 6, 4)
+    xc = x.astype(np.complex128)
+    for a, za in enumerate(pts[0]):
+        for b, zb in enumerate(pts[1]):
+            for c, zc in enumerate(pts[2]):
+                w = (za ** -np.arange(3))[:, None, None] * (zb ** -np.arange(4))[None, :, None] * \
+                    (zc ** -np.arange(5))[None, None, :]
+                assert abs(X[a, b, c] - np.sum(xc * w)) < 1e-12 * np.sum(np.abs(xc * w))
+
+
 # --------------------------------------------------------------------------- sampled slabs
 def test_sampled_slabs_equal_full():
     shape = (10, 6, 7)
