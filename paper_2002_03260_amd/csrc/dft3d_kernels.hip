@@ -54,6 +54,25 @@ inline dim3 grid_for(int64_t blocks)
     return dim3((unsigned)kMaxX, (unsigned)((blocks + kMaxX - 1) / kMaxX));
 }
 
+#ifdef DFT3D_TRACE
+// Diagnostic build only (never compiled into the shipped library): per-workgroup time stamps.
+__device__ unsigned long long* g_trace = nullptr;
+__device__ __forceinline__ void trace_mark(int slot)
+{
+    if (threadIdx.x == 0 && g_trace) {
+        const int64_t b = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+        g_trace[b * 8 + slot] = wall_clock64();
+        if (slot == 0) {
+            g_trace[b * 8 + 6] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));    // HW_ID
+            g_trace[b * 8 + 7] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11));   // XCC_ID
+        }
+    }
+}
+#define TRACE_MARK(s) trace_mark(s)
+#else
+#define TRACE_MARK(s)
+#endif
+
 __device__ __forceinline__ int64_t out_offset(const ContractArgs& a, int64_t o)
 {
     return (o / a.Olo) * a.sYohi + (o % a.Olo) * a.sYolo;
@@ -130,6 +149,7 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     int64_t t = linear_block_id();
     if (t >= total) return;
     t = xcd_remap(t, total);
+    TRACE_MARK(0);
     const int kt = (int)(t % tilesK);
     t /= tilesK;
     const int k0 = kt * TM;
@@ -218,6 +238,7 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     lstore(0);
     if (NB == 2 && nchunks > 1) gload(KC);
     __syncthreads();
+    TRACE_MARK(1);
 
     for (int c = 0; c < nchunks; ++c) {
         const int buf = (NB == 2) ? (c & 1) : 0;
@@ -303,6 +324,7 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
         __syncthreads();
     }
 
+    TRACE_MARK(2);
     // epilogue: scale, optional twiddle, store (16 consecutive columns per quarter-wave)
     const int K = a.M.K;
 #pragma unroll
@@ -341,6 +363,7 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
             }
         }
     }
+    TRACE_MARK(3);
 }
 
 // Contiguous-mode contraction (I == 1): out[o, k] = sum_n in[o, n] M[k, n].
@@ -578,6 +601,14 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
 // LDS pitches: xs rows (l) are B+16 apart so the two l-rows a half-wave reads sit 32 banks apart;
 // zs and os have odd pitches (B+1, A+1) so lanes that walk rows hit distinct banks.
 // ------------------------------------------------------------------------------------------
+// Column swizzle (in floats) of row n of an unpadded [P][P] fp32 plane: rows n, n+1, n+2, n+3
+// (n a multiple of 4) land on four distinct 16-bank groups.  Depends on n mod 4 only.
+template <int P>
+__device__ __forceinline__ constexpr int plane_swz(int n)
+{
+    return P == 64 ? 16 * (n & 3) : (P == 32 ? 16 * ((n >> 1) & 1) : 0);
+}
+
 template <int A, int B, int R, int NW, int MINW>
 __global__ __launch_bounds__(NW * 64, MINW) void k_fft_z(const float2* __restrict__ X, float2* __restrict__ Y,
                                                    int64_t nrows, DeviceMatrix FA, DeviceMatrix FB,
@@ -597,6 +628,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_z(const float2* __restric
     __shared__ __align__(16) float2 zs[R * A * ZP];
     __shared__ __align__(16) float far[A * FAP], fai[A * FAP];
     __shared__ __align__(16) float fbr[B * FBP], fbi[B * FBP];
+    // twiddles T[k_a][beta] in LDS when there is room: a global load inside the tile loop would
+    // queue behind the next tile's prefetch (loads return in order) and stall stage 1 on it
+    constexpr bool TWL = (A * B <= 2048);
+    __shared__ __align__(16) float2 tws[TWL ? A * B : 1];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -616,6 +651,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_z(const float2* __restric
         fbr[n * FBP + k] = FB.re[(int64_t)n * FB.ld + k];
         fbi[n * FBP + k] = FB.im[(int64_t)n * FB.ld + k] * isign;
     }
+
+    if (TWL)
+        for (int e = tid; e < A * B; e += NT) tws[e] = Tw[e];
+    const float2* tw_src = TWL ? tws : Tw;
 
     const int64_t ntiles = (nrows + R - 1) / R;
     const int64_t nwg = (int64_t)gridDim.x * gridDim.y;
@@ -660,7 +699,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_z(const float2* __restric
                 ci[u] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int v = 0; v < 4; ++v)      // requested now, needed after the MFMAs
-                    tw[u][v] = Tw[(bm[u] * 16 + 4 * lq + v) * B + bb[u] * 16 + l16];
+                    tw[u][v] = TWL ? tws[(bm[u] * 16 + 4 * lq + v) * B + bb[u] * 16 + l16]
+                                   : tw_src[(bm[u] * 16 + 4 * lq + v) * B + bb[u] * 16 + l16];
             }
 #pragma unroll
             for (int s = 0; s < A / 4; ++s) {
@@ -782,9 +822,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
     constexpr int NT = NW * 64;
     constexpr int N = A * B;
     constexpr int TC = 16;
-    // plane pitches that put the four rows a wave reads (l .. l+3) on four distinct 16-bank groups
-    constexpr int FAP = (A % 64 == 16 || A % 64 == 48) ? A : A + 16;
-    constexpr int FBP = (B % 64 == 16 || B % 64 == 48) ? B : B + 16;
+    // Stage-matrix planes are stored unpadded, [n][k] with pitch = dimension, and the column is
+    // XOR-swizzled by plane_swz so that the four rows a wave reads together (n = 4s + lq) fall on
+    // four distinct 16-bank groups.  The swizzle of row 4s + lq depends on lq only.
+    static_assert(A <= 64 && B <= 64, "plane swizzle is defined for dimensions 16, 32, 64");
+    constexpr int FAP = A, FBP = B;
     constexpr int RPP = NT / 8;                    // tile rows fetched per pass (8 threads x 16 B per row)
     static_assert(N % RPP == 0, "axis length must be a multiple of the rows per pass");
     constexpr int XL = N / RPP;                    // 16-byte loads per thread per tile
@@ -793,6 +835,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
     __shared__ __align__(16) float2 xs[N * TC];
     __shared__ __align__(16) float far[A * FAP], fai[A * FAP];
     __shared__ __align__(16) float fbr[B * FBP], fbi[B * FBP];
+    __shared__ __align__(16) float2 tws[A * B];     // twiddles T[k_a][beta]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -803,14 +846,26 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
 
     for (int e = tid; e < A * A; e += NT) {
         const int n = e / A, k = e % A;
-        far[n * FAP + k] = FA.re[(int64_t)n * FA.ld + k];
-        fai[n * FAP + k] = FA.im[(int64_t)n * FA.ld + k] * isign;
+        far[n * FAP + (k ^ plane_swz<A>(n))] = FA.re[(int64_t)n * FA.ld + k];
+        fai[n * FAP + (k ^ plane_swz<A>(n))] = FA.im[(int64_t)n * FA.ld + k] * isign;
     }
     for (int e = tid; e < B * B; e += NT) {
         const int n = e / B, k = e % B;
-        fbr[n * FBP + k] = FB.re[(int64_t)n * FB.ld + k];
-        fbi[n * FBP + k] = FB.im[(int64_t)n * FB.ld + k] * isign;
+        fbr[n * FBP + (k ^ plane_swz<B>(n))] = FB.re[(int64_t)n * FB.ld + k];
+        fbi[n * FBP + (k ^ plane_swz<B>(n))] = FB.im[(int64_t)n * FB.ld + k] * isign;
     }
+    for (int e = tid; e < A * B; e += NT) {
+        float2 w = Tw[e];
+        w.y *= isign;
+        tws[e] = w;
+    }
+    // per-lane operand columns of the planes (block bm, lane column l16, row swizzle of lq)
+    int fa_col[A / 16], fb_col[B / 16];
+#pragma unroll
+    for (int bm = 0; bm < A / 16; ++bm) fa_col[bm] = lq * FAP + ((bm * 16 + l16) ^ plane_swz<A>(lq));
+#pragma unroll
+    for (int bm = 0; bm < B / 16; ++bm) fb_col[bm] = lq * FBP + ((bm * 16 + l16) ^ plane_swz<B>(lq));
+    const int tw_rd = 4 * lq * B + wave;            // + ((16bm + v)*B + g*NW)
 
     // Swizzled LDS row of position pos = hi*B + beta is hi*B + (beta ^ (hi & 1)).  Every access
     // below is written as a per-lane base plus a compile-time offset so the addresses need no
@@ -832,16 +887,33 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
 
     f32x4 xreg[XL];
     auto tile_base = [&](int64_t tile) { return (tile / ctiles) * (int64_t)N * I + (tile % ctiles) * TC; };
-    auto gload = [&](int64_t tile) {
+    // The prefetch of the next tile is issued in NSLOT slices spread over the MFMA work of the
+    // current tile: a burst of all XL loads fills the memory pipeline and blocks the wave at issue.
+    constexpr int U1 = ((B / NW) % 4 == 0) ? 4 : (((B / NW) % 2 == 0) ? 2 : 1);
+    constexpr int U2 = ((A / NW) % 2 == 0 && B / 16 <= 2) ? 2 : 1;
+    constexpr int NSLOT = (B / NW) / U1 + (A / NW) / U2;
+    auto gload_slice = [&](int64_t tile, int slot) {
         const float2* src = X + tile_base(tile) + (int64_t)lrow * I + lcol;
 #pragma unroll
         for (int j = 0; j < XL; ++j)
-            xreg[j] = *reinterpret_cast<const f32x4*>(src + (int64_t)(j * RPP) * I);
+            if (j * NSLOT / XL == slot)
+                xreg[j] = *reinterpret_cast<const f32x4*>(src + (int64_t)(j * RPP) * I);
+    };
+    auto gload = [&](int64_t tile) {
+#pragma unroll
+        for (int sl = 0; sl < NSLOT; ++sl) gload_slice(tile, sl);
     };
 
+#ifdef DFT3D_TRACE
+    unsigned long long tacc[7] = {0, 0, 0, 0, 0, 0, 0}, tprev = wall_clock64();
+#define TRACE_ACC(i) { unsigned long long tn = wall_clock64(); tacc[i] += tn - tprev; tprev = tn; }
+#else
+#define TRACE_ACC(i)
+#endif
     int64_t tile = linear_block_id();
     if (tile < ntiles) gload(tile);
     for (; tile < ntiles; tile += nwg) {
+        TRACE_ACC(6);
         {
             // rows lrow + j*RPP: the swizzle bit ((row / B) & 1) is a per-thread constant when RPP
             // is a multiple of 2B, and known at compile time per j when RPP divides B
@@ -855,20 +927,17 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
                 *reinterpret_cast<f32x4*>(&xs[addr]) = xreg[j];
             }
         }
+        TRACE_ACC(0);
         __syncthreads();
-        if (tile + nwg < ntiles) gload(tile + nwg);
-
-        // The twiddles do not change from tile to tile; keeping all of them in registers across
-        // the tile loop costs more than re-reading them from cache, so the table pointer is made
-        // opaque here and the loads stay inside the loop.
-        const float2* tw_tab = Tw;
-        asm volatile("" : "+s"(tw_tab));
+        TRACE_ACC(1);
+        const bool more_tiles = tile + nwg < ntiles;
+        TRACE_ACC(2);
 
         // stage 1, in place; U1 beta groups in flight per wave
-        constexpr int U1 = ((B / NW) % 4 == 0) ? 4 : (((B / NW) % 2 == 0) ? 2 : 1);
         constexpr int BMA = A / 16;
 #pragma unroll
         for (int g = 0; g < B / NW; g += U1) {
+            if (more_tiles) gload_slice(tile + nwg, g / U1);
             f32x4 cr[U1][BMA], ci[U1][BMA];
             float2 tw[U1][BMA][4];
             int beta[U1];
@@ -880,18 +949,17 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
                     cr[u][bm] = f32x4{0.f, 0.f, 0.f, 0.f};
                     ci[u][bm] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) tw[u][bm][v] = tw_tab[(bm * 16 + 4 * lq + v) * B + beta[u]];
+                    for (int v = 0; v < 4; ++v) tw[u][bm][v] = tws[tw_rd + (bm * 16 + v) * B + (g + u) * NW];
                 }
             }
 #pragma unroll 4
             for (int s = 0; s < A / 4; ++s) {
-                const int l = 4 * s + lq;
                 float ar[BMA], ai[BMA];
                 f32x2 x[U1];
 #pragma unroll
                 for (int bm = 0; bm < BMA; ++bm) {
-                    ar[bm] = far[l * FAP + bm * 16 + l16];
-                    ai[bm] = fai[l * FAP + bm * 16 + l16];
+                    ar[bm] = far[fa_col[bm] + 4 * s * FAP];
+                    ai[bm] = fai[fa_col[bm] + 4 * s * FAP];
                 }
 #pragma unroll
                 for (int u = 0; u < U1; ++u)
@@ -919,21 +987,23 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
                 for (int bm = 0; bm < BMA; ++bm)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const float wx = tw[u][bm][v].x, wy = tw[u][bm][v].y * isign;   // k_a = 16bm + 4lq + v
+                        const float wx = tw[u][bm][v].x, wy = tw[u][bm][v].y;   // k_a = 16bm + 4lq + v (sign applied at load)
                         const float zr = cr[u][bm][v] * wx - ci[u][bm][v] * wy;
                         const float zi = cr[u][bm][v] * wy + ci[u][bm][v] * wx;
                         const int wr = ((v & 1) ? s1_wr_odd : s1_wr_even) + ((bm * 16 + v) * B + (g + u) * NW) * TC;
                         *reinterpret_cast<f32x2*>(&xs[wr]) = f32x2{zr, zi};
                     }
         }
+        TRACE_ACC(3);
         __syncthreads();
+        TRACE_ACC(4);
 
         // stage 2: U2 k_a groups at a time per wave (they share the FB operands), all k_b blocks in flight
         constexpr int BMB = B / 16;
-        constexpr int U2 = ((A / NW) % 2 == 0 && BMB <= 2) ? 2 : 1;
         float2* dst = Y + tile_base(tile) + l16;
 #pragma unroll
         for (int g = 0; g < A / NW; g += U2) {
+            if (more_tiles) gload_slice(tile + nwg, (B / NW) / U1 + g / U2);
             f32x4 cr[U2][BMB], ci[U2][BMB];
 #pragma unroll
             for (int u = 0; u < U2; ++u)
@@ -944,7 +1014,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
                 }
 #pragma unroll 4
             for (int s = 0; s < B / 4; ++s) {
-                const int beta = 4 * s + lq;
                 f32x2 z[U2];
 #pragma unroll
                 for (int u = 0; u < U2; ++u)
@@ -952,8 +1021,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
                 float ar[BMB], ai[BMB];
 #pragma unroll
                 for (int bm = 0; bm < BMB; ++bm) {
-                    ar[bm] = fbr[beta * FBP + bm * 16 + l16];
-                    ai[bm] = fbi[beta * FBP + bm * 16 + l16];
+                    ar[bm] = fbr[fb_col[bm] + 4 * s * FBP];
+                    ai[bm] = fbi[fb_col[bm] + 4 * s * FBP];
                 }
 #pragma unroll
                 for (int u = 0; u < U2; ++u)
@@ -985,8 +1054,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
                     }
             }
         }
+        TRACE_ACC(5);
         __syncthreads();
     }
+#ifdef DFT3D_TRACE
+    if (g_trace && (threadIdx.x & 63) == 0) {
+        const int64_t b = linear_block_id() * NW + (threadIdx.x >> 6);
+        for (int i = 0; i < 7; ++i) g_trace[b * 8 + i] = tacc[i];
+    }
+#endif
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1271,6 +1347,14 @@ hipError_t launch_fft_s(const float2* in, float2* out, int64_t O, int64_t I, int
     if (A == 32 && B == 32) return launch_fft_s_inst<32, 32, 8, 2, 1>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
     return hipErrorInvalidValue;
 }
+
+#ifdef DFT3D_TRACE
+extern "C" int dft3d_debug_set_trace(void* dev_ptr)
+{
+    unsigned long long* p = (unsigned long long*)dev_ptr;
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &p, sizeof(p));
+}
+#endif
 
 hipError_t launch_copy(const void* in, void* out, size_t bytes, int variant, hipStream_t stream)
 {
