@@ -11,7 +11,7 @@
  *     applied to every mode of the tensor (V1 (x) V2 (x) V3 acting on the row-major vector).
  *   - Eq. 12 (Section III-B): on a uniform grid the matrix entries are exp(-2 pi i n k / N).
  *
- * Readings taken where the paper is silent (listed in the design notes of the repository):
+ * Readings taken where the paper is silent:
  *   - forward transform: negative exponent, no scaling (Eq. 1 and Eq. 12 agree on this);
  *   - backward transform (uniform axes only): positive exponent, scaled by 1/(N1 N2 N3);
  *   - nonuniform axis: M[k, n] = exp(-2 pi i k c[n]) with integer frequency k = 0..N-1 and

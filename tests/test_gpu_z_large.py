@@ -21,7 +21,9 @@ pytestmark = pytest.mark.gpu
 
 TOL = 2e-5
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-_PROGRESS = os.path.join(ROOT, "gpurun_out", "test_progress.log")
+# progress lines also go to a scratch folder at the repository root when it exists (a file that
+# keeps growing shows a long test is alive even when stdout is captured)
+_PROGRESS = os.path.join(ROOT, os.environ.get("DFT3D_PROGRESS_DIR", "gpurun_out"), "test_progress.log")
 
 
 def say(msg):
