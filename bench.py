@@ -251,6 +251,10 @@ def main() -> int:
             "split": [list(s) for s in w.splits] if (form == dft.FFT and w.splits) else None,
         },
         "roofline": roofline,
+        # context only (another machine, with inter-core communication included): Table I of the paper
+        "paper_context": {"hardware": "full TPU v3 Pod, 2048 cores", "size": "8192^3",
+                          "kdft_seconds": 12.66, "fft_seconds": 8.30,
+                          "size_2048": {"kdft_seconds": 0.120, "fft_seconds": 0.118}},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, wl)

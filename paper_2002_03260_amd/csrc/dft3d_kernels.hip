@@ -1109,9 +1109,9 @@ __global__ __launch_bounds__(kThreads) void k_phase(const float2* __restrict__ i
 // ------------------------------------------------------------------------------------------
 // Re-ordering.  The swap of the x and y sub-indices only changes which output row an input row
 // goes to; the swap of the z sub-indices is a transposition [A][B] -> [B][A] inside each
-// contiguous row, done through LDS.  A workgroup takes a batch of G consecutive input rows
-// (G * nz contiguous complex numbers), reads them with EV-wide accesses, and writes every row
-// contiguously.  In LDS the element at slot s = ka*B + kb of batch row g sits at
+// contiguous row, done through LDS.  A workgroup produces a batch of G consecutive output rows
+// (G * nz contiguous complex numbers): it reads the input rows that land there with EV-wide
+// accesses and writes the batch contiguously.  In LDS the element at slot s = ka*B + kb of batch row g sits at
 // g*(nz + A) + s + ka: one padding element per B-row, so the transposed read walks ka with the
 // odd stride B + 1 and consecutive lanes hit distinct banks.
 // ------------------------------------------------------------------------------------------
@@ -1119,6 +1119,11 @@ __device__ __forceinline__ int swap_slot(int s, int A, int B)
 {
     // slot ka*B + kb  ->  natural index ka + A*kb
     return (s / B) + A * (s % B);
+}
+__device__ __forceinline__ int unswap_slot(int k, int A, int B)
+{
+    // natural index ka + A*kb  ->  slot ka*B + kb
+    return (k % A) * B + k / A;
 }
 
 template <int CAP, int EV>
@@ -1129,49 +1134,47 @@ __global__ __launch_bounds__(kThreads) void k_reorder_rows(ReorderArgs a, int64_
     const int nz = a.n[2];
     const int A = a.A[2], B = a.B[2];
     const int pitch = nz + A;
-    {
-        const int64_t b = linear_block_id();      // one batch per workgroup, launched in memory order
-        const int64_t r0 = b * G;
-        if (r0 >= nrows) return;
-        const int g_here = (int)((nrows - r0) < G ? (nrows - r0) : G);
-        const int count = g_here * nz;
-        const float2* __restrict__ src = a.in + r0 * (int64_t)nz;
-        if (!a.swap[2]) {
-            // rows keep their content: copy each to its permuted place
-            for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
-                const int g = e / nz, z = e - g * nz;
-                const int64_t r = r0 + g;
-                const int ix = (int)(r / a.n[1]), iy = (int)(r % a.n[1]);
-                const int ox = a.swap[0] ? swap_slot(ix, a.A[0], a.B[0]) : ix;
-                const int oy = a.swap[1] ? swap_slot(iy, a.A[1], a.B[1]) : iy;
-                *reinterpret_cast<xvec*>(a.out + ((int64_t)ox * a.n[1] + oy) * (int64_t)nz + z) =
-                    *reinterpret_cast<const xvec*>(src + e);
-            }
-            return;
-        }
+    // One batch of G consecutive OUTPUT rows per workgroup, launched in output order: the writes
+    // of the whole grid stream through memory contiguously and the reads gather whole input rows
+    // (reads tolerate the scatter better than writes do).
+    const int64_t b = linear_block_id();
+    const int64_t r0 = b * G;
+    if (r0 >= nrows) return;
+    const int g_here = (int)((nrows - r0) < G ? (nrows - r0) : G);
+    const int count = g_here * nz;
+    float2* __restrict__ dst = a.out + r0 * (int64_t)nz;
+    auto source_row = [&](int64_t r) {   // input row that lands in output row r
+        const int ox = (int)(r / a.n[1]), oy = (int)(r % a.n[1]);
+        const int ix = a.swap[0] ? unswap_slot(ox, a.A[0], a.B[0]) : ox;
+        const int iy = a.swap[1] ? unswap_slot(oy, a.A[1], a.B[1]) : oy;
+        return a.in + ((int64_t)ix * a.n[1] + iy) * (int64_t)nz;
+    };
+    if (!a.swap[2]) {
+        // rows keep their content: copy each from its permuted place
         for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
-            const xvec v = *reinterpret_cast<const xvec*>(src + e);
-            const int g = e / nz, s = e - g * nz;
-            store_cvec(&buf[g * pitch + s + s / B], v);   // s and s+1 share a B-row (B even when EV == 2)
+            const int g = e / nz, z = e - g * nz;
+            *reinterpret_cast<xvec*>(dst + e) = *reinterpret_cast<const xvec*>(source_row(r0 + g) + z);
         }
-        __syncthreads();
-        for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
-            const int g = e / nz, k = e - g * nz;          // natural index k = ka + A*kb
-            const int kb = k / A, ka = k - kb * A;
-            const float2* p = &buf[g * pitch + ka * (B + 1) + kb];
-            xvec v;
+        return;
+    }
+    for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
+        const int g = e / nz, s = e - g * nz;
+        const xvec v = *reinterpret_cast<const xvec*>(source_row(r0 + g) + s);
+        store_cvec(&buf[g * pitch + s + s / B], v);   // s and s+1 share a B-row (B even when EV == 2)
+    }
+    __syncthreads();
+    for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
+        const int g = e / nz, k = e - g * nz;          // natural index k = ka + A*kb
+        const int kb = k / A, ka = k - kb * A;
+        const float2* p = &buf[g * pitch + ka * (B + 1) + kb];
+        xvec v;
 #pragma unroll
-            for (int q = 0; q < EV; ++q) {                 // k+1 is the next ka (A even when EV == 2)
-                const float2 t = p[q * (B + 1)];
-                v[2 * q] = t.x;
-                v[2 * q + 1] = t.y;
-            }
-            const int64_t r = r0 + g;
-            const int ix = (int)(r / a.n[1]), iy = (int)(r % a.n[1]);
-            const int ox = a.swap[0] ? swap_slot(ix, a.A[0], a.B[0]) : ix;
-            const int oy = a.swap[1] ? swap_slot(iy, a.A[1], a.B[1]) : iy;
-            *reinterpret_cast<xvec*>(a.out + ((int64_t)ox * a.n[1] + oy) * (int64_t)nz + k) = v;
+        for (int q = 0; q < EV; ++q) {                 // k+1 is the next ka (A even when EV == 2)
+            const float2 t = p[q * (B + 1)];
+            v[2 * q] = t.x;
+            v[2 * q + 1] = t.y;
         }
+        *reinterpret_cast<xvec*>(dst + e) = v;
     }
 }
 
