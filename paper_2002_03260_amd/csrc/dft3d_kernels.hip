@@ -1115,11 +1115,6 @@ __global__ __launch_bounds__(kThreads) void k_phase(const float2* __restrict__ i
 // g*(nz + A) + s + ka: one padding element per B-row, so the transposed read walks ka with the
 // odd stride B + 1 and consecutive lanes hit distinct banks.
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ int swap_slot(int s, int A, int B)
-{
-    // slot ka*B + kb  ->  natural index ka + A*kb
-    return (s / B) + A * (s % B);
-}
 __device__ __forceinline__ int unswap_slot(int k, int A, int B)
 {
     // natural index ka + A*kb  ->  slot ka*B + kb
