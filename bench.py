@@ -24,6 +24,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_MFMA_F32_TFLOPS = 157.3      # 256 CU x 256 flop/clk x 2.4 GHz
+PEAK_MFMA_BF16_TFLOPS = 2500.0    # dense bf16 matrix-core peak
 PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
@@ -98,6 +99,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--three-m", action="store_true",
                     help="KDFT: three real products per complex product (DFT3D_FLAG_3M)")
+    ap.add_argument("--bf16x3", action="store_true",
+                    help="KDFT: fp32 accuracy from three bf16 levels on the bf16 matrix cores (DFT3D_FLAG_BF16X3)")
     ap.add_argument("--unfused", action="store_true",
                     help="FFT: run the twiddle and the re-ordering as separate memory-bound kernels")
     args = ap.parse_args()
@@ -166,6 +169,8 @@ def main() -> int:
         flags = dft.FLAG_UNFUSED     # 10 passes: needs the separate workspace
     if args.three_m and form == dft.KDFT:
         flags |= dft.FLAG_3M
+    if args.bf16x3 and form == dft.KDFT:
+        flags |= dft.FLAG_BF16X3
     plan = dft.Plan(w.shape, form, coords=coords, split=split, flags=flags)
     x = wl.make_input_device(w) if big else torch.from_numpy(wl.make_input(w)).to("cuda")
     out = torch.empty_like(x)
@@ -207,6 +212,14 @@ def main() -> int:
             "unit": "TFLOP/s", "avg_launch_ms": dom_ms,
             "flop_per_launch": flops,
         }
+        if args.bf16x3:
+            # each real fp32 product becomes six bf16 products (level pairs of total order <= 2):
+            # priced in bf16 flops against the bf16 peak
+            flops = 6.0 * 8.0 * n_dom * E
+            roofline.update({"kernel": "k_contract_bf16x3 (strided mode contraction, bf16 MFMA, 6 level products)",
+                             "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_BF16_TFLOPS,
+                             "flop_per_launch": flops,
+                             "fp32_equivalent_tflops": 8.0 * n_dom * E / (dom_ms * 1e-3) / 1e12})
     else:
         pass_names = ["z_stage1+twiddle", "z_stage2", "y_stage1+twiddle", "y_stage2+reorder",
                       "x_stage1+twiddle", "x_stage2+reorder", "z_reorder"]
@@ -246,6 +259,8 @@ def main() -> int:
             "workload": w.name + ("" if form_override is None else ("_fft" if form == dft.FFT else "_kdft")),
             "formulation": "FFT" if form == dft.FFT else "KDFT",
             "complex_scheme": "3M" if (args.three_m and form == dft.KDFT) else "4M",
+            "arithmetic": "bf16x3 split on bf16 MFMA, fp32 accumulate" if (args.bf16x3 and form == dft.KDFT)
+                          else "fp32 MFMA",
             "shape": list(w.shape), "input": f"complex64, iid {w.dist}, seed {w.seed}",
             "nonuniform": w.nonuniform,
             "split": [list(s) for s in w.splits] if (form == dft.FFT and w.splits) else None,

@@ -55,6 +55,11 @@ typedef enum { DFT3D_FORWARD = -1, DFT3D_BACKWARD = 1 } dft3d_direction;
 #define DFT3D_FLAG_CLOBBER_INPUT 1u /* exec may overwrite `in`; then no workspace is needed */
 #define DFT3D_FLAG_UNFUSED 2u       /* FFT: run the twiddle and the re-ordering as separate
                                        kernels instead of fusing them into the contractions */
+#define DFT3D_FLAG_BF16X3 8u        /* KDFT: float32 accuracy on the bf16 matrix cores -- every fp32
+                                       number is decomposed into three bf16 numbers and six cross
+                                       products are accumulated in fp32 (Section II-A of the paper);
+                                       used for modes whose shape is a whole number of 128x128 tiles,
+                                       other modes fall back to the fp32 kernels */
 #define DFT3D_FLAG_3M 4u            /* KDFT: three real products per complex product
                                        (Vr*Xr, Vi*Xi, (Vr+Vi)*(Xr+Xi)) instead of four: 25 % fewer
                                        MFMA operations, slightly larger rounding error in Im */

@@ -21,6 +21,7 @@ BACKWARD = 1
 FLAG_CLOBBER_INPUT = 1
 FLAG_UNFUSED = 2
 FLAG_3M = 4
+FLAG_BF16X3 = 8
 
 EXPORTS = [
     "dft3d_plan_create", "dft3d_plan_create_ex", "dft3d_plan_create_points",

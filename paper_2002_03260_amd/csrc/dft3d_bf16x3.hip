@@ -1,0 +1,307 @@
+// Mode contraction with fp32 accuracy on the bf16 matrix cores (gfx950, v_mfma_f32_32x32x16_bf16).
+//
+// The paper's MXU multiplies in bfloat16 and reaches float32 precision by decomposing each
+// float32 number into several bfloat16 numbers and accumulating the cross products (Section
+// II-A).  The same scheme on CDNA4, whose bf16 MFMA rate is 16x its fp32 rate:
+//
+//     x = x1 + x2 + x3   (each bf16, xj = bf16(x - x1 - .. - x(j-1)), residual ~2^-24 |x|)
+//     v*x ~= v1*x1 + v1*x2 + v2*x1 + v1*x3 + v3*x1 + v2*x2          (6 of the 9 cross products)
+//
+// all accumulated in the fp32 accumulators of the MFMA.  The matrix is split once at plan time
+// (from its fp64 entries); the data tile is split while it is staged into LDS.
+//
+// Kernel shape.  One kernel serves both contraction types:  out[row, col] = sum_n R[row,n] C[col,n]
+//   strided modes   : R = matrix (rows = k), C = data (cols = the contiguous index i)
+//   contiguous mode : R = data (rows = o),   C = matrix (cols = k)
+// Both operands of a 32x32x16 bf16 MFMA hold 8 consecutive n per lane, so the LDS tiles are
+// [plane][row or col][n] with n contiguous: RT and CT, 6 planes each (re, im) x (hi, mid, lo),
+// 128 rows x 16 n per chunk, 48-byte pitch (32 data + 16 pad: 16 consecutive rows hit 16 distinct
+// 16-byte bank groups).  A workgroup is 4 waves (one per SIMD, up to 512 VGPRs each) on a 128x128
+// tile, each wave 64x64 = 2x2 MFMA blocks x (re, im) accumulators; 96 MFMAs per chunk per wave.
+// Double-buffered LDS, register-staged prefetch one chunk ahead, one barrier per chunk.
+#include <hip/hip_runtime.h>
+
+#include "dft3d_internal.h"
+
+namespace dft3d {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kT = 256;
+constexpr int TM = 128, TN = 128, KC = 16;
+constexpr int kPlanes = 6;                 // (re, im) x (hi, mid, lo); plane = 3*part + level
+
+__device__ __forceinline__ int64_t block_id() { return (int64_t)blockIdx.y * gridDim.x + blockIdx.x; }
+
+__device__ __forceinline__ int64_t remap(int64_t wg, int64_t total)
+{
+    constexpr int64_t kXcds = 8;
+    if (total % kXcds != 0) return wg;
+    return (wg % kXcds) * (total / kXcds) + wg / kXcds;
+}
+
+__device__ __forceinline__ int64_t y_offset(const ContractArgs& a, int64_t o)
+{
+    return (o / a.Olo) * a.sYohi + (o % a.Olo) * a.sYolo;
+}
+
+// (a, b) -> packed (bf16(a) | bf16(b) << 16), round to nearest even
+__device__ __forceinline__ unsigned pack_bf16(float a, float b)
+{
+    bf16x2 p = __builtin_convertvector(f32x2{a, b}, bf16x2);
+    return __builtin_bit_cast(unsigned, p);
+}
+__device__ __forceinline__ float lo_as_float(unsigned p) { return __builtin_bit_cast(float, p << 16); }
+__device__ __forceinline__ float hi_as_float(unsigned p) { return __builtin_bit_cast(float, p & 0xffff0000u); }
+
+// Split 8 floats into three bf16 levels, each returned as 8 packed bf16 (16 bytes).
+__device__ __forceinline__ void split8(const float (&x)[8], u32x4& l0, u32x4& l1, u32x4& l2)
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const float a = x[2 * q], b = x[2 * q + 1];
+        const unsigned p0 = pack_bf16(a, b);
+        const float ra = a - lo_as_float(p0), rb = b - hi_as_float(p0);      // exact
+        const unsigned p1 = pack_bf16(ra, rb);
+        const float sa = ra - lo_as_float(p1), sb = rb - hi_as_float(p1);    // exact
+        const unsigned p2 = pack_bf16(sa, sb);
+        l0[q] = p0;
+        l1[q] = p1;
+        l2[q] = p2;
+    }
+}
+
+__device__ __forceinline__ f32x16 mfma_bf16(u32x4 a, u32x4 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b),
+                                                  c, 0, 0, 0);
+}
+
+template <bool STRIDED>
+__global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int tilesK, int64_t tilesOther,
+                                                           int64_t total)
+{
+    // [buffer][plane][row][3 x 16 bytes]: slots 0, 1 hold n = 0..7, 8..15 of the chunk, slot 2 is padding
+    __shared__ u32x4 RT[2][kPlanes][TM][3];
+    __shared__ u32x4 CT[2][kPlanes][TN][3];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wr0 = (wave >> 1) * 64;      // wave tile origin inside the 128 x 128 tile
+    const int wc0 = (wave & 1) * 64;
+    const int l32 = lane & 31;
+    const int kq = lane >> 5;
+
+    int64_t t = block_id();
+    if (t >= total) return;
+    t = remap(t, total);
+    const int kt = (int)(t % tilesK);
+    t /= tilesK;
+    const int k0 = kt * 128;
+
+    const int N = a.M.N;
+    const int64_t I = a.I;
+    const int ldn = a.M.split_ld;
+    const int64_t plane_stride = (int64_t)a.M.split_rows * ldn;
+    const unsigned short* __restrict__ Vs = a.M.split;
+
+    // this thread's piece of the matrix tile: row = tid / 2 (k), 8 consecutive n
+    const int vrow = tid >> 1, vhalf = tid & 1;
+    const unsigned short* vsrc = Vs + (int64_t)(k0 + vrow) * ldn + 8 * vhalf;
+
+    // this thread's piece of the data tile
+    int64_t tile_o = 0, c0 = 0, o0 = 0;
+    const float2* xsrc;
+    int xrow, xhalf;                       // LDS destination (row or column, which half of the chunk)
+    if (STRIDED) {
+        tile_o = t / tilesOther;
+        c0 = (t % tilesOther) * TN;
+        xrow = tid & 127;                  // column of the tile
+        xhalf = tid >> 7;                  // n = 8*xhalf .. +7, one load per n (stride I)
+        xsrc = a.X + tile_o * (int64_t)N * I + (int64_t)(8 * xhalf) * I + c0 + xrow;
+    } else {
+        o0 = t * TM;
+        xrow = tid >> 1;                   // row o of the tile
+        xhalf = tid & 1;                   // 8 consecutive n, contiguous in memory
+        xsrc = a.X + (o0 + xrow) * (int64_t)N + 8 * xhalf;
+    }
+
+    u32x4 vreg[kPlanes];
+    f32x2 xreg[8];
+    auto gload = [&](int n0) {
+#pragma unroll
+        for (int p = 0; p < kPlanes; ++p)
+            vreg[p] = *reinterpret_cast<const u32x4*>(vsrc + p * plane_stride + n0);
+        if (STRIDED) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                xreg[e] = *reinterpret_cast<const f32x2*>(xsrc + (int64_t)(n0 + e) * I);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(xsrc + n0 + 2 * e);
+                xreg[2 * e] = f32x2{v.x, v.y};
+                xreg[2 * e + 1] = f32x2{v.z, v.w};
+            }
+        }
+    };
+    const unsigned vflip = a.conj ? 0x80008000u : 0u;      // conjugate the matrix: flip the sign of Im
+    auto lstore = [&](int buf) {
+        u32x4 (*Vt)[TM][3] = STRIDED ? RT[buf] : CT[buf];
+        u32x4 (*Xt)[TM][3] = STRIDED ? CT[buf] : RT[buf];
+#pragma unroll
+        for (int p = 0; p < kPlanes; ++p) {
+            u32x4 v = vreg[p];
+            if (p >= 3) v ^= vflip;
+            Vt[p][vrow][vhalf] = v;
+        }
+        float xr[8], xi[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            xr[e] = xreg[e].x;
+            xi[e] = xreg[e].y;
+        }
+        u32x4 s0, s1, s2;
+        split8(xr, s0, s1, s2);
+        Xt[0][xrow][xhalf] = s0;
+        Xt[1][xrow][xhalf] = s1;
+        Xt[2][xrow][xhalf] = s2;
+        split8(xi, s0, s1, s2);
+        Xt[3][xrow][xhalf] = s0;
+        Xt[4][xrow][xhalf] = s1;
+        Xt[5][xrow][xhalf] = s2;
+    };
+
+    f32x16 accr[2][2], acci[2][2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                accr[rb][cb][v] = 0.f;
+                acci[rb][cb][v] = 0.f;
+            }
+
+    const int nchunks = N / KC;
+    gload(0);
+    lstore(0);
+    if (nchunks > 1) gload(KC);
+    __syncthreads();
+
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < nchunks) lstore(buf ^ 1);          // chunk c+1, requested one chunk ago
+        if (c + 2 < nchunks) gload((c + 2) * KC);
+
+        // operands of this chunk: 2 row blocks and 2 column blocks, 6 planes each
+        u32x4 Rr[2][3], Ri[2][3], Cr[2][3], Ci[2][3];
+#pragma unroll
+        for (int lvl = 0; lvl < 3; ++lvl)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                Rr[b][lvl] = RT[buf][lvl][wr0 + b * 32 + l32][kq];
+                Cr[b][lvl] = CT[buf][lvl][wc0 + b * 32 + l32][kq];
+                Ri[b][lvl] = RT[buf][3 + lvl][wr0 + b * 32 + l32][kq];
+                Ci[b][lvl] = CT[buf][3 + lvl][wc0 + b * 32 + l32][kq];
+            }
+        // the six cross products, smallest first; Im = Rr*Ci + Ri*Cr, Re = Rr*Cr - Ri*Ci
+        constexpr int PL[6] = {1, 2, 0, 1, 0, 0};
+        constexpr int QL[6] = {1, 0, 2, 0, 1, 0};
+#pragma unroll
+        for (int pq = 0; pq < 6; ++pq) {
+            // three passes over the four blocks so consecutive MFMAs never share an accumulator
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+                    acci[rb][cb] = mfma_bf16(Rr[rb][PL[pq]], Ci[cb][QL[pq]], acci[rb][cb]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+                    accr[rb][cb] = mfma_bf16(Rr[rb][PL[pq]], Cr[cb][QL[pq]], accr[rb][cb]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+                    acci[rb][cb] = mfma_bf16(Ri[rb][PL[pq]], Cr[cb][QL[pq]], acci[rb][cb]);
+        }
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int lvl = 0; lvl < 3; ++lvl) Ri[rb][lvl] ^= 0x80008000u;       // -Ri
+#pragma unroll
+        for (int pq = 0; pq < 6; ++pq)
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+                    accr[rb][cb] = mfma_bf16(Ri[rb][PL[pq]], Ci[cb][QL[pq]], accr[rb][cb]);
+        __syncthreads();
+    }
+
+    // epilogue: accumulator register v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const int col = wc0 + cb * 32 + l32;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = wr0 + rb * 32 + 8 * (v / 4) + 4 * kq + (v % 4);
+                const f32x2 y = f32x2{accr[rb][cb][v] * a.scale, acci[rb][cb][v] * a.scale};
+                if (STRIDED) {
+                    float2* Yo = a.Y + y_offset(a, tile_o);
+                    *reinterpret_cast<f32x2*>(Yo + (int64_t)(k0 + row) * a.sYk + c0 + col) = y;
+                } else {
+                    *reinterpret_cast<f32x2*>(a.Y + y_offset(a, o0 + row) + (int64_t)(k0 + col) * a.sYk) = y;
+                }
+            }
+        }
+    }
+}
+
+inline dim3 grid_for(int64_t blocks)
+{
+    const int64_t kMaxX = 1 << 22;
+    if (blocks <= kMaxX) return dim3((unsigned)blocks);
+    return dim3((unsigned)kMaxX, (unsigned)((blocks + kMaxX - 1) / kMaxX));
+}
+
+}  // namespace
+
+bool contract_bf16x3_supported(const ContractArgs& a)
+{
+    if (!a.M.split || a.Tw) return false;
+    const int K = a.M.K, N = a.M.N;
+    if (K % 128 != 0 || N % KC != 0 || N < KC) return false;
+    if (a.I == 1) return a.O % TM == 0;
+    return a.I % TN == 0;
+}
+
+hipError_t launch_contract_bf16x3(const ContractArgs& a, hipStream_t stream)
+{
+    const int tk = a.M.K / 128;
+    if (a.I == 1) {
+        // contiguous mode: rows = o, columns = k; the k-tile index runs fastest
+        const int64_t to = a.O / TM;
+        const int64_t total = (int64_t)tk * to;
+        hipLaunchKernelGGL(k_contract_bf16x3<false>, grid_for(total), dim3(kT), 0, stream, a, tk, to, total);
+    } else {
+        const int64_t ti = a.I / TN;
+        const int64_t total = (int64_t)tk * ti * a.O;
+        hipLaunchKernelGGL(k_contract_bf16x3<true>, grid_for(total), dim3(kT), 0, stream, a, tk, ti, total);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace dft3d

@@ -25,6 +25,12 @@ struct DeviceMatrix {
     int N = 0;     // contracted length (columns of M)
     int ld = 0;    // padded K
     int rows = 0;  // padded N
+    // Optional bf16 decomposition of the same matrix for the bf16-split contraction: six planes
+    // (Re hi, mid, lo, Im hi, mid, lo), each split_rows x split_ld bf16, ROW-major [k][n] with n
+    // contiguous (a bf16 MFMA operand lane holds 8 consecutive n), zero padded.
+    unsigned short* split = nullptr;
+    int split_ld = 0;     // padded N (multiple of 16)
+    int split_rows = 0;   // padded K (multiple of 128)
 };
 
 // ---- one mode contraction ---------------------------------------------------------------
@@ -45,9 +51,15 @@ struct ContractArgs {
     float scale;
     int conj;
     int three_m;   // use the three-real-product complex scheme where a kernel for it exists
+    int bf16x3;    // use the bf16-split kernel (M.split must be set) where the shape allows
 };
 
 hipError_t launch_contract(const ContractArgs& a, hipStream_t stream);
+
+// bf16-split variant (three bf16 levels per fp32 number, six cross products on bf16 MFMA);
+// only whole 128 x 128 tiles, no fused twiddle.
+bool contract_bf16x3_supported(const ContractArgs& a);
+hipError_t launch_contract_bf16x3(const ContractArgs& a, hipStream_t stream);
 
 // ---- twiddle (phase) multiply -------------------------------------------------------------
 // Tensor viewed as [outer][A][B][inner]; out = in * Tw[k_a * B + beta] (conjugated if conj).

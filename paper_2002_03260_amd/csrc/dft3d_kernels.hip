@@ -1239,6 +1239,7 @@ hipError_t launch_contract(const ContractArgs& a, hipStream_t stream)
 {
     const int K = a.M.K, N = a.M.N;
     if (a.O <= 0 || a.I <= 0 || K <= 0 || N <= 0) return hipSuccess;
+    if (a.bf16x3 && contract_bf16x3_supported(a)) return launch_contract_bf16x3(a, stream);
     constexpr int64_t kFillTiles = 512;   // two workgroups on each of the 256 CUs
     if (a.I == 1) {
         if (N <= 32 && K <= 32) return launch_c<128, 32, 32, 32, 16>(a, stream);

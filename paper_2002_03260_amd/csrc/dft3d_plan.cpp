@@ -30,7 +30,64 @@ inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 void free_matrix(DeviceMatrix& m)
 {
     if (m.re) (void)hipFree(m.re);
+    if (m.split) (void)hipFree(m.split);
     m = DeviceMatrix{};
+}
+
+// round-to-nearest-even conversion of a double to bfloat16 (returned as its 16 bits)
+unsigned short to_bf16(double v)
+{
+    float f = (float)v;
+    unsigned u;
+    std::memcpy(&u, &f, 4);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (unsigned short)(u >> 16);   // inf / nan
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+double from_bf16(unsigned short h)
+{
+    unsigned u = (unsigned)h << 16;
+    float f;
+    std::memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+// Build and upload the three-level bf16 decomposition of a K x N complex matrix given as fp64
+// row-major planes: v = v1 + v2 + v3 with vj = bf16(v - v1 - .. - v(j-1)).
+dft3d_status upload_split(const std::vector<double>& re, const std::vector<double>& im, int K, int N,
+                          DeviceMatrix* m)
+{
+    const int ld = round_up(N, 16), rows = round_up(K, 128);
+    const size_t plane = (size_t)ld * rows;
+    std::vector<unsigned short> host(6 * plane, 0);
+    for (int part = 0; part < 2; ++part) {
+        const std::vector<double>& src = part ? im : re;
+        for (int k = 0; k < K; ++k)
+            for (int n = 0; n < N; ++n) {
+                double r = src[(size_t)k * N + n];
+                for (int lvl = 0; lvl < 3; ++lvl) {
+                    const unsigned short h = to_bf16(r);
+                    host[(size_t)(3 * part + lvl) * plane + (size_t)k * ld + n] = h;
+                    r -= from_bf16(h);
+                }
+            }
+    }
+    unsigned short* dev = nullptr;
+    hipError_t e = hipMalloc((void**)&dev, 6 * plane * sizeof(unsigned short));
+    if (e != hipSuccess) {
+        set_error("hipMalloc of the bf16 decomposition of a %d x %d matrix failed: %s", K, N, hipGetErrorString(e));
+        return DFT3D_ERR_ALLOC;
+    }
+    e = hipMemcpy(dev, host.data(), 6 * plane * sizeof(unsigned short), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(dev);
+        set_error("upload of the bf16 decomposition failed: %s", hipGetErrorString(e));
+        return DFT3D_ERR_HIP;
+    }
+    m->split = dev;
+    m->split_ld = ld;
+    m->split_rows = rows;
+    return DFT3D_OK;
 }
 
 // Upload a K x N complex matrix given as row-major host planes into the padded, transposed
@@ -68,12 +125,21 @@ dft3d_status upload_matrix(const std::vector<float>& re, const std::vector<float
     return DFT3D_OK;
 }
 
-dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out)
+dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out, bool with_split = false)
 {
     std::vector<float> re((size_t)n * n), im((size_t)n * n);
     dft3d_status s = dft3d_generate_matrix(n, coords, DFT3D_FORWARD, re.data(), im.data());
     if (s != DFT3D_OK) return s;
-    return upload_matrix(re, im, (int)n, (int)n, out);
+    s = upload_matrix(re, im, (int)n, (int)n, out);
+    if (s != DFT3D_OK || !with_split) return s;
+    // the bf16 levels are taken from the fp64 entries, not from their fp32 roundings
+    std::vector<double> dre((size_t)n * n), dim((size_t)n * n);
+    for (int64_t k = 0; k < n; ++k)
+        for (int64_t j = 0; j < n; ++j) {
+            if (coords) unit_root_turns((double)k * coords[j], DFT3D_FORWARD, &dre[k * n + j], &dim[k * n + j]);
+            else unit_root_ratio(k * j, n, DFT3D_FORWARD, &dre[k * n + j], &dim[k * n + j]);
+        }
+    return upload_split(dre, dim, (int)n, (int)n, out);
 }
 
 // Default first-stage length: 2^floor(log2(N)/2) for powers of two, else the divisor pair
@@ -183,6 +249,7 @@ hipError_t run_mode(const dft3d_plan_s* p, int axis, const float2* in, float2* o
     a.scale = scale;
     a.conj = conj;
     a.three_m = (p->flags & DFT3D_FLAG_3M) ? 1 : 0;
+    a.bf16x3 = (p->flags & DFT3D_FLAG_BF16X3) ? 1 : 0;
     return launch_contract(a, st);
 }
 
@@ -334,7 +401,7 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
         set_error("plan_create: unknown formulation %d", (int)f);
         return DFT3D_ERR_INVALID_ARG;
     }
-    if (flags & ~(DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_UNFUSED | DFT3D_FLAG_3M)) {
+    if (flags & ~(DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_UNFUSED | DFT3D_FLAG_3M | DFT3D_FLAG_BF16X3)) {
         set_error("plan_create: unknown flag bits 0x%x", flags);
         return DFT3D_ERR_INVALID_ARG;
     }
@@ -364,7 +431,7 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
             p->M_owner[j] = j;
             for (int i = 0; i < j; ++i)
                 if (!c[j] && !c[i] && n[i] == n[j]) { p->M_owner[j] = i; break; }
-            if (p->M_owner[j] == j) s = make_axis_matrix(n[j], c[j], &p->M[j]);
+            if (p->M_owner[j] == j) s = make_axis_matrix(n[j], c[j], &p->M[j], (flags & DFT3D_FLAG_BF16X3) != 0);
             else p->M[j] = p->M[p->M_owner[j]];
         }
     } else {

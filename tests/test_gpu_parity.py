@@ -162,6 +162,24 @@ def test_kdft_arbitrary_evaluation_points(dft, shape, ks):
             assert report(f"points mode {axis}", to_host(yd), y) <= TOL
 
 
+@pytest.mark.parametrize("shape", [(128, 128, 128), (256, 256, 256), (128, 384, 256), (130, 256, 128)])
+def test_kdft_bf16_split_scheme(dft, shape):
+    """DFT3D_FLAG_BF16X3: three bf16 levels per fp32 number on the bf16 matrix cores; same tolerance."""
+    say(f"case kdft bf16x3 {shape}")
+    x = wl.draw_complex(shape, "normal", 2700 + sum(shape))
+    want = orc.dft3d(x)
+    with dft.Plan(shape, dft.KDFT, flags=dft.FLAG_BF16X3) as p:
+        xd = to_dev(x)
+        got = to_host(p.exec(xd))
+        assert report(f"kdft bf16x3 {shape}", got, want) <= TOL
+        gotb = to_host(p.exec(xd, direction=dft.BACKWARD))
+        assert report(f"kdft bf16x3 backward {shape}", gotb, orc.dft3d(x, sign=orc.BACKWARD)) <= TOL
+        for axis in range(3):
+            M = orc.dft_matrix(shape[axis])
+            gm = to_host(p.mode_contract(axis, xd))
+            assert report(f"bf16x3 mode {axis}", gm, orc.mode_contract(M, x, axis)) <= TOL
+
+
 def test_kdft_clobber_input(dft):
     shape = (16, 24, 40)
     x = wl.draw_complex(shape, "normal", 78)
