@@ -21,6 +21,8 @@
 // Double-buffered LDS, register-staged prefetch one chunk ahead, one barrier per chunk.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "dft3d_internal.h"
 
 namespace dft3d {
@@ -75,6 +77,17 @@ __device__ __forceinline__ void split8(const float (&x)[8], u32x4& l0, u32x4& l1
         l0[q] = p0;
         l1[q] = p1;
         l2[q] = p2;
+    }
+}
+
+// f(integral_constant<int, B>), ..., f(integral_constant<int, E - 1>): unrolling that does not depend
+// on the optimizer's size limits
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
     }
 }
 
@@ -134,50 +147,76 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int t
         xsrc = a.X + (o0 + xrow) * (int64_t)N + 8 * xhalf;
     }
 
+    // Register staging of the global loads: every register is requested again right after the
+    // staging code has consumed it, so a load has almost a whole iteration (~1.5 us of MFMA work)
+    // to arrive.  (Two register sets and a distance of two iterations measured slower.)
     u32x4 vreg[kPlanes];
     f32x2 xreg[8];
-    auto gload = [&](int n0) {
-#pragma unroll
-        for (int p = 0; p < kPlanes; ++p)
-            vreg[p] = *reinterpret_cast<const u32x4*>(vsrc + p * plane_stride + n0);
+    constexpr int kXLoads = STRIDED ? 8 : 4;
+    auto load_v = [&](int n0, int p) {
+        vreg[p] = *reinterpret_cast<const u32x4*>(vsrc + p * plane_stride + n0);
+    };
+    auto load_x = [&](int n0, int j) {           // j < kXLoads
         if (STRIDED) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                xreg[e] = *reinterpret_cast<const f32x2*>(xsrc + (int64_t)(n0 + e) * I);
+            xreg[j] = *reinterpret_cast<const f32x2*>(xsrc + (int64_t)(n0 + j) * I);
         } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const f32x4 v = *reinterpret_cast<const f32x4*>(xsrc + n0 + 2 * e);
-                xreg[2 * e] = f32x2{v.x, v.y};
-                xreg[2 * e + 1] = f32x2{v.z, v.w};
-            }
+            const f32x4 v = *reinterpret_cast<const f32x4*>(xsrc + n0 + 2 * j);
+            xreg[2 * j] = f32x2{v.x, v.y};
+            xreg[2 * j + 1] = f32x2{v.z, v.w};
         }
     };
+    auto gload = [&](int n0) {           // same order as the main loop requests them
+#pragma unroll
+        for (int j = 0; j < kXLoads; ++j) load_x(n0, j);
+#pragma unroll
+        for (int p = 0; p < kPlanes; ++p) load_v(n0, p);
+    };
+
+    // Staging of a chunk into LDS, cut into small steps.  The data values are split into their
+    // three bf16 levels two at a time (pair q = values 2q, 2q+1 of the 8 this thread holds; part 0 =
+    // real, 1 = imaginary); a split takes three steps (one per level).
     const unsigned vflip = a.conj ? 0x80008000u : 0u;      // conjugate the matrix: flip the sign of Im
-    auto lstore = [&](int buf) {
-        u32x4 (*Vt)[TM][3] = STRIDED ? RT[buf] : CT[buf];
+    u32x4 lv[2][3];                 // [part][level], dword q = pair q
+    float res0[2], res1[2];         // residuals carried between the steps of one split, per part
+    auto split_step = [&](int part, int q, int step) {
+        if (step == 0) {
+            const float x0 = part ? xreg[2 * q].y : xreg[2 * q].x;
+            const float x1 = part ? xreg[2 * q + 1].y : xreg[2 * q + 1].x;
+            const unsigned p0 = pack_bf16(x0, x1);
+            res0[part] = x0 - lo_as_float(p0);      // exact
+            res1[part] = x1 - hi_as_float(p0);
+            lv[part][0][q] = p0;
+        } else if (step == 1) {
+            const unsigned p1 = pack_bf16(res0[part], res1[part]);
+            res0[part] -= lo_as_float(p1);          // exact
+            res1[part] -= hi_as_float(p1);
+            lv[part][1][q] = p1;
+        } else {
+            lv[part][2][q] = pack_bf16(res0[part], res1[part]);
+        }
+    };
+    auto store_x = [&](int buf, int part, int level) {
         u32x4 (*Xt)[TM][3] = STRIDED ? CT[buf] : RT[buf];
+        Xt[3 * part + level][xrow][xhalf] = lv[part][level];
+    };
+    auto store_v = [&](int buf, int p) {
+        u32x4 (*Vt)[TM][3] = STRIDED ? RT[buf] : CT[buf];
+        u32x4 v = vreg[p];
+        if (p >= 3) v ^= vflip;
+        Vt[p][vrow][vhalf] = v;
+    };
+    auto lstore = [&](int buf) {
 #pragma unroll
-        for (int p = 0; p < kPlanes; ++p) {
-            u32x4 v = vreg[p];
-            if (p >= 3) v ^= vflip;
-            Vt[p][vrow][vhalf] = v;
-        }
-        float xr[8], xi[8];
+        for (int part = 0; part < 2; ++part) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            xr[e] = xreg[e].x;
-            xi[e] = xreg[e].y;
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int step = 0; step < 3; ++step) split_step(part, q, step);
+#pragma unroll
+            for (int level = 0; level < 3; ++level) store_x(buf, part, level);
         }
-        u32x4 s0, s1, s2;
-        split8(xr, s0, s1, s2);
-        Xt[0][xrow][xhalf] = s0;
-        Xt[1][xrow][xhalf] = s1;
-        Xt[2][xrow][xhalf] = s2;
-        split8(xi, s0, s1, s2);
-        Xt[3][xrow][xhalf] = s0;
-        Xt[4][xrow][xhalf] = s1;
-        Xt[5][xrow][xhalf] = s2;
+#pragma unroll
+        for (int p = 0; p < kPlanes; ++p) store_v(buf, p);
     };
 
     f32x16 accr[2][2], acci[2][2];
@@ -192,60 +231,91 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int t
             }
 
     const int nchunks = N / KC;
+    auto chunk_n0 = [&](int j) { return (j < nchunks ? j : nchunks - 1) * KC; };     // clamped: tail re-reads the last chunk
     gload(0);
     lstore(0);
-    if (nchunks > 1) gload(KC);
+    gload(chunk_n0(1));
     __syncthreads();
 
+    // Level pairs of the six cross products.  With R = Rr + i Ri and C = Cr + i Ci,
+    // Im = Ri*Cr + Rr*Ci and Re = Rr*Cr - Ri*Ci: four phases of 24 MFMAs, inside a phase the four
+    // blocks of the wave tile take turns so neighbours never share an accumulator.
+    //
+    // A wave issues in order and only one MFMA (32 cycles) can be in flight ahead of it, so the
+    // wave's other work of the iteration -- converting and storing chunk c+1, requesting chunk
+    // c+2, negating Ri -- is cut into steps of a few instructions and at most one step is placed
+    // in front of each of the 96 MFMAs, where it issues in the shadow of the previous one.
+    constexpr int PL[6] = {1, 2, 0, 1, 0, 0};
+    constexpr int QL[6] = {1, 0, 2, 0, 1, 0};
+    // The steps in order: per pair 3 + 3 split steps and the pair's loads; 6 negations of Ri
+    // operands; 6 stores of the data levels; 6 x (store a matrix plane, request it again).  They are
+    // spread evenly over the 96 MFMA slots.
+    constexpr int kPerPair = 6 + kXLoads / 4;
+    constexpr int kNegAt = 4 * kPerPair;
+    constexpr int kXStoreAt = kNegAt + 6;
+    constexpr int kVAt = kXStoreAt + 6;
+    constexpr int kSteps = kVAt + 12;
+    static_assert(kSteps <= 96, "one step per MFMA at most");
+    // Ri is negated between its positive uses (phase 0, slots < 24) and its negative ones (>= 72)
+    static_assert((kNegAt * 96) / kSteps >= 24 && ((kNegAt + 5) * 96) / kSteps < 72, "negation slots");
     for (int c = 0; c < nchunks; ++c) {
         const int buf = c & 1;
-        if (c + 1 < nchunks) lstore(buf ^ 1);          // chunk c+1, requested one chunk ago
-        if (c + 2 < nchunks) gload((c + 2) * KC);
+        const int n2 = chunk_n0(c + 2);
 
-        // operands of this chunk: 2 row blocks and 2 column blocks, 6 planes each
+        // MFMAs of chunk c from LDS buffer c % 2; chunk c+1 goes to the other buffer (after the last
+        // chunk: a harmless re-store, nobody reads it)
         u32x4 Rr[2][3], Ri[2][3], Cr[2][3], Ci[2][3];
 #pragma unroll
-        for (int lvl = 0; lvl < 3; ++lvl)
+        for (int j = 0; j < 3; ++j) {
+            const int lr = PL[j], lc = QL[j];        // (1,1), (2,0), (0,2): each level once, in order of first use
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
-                Rr[b][lvl] = RT[buf][lvl][wr0 + b * 32 + l32][kq];
-                Cr[b][lvl] = CT[buf][lvl][wc0 + b * 32 + l32][kq];
-                Ri[b][lvl] = RT[buf][3 + lvl][wr0 + b * 32 + l32][kq];
-                Ci[b][lvl] = CT[buf][3 + lvl][wc0 + b * 32 + l32][kq];
+                Ri[b][lr] = RT[buf][3 + lr][wr0 + b * 32 + l32][kq];
+                Cr[b][lc] = CT[buf][lc][wc0 + b * 32 + l32][kq];
             }
-        // the six cross products, smallest first; Im = Rr*Ci + Ri*Cr, Re = Rr*Cr - Ri*Ci
-        constexpr int PL[6] = {1, 2, 0, 1, 0, 0};
-        constexpr int QL[6] = {1, 0, 2, 0, 1, 0};
-#pragma unroll
-        for (int pq = 0; pq < 6; ++pq) {
-            // three passes over the four blocks so consecutive MFMAs never share an accumulator
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
-                    acci[rb][cb] = mfma_bf16(Rr[rb][PL[pq]], Ci[cb][QL[pq]], acci[rb][cb]);
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
-                    accr[rb][cb] = mfma_bf16(Rr[rb][PL[pq]], Cr[cb][QL[pq]], accr[rb][cb]);
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
-                    acci[rb][cb] = mfma_bf16(Ri[rb][PL[pq]], Cr[cb][QL[pq]], acci[rb][cb]);
         }
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int j = 0; j < 3; ++j) {
+            const int lr = PL[j], lc = QL[j];
 #pragma unroll
-            for (int lvl = 0; lvl < 3; ++lvl) Ri[rb][lvl] ^= 0x80008000u;       // -Ri
-#pragma unroll
-        for (int pq = 0; pq < 6; ++pq)
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
-                    accr[rb][cb] = mfma_bf16(Ri[rb][PL[pq]], Ci[cb][QL[pq]], accr[rb][cb]);
+            for (int b = 0; b < 2; ++b) {
+                Rr[b][lr] = RT[buf][lr][wr0 + b * 32 + l32][kq];
+                Ci[b][lc] = CT[buf][3 + lc][wc0 + b * 32 + l32][kq];
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        static_for<0, 96>([&](auto slot) {
+            constexpr int s = decltype(slot)::value;
+            // ---- at most one step of side work: step i sits in slot i * 96 / kSteps
+            constexpr int step = (s * kSteps + 95) / 96;
+            if constexpr (step < kSteps && (step * 96) / kSteps == s) {
+                if constexpr (step < kNegAt) {
+                    constexpr int q = step / kPerPair, w = step % kPerPair;
+                    if constexpr (w < 6) split_step(w / 3, q, w % 3);
+                    else if constexpr (STRIDED) load_x(n2, 2 * q + (w - 6));
+                    else load_x(n2, q);
+                } else if constexpr (step < kXStoreAt) {
+                    constexpr int w = step - kNegAt;
+                    Ri[w & 1][w >> 1] ^= 0x80008000u;
+                } else if constexpr (step < kVAt) {
+                    constexpr int w = step - kXStoreAt;
+                    store_x(buf ^ 1, w / 3, w % 3);
+                } else {
+                    constexpr int w = step - kVAt;
+                    if constexpr ((w & 1) == 0) store_v(buf ^ 1, w >> 1);
+                    else load_v(n2, w >> 1);
+                }
+            }
+            // ---- one MFMA
+            constexpr int phase = s / 24, pq = (s % 24) / 4, rb = (s >> 1) & 1, cb = s & 1;
+            constexpr int lr = PL[pq], lc = QL[pq];
+            if constexpr (phase == 0) acci[rb][cb] = mfma_bf16(Ri[rb][lr], Cr[cb][lc], acci[rb][cb]);
+            else if constexpr (phase == 1) acci[rb][cb] = mfma_bf16(Rr[rb][lr], Ci[cb][lc], acci[rb][cb]);
+            else if constexpr (phase == 2) accr[rb][cb] = mfma_bf16(Rr[rb][lr], Cr[cb][lc], accr[rb][cb]);
+            else accr[rb][cb] = mfma_bf16(Ri[rb][lr], Ci[cb][lc], accr[rb][cb]);      // Ri negated
+            __builtin_amdgcn_sched_barrier(0);
+        });
         __syncthreads();
     }
 
