@@ -95,7 +95,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="cfg2",
-                    help="cfg1..cfg4, cfg5-kdft, cfg5-fft, or copy (default cfg2 = KDFT 256^3)")
+                    help="cfg1..cfg4, cfg5-kdft, cfg5-fft, 2d-8192-kdft, 2d-8192-fft or copy (default cfg2 = KDFT 256^3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--three-m", action="store_true",
                     help="KDFT: three real products per complex product (DFT3D_FLAG_3M)")
@@ -152,9 +152,9 @@ def main() -> int:
                                        "bytes_per_launch": 2.0 * n * 8}}), flush=True)
         return 0
     form_override = None
-    if name.startswith("cfg5"):
+    if name.startswith("cfg5") or name.startswith("2d-8192"):
         form_override = dft.FFT if name.endswith("fft") else dft.KDFT
-        w = wl.WORKLOADS["cfg5"]
+        w = wl.WORKLOADS["cfg5"] if name.startswith("cfg5") else wl.EXTRA_WORKLOADS["2d-8192"]
     else:
         w = wl.WORKLOADS[name]
     form = form_override if form_override is not None else w.formulation
@@ -199,11 +199,13 @@ def main() -> int:
     pass_ms = [sum(p[i] for p in per_exec) / steps for i in range(npass)]
 
     if form == dft.KDFT:
-        pass_names = ["mode_z(contiguous)", "mode_y(strided)", "mode_x(strided)"]
-        # the strided contraction kernel runs two of the three passes: the dominant kernel
-        dom = [1, 2]
+        # one pass per axis of length > 1, in the order z, y, x
+        live = [ax for ax in (2, 1, 0) if w.shape[ax] > 1] or [2]
+        pass_names = [f"mode_{'xyz'[ax]}({'contiguous' if ax == 2 else 'strided'})" for ax in live]
+        # the strided contraction kernel runs all passes but the first: the dominant kernel
+        dom = [i for i, ax in enumerate(live) if ax != 2] or [0]
         dom_ms = sum(pass_ms[i] for i in dom) / len(dom)
-        n_dom = sum(w.shape[2 - i] for i in dom) / len(dom)       # contracted length of those passes
+        n_dom = sum(w.shape[live[i]] for i in dom) / len(dom)     # contracted length of those passes
         # 4 (or, with --three-m, 3) real products per complex multiply-add
         flops = (6.0 if args.three_m else 8.0) * n_dom * E
         roofline = {
@@ -225,6 +227,8 @@ def main() -> int:
                       "x_stage1+twiddle", "x_stage2+reorder", "z_reorder"]
         if args.unfused:
             pass_names = [f"{ax}_{st}" for ax in "zyx" for st in ("stage1", "phase", "stage2")] + ["reorder_xyz"]
+        elif w.shape[0] == 1:
+            pass_names = pass_names[0:4] + ["z_reorder"]          # no pass for the axis of length 1
         elif npass == 5:
             pass_names = ["z_fused_axis"] + pass_names[2:6]
         elif npass == 3:

@@ -51,6 +51,13 @@ WORKLOADS = {
                      splits=((32, 64),) * 3),
 }
 
+# Beyond the five configurations: the paper's two-dimensional size (Section IV, strong-scaling
+# figure of the 2-D KDFT), given as a 3-D shape whose first axis has length 1.
+EXTRA_WORKLOADS = {
+    "2d-8192": Workload("next_2d_8192", 6, (1, 8192, 8192), KDFT, "normal",
+                        splits=((1, 1), (64, 128), (64, 128))),
+}
+
 
 def draw_complex(shape, dist: str, seed: int) -> np.ndarray:
     """complex64 tensor whose real and imaginary parts are iid ``dist`` from ``seed``."""

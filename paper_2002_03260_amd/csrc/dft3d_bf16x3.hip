@@ -63,23 +63,6 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b)
 __device__ __forceinline__ float lo_as_float(unsigned p) { return __builtin_bit_cast(float, p << 16); }
 __device__ __forceinline__ float hi_as_float(unsigned p) { return __builtin_bit_cast(float, p & 0xffff0000u); }
 
-// Split 8 floats into three bf16 levels, each returned as 8 packed bf16 (16 bytes).
-__device__ __forceinline__ void split8(const float (&x)[8], u32x4& l0, u32x4& l1, u32x4& l2)
-{
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const float a = x[2 * q], b = x[2 * q + 1];
-        const unsigned p0 = pack_bf16(a, b);
-        const float ra = a - lo_as_float(p0), rb = b - hi_as_float(p0);      // exact
-        const unsigned p1 = pack_bf16(ra, rb);
-        const float sa = ra - lo_as_float(p1), sb = rb - hi_as_float(p1);    // exact
-        const unsigned p2 = pack_bf16(sa, sb);
-        l0[q] = p0;
-        l1[q] = p1;
-        l2[q] = p2;
-    }
-}
-
 // f(integral_constant<int, B>), ..., f(integral_constant<int, E - 1>): unrolling that does not depend
 // on the optimizer's size limits
 template <int B, int E, class F>

@@ -828,18 +828,37 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
     //         3 passes when all axes fuse, 7 when none does.
     //   FFT unfused: per axis first stage, twiddle pass, second stage; one re-ordering pass of
     //         all three axes at the end (10 passes -> starts with in -> other).
+    //   An axis of length 1 (a 2-D or 1-D transform given as n1 = 1 and/or n2 = 1) is the identity
+    //   and takes no pass, unless that would leave no pass at all or, with CLOBBER_INPUT, an even
+    //   number of them.
     const bool zfused = !unfused && z_axis_fusable(p);
     bool sfused[2] = {!unfused && strided_axis_fusable(p, 0), !unfused && strided_axis_fusable(p, 1)};
+    bool skip[3] = {!unfused && p->n[0] == 1, !unfused && p->n[1] == 1, !unfused && p->n[2] == 1};
     auto count_passes = [&]() {
-        if (p->form != DFT3D_FFT) return 3;
+        if (p->form != DFT3D_FFT) return 3 - (int)skip[0] - (int)skip[1] - (int)skip[2];
         if (unfused) return 10;
-        return (zfused ? 1 : 3) + (sfused[0] ? 1 : 2) + (sfused[1] ? 1 : 2);
+        int c = 0;
+        if (!skip[2]) c += zfused ? 1 : 3;
+        for (int axis = 0; axis < 2; ++axis)
+            if (!skip[axis]) c += sfused[axis] ? 1 : 2;
+        return c;
     };
     int npass = count_passes();
+    if (npass == 0) {
+        skip[2] = false;
+        npass = count_passes();
+    }
     if (clobber && (npass % 2 == 0)) {
-        // ping-ponging between in and out needs an odd pass count: split one fused strided axis
-        if (sfused[1]) sfused[1] = false;
-        else if (sfused[0]) sfused[0] = false;
+        // ping-ponging between in and out needs an odd pass count: try, one at a time, keeping the
+        // identity pass(es) of a length-1 axis or splitting a fused strided axis into its two stages
+        bool* knobs[5] = {&skip[2], &skip[1], &skip[0], &sfused[1], &sfused[0]};
+        for (bool* knob : knobs) {
+            if (!*knob) continue;
+            *knob = false;
+            npass = count_passes();
+            if (npass % 2 == 1) break;
+            *knob = true;
+        }
         npass = count_passes();
         if (npass % 2 == 0) {
             set_error("exec: CLOBBER_INPUT cannot be combined with this pass structure");
@@ -865,12 +884,14 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
     hipError_t e = hipSuccess;
     if (p->form == DFT3D_KDFT) {
         for (int axis = 2; axis >= 0 && e == hipSuccess; --axis) {
+            if (skip[axis]) continue;
             mark(0);
             e = run_mode(p, axis, src, dst, conj, axis_scale(p, axis, direction), st);
             advance();
         }
     } else {
         for (int axis = 2; axis >= 0 && e == hipSuccess; --axis) {
+            if (skip[axis]) continue;
             if (axis == 2 && zfused) {
                 mark(0);
                 e = run_fused_z(p, src, dst, conj, axis_scale(p, axis, direction), st);
@@ -898,7 +919,7 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
             e = run_second_stage(p, axis, src, dst, conj, axis_scale(p, axis, direction), fold, st);
             advance();
         }
-        if (e == hipSuccess && !zfused) {
+        if (e == hipSuccess && !zfused && !skip[2]) {
             mark(0);
             e = run_reorder(p, unfused ? 7 : 4, src, dst, st);
             advance();

@@ -312,6 +312,31 @@ def test_fft_exec_matches_oracle(dft, shape, split, flags):
         assert report(f"fft exec backward {shape}", gotb, orc.dft3d(x, sign=orc.BACKWARD)) <= TOL
 
 
+@pytest.mark.parametrize("shape", [(1, 96, 160), (1, 1, 256), (1, 256, 1), (40, 1, 48), (1, 1, 1), (1, 256, 512)])
+@pytest.mark.parametrize("form", ["kdft", "fft"])
+@pytest.mark.parametrize("flags", [0, 1])
+def test_lower_dimensional_transforms(dft, shape, form, flags):
+    """Axes of length 1 (2-D and 1-D transforms) take no pass; the result is still the 3-D definition."""
+    import torch
+
+    say(f"case {form} {shape} flags {flags}")
+    x = wl.draw_complex(shape, "normal", 7000 + sum(shape))
+    want = orc.dft3d(x)
+    with dft.Plan(shape, dft.KDFT if form == "kdft" else dft.FFT, flags=flags) as p:
+        got = to_host(p.exec(to_dev(x)))
+        assert report(f"{form} {shape} flags {flags}", got, want) <= TOL
+        gotb = to_host(p.exec(to_dev(x), direction=dft.BACKWARD))
+        assert report(f"{form} backward {shape}", gotb, orc.dft3d(x, sign=orc.BACKWARD)) <= TOL
+        if flags == 0:
+            p.enable_profiling(1)
+            p.exec(to_dev(x))
+            torch.cuda.synchronize()
+            npass = len(p.read_profile(0))
+            live = sum(1 for n in shape if n > 1)
+            if form == "kdft":
+                assert npass == max(live, 1)
+
+
 def test_kdft_and_fft_agree(dft):
     import torch
 

@@ -72,6 +72,40 @@ def test_cfg3_fft_512_full_oracle(dft):
     assert r <= TOL
 
 
+@pytest.mark.timeout(600)
+def test_2d_8192_sampled_outputs(dft):
+    """The paper's 2-D size (8192 x 8192, given as 1 x 8192 x 8192): both formulations against
+    oracle values at sampled outputs, against each other everywhere, and Parseval."""
+    import torch
+
+    shape = (1, 8192, 8192)
+    say(f"case 2-D {shape}: drawing input")
+    x = wl.draw_complex(shape, "normal", 200203260 + 77)
+    xd = torch.from_numpy(x).to("cuda")
+    outs = {}
+    for form, name in ((dft.KDFT, "kdft"), (dft.FFT, "fft")):
+        with dft.Plan(shape, form) as p:
+            outs[name] = p.exec(xd)
+            torch.cuda.synchronize()
+        say(f"  {name} done")
+    k2s, k3s = [0, 1, 4097, 8191, 3000], [0, 5, 8191, 4096]
+    say(f"  oracle: outputs at k2 = {k2s}, k3 = {k3s}")
+    want = orc.dft3d_pencils(x, k2s, k3s)
+    for name, out in outs.items():
+        got = out[:, k2s][:, :, k3s].cpu().numpy()
+        r = rel_l2(got, want)
+        say(f"[parity] 2-D 8192 {name} sampled: relL2={r:.3e} max|err|={np.max(np.abs(got - want)):.3e}")
+        assert r <= TOL
+    a, b = outs["kdft"].to(torch.complex128), outs["fft"].to(torch.complex128)
+    r = (torch.linalg.vector_norm(a - b) / torch.linalg.vector_norm(a)).item()
+    say(f"[parity] 2-D 8192 kdft vs fft: relL2={r:.3e}")
+    assert r <= 2 * TOL
+    e_in = torch.linalg.vector_norm(xd.to(torch.complex128)).item() ** 2
+    e_out = torch.linalg.vector_norm(a).item() ** 2 / (8192.0 * 8192.0)
+    say(f"[parity] 2-D 8192 Parseval: {e_out / e_in - 1:.3e}")
+    assert abs(e_out / e_in - 1) <= 1e-5
+
+
 # ----------------------------------------------------------------------------- 2048^3
 def _device_rel_l2(a, b, chunk=64):
     """relative L2 distance of two huge device tensors, reduced in fp64 plane-chunk by chunk."""
