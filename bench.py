@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 PEAK_MFMA_F32_TFLOPS = 157.3      # 256 CU x 256 flop/clk x 2.4 GHz
 PEAK_MFMA_BF16_TFLOPS = 2500.0    # dense bf16 matrix-core peak
+PEAK_MFMA_F64_TFLOPS = 78.6
 PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
@@ -101,6 +102,8 @@ def main() -> int:
                     help="KDFT: three real products per complex product (DFT3D_FLAG_3M)")
     ap.add_argument("--bf16x3", action="store_true",
                     help="KDFT: fp32 accuracy from three bf16 levels on the bf16 matrix cores (DFT3D_FLAG_BF16X3)")
+    ap.add_argument("--complex128", action="store_true",
+                    help="KDFT: complex128 tensors on the fp64 matrix cores (DFT3D_FLAG_COMPLEX128)")
     ap.add_argument("--unfused", action="store_true",
                     help="FFT: run the twiddle and the re-ordering as separate memory-bound kernels")
     args = ap.parse_args()
@@ -171,8 +174,17 @@ def main() -> int:
         flags |= dft.FLAG_3M
     if args.bf16x3 and form == dft.KDFT:
         flags |= dft.FLAG_BF16X3
+    c128 = args.complex128 and form == dft.KDFT
+    if c128:
+        if big:
+            print("bench.py: a complex128 tensor of this workload and its output do not fit one GPU", file=sys.stderr)
+            return 2
+        flags = (flags & dft.FLAG_CLOBBER_INPUT) | dft.FLAG_COMPLEX128
     plan = dft.Plan(w.shape, form, coords=coords, split=split, flags=flags)
-    x = wl.make_input_device(w) if big else torch.from_numpy(wl.make_input(w)).to("cuda")
+    if c128:
+        x = torch.from_numpy(wl.draw_complex128(w.shape, w.seed)).to("cuda")
+    else:
+        x = wl.make_input_device(w) if big else torch.from_numpy(wl.make_input(w)).to("cuda")
     out = torch.empty_like(x)
     plan.ensure_workspace()
     stream = torch.cuda.current_stream()
@@ -214,7 +226,10 @@ def main() -> int:
             "unit": "TFLOP/s", "avg_launch_ms": dom_ms,
             "flop_per_launch": flops,
         }
-        if args.bf16x3:
+        if c128:
+            roofline.update({"kernel": "k_contract_f64 (strided mode contraction, fp64 MFMA)",
+                             "peak": PEAK_MFMA_F64_TFLOPS})
+        elif args.bf16x3:
             # each real fp32 product becomes six bf16 products (level pairs of total order <= 2):
             # priced in bf16 flops against the bf16 peak
             flops = 6.0 * 8.0 * n_dom * E
@@ -257,15 +272,16 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f64" if c128 else "f32",
         "data": "synthetic",
         "config": {
             "workload": w.name + ("" if form_override is None else ("_fft" if form == dft.FFT else "_kdft")),
             "formulation": "FFT" if form == dft.FFT else "KDFT",
             "complex_scheme": "3M" if (args.three_m and form == dft.KDFT) else "4M",
-            "arithmetic": "bf16x3 split on bf16 MFMA, fp32 accumulate" if (args.bf16x3 and form == dft.KDFT)
+            "arithmetic": "fp64 MFMA" if c128 else
+                          "bf16x3 split on bf16 MFMA, fp32 accumulate" if (args.bf16x3 and form == dft.KDFT)
                           else "fp32 MFMA",
-            "shape": list(w.shape), "input": f"complex64, iid {w.dist}, seed {w.seed}",
+            "shape": list(w.shape), "input": f"{'complex128' if c128 else 'complex64'}, iid {w.dist}, seed {w.seed}",
             "nonuniform": w.nonuniform,
             "split": [list(s) for s in w.splits] if (form == dft.FFT and w.splits) else None,
         },

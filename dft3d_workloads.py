@@ -72,6 +72,13 @@ def draw_complex(shape, dist: str, seed: int) -> np.ndarray:
     return buf.view(np.complex64).reshape(shape)
 
 
+def draw_complex128(shape, seed: int) -> np.ndarray:
+    """complex128 tensor with iid N(0,1) real and imaginary parts (full fp64 mantissas)."""
+    rng = np.random.default_rng(seed)
+    n = int(np.prod(shape, dtype=np.int64))
+    return rng.standard_normal(2 * n).view(np.complex128).reshape(shape)
+
+
 def make_input(w: Workload) -> np.ndarray:
     """Host input tensor of a workload (not for cfg5: 64 GiB does not fit a host array here)."""
     if w.elements > (1 << 30):

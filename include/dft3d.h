@@ -60,6 +60,11 @@ typedef enum { DFT3D_FORWARD = -1, DFT3D_BACKWARD = 1 } dft3d_direction;
                                        products are accumulated in fp32 (Section II-A of the paper);
                                        used for modes whose shape is a whole number of 128x128 tiles,
                                        other modes fall back to the fp32 kernels */
+#define DFT3D_FLAG_COMPLEX128 16u   /* KDFT: tensors are complex128 (interleaved doubles), matrices are kept
+                                       in fp64 and the contractions run on the fp64 matrix cores (the
+                                       float64 precision the paper leaves as future work, Section VI).
+                                       Every byte count below doubles (16 bytes per element).  Not
+                                       combined with 3M / BF16X3; not offered for FFT or point plans */
 #define DFT3D_FLAG_3M 4u            /* KDFT: three real products per complex product
                                        (Vr*Xr, Vi*Xi, (Vr+Vi)*(Xr+Xi)) instead of four: 25 % fewer
                                        MFMA operations, slightly larger rounding error in Im */
@@ -78,8 +83,9 @@ typedef enum { DFT3D_FORWARD = -1, DFT3D_BACKWARD = 1 } dft3d_direction;
  *             Default: A = 2^floor(log2(N)/2) for powers of two, else the divisor pair closest
  *             to sqrt(N) with A <= B.  (512 -> 16*32, 2048 -> 32*64.)
  *   flags     DFT3D_FLAG_* bits
- * Errors: INVALID_ARG (NULL plan pointer, size < 1, bad split, unknown formulation),
- * UNSUPPORTED (FFT with coordinates), ALLOC / HIP (device allocation or copy failed).
+ * Errors: INVALID_ARG (NULL plan pointer, size < 1, bad split, unknown formulation or flag),
+ * UNSUPPORTED (FFT with coordinates, COMPLEX128 on an FFT plan or together with 3M / BF16X3),
+ * ALLOC / HIP (device allocation or copy failed).
  */
 dft3d_status dft3d_plan_create(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
                                dft3d_formulation f, const double* cx, const double* cy,
@@ -113,7 +119,8 @@ dft3d_status dft3d_plan_get_output_shape(dft3d_plan plan, int64_t* kx, int64_t* 
 dft3d_status dft3d_plan_destroy(dft3d_plan plan);
 
 /* Bytes of caller-provided device workspace dft3d_exec needs: 0 with CLOBBER_INPUT, else the
- * size of one tensor (8 * nx*ny*nz).  The step calls below need none. */
+ * size of one tensor (8 * nx*ny*nz; 16 * nx*ny*nz for a COMPLEX128 plan).  The step calls below
+ * need none. */
 size_t dft3d_plan_workspace_bytes(dft3d_plan plan);
 
 /* Hands the plan a DEVICE buffer of at least dft3d_plan_workspace_bytes bytes.  The caller

@@ -22,6 +22,7 @@ FLAG_CLOBBER_INPUT = 1
 FLAG_UNFUSED = 2
 FLAG_3M = 4
 FLAG_BF16X3 = 8
+FLAG_COMPLEX128 = 16
 
 EXPORTS = [
     "dft3d_plan_create", "dft3d_plan_create_ex", "dft3d_plan_create_points",
@@ -246,15 +247,16 @@ class Plan:
 
         in_shape = self.shape if in_shape is None else in_shape
         out_shape = self.out_shape if out_shape is None else out_shape
-        if x.dtype != torch.complex64 or not x.is_cuda or not x.is_contiguous():
-            raise ValueError("input must be a contiguous complex64 CUDA tensor")
+        dtype = torch.complex128 if (self.flags & FLAG_COMPLEX128) else torch.complex64
+        if x.dtype != dtype or not x.is_cuda or not x.is_contiguous():
+            raise ValueError(f"input must be a contiguous {dtype} CUDA tensor")
         if tuple(x.shape) != tuple(in_shape):
             raise ValueError(f"input shape {tuple(x.shape)} does not match {tuple(in_shape)}")
         if out is None:
-            out = torch.empty(tuple(out_shape), dtype=torch.complex64, device=x.device)
-        elif (out.dtype != torch.complex64 or not out.is_cuda or not out.is_contiguous()
+            out = torch.empty(tuple(out_shape), dtype=dtype, device=x.device)
+        elif (out.dtype != dtype or not out.is_cuda or not out.is_contiguous()
               or tuple(out.shape) != tuple(out_shape)):
-            raise ValueError(f"output must be a contiguous complex64 CUDA tensor of shape {tuple(out_shape)}")
+            raise ValueError(f"output must be a contiguous {dtype} CUDA tensor of shape {tuple(out_shape)}")
         return ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(out.data_ptr()), out
 
     def stage_shapes(self, axis):

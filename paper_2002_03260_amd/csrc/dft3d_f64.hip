@@ -1,0 +1,252 @@
+// Mode contraction in double precision (complex128 tensors) on the fp64 matrix cores of gfx950
+// (v_mfma_f64_16x16x4_f64): the same mode-wise dense contraction as the single-precision path
+// (paper Eq. 6, per-mode products with the transform matrix), for callers that need the
+// float64 accuracy the paper names as future work (Section VI).
+//
+// One kernel serves both contraction types:  out[row, col] = sum_n R[row, n] C[col, n]
+//   strided modes   : R = matrix (rows = k), C = data (cols = the contiguous index i)
+//   contiguous mode : R = data (rows = o),   C = matrix (cols = k)
+// A workgroup is 4 waves on a 64 x 64 tile (each wave 32 x 32 = 2 x 2 MFMA blocks, re and im
+// accumulators), the contracted index advances in chunks of 16 through double-buffered LDS planes
+// [n][row or col] (re and im apart), filled from registers that were loaded one chunk earlier.
+// The complex product takes four real MFMAs per block.  Two workgroups fit a CU (64 KiB LDS each),
+// so one workgroup's staging and barriers hide behind the other's MFMAs.
+//
+// MFMA operand layout (checked on hardware): A[i = lane % 16][k = lane / 16], B[k = lane / 16][j = lane % 16],
+// D register v of a lane = row 4 * v + lane / 16, column lane % 16.
+#include <hip/hip_runtime.h>
+
+#include "dft3d_internal.h"
+
+namespace dft3d {
+
+namespace {
+
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kT = 256;
+constexpr int TM = 64, TN = 64, KC = 16;
+
+__device__ __forceinline__ int64_t block_id() { return (int64_t)blockIdx.y * gridDim.x + blockIdx.x; }
+
+__device__ __forceinline__ int64_t remap(int64_t wg, int64_t total)
+{
+    constexpr int64_t kXcds = 8;
+    if (total % kXcds != 0) return wg;
+    return (wg % kXcds) * (total / kXcds) + wg / kXcds;
+}
+
+__device__ __forceinline__ int64_t y_offset(const ContractArgs64& a, int64_t o)
+{
+    return (o / a.Olo) * a.sYohi + (o % a.Olo) * a.sYolo;
+}
+
+__device__ __forceinline__ f64x4 mfma_f64(double a, double b, f64x4 c)
+{
+    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+
+template <bool STRIDED>
+__global__ __launch_bounds__(kT, 2) void k_contract_f64(ContractArgs64 a, int tilesK, int64_t tilesOther,
+                                                        int64_t total)
+{
+    // [buffer][part: re, im][n][row or col]
+    __shared__ double RT[2][2][KC][TM];
+    __shared__ double CT[2][2][KC][TN];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wr0 = (wave >> 1) * 32;      // wave tile origin inside the 64 x 64 tile
+    const int wc0 = (wave & 1) * 32;
+    const int l16 = lane & 15;
+    const int lq = lane >> 4;
+
+    int64_t t = block_id();
+    if (t >= total) return;
+    t = remap(t, total);
+    const int kt = (int)(t % tilesK);
+    t /= tilesK;
+    const int k0 = kt * 64;
+
+    const int N = a.N, K = a.K;
+    const int64_t I = a.I;
+    const int ld = a.ld;
+    const int64_t plane = (int64_t)a.rows * ld;
+
+    // matrix tile: 16 n x 64 k per chunk; this thread: n = tid / 16, four consecutive k (zero padded planes: no masks)
+    const int vn = tid >> 4, vk = (tid & 15) * 4;
+    const double* vsrc = a.M + (int64_t)vn * ld + k0 + vk;
+
+    // data tile
+    int64_t tile_o = 0, c0 = 0, o0 = 0;
+    const f64x2* xsrc;
+    int xa, xb;          // strided: n = xa, columns xb..xb+3;  contiguous: row = xa, n = xb..xb+3
+    bool xok[4];         // strided: column xb+e exists;  contiguous: row exists (all four equal)
+    int xcol[4];         // strided: column of element e inside its row of I, 0 where it does not exist
+    if (STRIDED) {
+        tile_o = t / tilesOther;
+        c0 = (t % tilesOther) * TN;
+        xa = tid >> 4;
+        xb = (tid & 15) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            xok[e] = c0 + xb + e < I;
+            xcol[e] = xok[e] ? (int)(c0 + xb + e) : 0;
+        }
+        xsrc = reinterpret_cast<const f64x2*>(a.X) + tile_o * (int64_t)N * I;
+    } else {
+        o0 = t * TM;
+        xa = tid >> 2;
+        xb = (tid & 3) * 4;
+        const bool ok = o0 + xa < a.O;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) xok[e] = ok;
+        xsrc = reinterpret_cast<const f64x2*>(a.X) + (ok ? o0 + xa : 0) * (int64_t)N;
+    }
+
+    f64x4 vr, vi;
+    f64x2 xreg[4];
+    auto gload = [&](int n0) {
+        vr = *reinterpret_cast<const f64x4*>(vsrc + (int64_t)n0 * ld);
+        vi = *reinterpret_cast<const f64x4*>(vsrc + plane + (int64_t)n0 * ld);
+        if (STRIDED) {
+            const int n = n0 + xa;
+            const bool nok = n < N;
+            const f64x2* src = xsrc + (int64_t)(nok ? n : 0) * I;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const f64x2 v = src[xcol[e]];
+                xreg[e] = (nok && xok[e]) ? v : f64x2{0.0, 0.0};
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int n = n0 + xb + e;
+                const bool nok = n < N;
+                const f64x2 v = xsrc[nok ? n : 0];
+                xreg[e] = (nok && xok[e]) ? v : f64x2{0.0, 0.0};
+            }
+        }
+    };
+    const double isign = a.conj ? -1.0 : 1.0;      // conjugate the matrix
+    auto lstore = [&](int buf) {
+        double (*Vt)[KC][TM] = STRIDED ? RT[buf] : CT[buf];
+        double (*Xt)[KC][TM] = STRIDED ? CT[buf] : RT[buf];
+        *reinterpret_cast<f64x4*>(&Vt[0][vn][vk]) = vr;
+        *reinterpret_cast<f64x4*>(&Vt[1][vn][vk]) = vi * isign;
+        if (STRIDED) {
+            *reinterpret_cast<f64x4*>(&Xt[0][xa][xb]) = f64x4{xreg[0].x, xreg[1].x, xreg[2].x, xreg[3].x};
+            *reinterpret_cast<f64x4*>(&Xt[1][xa][xb]) = f64x4{xreg[0].y, xreg[1].y, xreg[2].y, xreg[3].y};
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                Xt[0][xb + e][xa] = xreg[e].x;
+                Xt[1][xb + e][xa] = xreg[e].y;
+            }
+        }
+    };
+
+    f64x4 accr[2][2], acci[2][2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            accr[rb][cb] = f64x4{0, 0, 0, 0};
+            acci[rb][cb] = f64x4{0, 0, 0, 0};
+        }
+
+    const int nchunks = (N + KC - 1) / KC;
+    gload(0);
+    lstore(0);
+    if (nchunks > 1) gload(KC);
+    __syncthreads();
+
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < nchunks) lstore(buf ^ 1);          // chunk c+1, requested one chunk ago
+        if (c + 2 < nchunks) gload((c + 2) * KC);
+#pragma unroll
+        for (int ks = 0; ks < KC / 4; ++ks) {
+            const int n = 4 * ks + lq;
+            double rr[2], ri[2], cr[2], ci[2], nri[2];
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                rr[b] = RT[buf][0][n][wr0 + 16 * b + l16];
+                ri[b] = RT[buf][1][n][wr0 + 16 * b + l16];
+                cr[b] = CT[buf][0][n][wc0 + 16 * b + l16];
+                ci[b] = CT[buf][1][n][wc0 + 16 * b + l16];
+                nri[b] = -ri[b];
+            }
+            // (rr + i ri)(cr + i ci): four passes over the four blocks, neighbours use different accumulators
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) accr[rb][cb] = mfma_f64(rr[rb], cr[cb], accr[rb][cb]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) acci[rb][cb] = mfma_f64(rr[rb], ci[cb], acci[rb][cb]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) accr[rb][cb] = mfma_f64(nri[rb], ci[cb], accr[rb][cb]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) acci[rb][cb] = mfma_f64(ri[rb], cr[cb], acci[rb][cb]);
+        }
+        __syncthreads();
+    }
+
+    // epilogue: accumulator register v of a lane is row 4 * v + lane / 16, column lane % 16 of its block
+    f64x2* Y = reinterpret_cast<f64x2*>(a.Y);
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = wr0 + 16 * rb + 4 * v + lq;
+                const int col = wc0 + 16 * cb + l16;
+                const f64x2 y = f64x2{accr[rb][cb][v] * a.scale, acci[rb][cb][v] * a.scale};
+                if (STRIDED) {
+                    if (k0 + row < K && c0 + col < I)
+                        Y[y_offset(a, tile_o) + (int64_t)(k0 + row) * a.sYk + c0 + col] = y;
+                } else {
+                    if (o0 + row < a.O && k0 + col < K)
+                        Y[y_offset(a, o0 + row) + (int64_t)(k0 + col) * a.sYk] = y;
+                }
+            }
+}
+
+inline dim3 grid_for(int64_t blocks)
+{
+    const int64_t kMaxX = 1 << 22;
+    if (blocks <= kMaxX) return dim3((unsigned)blocks);
+    return dim3((unsigned)kMaxX, (unsigned)((blocks + kMaxX - 1) / kMaxX));
+}
+
+}  // namespace
+
+hipError_t launch_contract_f64(const ContractArgs64& a, hipStream_t stream)
+{
+    if (a.O < 1 || a.I < 1 || a.N < 1 || a.K < 1) return hipErrorInvalidValue;
+    // the kernel reads whole 64-wide, 16-deep tiles of the zero-padded planes
+    if (a.ld % 64 != 0 || a.ld < a.K || a.rows % KC != 0 || a.rows < a.N) return hipErrorInvalidValue;
+    const int tk = (a.K + 63) / 64;
+    if (a.I == 1) {
+        // contiguous mode: rows = o, columns = k; the k-tile index runs fastest
+        const int64_t to = (a.O + TM - 1) / TM;
+        const int64_t total = (int64_t)tk * to;
+        hipLaunchKernelGGL(k_contract_f64<false>, grid_for(total), dim3(kT), 0, stream, a, tk, to, total);
+    } else {
+        const int64_t ti = (a.I + TN - 1) / TN;
+        const int64_t total = (int64_t)tk * ti * a.O;
+        hipLaunchKernelGGL(k_contract_f64<true>, grid_for(total), dim3(kT), 0, stream, a, tk, ti, total);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace dft3d

@@ -31,6 +31,11 @@ struct DeviceMatrix {
     unsigned short* split = nullptr;
     int split_ld = 0;     // padded N (multiple of 16)
     int split_rows = 0;   // padded K (multiple of 128)
+    // Optional fp64 copy for complex128 plans: planes re, im (rows64 * ld64 doubles apart), transposed
+    // like the fp32 planes, plane[n * ld64 + k].
+    double* f64 = nullptr;
+    int ld64 = 0;         // padded K (multiple of 64)
+    int rows64 = 0;       // padded N (multiple of 16)
 };
 
 // ---- one mode contraction ---------------------------------------------------------------
@@ -60,6 +65,23 @@ hipError_t launch_contract(const ContractArgs& a, hipStream_t stream);
 // only whole 128 x 128 tiles, no fused twiddle.
 bool contract_bf16x3_supported(const ContractArgs& a);
 hipError_t launch_contract_bf16x3(const ContractArgs& a, hipStream_t stream);
+
+// ---- double-precision mode contraction (complex128 tensors) ----------------------------------
+// Same operation and output addressing as ContractArgs, on interleaved (re, im) doubles.  The
+// matrix is two fp64 planes (re, then im, `rows * ld` doubles apart) stored transposed and zero
+// padded like the fp32 planes: plane[n * ld + k], ld a multiple of 64, rows a multiple of 16.
+struct ContractArgs64 {
+    const void* X;
+    void* Y;
+    const double* M;
+    int K, N, ld, rows;
+    int64_t O;
+    int64_t I;
+    int64_t Olo, sYohi, sYolo, sYk;
+    double scale;
+    int conj;
+};
+hipError_t launch_contract_f64(const ContractArgs64& a, hipStream_t stream);
 
 // ---- twiddle (phase) multiply -------------------------------------------------------------
 // Tensor viewed as [outer][A][B][inner]; out = in * Tw[k_a * B + beta] (conjugated if conj).

@@ -31,6 +31,7 @@ void free_matrix(DeviceMatrix& m)
 {
     if (m.re) (void)hipFree(m.re);
     if (m.split) (void)hipFree(m.split);
+    if (m.f64) (void)hipFree(m.f64);
     m = DeviceMatrix{};
 }
 
@@ -90,6 +91,37 @@ dft3d_status upload_split(const std::vector<double>& re, const std::vector<doubl
     return DFT3D_OK;
 }
 
+// Upload the fp64 planes of a K x N complex matrix (row-major host planes) in the transposed, zero
+// padded layout plane[n * ld + k]: re plane, then im plane.
+dft3d_status upload_f64(const std::vector<double>& re, const std::vector<double>& im, int K, int N,
+                        DeviceMatrix* m)
+{
+    const int ld = round_up(K, 64), rows = round_up(N, 16);
+    const size_t plane = (size_t)ld * rows;
+    std::vector<double> host(2 * plane, 0.0);
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n) {
+            host[(size_t)n * ld + k] = re[(size_t)k * N + n];
+            host[plane + (size_t)n * ld + k] = im[(size_t)k * N + n];
+        }
+    double* dev = nullptr;
+    hipError_t e = hipMalloc((void**)&dev, 2 * plane * sizeof(double));
+    if (e != hipSuccess) {
+        set_error("hipMalloc of the fp64 planes of a %d x %d matrix failed: %s", K, N, hipGetErrorString(e));
+        return DFT3D_ERR_ALLOC;
+    }
+    e = hipMemcpy(dev, host.data(), 2 * plane * sizeof(double), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(dev);
+        set_error("upload of the fp64 planes failed: %s", hipGetErrorString(e));
+        return DFT3D_ERR_HIP;
+    }
+    m->f64 = dev;
+    m->ld64 = ld;
+    m->rows64 = rows;
+    return DFT3D_OK;
+}
+
 // Upload a K x N complex matrix given as row-major host planes into the padded, transposed
 // device layout.  re and im share one allocation.
 dft3d_status upload_matrix(const std::vector<float>& re, const std::vector<float>& im, int K, int N,
@@ -125,25 +157,26 @@ dft3d_status upload_matrix(const std::vector<float>& re, const std::vector<float
     return DFT3D_OK;
 }
 
-dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out, bool with_split = false)
+dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out, bool with_split = false,
+                              bool with_f64 = false)
 {
     std::vector<float> re((size_t)n * n), im((size_t)n * n);
     dft3d_status s = dft3d_generate_matrix(n, coords, DFT3D_FORWARD, re.data(), im.data());
     if (s != DFT3D_OK) return s;
     s = upload_matrix(re, im, (int)n, (int)n, out);
-    if (s != DFT3D_OK || !with_split) return s;
-    // the bf16 levels are taken from the fp64 entries, not from their fp32 roundings
+    if (s != DFT3D_OK || (!with_split && !with_f64)) return s;
+    // the bf16 levels and the fp64 planes are taken from the fp64 entries, not from their fp32 roundings
     std::vector<double> dre((size_t)n * n), dim((size_t)n * n);
     for (int64_t k = 0; k < n; ++k)
         for (int64_t j = 0; j < n; ++j) {
             if (coords) unit_root_turns((double)k * coords[j], DFT3D_FORWARD, &dre[k * n + j], &dim[k * n + j]);
             else unit_root_ratio(k * j, n, DFT3D_FORWARD, &dre[k * n + j], &dim[k * n + j]);
         }
-    return upload_split(dre, dim, (int)n, (int)n, out);
+    if (with_split) s = upload_split(dre, dim, (int)n, (int)n, out);
+    if (s == DFT3D_OK && with_f64) s = upload_f64(dre, dim, (int)n, (int)n, out);
+    return s;
 }
 
-// Default first-stage length: 2^floor(log2(N)/2) for powers of two, else the divisor pair
-// closest to sqrt(N) with A <= B.
 int64_t default_split(int64_t n)
 {
     if ((n & (n - 1)) == 0) {
@@ -189,6 +222,8 @@ struct dft3d_plan_s {
     int prof_capacity = 0;
     int prof_next = 0;
 
+    bool complex128() const { return (flags & DFT3D_FLAG_COMPLEX128) != 0; }
+    size_t elem_bytes() const { return complex128() ? 16 : 8; }
     int64_t elements() const { return n[0] * n[1] * n[2]; }
     int64_t out_elements() const { return k[0] * k[1] * k[2]; }
     // Modes are applied in the order z, y, x, so when `axis` is contracted the axes after it
@@ -212,8 +247,8 @@ dft3d_status check_buffers(const dft3d_plan_s* p, const void* in, void* out, con
         set_error("%s: tensor pointers must be 16-byte aligned", who);
         return DFT3D_ERR_INVALID_ARG;
     }
-    const uintptr_t abytes = (uintptr_t)(in_elems >= 0 ? in_elems : p->elements()) * 8;
-    const uintptr_t bbytes = (uintptr_t)(out_elems >= 0 ? out_elems : p->out_elements()) * 8;
+    const uintptr_t abytes = (uintptr_t)(in_elems >= 0 ? in_elems : p->elements()) * p->elem_bytes();
+    const uintptr_t bbytes = (uintptr_t)(out_elems >= 0 ? out_elems : p->out_elements()) * p->elem_bytes();
     const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
     if (a < b + bbytes && b < a + abytes) {
         set_error("%s: in and out overlap (the transform is out of place)", who);
@@ -233,6 +268,28 @@ dft3d_status hip_status(hipError_t e, const char* who)
 hipError_t run_mode(const dft3d_plan_s* p, int axis, const float2* in, float2* out, int conj,
                     float scale, hipStream_t st)
 {
+    if (p->complex128()) {
+        // `in` / `out` are complex128 tensors here; the pointers are only passed through
+        const DeviceMatrix& M = p->M[axis];
+        ContractArgs64 d{};
+        d.X = in;
+        d.Y = out;
+        d.M = M.f64;
+        d.K = M.K;
+        d.N = M.N;
+        d.ld = M.ld64;
+        d.rows = M.rows64;
+        d.O = p->outer(axis);
+        d.I = p->inner(axis);
+        d.Olo = 1;
+        d.sYohi = (int64_t)M.K * d.I;
+        d.sYolo = 0;
+        d.sYk = d.I;
+        d.scale = conj ? 1.0 / (double)M.N : 1.0;     // BACKWARD on a uniform axis: exact reciprocal in fp64
+        d.conj = conj;
+        (void)scale;
+        return launch_contract_f64(d, st);
+    }
     ContractArgs a{};
     a.X = in;
     a.Y = out;
@@ -401,9 +458,15 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
         set_error("plan_create: unknown formulation %d", (int)f);
         return DFT3D_ERR_INVALID_ARG;
     }
-    if (flags & ~(DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_UNFUSED | DFT3D_FLAG_3M | DFT3D_FLAG_BF16X3)) {
+    if (flags & ~(DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_UNFUSED | DFT3D_FLAG_3M | DFT3D_FLAG_BF16X3 |
+                  DFT3D_FLAG_COMPLEX128)) {
         set_error("plan_create: unknown flag bits 0x%x", flags);
         return DFT3D_ERR_INVALID_ARG;
+    }
+    if ((flags & DFT3D_FLAG_COMPLEX128) &&
+        (f != DFT3D_KDFT || (flags & (DFT3D_FLAG_3M | DFT3D_FLAG_BF16X3)))) {
+        set_error("plan_create: COMPLEX128 is offered for KDFT plans without 3M / BF16X3");
+        return DFT3D_ERR_UNSUPPORTED;
     }
     if (f == DFT3D_FFT && (cx || cy || cz)) {
         set_error("plan_create: the FFT formulation requires uniform sampling on every axis");
@@ -431,7 +494,9 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
             p->M_owner[j] = j;
             for (int i = 0; i < j; ++i)
                 if (!c[j] && !c[i] && n[i] == n[j]) { p->M_owner[j] = i; break; }
-            if (p->M_owner[j] == j) s = make_axis_matrix(n[j], c[j], &p->M[j], (flags & DFT3D_FLAG_BF16X3) != 0);
+            if (p->M_owner[j] == j)
+                s = make_axis_matrix(n[j], c[j], &p->M[j], (flags & DFT3D_FLAG_BF16X3) != 0,
+                                     (flags & DFT3D_FLAG_COMPLEX128) != 0);
             else p->M[j] = p->M[p->M_owner[j]];
         }
     } else {
@@ -617,7 +682,7 @@ size_t dft3d_plan_workspace_bytes(dft3d_plan p)
     if (p->points)   // two intermediates of different shapes: after mode z and after mode y
         return (size_t)(p->stage_out_elements(2) + p->stage_out_elements(1)) * 8;
     if (p->flags & DFT3D_FLAG_CLOBBER_INPUT) return 0;
-    return (size_t)p->elements() * 8;
+    return (size_t)p->elements() * p->elem_bytes();
 }
 
 dft3d_status dft3d_plan_set_workspace(dft3d_plan p, void* dev, size_t bytes)

@@ -180,6 +180,72 @@ def test_kdft_bf16_split_scheme(dft, shape):
             assert report(f"bf16x3 mode {axis}", gm, orc.mode_contract(M, x, axis)) <= TOL
 
 
+TOL_F64 = 1e-12     # fp64 unit roundoff 1.1e-16, three modes of length <= 2^11 on either side: ~1e-14 expected
+
+
+def _oracle_c128(x, coords=(None, None, None), sign=None):
+    """The transform of a complex128 tensor from the oracle's own mode products (z, y, x)."""
+    sign = orc.FORWARD if sign is None else sign
+    y = x
+    for axis in (2, 1, 0):
+        y = orc.mode_contract(orc.dft_matrix(x.shape[axis], coords[axis], sign), y, axis)
+    return y / x.size if sign == orc.BACKWARD else y
+
+
+@pytest.mark.parametrize("shape", [(6, 10, 12), (40, 33, 70), (64, 64, 64), (128, 130, 64), (3, 5, 260),
+                                   (1, 256, 192), (2, 2, 2)])
+def test_kdft_complex128(dft, shape):
+    """DFT3D_FLAG_COMPLEX128: complex128 tensors, fp64 matrices, fp64 matrix cores."""
+    import torch
+
+    say(f"case kdft complex128 {shape}")
+    x = wl.draw_complex128(shape, 8100 + sum(shape))
+    want = _oracle_c128(x)
+    with dft.Plan(shape, dft.KDFT, flags=dft.FLAG_COMPLEX128) as p:
+        xd = torch.from_numpy(x).to("cuda")
+        got = p.exec(xd).cpu().numpy()
+        assert got.dtype == np.complex128
+        assert report(f"kdft complex128 {shape}", got, want) <= TOL_F64
+        assert np.array_equal(xd.cpu().numpy(), x), "input must be left intact"
+        gotb = p.exec(xd, direction=dft.BACKWARD).cpu().numpy()
+        assert report(f"kdft complex128 backward {shape}", gotb, _oracle_c128(x, sign=orc.BACKWARD)) <= TOL_F64
+        back = p.exec(torch.from_numpy(got).to("cuda"), direction=dft.BACKWARD).cpu().numpy()
+        assert report(f"kdft complex128 round trip {shape}", back, x) <= TOL_F64
+        for axis in range(3):
+            gm = p.mode_contract(axis, xd).cpu().numpy()
+            assert report(f"complex128 mode {axis}", gm,
+                          orc.mode_contract(orc.dft_matrix(shape[axis]), x, axis)) <= TOL_F64
+    with dft.Plan(shape, dft.KDFT, flags=dft.FLAG_COMPLEX128 | dft.FLAG_CLOBBER_INPUT) as p:
+        assert p.workspace_bytes() == 0
+        got = p.exec(torch.from_numpy(x).to("cuda")).cpu().numpy()
+        assert report(f"kdft complex128 clobber {shape}", got, want) <= TOL_F64
+
+
+def test_kdft_complex128_nonuniform(dft):
+    import torch
+
+    shape = (24, 40, 36)
+    rng = np.random.default_rng(8200)
+    coords = tuple(np.sort(rng.random(n)) for n in shape)
+    x = wl.draw_complex128(shape, 8201)
+    with dft.Plan(shape, dft.KDFT, coords=coords, flags=dft.FLAG_COMPLEX128) as p:
+        got = p.exec(torch.from_numpy(x).to("cuda")).cpu().numpy()
+    assert report("kdft complex128 nonuniform", got, _oracle_c128(x, coords)) <= TOL_F64
+
+
+def test_complex128_plan_restrictions(dft):
+    with pytest.raises(dft.Dft3dError) as e:
+        dft.Plan((8, 8, 8), dft.FFT, flags=dft.FLAG_COMPLEX128)
+    assert e.value.status_name == "DFT3D_ERR_UNSUPPORTED"
+    with pytest.raises(dft.Dft3dError):
+        dft.Plan((8, 8, 8), dft.KDFT, flags=dft.FLAG_COMPLEX128 | dft.FLAG_3M)
+    import torch
+
+    with dft.Plan((8, 8, 8), dft.KDFT, flags=dft.FLAG_COMPLEX128) as p:
+        with pytest.raises(ValueError):
+            p.exec(torch.zeros((8, 8, 8), dtype=torch.complex64, device="cuda"))
+
+
 def test_kdft_clobber_input(dft):
     shape = (16, 24, 40)
     x = wl.draw_complex(shape, "normal", 78)
