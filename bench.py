@@ -250,12 +250,36 @@ def main() -> int:
             pass_names = ["z_fused_axis", "y_fused_axis", "x_fused_axis"]
         dom = max(range(npass), key=lambda i: pass_ms[i])
         dom_ms = pass_ms[dom]
+        dom_name = pass_names[dom] if dom < len(pass_names) else f"pass{dom}"
         nbytes = 16.0 * E
-        roofline = {
-            "bound": "hbm", "kernel": pass_names[dom] if dom < len(pass_names) else f"pass{dom}",
-            "achieved": nbytes / (dom_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-            "avg_launch_ms": dom_ms, "bytes_per_launch": nbytes,
-        }
+        # fp32 flop of that pass: 8 per complex multiply-add of its stage matrices (+6 for a fused twiddle)
+        ax = {"z": 2, "y": 1, "x": 0}.get(dom_name[0])
+        flops = 0.0
+        if ax is not None and w.splits and "reorder_xyz" not in dom_name and "z_reorder" != dom_name and "phase" not in dom_name:
+            A, B = w.splits[ax]
+            if "fused" in dom_name:
+                flops = (8.0 * (A + B) + 6.0) * E
+            elif "stage1" in dom_name:
+                flops = (8.0 * A + (0.0 if args.unfused else 6.0)) * E
+            elif "stage2" in dom_name:
+                flops = 8.0 * B * E
+        hbm_frac = nbytes / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBS
+        mfma_frac = flops / (dom_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS
+        # the pass is bound by whichever of the two takes longer at its peak rate
+        if mfma_frac > hbm_frac:
+            roofline = {
+                "bound": "mfma", "kernel": dom_name,
+                "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+                "avg_launch_ms": dom_ms, "flop_per_launch": flops, "bytes_per_launch": nbytes,
+                "hbm_frac": hbm_frac,
+            }
+        else:
+            roofline = {
+                "bound": "hbm", "kernel": dom_name,
+                "achieved": nbytes / (dom_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "avg_launch_ms": dom_ms, "bytes_per_launch": nbytes, "flop_per_launch": flops,
+                "mfma_frac": mfma_frac,
+            }
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline["traffic"] = MEASURED_TRAFFIC.get(name)
     roofline["passes_ms"] = {(pass_names[i] if i < len(pass_names) else f"pass{i}"): round(pass_ms[i], 5)
