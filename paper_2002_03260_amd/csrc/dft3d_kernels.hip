@@ -1307,6 +1307,7 @@ hipError_t launch_fft_z(const float2* in, float2* out, int64_t nrows, int A, int
                         int conj, hipStream_t stream)
 {
     if (nrows <= 0) return hipSuccess;
+    if (fft_zr_supported(A, B)) return launch_fft_zr(in, out, nrows, A, B, FA, FB, Tw, scale, conj, stream);
     if (A == 16 && B == 16) return launch_fft_z_inst<16, 16, 8, 4, 2, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     if (A == 16 && B == 32) return launch_fft_z_inst<16, 32, 4, 8, 4, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     if (A == 32 && B == 32) return launch_fft_z_inst<32, 32, 2, 4, 2, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
