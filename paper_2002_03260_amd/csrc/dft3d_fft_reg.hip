@@ -274,6 +274,168 @@ __global__ __launch_bounds__(256, MINW) void k_fft_zr(const float2* __restrict__
     }
 }
 
+// ---- strided axes ------------------------------------------------------------------------------
+// Tensor viewed as [O][N = A*B][I]; a workgroup of four waves transforms one tile of all N positions
+// x 16 contiguous columns at a time.  The columns are the MFMA column index (lane % 16), so the
+// data is the B operand of both stages and 16 lanes cover one 128-byte segment:
+//   stage 1 (wave w takes beta = w, w+4, ..):  D[k_a, i] = sum_l FA[k_a, l] x[B*l + beta, i]
+//     with x straight from global memory into the operand registers -- the whole tile sits in
+//     registers, requested one tile ahead, each register re-requested right after its last use;
+//     twiddle on D; D goes to LDS as Z[k_a][beta][i];
+//   stage 2 (wave w takes k_a = w, w+4, ..):   D[k_b, i] = sum_beta FB[k_b, beta] Z[k_a][beta][i]
+//     with Z read from LDS in the order of the contraction; D is stored straight to global
+//     memory at row k_a + A*k_b.
+// Only Z passes through LDS (one write, one read, both conflict free without padding), with two
+// barriers per tile; the stage matrices are constant operand registers.  Three real products per
+// complex product (see the contiguous-axis kernel).
+template <int A, int B, int MINW>
+__global__ __launch_bounds__(256, MINW) void k_fft_sr(const float2* __restrict__ X, float2* __restrict__ Y,
+                                                       int64_t O, int64_t I, DeviceMatrix FA, DeviceMatrix FB,
+                                                       const float2* __restrict__ Tw, float scale, int conj)
+{
+    constexpr int N = A * B;
+    static_assert(A == 16, "one block of k_a per stage-1 product");
+    constexpr int NBB = B / 16;      // blocks of k_b
+    constexpr int NS1 = A / 4;       // k-steps of stage 1 (over l)
+    constexpr int NS2 = B / 4;       // k-steps of stage 2 (over beta)
+    constexpr int NG = B / 4;        // beta values per wave
+    constexpr int NH = A / 4;        // k_a values per wave
+
+    __shared__ __align__(16) float2 Zs[N * 16];       // [k_a][beta][i]
+    __shared__ __align__(16) float2 tws[N];           // T[k_a][beta], conjugated for BACKWARD
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // uniform: addresses built from it stay scalar
+    const int l16 = lane & 15, lq = lane >> 4;
+    const float isign = conj ? -1.0f : 1.0f;
+
+    for (int e = tid; e < N; e += 256) {
+        float2 t = Tw[e];
+        t.y *= isign;
+        tws[e] = t;
+    }
+    // stage-1 A operand: FA[k_a = l16][l = 4*s + lq]   (matrix planes are plane[n * ld + k])
+    float fa_r[NS1], fa_i[NS1], fa_s[NS1];
+#pragma unroll
+    for (int s = 0; s < NS1; ++s) {
+        const int idx = (4 * s + lq) * FA.ld + l16;
+        fa_r[s] = FA.re[idx];
+        fa_i[s] = FA.im[idx] * isign;
+        fa_s[s] = fa_r[s] + fa_i[s];
+    }
+    // stage-2 A operand: scale * FB[k_b = 16*kbb + l16][beta = 4*s + lq]
+    float fb_r[NBB][NS2], fb_i[NBB][NS2], fb_s[NBB][NS2];
+#pragma unroll
+    for (int kbb = 0; kbb < NBB; ++kbb)
+#pragma unroll
+        for (int s = 0; s < NS2; ++s) {
+            const int idx = (4 * s + lq) * FB.ld + 16 * kbb + l16;
+            fb_r[kbb][s] = FB.re[idx] * scale;
+            fb_i[kbb][s] = FB.im[idx] * (scale * isign);
+            fb_s[kbb][s] = fb_r[kbb][s] + fb_i[kbb][s];
+        }
+
+    const int64_t ctiles = I / 16;                 // column tiles per o (I is a multiple of 16)
+    const int64_t ntiles = O * ctiles;
+    const int64_t nwg = (int64_t)gridDim.x * gridDim.y;
+    // Addresses = uniform 64-bit base (tile, wave, compile-time row) + 32-bit lane offset; the host
+    // side guarantees that the lane offsets fit (I <= 2^21).
+    auto tile_base = [&](int64_t tile) { return (tile / ctiles) * (int64_t)N * I + (tile % ctiles) * 16; };
+    const unsigned ld_lane = (unsigned)(B * lq) * (unsigned)I + l16;        // row B*lq, column l16
+    const unsigned st_lane = (unsigned)(A * 4 * lq) * (unsigned)I + l16;    // row A*4*lq, column l16
+
+    // operand registers of the tile: xq[g][s] = x[B*(4*s + lq) + beta_g, i], beta_g = wave + 4*g
+    f32x2 xq[NG][NS1];
+    auto request = [&](int64_t tile, int g) {
+        const f32x2* src = reinterpret_cast<const f32x2*>(X) + tile_base(tile) + (int64_t)(wave + 4 * g) * I;
+#pragma unroll
+        for (int s = 0; s < NS1; ++s) xq[g][s] = (src + (int64_t)(4 * B * s) * I)[ld_lane];
+    };
+
+    int64_t tile = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    if (tile < ntiles) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) request(tile, g);
+    }
+    __syncthreads();                               // twiddle table
+    for (; tile < ntiles; tile += nwg) {
+        const int64_t next = tile + nwg < ntiles ? tile + nwg : tile;    // past the end: a harmless re-read
+
+        // ---- stage 1: two beta values at a time
+#pragma unroll
+        for (int g = 0; g < NG; g += 2) {
+            f32x4 p1[2], p2[2], p3[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                p1[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                p2[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                p3[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int s = 0; s < NS1; ++s)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const f32x2 x = xq[g + u][s];
+                    p1[u] = mfma(fa_r[s], x.x, p1[u]);
+                    p2[u] = mfma(fa_i[s], x.y, p2[u]);
+                    p3[u] = mfma(fa_s[s], x.x + x.y, p3[u]);
+                }
+            // the registers of these two beta values are free: request them for the next tile
+            request(next, g);
+            request(next, g + 1);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int beta = wave + 4 * (g + u);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int ka = 4 * lq + v;
+                    const float2 t = tws[ka * B + beta];
+                    const float a = p1[u][v] - p2[u][v];
+                    const float b = p3[u][v] - p1[u][v] - p2[u][v];
+                    *reinterpret_cast<f32x2*>(&Zs[(ka * B + beta) * 16 + l16]) =
+                        f32x2{a * t.x - b * t.y, a * t.y + b * t.x};
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- stage 2: one k_a at a time, all blocks of k_b in flight
+        f32x2* dst = reinterpret_cast<f32x2*>(Y) + tile_base(tile);         // uniform
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            const int ka = wave + 4 * h;
+            f32x4 q1[NBB], q2[NBB], q3[NBB];
+#pragma unroll
+            for (int kbb = 0; kbb < NBB; ++kbb) {
+                q1[kbb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                q2[kbb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                q3[kbb] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int s = 0; s < NS2; ++s) {
+                const f32x2 z = *reinterpret_cast<const f32x2*>(&Zs[(ka * B + 4 * s + lq) * 16 + l16]);
+                const float zs = z.x + z.y;
+#pragma unroll
+                for (int kbb = 0; kbb < NBB; ++kbb) {
+                    q1[kbb] = mfma(fb_r[kbb][s], z.x, q1[kbb]);
+                    q2[kbb] = mfma(fb_i[kbb][s], z.y, q2[kbb]);
+                    q3[kbb] = mfma(fb_s[kbb][s], zs, q3[kbb]);
+                }
+            }
+#pragma unroll
+            for (int kbb = 0; kbb < NBB; ++kbb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    // row k_a + A*k_b with k_b = 16*kbb + 4*lq + v: the lq part is in st_lane
+                    (dst + (int64_t)(ka + A * (16 * kbb + v)) * I)[st_lane] =
+                        f32x2{q1[kbb][v] - q2[kbb][v], q3[kbb][v] - q1[kbb][v] - q2[kbb][v]};
+                }
+        }
+        __syncthreads();                           // Z is rewritten by the next tile
+    }
+}
+
 template <int A, int B, int MINW, bool M3>
 hipError_t launch_inst(const float2* in, float2* out, int64_t nrows, const DeviceMatrix& FA,
                        const DeviceMatrix& FB, const float2* Tw, float scale, int conj, hipStream_t stream)
@@ -287,7 +449,36 @@ hipError_t launch_inst(const float2* in, float2* out, int64_t nrows, const Devic
     return hipGetLastError();
 }
 
+template <int A, int B, int MINW>
+hipError_t launch_s_inst(const float2* in, float2* out, int64_t O, int64_t I, const DeviceMatrix& FA,
+                         const DeviceMatrix& FB, const float2* Tw, float scale, int conj, hipStream_t stream)
+{
+    const int64_t ntiles = O * (I / 16);
+    const int64_t resident = 256 * MINW;           // persistent workgroups: MINW per CU
+    const int64_t blocks = ntiles < resident ? ntiles : resident;
+    hipLaunchKernelGGL((k_fft_sr<A, B, MINW>), dim3((unsigned)blocks), dim3(256), 0, stream, in, out, O, I, FA, FB,
+                       Tw, scale, conj);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+bool fft_sr_supported(int A, int B, int64_t I)
+{
+    // 32-bit lane offsets inside the kernel: (12*A + 1) rows of I complex numbers must stay below 2^32 bytes
+    return I % 16 == 0 && I <= (int64_t(1) << 21) && A == 16 && (B == 16 || B == 32);
+}
+
+hipError_t launch_fft_sr(const float2* in, float2* out, int64_t O, int64_t I, int A, int B,
+                         const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
+                         int conj, hipStream_t stream)
+{
+    if (O <= 0 || I <= 0) return hipSuccess;
+    if (!fft_sr_supported(A, B, I) || FA.K != A || FA.N != A || FB.K != B || FB.N != B || !Tw) return hipErrorInvalidValue;
+    if (A == 16 && B == 16) return launch_s_inst<16, 16, 4>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
+    if (A == 16 && B == 32) return launch_s_inst<16, 32, 2>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
+    return hipErrorInvalidValue;
+}
 
 bool fft_zr_supported(int A, int B)
 {

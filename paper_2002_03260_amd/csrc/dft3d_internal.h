@@ -123,6 +123,14 @@ hipError_t launch_fft_s(const float2* in, float2* out, int64_t O, int64_t I, int
                         const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
                         int conj, hipStream_t stream);
 
+// Variant of the strided-axis pass with the data as MFMA operands straight from global memory
+// (only the intermediate of the two stages passes through LDS); launch_fft_s uses it for the
+// splits it covers.
+bool fft_sr_supported(int A, int B, int64_t I);
+hipError_t launch_fft_sr(const float2* in, float2* out, int64_t O, int64_t I, int A, int B,
+                         const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
+                         int conj, hipStream_t stream);
+
 // ---- plain copy (bandwidth reference / counter calibration) -------------------------------
 // variant: units digit = accesses in flight per thread (1, 2, else 4); tens digit t > 0 caps the
 // grid at 256*t workgroups (grid-stride), 0 launches one chunk per workgroup.

@@ -1342,6 +1342,7 @@ hipError_t launch_fft_s(const float2* in, float2* out, int64_t O, int64_t I, int
                         int conj, hipStream_t stream)
 {
     if (O <= 0 || I <= 0) return hipSuccess;
+    if (fft_sr_supported(A, B, I)) return launch_fft_sr(in, out, O, I, A, B, FA, FB, Tw, scale, conj, stream);
     if (A == 16 && B == 16) return launch_fft_s_inst<16, 16, 4, 2, 2>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
     if (A == 16 && B == 32) return launch_fft_s_inst<16, 32, 4, 2, 2>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
     if (A == 32 && B == 32) return launch_fft_s_inst<32, 32, 8, 2, 1>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
