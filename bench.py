@@ -258,7 +258,9 @@ def main() -> int:
         if ax is not None and w.splits and "reorder_xyz" not in dom_name and "z_reorder" != dom_name and "phase" not in dom_name:
             A, B = w.splits[ax]
             if "fused" in dom_name:
-                flops = (8.0 * (A + B) + 6.0) * E
+                # the 16x16 and 16x32 fused kernels use three real products per complex product
+                per_cmac = 6.0 if (A == 16 and B in (16, 32)) else 8.0
+                flops = (per_cmac * (A + B) + 6.0) * E
             elif "stage1" in dom_name:
                 flops = (8.0 * A + (0.0 if args.unfused else 6.0)) * E
             elif "stage2" in dom_name:
