@@ -119,8 +119,9 @@ dft3d_status dft3d_plan_get_output_shape(dft3d_plan plan, int64_t* kx, int64_t* 
 dft3d_status dft3d_plan_destroy(dft3d_plan plan);
 
 /* Bytes of caller-provided device workspace dft3d_exec needs: 0 with CLOBBER_INPUT, else the
- * size of one tensor (8 * nx*ny*nz; 16 * nx*ny*nz for a COMPLEX128 plan).  The step calls below
- * need none. */
+ * size of one tensor (8 * nx*ny*nz; 16 * nx*ny*nz for a COMPLEX128 plan) or, for FFT plans that
+ * keep their intermediate with a padded row pitch, 8 * nx*ny*(nz+16).  Always query; the step
+ * calls below need none. */
 size_t dft3d_plan_workspace_bytes(dft3d_plan plan);
 
 /* Hands the plan a DEVICE buffer of at least dft3d_plan_workspace_bytes bytes.  The caller

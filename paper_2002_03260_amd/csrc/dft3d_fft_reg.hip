@@ -289,10 +289,11 @@ __global__ __launch_bounds__(256, MINW) void k_fft_zr(const float2* __restrict__
 // barriers per tile; the stage matrices are constant operand registers.  Three real products per
 // complex product (see the contiguous-axis kernel).
 template <int A, int B, int MINW>
-__global__ __launch_bounds__(256, MINW) void k_fft_sr(const float2* __restrict__ X, float2* __restrict__ Y,
-                                                       int64_t O, int64_t I, DeviceMatrix FA, DeviceMatrix FB,
+__global__ __launch_bounds__(256, MINW) void k_fft_sr(FftStridedArgs a, DeviceMatrix FA, DeviceMatrix FB,
                                                        const float2* __restrict__ Tw, float scale, int conj)
 {
+    const float2* __restrict__ X = a.X;
+    float2* __restrict__ Y = a.Y;
     constexpr int N = A * B;
     static_assert(A == 16, "one block of k_a per stage-1 product");
     constexpr int NBB = B / 16;      // blocks of k_b
@@ -336,21 +337,30 @@ __global__ __launch_bounds__(256, MINW) void k_fft_sr(const float2* __restrict__
             fb_s[kbb][s] = fb_r[kbb][s] + fb_i[kbb][s];
         }
 
-    const int64_t ctiles = I / 16;                 // column tiles per o (I is a multiple of 16)
-    const int64_t ntiles = O * ctiles;
+    // tile -> (o, y, 16-column group); input and output have their own strides (see FftStridedArgs)
+    const int64_t per_o = a.Yn * a.Zt;
+    const int64_t ntiles = a.O * per_o;
     const int64_t nwg = (int64_t)gridDim.x * gridDim.y;
     // Addresses = uniform 64-bit base (tile, wave, compile-time row) + 32-bit lane offset; the host
-    // side guarantees that the lane offsets fit (I <= 2^21).
-    auto tile_base = [&](int64_t tile) { return (tile / ctiles) * (int64_t)N * I + (tile % ctiles) * 16; };
-    const unsigned ld_lane = (unsigned)(B * lq) * (unsigned)I + l16;        // row B*lq, column l16
-    const unsigned st_lane = (unsigned)(A * 4 * lq) * (unsigned)I + l16;    // row A*4*lq, column l16
+    // side guarantees that the lane offsets fit.
+    auto in_base = [&](int64_t tile) {
+        const int64_t o = tile / per_o, r = tile % per_o;
+        return o * a.inO + (r / a.Zt) * a.inY + (r % a.Zt) * 16;
+    };
+    auto out_base = [&](int64_t tile) {
+        const int64_t o = tile / per_o, r = tile % per_o;
+        return o * a.outO + (r / a.Zt) * a.outY + (r % a.Zt) * 16;
+    };
+    const int64_t inN = a.inN, outN = a.outN;
+    const unsigned ld_lane = (unsigned)(B * lq) * (unsigned)inN + l16;        // row B*lq, column l16
+    const unsigned st_lane = (unsigned)(A * 4 * lq) * (unsigned)outN + l16;   // row A*4*lq, column l16
 
     // operand registers of the tile: xq[g][s] = x[B*(4*s + lq) + beta_g, i], beta_g = wave + 4*g
     f32x2 xq[NG][NS1];
     auto request = [&](int64_t tile, int g) {
-        const f32x2* src = reinterpret_cast<const f32x2*>(X) + tile_base(tile) + (int64_t)(wave + 4 * g) * I;
+        const f32x2* src = reinterpret_cast<const f32x2*>(X) + in_base(tile) + (int64_t)(wave + 4 * g) * inN;
 #pragma unroll
-        for (int s = 0; s < NS1; ++s) xq[g][s] = (src + (int64_t)(4 * B * s) * I)[ld_lane];
+        for (int s = 0; s < NS1; ++s) xq[g][s] = (src + (int64_t)(4 * B * s) * inN)[ld_lane];
     };
 
     int64_t tile = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
@@ -401,7 +411,7 @@ __global__ __launch_bounds__(256, MINW) void k_fft_sr(const float2* __restrict__
         __syncthreads();
 
         // ---- stage 2: one k_a at a time, all blocks of k_b in flight
-        f32x2* dst = reinterpret_cast<f32x2*>(Y) + tile_base(tile);         // uniform
+        f32x2* dst = reinterpret_cast<f32x2*>(Y) + out_base(tile);          // uniform
 #pragma unroll
         for (int h = 0; h < NH; ++h) {
             const int ka = wave + 4 * h;
@@ -428,7 +438,7 @@ __global__ __launch_bounds__(256, MINW) void k_fft_sr(const float2* __restrict__
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     // row k_a + A*k_b with k_b = 16*kbb + 4*lq + v: the lq part is in st_lane
-                    (dst + (int64_t)(ka + A * (16 * kbb + v)) * I)[st_lane] =
+                    (dst + (int64_t)(ka + A * (16 * kbb + v)) * outN)[st_lane] =
                         f32x2{q1[kbb][v] - q2[kbb][v], q3[kbb][v] - q1[kbb][v] - q2[kbb][v]};
                 }
         }
@@ -450,14 +460,14 @@ hipError_t launch_inst(const float2* in, float2* out, int64_t nrows, const Devic
 }
 
 template <int A, int B, int MINW>
-hipError_t launch_s_inst(const float2* in, float2* out, int64_t O, int64_t I, const DeviceMatrix& FA,
-                         const DeviceMatrix& FB, const float2* Tw, float scale, int conj, hipStream_t stream)
+hipError_t launch_s_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw,
+                         float scale, int conj, hipStream_t stream)
 {
-    const int64_t ntiles = O * (I / 16);
+    const int64_t ntiles = a.O * a.Yn * a.Zt;
     const int64_t resident = 256 * MINW;           // persistent workgroups: MINW per CU
     const int64_t blocks = ntiles < resident ? ntiles : resident;
-    hipLaunchKernelGGL((k_fft_sr<A, B, MINW>), dim3((unsigned)blocks), dim3(256), 0, stream, in, out, O, I, FA, FB,
-                       Tw, scale, conj);
+    hipLaunchKernelGGL((k_fft_sr<A, B, MINW>), dim3((unsigned)blocks), dim3(256), 0, stream, a, FA, FB, Tw, scale,
+                       conj);
     return hipGetLastError();
 }
 
@@ -465,8 +475,21 @@ hipError_t launch_s_inst(const float2* in, float2* out, int64_t O, int64_t I, co
 
 bool fft_sr_supported(int A, int B, int64_t I)
 {
-    // 32-bit lane offsets inside the kernel: (12*A + 1) rows of I complex numbers must stay below 2^32 bytes
+    // 32-bit lane offsets inside the kernel: (12*A + 1) rows must stay below 2^32 bytes
     return I % 16 == 0 && I <= (int64_t(1) << 21) && A == 16 && (B == 16 || B == 32);
+}
+
+hipError_t launch_fft_sr_ex(const FftStridedArgs& a, int A, int B, const DeviceMatrix& FA,
+                            const DeviceMatrix& FB, const float2* Tw, float scale, int conj, hipStream_t stream)
+{
+    if (a.O <= 0 || a.Yn <= 0 || a.Zt <= 0) return hipSuccess;
+    const int64_t lim = int64_t(1) << 21;
+    if (a.inN < 16 || a.outN < 16 || a.inN > lim || a.outN > lim || FA.K != A || FA.N != A || FB.K != B ||
+        FB.N != B || !Tw)
+        return hipErrorInvalidValue;
+    if (A == 16 && B == 16) return launch_s_inst<16, 16, 4>(a, FA, FB, Tw, scale, conj, stream);
+    if (A == 16 && B == 32) return launch_s_inst<16, 32, 2>(a, FA, FB, Tw, scale, conj, stream);
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_fft_sr(const float2* in, float2* out, int64_t O, int64_t I, int A, int B,
@@ -474,10 +497,18 @@ hipError_t launch_fft_sr(const float2* in, float2* out, int64_t O, int64_t I, in
                          int conj, hipStream_t stream)
 {
     if (O <= 0 || I <= 0) return hipSuccess;
-    if (!fft_sr_supported(A, B, I) || FA.K != A || FA.N != A || FB.K != B || FB.N != B || !Tw) return hipErrorInvalidValue;
-    if (A == 16 && B == 16) return launch_s_inst<16, 16, 4>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
-    if (A == 16 && B == 32) return launch_s_inst<16, 32, 2>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
-    return hipErrorInvalidValue;
+    if (!fft_sr_supported(A, B, I)) return hipErrorInvalidValue;
+    // contiguous [O][A*B][I] on both sides
+    FftStridedArgs a{};
+    a.X = in;
+    a.Y = out;
+    a.O = O;
+    a.Yn = 1;
+    a.Zt = I / 16;
+    a.inO = a.outO = (int64_t)A * B * I;
+    a.inN = a.outN = I;
+    a.inY = a.outY = 0;
+    return launch_fft_sr_ex(a, A, B, FA, FB, Tw, scale, conj, stream);
 }
 
 bool fft_zr_supported(int A, int B)

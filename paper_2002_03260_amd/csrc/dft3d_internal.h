@@ -126,6 +126,18 @@ hipError_t launch_fft_s(const float2* in, float2* out, int64_t O, int64_t I, int
 // Variant of the strided-axis pass with the data as MFMA operands straight from global memory
 // (only the intermediate of the two stages passes through LDS); launch_fft_s uses it for the
 // splits it covers.
+// General addressing of that kernel: the tensor is [O][N = A*B][Yn][16 * Zt] with separate element
+// strides on the input and the output side (o: inO / outO, n: inN / outN, y: inY / outY; the last
+// index is contiguous).  Lets an intermediate tensor carry a padded row pitch.
+struct FftStridedArgs {
+    const float2* X;
+    float2* Y;
+    int64_t O, Yn, Zt;
+    int64_t inO, inN, inY;
+    int64_t outO, outN, outY;
+};
+hipError_t launch_fft_sr_ex(const FftStridedArgs& a, int A, int B, const DeviceMatrix& FA,
+                            const DeviceMatrix& FB, const float2* Tw, float scale, int conj, hipStream_t stream);
 bool fft_sr_supported(int A, int B, int64_t I);
 hipError_t launch_fft_sr(const float2* in, float2* out, int64_t O, int64_t I, int A, int B,
                          const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
