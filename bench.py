@@ -31,8 +31,10 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/); None until measured for a workload.
 MEASURED_TRAFFIC = {
-    "cfg2": 2.80e8,      # strided contraction: 2 * FETCH_SIZE + WRITE_SIZE (calibrated), bytes per launch
-    "cfg3": 2.148e9,     # fused axis kernel
+    "cfg2": 2.80e8,             # strided contraction: 2 * FETCH_SIZE + WRITE_SIZE (calibrated), bytes per launch
+    "cfg2+bf16x3": 2.94e8,      # bf16-split contraction (six bf16 matrix planes instead of two fp32 ones)
+    "cfg2+complex128": 6.05e8,  # fp64 contraction
+    "cfg3": 2.172e9,            # fused strided-axis kernel
 }
 
 
@@ -283,7 +285,8 @@ def main() -> int:
                 "mfma_frac": mfma_frac,
             }
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    roofline["traffic"] = MEASURED_TRAFFIC.get(name)
+    variant = "+complex128" if c128 else ("+bf16x3" if (args.bf16x3 and form == dft.KDFT) else "")
+    roofline["traffic"] = None if (args.three_m or args.unfused) else MEASURED_TRAFFIC.get(name + variant)
     roofline["passes_ms"] = {(pass_names[i] if i < len(pass_names) else f"pass{i}"): round(pass_ms[i], 5)
                              for i in range(npass)}
 
