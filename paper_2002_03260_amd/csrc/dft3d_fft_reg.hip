@@ -446,6 +446,144 @@ __global__ __launch_bounds__(256, MINW) void k_fft_sr(FftStridedArgs a, DeviceMa
     }
 }
 
+// ---- strided contraction with a small square matrix ----------------------------------------------
+// out[o, k, i] = scale * tw * sum_n M[k, n] in[o, n, i] for NK x NK matrices, NK = 16, 32 or 64 (the
+// single stages of the FFT formulation when an axis has no fused kernel, and small KDFT modes).
+// Such a pass moves 16 bytes per 8*NK flop: it is bound by HBM, so the kernel is built to stream.
+// ONE wavefront owns a tile of all NK rows x 16 contiguous columns: the rows are the MFMA B operand
+// straight from global memory (16 lanes = one 128-byte segment), the matrix is the A operand read
+// from LDS (filled once per workgroup, never written again: no barrier in the loop), and the
+// accumulator rows are stored straight to global memory.  Two register sets alternate so the next
+// tile's loads are in flight during the current tile.  Three real products per complex product.
+template <int NK, int CT, int MINW>
+__global__ __launch_bounds__(256, MINW) void k_contract_sr(ContractArgs a, int64_t ntiles)
+{
+    constexpr int NB = NK / 16;      // blocks of k
+    constexpr int NS = NK / 4;       // k-steps (over n)
+    constexpr int TC = 16 * CT;      // columns per tile: CT groups of 16 (CT x 128 contiguous bytes per row)
+    constexpr int P = NK + 16;       // LDS pitch: lane groups 0,1 (and 2,3) of a read fall on disjoint halves of the banks
+    __shared__ float mr[NK * P], mi[NK * P];      // [n][k]: re, im (scale and conjugation applied)
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const float isign = a.conj ? -1.0f : 1.0f;
+    for (int e = tid; e < NK * NK; e += 256) {
+        const int n = e / NK, k = e % NK;
+        const float r = a.M.re[(int64_t)n * a.M.ld + k] * a.scale;
+        const float i = a.M.im[(int64_t)n * a.M.ld + k] * (a.scale * isign);
+        mr[n * P + k] = r;
+        mi[n * P + k] = i;
+    }
+    __syncthreads();
+
+    // tile indices are wave-uniform 32-bit numbers (the host checks the count): the index
+    // arithmetic, divisions included, stays cheap
+    const unsigned wave = (blockIdx.x * 4u) + (unsigned)__builtin_amdgcn_readfirstlane(tid >> 6);
+    const unsigned nwaves = gridDim.x * 4u;
+    if (wave >= ntiles) return;                   // after the only barrier
+
+    const int64_t I = a.I;
+    const unsigned ctiles = (unsigned)(I / TC);   // column tiles per o
+    const unsigned olo = (unsigned)a.Olo;
+    const int m_rd = lq * P + l16;                // + 4*s*P + 16*kb
+
+    auto load_tile = [&](f32x2 (&x)[CT][NS], unsigned tile) {
+        const unsigned o = tile / ctiles, c0 = (tile - o * ctiles) * TC;
+        const f32x2* src = reinterpret_cast<const f32x2*>(a.X) + (int64_t)o * NK * I + c0 + l16 + (int64_t)lq * I;
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int g = 0; g < CT; ++g) x[g][s] = src[(int64_t)(4 * s) * I + 16 * g];
+    };
+    auto transform_tile = [&](const f32x2 (&x)[CT][NS], unsigned tile) {
+        f32x4 p1[CT][NB], p2[CT][NB], p3[CT][NB];
+#pragma unroll
+        for (int g = 0; g < CT; ++g)
+#pragma unroll
+            for (int kb = 0; kb < NB; ++kb) {
+                p1[g][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                p2[g][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                p3[g][kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            float fr[NB], fi[NB], fs[NB];
+#pragma unroll
+            for (int kb = 0; kb < NB; ++kb) {
+                fr[kb] = mr[m_rd + 4 * s * P + 16 * kb];
+                fi[kb] = mi[m_rd + 4 * s * P + 16 * kb];
+                fs[kb] = fr[kb] + fi[kb];
+            }
+#pragma unroll
+            for (int g = 0; g < CT; ++g) {
+                const float xs = x[g][s].x + x[g][s].y;
+#pragma unroll
+                for (int kb = 0; kb < NB; ++kb) {
+                    p1[g][kb] = mfma(fr[kb], x[g][s].x, p1[g][kb]);
+                    p2[g][kb] = mfma(fi[kb], x[g][s].y, p2[g][kb]);
+                    p3[g][kb] = mfma(fs[kb], xs, p3[g][kb]);
+                }
+            }
+        }
+        const unsigned o = tile / ctiles, c0 = (tile - o * ctiles) * TC;
+        const unsigned ohi = o / olo;
+        const int64_t col = (int64_t)c0 + l16;
+        f32x2* dst = reinterpret_cast<f32x2*>(a.Y) + (int64_t)ohi * a.sYohi + (int64_t)(o - ohi * olo) * a.sYolo + col;
+        const int beta = a.Tw ? (int)((uint32_t)c0 / (uint32_t)a.twInner) : 0;     // uniform: twInner is a multiple of TC
+#pragma unroll
+        for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int k = 16 * kb + 4 * lq + v;
+                float2 w = make_float2(1.f, 0.f);
+                if (a.Tw) {
+                    w = a.Tw[(int64_t)k * a.twB + beta];
+                    w.y *= isign;
+                }
+#pragma unroll
+                for (int g = 0; g < CT; ++g) {
+                    float yr = p1[g][kb][v] - p2[g][kb][v];
+                    float yi = p3[g][kb][v] - p1[g][kb][v] - p2[g][kb][v];
+                    if (a.Tw) {
+                        const float tr = yr * w.x - yi * w.y;
+                        yi = yr * w.y + yi * w.x;
+                        yr = tr;
+                    }
+                    dst[(int64_t)k * a.sYk + 16 * g] = f32x2{yr, yi};
+                }
+            }
+    };
+
+    f32x2 xa[CT][NS], xb[CT][NS];
+    load_tile(xa, wave);
+    const unsigned nt = (unsigned)ntiles;
+    for (unsigned tile = wave; tile < nt; tile += 2 * nwaves) {
+        // a request past the end re-reads the wave's current tile (in bounds, never used)
+        const unsigned t1 = tile + nwaves, t2 = tile + 2 * nwaves;
+        load_tile(xb, t1 < nt ? t1 : tile);
+        __builtin_amdgcn_sched_barrier(0);
+        transform_tile(xa, tile);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t1 >= nt) break;
+        load_tile(xa, t2 < nt ? t2 : tile);
+        __builtin_amdgcn_sched_barrier(0);
+        transform_tile(xb, t1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <int NK, int CT, int MINW>
+hipError_t launch_csr_inst(const ContractArgs& a, hipStream_t stream)
+{
+    const int64_t ntiles = a.O * (a.I / (16 * CT));
+    const int64_t resident = 256 * MINW;                 // workgroups of 4 waves, MINW waves per SIMD
+    const int64_t want = (ntiles + 3) / 4;
+    const int64_t blocks = want < resident ? want : resident;
+    hipLaunchKernelGGL((k_contract_sr<NK, CT, MINW>), dim3((unsigned)blocks), dim3(256), 0, stream, a, ntiles);
+    return hipGetLastError();
+}
+
 template <int A, int B, int MINW, bool M3>
 hipError_t launch_inst(const float2* in, float2* out, int64_t nrows, const DeviceMatrix& FA,
                        const DeviceMatrix& FB, const float2* Tw, float scale, int conj, hipStream_t stream)
@@ -472,6 +610,36 @@ hipError_t launch_s_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const 
 }
 
 }  // namespace
+
+bool contract_sr_supported(const ContractArgs& a)
+{
+    const int N = a.M.N;
+    if (a.M.K != N || (N != 16 && N != 32 && N != 64)) return false;
+    if (a.I < 16 || a.I % 16 != 0 || a.three_m || a.bf16x3) return false;
+    if (a.Tw && a.twInner % 16 != 0) return false;       // one twiddle column per tile
+    // 32-bit tile arithmetic in the kernel, with room for the two-tile look-ahead of 2 * 12288 waves
+    if (a.O >= (int64_t(1) << 30) || a.Olo >= (int64_t(1) << 30) || a.O * (a.I / 16) >= (int64_t(1) << 31) - 65536)
+        return false;
+    return true;
+}
+
+hipError_t launch_contract_sr(const ContractArgs& a, hipStream_t stream)
+{
+    if (!contract_sr_supported(a)) return hipErrorInvalidValue;
+    // widest tile (CT groups of 16 columns) that divides the inner extent and, with a twiddle, stays
+    // inside one twiddle column
+    auto fits = [&](int ct) { return a.I % (16 * ct) == 0 && (!a.Tw || a.twInner % (16 * ct) == 0); };
+    if (a.M.N == 16) {
+        if (fits(4)) return launch_csr_inst<16, 4, 3>(a, stream);
+        if (fits(2)) return launch_csr_inst<16, 2, 4>(a, stream);
+        return launch_csr_inst<16, 1, 8>(a, stream);
+    }
+    if (a.M.N == 32) {
+        if (fits(2)) return launch_csr_inst<32, 2, 3>(a, stream);
+        return launch_csr_inst<32, 1, 4>(a, stream);
+    }
+    return launch_csr_inst<64, 1, 2>(a, stream);
+}
 
 bool fft_sr_supported(int A, int B, int64_t I)
 {

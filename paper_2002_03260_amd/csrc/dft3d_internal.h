@@ -61,6 +61,11 @@ struct ContractArgs {
 
 hipError_t launch_contract(const ContractArgs& a, hipStream_t stream);
 
+// Streaming variant for strided modes with a small square matrix (16, 32 or 64) and an inner
+// extent that is a multiple of 16: one wavefront per 16-column tile, no staging of the data in LDS.
+bool contract_sr_supported(const ContractArgs& a);
+hipError_t launch_contract_sr(const ContractArgs& a, hipStream_t stream);
+
 // bf16-split variant (three bf16 levels per fp32 number, six cross products on bf16 MFMA);
 // only whole 128 x 128 tiles, no fused twiddle.
 bool contract_bf16x3_supported(const ContractArgs& a);

@@ -1248,6 +1248,7 @@ hipError_t launch_contract(const ContractArgs& a, hipStream_t stream)
         if (a.three_m) return launch_c<128, 64, 64, 32, 16, 3>(a, stream);
         return launch_c<128, 128, 64, 64, 16>(a, stream);
     }
+    if (contract_sr_supported(a)) return launch_contract_sr(a, stream);
     if (K <= 16 && N <= 16) return launch_s<16, 256, 16, 64, 16, 1>(a, stream);
     if (K <= 32 && N <= 32) return launch_s<32, 128, 32, 32, 32, 1>(a, stream);
     if (K <= 64 && N <= 64) return launch_s<64, 128, 64, 32, 16, 2>(a, stream);
