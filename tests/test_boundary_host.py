@@ -42,6 +42,26 @@ def ulp32(x):
     return np.spacing(np.abs(x).astype(np.float32)).astype(np.float64)
 
 
+
+def test_binding_constants_match_the_header():
+    """Flags, formulations, directions and status codes of the Python binding equal the header's."""
+    import re
+
+    import paper_2002_03260_amd as dft
+    from paper_2002_03260_amd import binding
+
+    text = open(os.path.join(ROOT, "include", "dft3d.h")).read()
+    flags = {m.group(1): int(m.group(2)) for m in re.finditer(r"#define\s+DFT3D_FLAG_(\w+)\s+(\d+)u", text)}
+    assert flags == {"CLOBBER_INPUT": dft.FLAG_CLOBBER_INPUT, "UNFUSED": dft.FLAG_UNFUSED, "3M": dft.FLAG_3M,
+                     "BF16X3": dft.FLAG_BF16X3, "COMPLEX128": dft.FLAG_COMPLEX128}
+    assert len(set(flags.values())) == len(flags) and all(v & (v - 1) == 0 for v in flags.values())
+    enums = {m.group(1): int(m.group(2)) for m in re.finditer(r"DFT3D_(\w+)\s*=\s*(-?\d+)", text)}
+    assert enums["KDFT"] == dft.KDFT and enums["FFT"] == dft.FFT
+    assert enums["FORWARD"] == dft.FORWARD and enums["BACKWARD"] == dft.BACKWARD
+    assert int(re.search(r"#define\s+DFT3D_MAX_PASSES\s+(\d+)", text).group(1)) == 16
+    assert binding.EXPORTS == sorted(set(binding.EXPORTS)) or len(binding.EXPORTS) == len(set(binding.EXPORTS))
+
+
 @pytest.mark.parametrize("n,nonuniform", [(2, False), (4, False), (8, False), (30, False), (37, False),
                                           (256, False), (2048, False), (128, True), (45, True)])
 def test_generated_matrix_is_oracle_matrix_rounded_once(lib, n, nonuniform):
