@@ -228,6 +228,12 @@ def main() -> int:
             "unit": "TFLOP/s", "avg_launch_ms": dom_ms,
             "flop_per_launch": flops,
         }
+        if (not c128 and not args.bf16x3 and not args.three_m
+                and all(w.shape[live[i]] in (16, 32, 64) for i in dom) and w.shape[2] % 16 == 0):
+            # small square matrices run the streaming kernel, which uses three real products per complex one
+            flops = 6.0 * n_dom * E
+            roofline.update({"kernel": "k_contract_sr (streaming strided mode contraction, fp32 MFMA, 3M)",
+                             "achieved": flops / (dom_ms * 1e-3) / 1e12, "flop_per_launch": flops})
         if c128:
             roofline.update({"kernel": "k_contract_f64 (strided mode contraction, fp64 MFMA)",
                              "peak": PEAK_MFMA_F64_TFLOPS})
