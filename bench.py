@@ -266,13 +266,18 @@ def main() -> int:
         if ax is not None and w.splits and "reorder_xyz" not in dom_name and "z_reorder" != dom_name and "phase" not in dom_name:
             A, B = w.splits[ax]
             if "fused" in dom_name:
-                # the 16x16 and 16x32 fused kernels use three real products per complex product
-                per_cmac = 6.0 if (A == 16 and B in (16, 32)) else 8.0
+                # fused kernels with three real products per complex product: 16x16 and 16x32 on every
+                # axis, 32x64 on the contiguous axis; the others use four
+                three = (A == 16 and B in (16, 32)) or (ax == 2 and (A, B) == (32, 64))
+                per_cmac = 6.0 if three else 8.0
                 flops = (per_cmac * (A + B) + 6.0) * E
             elif "stage1" in dom_name:
-                flops = (8.0 * A + (0.0 if args.unfused else 6.0)) * E
+                # strided stages with a 16 / 32 / 64 matrix run the three-product streaming kernel
+                per_cmac = 6.0 if (ax != 2 and A in (16, 32, 64)) else 8.0
+                flops = (per_cmac * A + (0.0 if args.unfused else 6.0)) * E
             elif "stage2" in dom_name:
-                flops = 8.0 * B * E
+                per_cmac = 6.0 if (ax != 2 and B in (16, 32, 64)) else 8.0
+                flops = per_cmac * B * E
         hbm_frac = nbytes / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBS
         mfma_frac = flops / (dom_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS
         # the pass is bound by whichever of the two takes longer at its peak rate

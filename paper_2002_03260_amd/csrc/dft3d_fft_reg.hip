@@ -274,6 +274,155 @@ __global__ __launch_bounds__(256, MINW) void k_fft_zr(const float2* __restrict__
     }
 }
 
+// Contiguous axis, larger splits (32 x 64): the same one-wavefront-per-row scheme, but the stage
+// matrices and the twiddle table no longer fit the register file next to the row's intermediate,
+// so they sit in LDS, pre-arranged in per-lane operand order ([...][lane]: every read is lane
+// contiguous and conflict free) and never written after the fill -- still no barrier in the row
+// loop.  Stage 1 runs one block of 16 beta at a time (its data requested one block ahead, across
+// rows), stage 2 one block of 16 k_b at a time with its results stored at once, so the registers
+// hold the intermediate Z of the row (A*B/32 of them) plus one block of accumulators.  Three real
+// products per complex product.
+template <int A, int B>
+__global__ __launch_bounds__(512, 2) void k_fft_zl(const float2* __restrict__ in, float2* __restrict__ out,
+                                                    int64_t nrows, DeviceMatrix FA, DeviceMatrix FB,
+                                                    const float2* __restrict__ Tw, float scale, int conj)
+{
+    constexpr int N = A * B;
+    constexpr int NAB = A / 16;      // blocks of k_a
+    constexpr int NBB = B / 16;      // blocks of beta (and of k_b)
+    constexpr int NS1 = A / 4;       // k-steps of stage 1 (over l)
+
+    __shared__ float fa_r[NAB * NS1 * 64], fa_i[NAB * NS1 * 64];             // [ab][s][lane]
+    __shared__ float fb_r[NBB * NBB * 4 * 64], fb_i[NBB * NBB * 4 * 64];     // [kbb][bb][v][lane]
+    __shared__ float2 tws[NBB * NAB * 4 * 64];                               // [bb][ab][v][lane]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const float isign = conj ? -1.0f : 1.0f;
+
+    for (int e = tid; e < NAB * NS1 * 64; e += 512) {
+        const int ln = e & 63, s = (e >> 6) % NS1, ab = (e >> 6) / NS1;
+        const int idx = (4 * s + (ln >> 4)) * FA.ld + 16 * ab + (ln & 15);       // FA[k_a][l] at plane[l * ld + k_a]
+        fa_r[e] = FA.re[idx];
+        fa_i[e] = FA.im[idx] * isign;
+    }
+    for (int e = tid; e < NBB * NBB * 4 * 64; e += 512) {
+        const int ln = e & 63, v = (e >> 6) & 3, bb = (e >> 8) % NBB, kbb = (e >> 8) / NBB;
+        const int idx = (16 * bb + 4 * (ln >> 4) + v) * FB.ld + 16 * kbb + (ln & 15);   // FB[k_b][beta]
+        fb_r[e] = FB.re[idx] * scale;
+        fb_i[e] = FB.im[idx] * (scale * isign);
+    }
+    for (int e = tid; e < NBB * NAB * 4 * 64; e += 512) {
+        const int ln = e & 63, v = (e >> 6) & 3, ab = (e >> 8) % NAB, bb = (e >> 8) / NAB;
+        float2 t = Tw[(16 * ab + (ln & 15)) * B + 16 * bb + 4 * (ln >> 4) + v];  // T[k_a][beta]
+        t.y *= isign;
+        tws[e] = t;
+    }
+    __syncthreads();
+
+    const int64_t wave = (int64_t)blockIdx.x * 8 + (tid >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 8;
+    if (wave >= nrows) return;                    // after the only barrier
+
+    const int ld_off = B * lq + l16;              // + B*4*s + 16*bb
+    auto load_block = [&](f32x2 (&x)[NS1], int64_t row, int bb) {
+        const f32x2* src = reinterpret_cast<const f32x2*>(in) + row * N + ld_off + 16 * bb;
+#pragma unroll
+        for (int s = 0; s < NS1; ++s) x[s] = src[4 * B * s];
+    };
+
+    f32x4 zr[NBB][NAB], zi[NBB][NAB];
+    auto stage1_block = [&](const f32x2 (&x)[NS1], int bb) {
+        f32x4 p1[NAB], p2[NAB], p3[NAB];
+#pragma unroll
+        for (int ab = 0; ab < NAB; ++ab) {
+            p1[ab] = f32x4{0.f, 0.f, 0.f, 0.f};
+            p2[ab] = f32x4{0.f, 0.f, 0.f, 0.f};
+            p3[ab] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int s = 0; s < NS1; ++s) {
+            const float xs = x[s].x + x[s].y;
+#pragma unroll
+            for (int ab = 0; ab < NAB; ++ab) {
+                const float fr = fa_r[(ab * NS1 + s) * 64 + lane], fi = fa_i[(ab * NS1 + s) * 64 + lane];
+                p1[ab] = mfma(x[s].x, fr, p1[ab]);
+                p2[ab] = mfma(x[s].y, fi, p2[ab]);
+                p3[ab] = mfma(xs, fr + fi, p3[ab]);
+            }
+        }
+#pragma unroll
+        for (int ab = 0; ab < NAB; ++ab)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float2 t = tws[((bb * NAB + ab) * 4 + v) * 64 + lane];
+                const float a = p1[ab][v] - p2[ab][v];
+                const float b = p3[ab][v] - p1[ab][v] - p2[ab][v];
+                zr[bb][ab][v] = a * t.x - b * t.y;
+                zi[bb][ab][v] = a * t.y + b * t.x;
+            }
+    };
+    auto stage2_block = [&](int64_t row, int kbb) {
+        f32x4 q1[NAB], q2[NAB], q3[NAB];
+#pragma unroll
+        for (int ab = 0; ab < NAB; ++ab) {
+            q1[ab] = f32x4{0.f, 0.f, 0.f, 0.f};
+            q2[ab] = f32x4{0.f, 0.f, 0.f, 0.f};
+            q3[ab] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int bb = 0; bb < NBB; ++bb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                if (v == 0 && bb > 0) __builtin_amdgcn_sched_barrier(0);
+                const float gr = fb_r[((kbb * NBB + bb) * 4 + v) * 64 + lane];
+                const float gi = fb_i[((kbb * NBB + bb) * 4 + v) * 64 + lane];
+                const float gs = gr + gi;
+#pragma unroll
+                for (int ab = 0; ab < NAB; ++ab) {
+                    q1[ab] = mfma(gr, zr[bb][ab][v], q1[ab]);
+                    q2[ab] = mfma(gi, zi[bb][ab][v], q2[ab]);
+                    q3[ab] = mfma(gs, zr[bb][ab][v] + zi[bb][ab][v], q3[ab]);
+                }
+            }
+        // natural order: k = k_a + A * k_b
+        f32x2* dst = reinterpret_cast<f32x2*>(out) + row * N + l16 + A * 4 * lq + A * 16 * kbb;
+#pragma unroll
+        for (int ab = 0; ab < NAB; ++ab)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                dst[16 * ab + A * v] = f32x2{q1[ab][v] - q2[ab][v], q3[ab][v] - q1[ab][v] - q2[ab][v]};
+    };
+
+    static_assert(NBB % 2 == 0, "the two data register sets alternate block by block");
+    f32x2 xa[NS1], xb[NS1];
+    load_block(xa, wave, 0);
+    for (int64_t row = wave; row < nrows; row += nwaves) {
+        const int64_t next = row + nwaves < nrows ? row + nwaves : row;    // past the end: a harmless re-read
+        // the tables are loop invariant, but keeping them in registers across rows is exactly what
+        // does not fit: make the compiler read them again in every row
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int bb = 0; bb < NBB; bb += 2) {
+            load_block(xb, row, bb + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            stage1_block(xa, bb);
+            __builtin_amdgcn_sched_barrier(0);
+            if (bb + 2 < NBB) load_block(xa, row, bb + 2);
+            else load_block(xa, next, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            stage1_block(xb, bb + 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int kbb = 0; kbb < NBB; ++kbb) {
+            stage2_block(row, kbb);
+            __builtin_amdgcn_sched_barrier(0);      // keeps the table reads of later blocks from being issued early
+        }
+    }
+}
+
 // ---- strided axes ------------------------------------------------------------------------------
 // Tensor viewed as [O][N = A*B][I]; a workgroup of four waves transforms one tile of all N positions
 // x 16 contiguous columns at a time.  The columns are the MFMA column index (lane % 16), so the
@@ -681,7 +830,7 @@ hipError_t launch_fft_sr(const float2* in, float2* out, int64_t O, int64_t I, in
 
 bool fft_zr_supported(int A, int B)
 {
-    return (A == 16 && B == 16) || (A == 16 && B == 32) || (A == 32 && B == 32);
+    return (A == 16 && B == 16) || (A == 16 && B == 32) || (A == 32 && B == 32) || (A == 32 && B == 64);
 }
 
 hipError_t launch_fft_zr(const float2* in, float2* out, int64_t nrows, int A, int B, const DeviceMatrix& FA,
@@ -695,6 +844,14 @@ hipError_t launch_fft_zr(const float2* in, float2* out, int64_t nrows, int A, in
     if (A == 16 && B == 16) return launch_inst<16, 16, 6, true>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     if (A == 16 && B == 32) return launch_inst<16, 32, 3, true>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     if (A == 32 && B == 32) return launch_inst<32, 32, 2, false>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (A == 32 && B == 64) {
+        // eight waves per workgroup, one workgroup per CU
+        const int64_t want = (nrows + 7) / 8;
+        const int64_t blocks = want < 256 ? want : 256;
+        hipLaunchKernelGGL((k_fft_zl<32, 64>), dim3((unsigned)blocks), dim3(512), 0, stream, in, out, nrows, FA, FB, Tw,
+                           scale, conj);
+        return hipGetLastError();
+    }
     return hipErrorInvalidValue;
 }
 
