@@ -323,6 +323,239 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int t
     }
 }
 
+// Three-product variant (DFT3D_FLAG_BF16X3 together with DFT3D_FLAG_3M).  With P1 = sum Vr*Xr,
+// P2 = sum Vi*Xi and P3 = sum (Vr+Vi)*(Xr+Xi):  Re = P1 - P2,  Im = P3 - P1 - P2, each real product
+// again as six bf16 level products: 18 instead of 24 MFMAs per complex block and chunk.  The sums
+// Vr+Vi (at plan time, from fp64) and Xr+Xi (in fp32 while staging) are split into their own three
+// levels, so each operand has nine planes: (re, im, sum) x (hi, mid, lo), plane = 3*part + level.
+// LDS rows are 32 bytes (two 16-byte slots) without padding; the slot is XOR-ed with bit 2 of the row
+// so that the eight rows one LDS cycle serves fall on eight different 16-byte bank groups.
+// Three accumulator sets (192 AGPRs) and nine operand planes per side (144 VGPRs): one wave per SIMD.
+constexpr int kPlanes3 = 9;
+
+template <bool STRIDED>
+__global__ __launch_bounds__(kT, 1) void k_contract_bf16x3m(ContractArgs a, int tilesK, int64_t tilesOther,
+                                                            int64_t total)
+{
+    // [buffer][plane][row][2 x 16 bytes]: slots hold n = 0..7 and 8..15 of the chunk, swizzled by row
+    __shared__ u32x4 RT[2][kPlanes3][TM][2];
+    __shared__ u32x4 CT[2][kPlanes3][TN][2];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wr0 = (wave >> 1) * 64;      // wave tile origin inside the 128 x 128 tile
+    const int wc0 = (wave & 1) * 64;
+    const int l32 = lane & 31;
+    const int kq = lane >> 5;
+
+    int64_t t = block_id();
+    if (t >= total) return;
+    t = remap(t, total);
+    const int kt = (int)(t % tilesK);
+    t /= tilesK;
+    const int k0 = kt * 128;
+
+    const int N = a.M.N;
+    const int64_t I = a.I;
+    const int ldn = a.M.split_ld;
+    const int64_t plane_stride = (int64_t)a.M.split_rows * ldn;
+    const unsigned short* __restrict__ Vs = a.M.split;
+
+    // this thread's piece of the matrix tile: row = tid / 2 (k), 8 consecutive n
+    const int vrow = tid >> 1, vhalf = tid & 1;
+    const unsigned short* vsrc = Vs + (int64_t)(k0 + vrow) * ldn + 8 * vhalf;
+
+    // this thread's piece of the data tile
+    int64_t tile_o = 0, c0 = 0, o0 = 0;
+    const float2* xsrc;
+    int xrow, xhalf;                       // LDS destination (row or column, which half of the chunk)
+    if (STRIDED) {
+        tile_o = t / tilesOther;
+        c0 = (t % tilesOther) * TN;
+        xrow = tid & 127;
+        xhalf = tid >> 7;
+        xsrc = a.X + tile_o * (int64_t)N * I + (int64_t)(8 * xhalf) * I + c0 + xrow;
+    } else {
+        o0 = t * TM;
+        xrow = tid >> 1;
+        xhalf = tid & 1;
+        xsrc = a.X + (o0 + xrow) * (int64_t)N + 8 * xhalf;
+    }
+    const int vslot = vhalf ^ ((vrow >> 2) & 1);
+    const int xslot = xhalf ^ ((xrow >> 2) & 1);
+
+    u32x4 vreg[kPlanes3];
+    f32x2 xreg[8];
+    constexpr int kXLoads = STRIDED ? 8 : 4;
+    auto load_v = [&](int n0, int p) {
+        vreg[p] = *reinterpret_cast<const u32x4*>(vsrc + p * plane_stride + n0);
+    };
+    auto load_x = [&](int n0, int j) {           // j < kXLoads
+        if (STRIDED) {
+            xreg[j] = *reinterpret_cast<const f32x2*>(xsrc + (int64_t)(n0 + j) * I);
+        } else {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(xsrc + n0 + 2 * j);
+            xreg[2 * j] = f32x2{v.x, v.y};
+            xreg[2 * j + 1] = f32x2{v.z, v.w};
+        }
+    };
+    auto gload = [&](int n0) {           // same order as the main loop requests them
+#pragma unroll
+        for (int j = 0; j < kXLoads; ++j) load_x(n0, j);
+#pragma unroll
+        for (int p = 0; p < kPlanes3; ++p) load_v(n0, p);
+    };
+
+    // Staging in small steps, as in the four-product kernel; part 0 = real, 1 = imaginary, 2 = their sum.
+    // Conjugating the matrix flips the sign of Vi and turns Vr+Vi into Vr-Vi, which is not a stored
+    // plane: BACKWARD instead conjugates the data and the result (conj(V) x = conj(V conj(x))).
+    const float xsign = a.conj ? -1.0f : 1.0f;
+    u32x4 lv[3][3];                 // [part][level], dword q = pair q
+    float res0[3], res1[3];
+    auto split_step = [&](int part, int q, int step) {
+        if (step == 0) {
+            float x0, x1;
+            if (part == 0) {
+                x0 = xreg[2 * q].x;
+                x1 = xreg[2 * q + 1].x;
+            } else if (part == 1) {
+                x0 = xreg[2 * q].y * xsign;
+                x1 = xreg[2 * q + 1].y * xsign;
+            } else {
+                x0 = xreg[2 * q].x + xreg[2 * q].y * xsign;
+                x1 = xreg[2 * q + 1].x + xreg[2 * q + 1].y * xsign;
+            }
+            const unsigned p0 = pack_bf16(x0, x1);
+            res0[part] = x0 - lo_as_float(p0);      // exact
+            res1[part] = x1 - hi_as_float(p0);
+            lv[part][0][q] = p0;
+        } else if (step == 1) {
+            const unsigned p1 = pack_bf16(res0[part], res1[part]);
+            res0[part] -= lo_as_float(p1);          // exact
+            res1[part] -= hi_as_float(p1);
+            lv[part][1][q] = p1;
+        } else {
+            lv[part][2][q] = pack_bf16(res0[part], res1[part]);
+        }
+    };
+    auto store_x = [&](int buf, int part, int level) {
+        u32x4 (*Xt)[TM][2] = STRIDED ? CT[buf] : RT[buf];
+        Xt[3 * part + level][xrow][xslot] = lv[part][level];
+    };
+    auto store_v = [&](int buf, int p) {
+        u32x4 (*Vt)[TM][2] = STRIDED ? RT[buf] : CT[buf];
+        Vt[p][vrow][vslot] = vreg[p];
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int part = 0; part < 3; ++part) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int step = 0; step < 3; ++step) split_step(part, q, step);
+#pragma unroll
+            for (int level = 0; level < 3; ++level) store_x(buf, part, level);
+        }
+#pragma unroll
+        for (int p = 0; p < kPlanes3; ++p) store_v(buf, p);
+    };
+
+    f32x16 acc[3][2][2];            // [P1, P2, P3][row block][column block]
+#pragma unroll
+    for (int part = 0; part < 3; ++part)
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[part][rb][cb][v] = 0.f;
+
+    const int nchunks = N / KC;
+    auto chunk_n0 = [&](int j) { return (j < nchunks ? j : nchunks - 1) * KC; };     // clamped: tail re-reads the last chunk
+    gload(0);
+    lstore(0);
+    gload(chunk_n0(1));
+    __syncthreads();
+
+    constexpr int PL[6] = {1, 2, 0, 1, 0, 0};
+    constexpr int QL[6] = {1, 0, 2, 0, 1, 0};
+    // the steps of the side work in order: per pair 9 split steps (3 parts x 3 levels) and the pair's
+    // loads; 9 stores of the data planes; 9 x (store a matrix plane, request it again)
+    constexpr int kPerPair = 9 + kXLoads / 4;
+    constexpr int kXStoreAt = 4 * kPerPair;
+    constexpr int kVAt = kXStoreAt + 9;
+    constexpr int kSteps = kVAt + 18;
+    static_assert(kSteps <= 72, "one step per MFMA at most");
+    // read offsets of this lane: rows r0 + l32 (r0 a multiple of 32) share bit 2 with l32
+    const int rslot = kq ^ ((l32 >> 2) & 1);
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        const int n2 = chunk_n0(c + 2);
+
+        u32x4 R[3][2][3], C[3][2][3];        // [part][block][level]
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+            const int lr = PL[j], lc = QL[j];        // (1,1), (2,0), (0,2): each level once, in order of first use
+#pragma unroll
+            for (int part = 0; part < 3; ++part)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    R[part][b][lr] = RT[buf][3 * part + lr][wr0 + b * 32 + l32][rslot];
+                    C[part][b][lc] = CT[buf][3 * part + lc][wc0 + b * 32 + l32][rslot];
+                }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        static_for<0, 72>([&](auto slot) {
+            constexpr int s = decltype(slot)::value;
+            // ---- at most one step of side work: step i sits in slot i * 72 / kSteps
+            constexpr int step = (s * kSteps + 71) / 72;
+            if constexpr (step < kSteps && (step * 72) / kSteps == s) {
+                if constexpr (step < kXStoreAt) {
+                    constexpr int q = step / kPerPair, w = step % kPerPair;
+                    if constexpr (w < 9) split_step(w / 3, q, w % 3);
+                    else if constexpr (STRIDED) load_x(n2, 2 * q + (w - 9));
+                    else load_x(n2, q);
+                } else if constexpr (step < kVAt) {
+                    constexpr int w = step - kXStoreAt;
+                    store_x(buf ^ 1, w / 3, w % 3);
+                } else {
+                    constexpr int w = step - kVAt;
+                    if constexpr ((w & 1) == 0) store_v(buf ^ 1, w >> 1);
+                    else load_v(n2, w >> 1);
+                }
+            }
+            // ---- one MFMA: product part = s / 24, level pair (s % 24) / 4, block s % 4
+            constexpr int part = s / 24, pq = (s % 24) / 4, rb = (s >> 1) & 1, cb = s & 1;
+            acc[part][rb][cb] = mfma_bf16(R[part][rb][PL[pq]], C[part][cb][QL[pq]], acc[part][rb][cb]);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        __syncthreads();
+    }
+
+    // epilogue: accumulator register v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const int col = wc0 + cb * 32 + l32;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = wr0 + rb * 32 + 8 * (v / 4) + 4 * kq + (v % 4);
+                const float p1 = acc[0][rb][cb][v], p2 = acc[1][rb][cb][v], p3 = acc[2][rb][cb][v];
+                const f32x2 y = f32x2{(p1 - p2) * a.scale, (p3 - p1 - p2) * (a.scale * xsign)};
+                if (STRIDED) {
+                    float2* Yo = a.Y + y_offset(a, tile_o);
+                    *reinterpret_cast<f32x2*>(Yo + (int64_t)(k0 + row) * a.sYk + c0 + col) = y;
+                } else {
+                    *reinterpret_cast<f32x2*>(a.Y + y_offset(a, o0 + row) + (int64_t)(k0 + col) * a.sYk) = y;
+                }
+            }
+        }
+    }
+}
+
 inline dim3 grid_for(int64_t blocks)
 {
     const int64_t kMaxX = 1 << 22;
@@ -344,6 +577,18 @@ bool contract_bf16x3_supported(const ContractArgs& a)
 hipError_t launch_contract_bf16x3(const ContractArgs& a, hipStream_t stream)
 {
     const int tk = a.M.K / 128;
+    if (a.three_m && a.M.split_planes == 9) {
+        if (a.I == 1) {
+            const int64_t to = a.O / TM;
+            const int64_t total = (int64_t)tk * to;
+            hipLaunchKernelGGL(k_contract_bf16x3m<false>, grid_for(total), dim3(kT), 0, stream, a, tk, to, total);
+        } else {
+            const int64_t ti = a.I / TN;
+            const int64_t total = (int64_t)tk * ti * a.O;
+            hipLaunchKernelGGL(k_contract_bf16x3m<true>, grid_for(total), dim3(kT), 0, stream, a, tk, ti, total);
+        }
+        return hipGetLastError();
+    }
     if (a.I == 1) {
         // contiguous mode: rows = o, columns = k; the k-tile index runs fastest
         const int64_t to = a.O / TM;

@@ -31,6 +31,7 @@ struct DeviceMatrix {
     unsigned short* split = nullptr;
     int split_ld = 0;     // padded N (multiple of 16)
     int split_rows = 0;   // padded K (multiple of 128)
+    int split_planes = 0; // 6, or 9 with the planes of Re + Im appended (three-product scheme)
     // Optional fp64 copy for complex128 plans: planes re, im (rows64 * ld64 doubles apart), transposed
     // like the fp32 planes, plane[n * ld64 + k].
     double* f64 = nullptr;
