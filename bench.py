@@ -240,8 +240,9 @@ def main() -> int:
         elif args.bf16x3:
             # each real fp32 product becomes six bf16 products (level pairs of total order <= 2):
             # priced in bf16 flops against the bf16 peak
-            flops = 6.0 * 8.0 * n_dom * E
-            roofline.update({"kernel": "k_contract_bf16x3 (strided mode contraction, bf16 MFMA, 6 level products)",
+            flops = 6.0 * (6.0 if args.three_m else 8.0) * n_dom * E
+            roofline.update({"kernel": "k_contract_bf16x3%s (strided mode contraction, bf16 MFMA, 6 level products)"
+                                       % ("m" if args.three_m else ""),
                              "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_BF16_TFLOPS,
                              "flop_per_launch": flops,
                              "fp32_equivalent_tflops": 8.0 * n_dom * E / (dom_ms * 1e-3) / 1e12})
@@ -298,6 +299,8 @@ def main() -> int:
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     variant = "+complex128" if c128 else ("+bf16x3" if (args.bf16x3 and form == dft.KDFT) else "")
     roofline["traffic"] = None if (args.three_m or args.unfused) else MEASURED_TRAFFIC.get(name + variant)
+    if args.three_m and form == dft.KDFT and not c128:
+        roofline["complex_scheme"] = "3M"
     roofline["passes_ms"] = {(pass_names[i] if i < len(pass_names) else f"pass{i}"): round(pass_ms[i], 5)
                              for i in range(npass)}
 

@@ -105,13 +105,14 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int t
 
     const int N = a.M.N;
     const int64_t I = a.I;
-    const int ldn = a.M.split_ld;
-    const int64_t plane_stride = (int64_t)a.M.split_rows * ldn;
+    // the bf16 planes are stored tile by tile: [k tile of 128][chunk of 16 n][plane][128 k][16 n], so the
+    // 128 x 16 piece of every plane that one chunk needs is 4 KiB of contiguous memory
     const unsigned short* __restrict__ Vs = a.M.split;
+    const int vchunks = a.M.split_ld / KC;
 
     // this thread's piece of the matrix tile: row = tid / 2 (k), 8 consecutive n
     const int vrow = tid >> 1, vhalf = tid & 1;
-    const unsigned short* vsrc = Vs + (int64_t)(k0 + vrow) * ldn + 8 * vhalf;
+    const unsigned short* vsrc = Vs + (int64_t)kt * vchunks * (kPlanes * 2048) + vrow * 16 + 8 * vhalf;
 
     // this thread's piece of the data tile
     int64_t tile_o = 0, c0 = 0, o0 = 0;
@@ -137,7 +138,7 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int t
     f32x2 xreg[8];
     constexpr int kXLoads = STRIDED ? 8 : 4;
     auto load_v = [&](int n0, int p) {
-        vreg[p] = *reinterpret_cast<const u32x4*>(vsrc + p * plane_stride + n0);
+        vreg[p] = *reinterpret_cast<const u32x4*>(vsrc + (int64_t)(n0 / KC) * (kPlanes * 2048) + p * 2048);
     };
     auto load_x = [&](int n0, int j) {           // j < kXLoads
         if (STRIDED) {
@@ -328,8 +329,9 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int t
 // again as six bf16 level products: 18 instead of 24 MFMAs per complex block and chunk.  The sums
 // Vr+Vi (at plan time, from fp64) and Xr+Xi (in fp32 while staging) are split into their own three
 // levels, so each operand has nine planes: (re, im, sum) x (hi, mid, lo), plane = 3*part + level.
-// LDS rows are 32 bytes (two 16-byte slots) without padding; the slot is XOR-ed with bit 2 of the row
-// so that the eight rows one LDS cycle serves fall on eight different 16-byte bank groups.
+// LDS rows are 32 bytes (two 16-byte slots) without padding; the slot is XOR-ed with bits 2 and 3 of
+// the row, so that any 8 (and any 16) consecutive rows read at the same slot fall on 8 (16) different
+// 16-byte bank groups.
 // Three accumulator sets (192 AGPRs) and nine operand planes per side (144 VGPRs): one wave per SIMD.
 constexpr int kPlanes3 = 9;
 
@@ -358,13 +360,14 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3m(ContractArgs a, int 
 
     const int N = a.M.N;
     const int64_t I = a.I;
-    const int ldn = a.M.split_ld;
-    const int64_t plane_stride = (int64_t)a.M.split_rows * ldn;
+    // the bf16 planes are stored tile by tile: [k tile of 128][chunk of 16 n][plane][128 k][16 n], so the
+    // 128 x 16 piece of every plane that one chunk needs is 4 KiB of contiguous memory
     const unsigned short* __restrict__ Vs = a.M.split;
+    const int vchunks = a.M.split_ld / KC;
 
     // this thread's piece of the matrix tile: row = tid / 2 (k), 8 consecutive n
     const int vrow = tid >> 1, vhalf = tid & 1;
-    const unsigned short* vsrc = Vs + (int64_t)(k0 + vrow) * ldn + 8 * vhalf;
+    const unsigned short* vsrc = Vs + (int64_t)kt * vchunks * (kPlanes3 * 2048) + vrow * 16 + 8 * vhalf;
 
     // this thread's piece of the data tile
     int64_t tile_o = 0, c0 = 0, o0 = 0;
@@ -382,14 +385,14 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3m(ContractArgs a, int 
         xhalf = tid & 1;
         xsrc = a.X + (o0 + xrow) * (int64_t)N + 8 * xhalf;
     }
-    const int vslot = vhalf ^ ((vrow >> 2) & 1);
-    const int xslot = xhalf ^ ((xrow >> 2) & 1);
+    const int vslot = vhalf ^ ((vrow >> 2) & 1) ^ ((vrow >> 3) & 1);
+    const int xslot = xhalf ^ ((xrow >> 2) & 1) ^ ((xrow >> 3) & 1);
 
     u32x4 vreg[kPlanes3];
     f32x2 xreg[8];
     constexpr int kXLoads = STRIDED ? 8 : 4;
     auto load_v = [&](int n0, int p) {
-        vreg[p] = *reinterpret_cast<const u32x4*>(vsrc + p * plane_stride + n0);
+        vreg[p] = *reinterpret_cast<const u32x4*>(vsrc + (int64_t)(n0 / KC) * (kPlanes3 * 2048) + p * 2048);
     };
     auto load_x = [&](int n0, int j) {           // j < kXLoads
         if (STRIDED) {
@@ -487,8 +490,8 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3m(ContractArgs a, int 
     constexpr int kVAt = kXStoreAt + 9;
     constexpr int kSteps = kVAt + 18;
     static_assert(kSteps <= 72, "one step per MFMA at most");
-    // read offsets of this lane: rows r0 + l32 (r0 a multiple of 32) share bit 2 with l32
-    const int rslot = kq ^ ((l32 >> 2) & 1);
+    // read offsets of this lane: rows r0 + l32 (r0 a multiple of 32) share bits 2 and 3 with l32
+    const int rslot = kq ^ ((l32 >> 2) & 1) ^ ((l32 >> 3) & 1);
     for (int c = 0; c < nchunks; ++c) {
         const int buf = c & 1;
         const int n2 = chunk_n0(c + 2);

@@ -26,8 +26,9 @@ struct DeviceMatrix {
     int ld = 0;    // padded K
     int rows = 0;  // padded N
     // Optional bf16 decomposition of the same matrix for the bf16-split contraction: six planes
-    // (Re hi, mid, lo, Im hi, mid, lo), each split_rows x split_ld bf16, ROW-major [k][n] with n
-    // contiguous (a bf16 MFMA operand lane holds 8 consecutive n), zero padded.
+    // (Re hi, mid, lo, Im hi, mid, lo), zero padded to split_rows x split_ld, stored tile by tile as
+    // [k tile of 128][chunk of 16 n][plane][128 k][16 n] (n contiguous: a bf16 MFMA operand lane
+    // holds 8 consecutive n; the piece one kernel iteration needs is contiguous).
     unsigned short* split = nullptr;
     int split_ld = 0;     // padded N (multiple of 16)
     int split_rows = 0;   // padded K (multiple of 128)

@@ -55,31 +55,35 @@ double from_bf16(unsigned short h)
 
 // Build and upload the three-level bf16 decomposition of a K x N complex matrix given as fp64
 // row-major planes: v = v1 + v2 + v3 with vj = bf16(v - v1 - .. - v(j-1)).
+// With with_sum the planes of Re + Im (formed in fp64) follow, for the three-product scheme.
 dft3d_status upload_split(const std::vector<double>& re, const std::vector<double>& im, int K, int N,
-                          DeviceMatrix* m)
+                          bool with_sum, DeviceMatrix* m)
 {
     const int ld = round_up(N, 16), rows = round_up(K, 128);
     const size_t plane = (size_t)ld * rows;
-    std::vector<unsigned short> host(6 * plane, 0);
-    for (int part = 0; part < 2; ++part) {
-        const std::vector<double>& src = part ? im : re;
+    const int parts = with_sum ? 3 : 2;
+    std::vector<unsigned short> host((size_t)(3 * parts) * plane, 0);
+    for (int part = 0; part < parts; ++part) {
         for (int k = 0; k < K; ++k)
             for (int n = 0; n < N; ++n) {
-                double r = src[(size_t)k * N + n];
+                const size_t e = (size_t)k * N + n;
+                double r = part == 0 ? re[e] : (part == 1 ? im[e] : re[e] + im[e]);
+                // tiled layout: [k tile of 128][chunk of 16 n][plane][128 k][16 n]
+                const size_t tile = ((size_t)(k / 128) * (ld / 16) + n / 16) * (size_t)(3 * parts);
                 for (int lvl = 0; lvl < 3; ++lvl) {
                     const unsigned short h = to_bf16(r);
-                    host[(size_t)(3 * part + lvl) * plane + (size_t)k * ld + n] = h;
+                    host[(tile + 3 * part + lvl) * 2048 + (size_t)(k % 128) * 16 + n % 16] = h;
                     r -= from_bf16(h);
                 }
             }
     }
     unsigned short* dev = nullptr;
-    hipError_t e = hipMalloc((void**)&dev, 6 * plane * sizeof(unsigned short));
+    hipError_t e = hipMalloc((void**)&dev, host.size() * sizeof(unsigned short));
     if (e != hipSuccess) {
         set_error("hipMalloc of the bf16 decomposition of a %d x %d matrix failed: %s", K, N, hipGetErrorString(e));
         return DFT3D_ERR_ALLOC;
     }
-    e = hipMemcpy(dev, host.data(), 6 * plane * sizeof(unsigned short), hipMemcpyHostToDevice);
+    e = hipMemcpy(dev, host.data(), host.size() * sizeof(unsigned short), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
         (void)hipFree(dev);
         set_error("upload of the bf16 decomposition failed: %s", hipGetErrorString(e));
@@ -88,6 +92,7 @@ dft3d_status upload_split(const std::vector<double>& re, const std::vector<doubl
     m->split = dev;
     m->split_ld = ld;
     m->split_rows = rows;
+    m->split_planes = 3 * parts;
     return DFT3D_OK;
 }
 
@@ -158,7 +163,7 @@ dft3d_status upload_matrix(const std::vector<float>& re, const std::vector<float
 }
 
 dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out, bool with_split = false,
-                              bool with_f64 = false)
+                              bool with_f64 = false, bool split_sum = false)
 {
     std::vector<float> re((size_t)n * n), im((size_t)n * n);
     dft3d_status s = dft3d_generate_matrix(n, coords, DFT3D_FORWARD, re.data(), im.data());
@@ -172,7 +177,7 @@ dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out
             if (coords) unit_root_turns((double)k * coords[j], DFT3D_FORWARD, &dre[k * n + j], &dim[k * n + j]);
             else unit_root_ratio(k * j, n, DFT3D_FORWARD, &dre[k * n + j], &dim[k * n + j]);
         }
-    if (with_split) s = upload_split(dre, dim, (int)n, (int)n, out);
+    if (with_split) s = upload_split(dre, dim, (int)n, (int)n, split_sum, out);
     if (s == DFT3D_OK && with_f64) s = upload_f64(dre, dim, (int)n, (int)n, out);
     return s;
 }
@@ -535,7 +540,7 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
                 if (!c[j] && !c[i] && n[i] == n[j]) { p->M_owner[j] = i; break; }
             if (p->M_owner[j] == j)
                 s = make_axis_matrix(n[j], c[j], &p->M[j], (flags & DFT3D_FLAG_BF16X3) != 0,
-                                     (flags & DFT3D_FLAG_COMPLEX128) != 0);
+                                     (flags & DFT3D_FLAG_COMPLEX128) != 0, (flags & DFT3D_FLAG_3M) != 0);
             else p->M[j] = p->M[p->M_owner[j]];
         }
     } else {

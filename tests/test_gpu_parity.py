@@ -163,12 +163,14 @@ def test_kdft_arbitrary_evaluation_points(dft, shape, ks):
 
 
 @pytest.mark.parametrize("shape", [(128, 128, 128), (256, 256, 256), (128, 384, 256), (130, 256, 128)])
-def test_kdft_bf16_split_scheme(dft, shape):
-    """DFT3D_FLAG_BF16X3: three bf16 levels per fp32 number on the bf16 matrix cores; same tolerance."""
-    say(f"case kdft bf16x3 {shape}")
+@pytest.mark.parametrize("three_m", [False, True])
+def test_kdft_bf16_split_scheme(dft, shape, three_m):
+    """DFT3D_FLAG_BF16X3: three bf16 levels per fp32 number on the bf16 matrix cores; same tolerance.
+    Together with DFT3D_FLAG_3M: three real products per complex product (nine planes per operand)."""
+    say(f"case kdft bf16x3 {shape} three_m={three_m}")
     x = wl.draw_complex(shape, "normal", 2700 + sum(shape))
     want = orc.dft3d(x)
-    with dft.Plan(shape, dft.KDFT, flags=dft.FLAG_BF16X3) as p:
+    with dft.Plan(shape, dft.KDFT, flags=dft.FLAG_BF16X3 | (dft.FLAG_3M if three_m else 0)) as p:
         xd = to_dev(x)
         got = to_host(p.exec(xd))
         assert report(f"kdft bf16x3 {shape}", got, want) <= TOL
