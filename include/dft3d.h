@@ -59,7 +59,8 @@ typedef enum { DFT3D_FORWARD = -1, DFT3D_BACKWARD = 1 } dft3d_direction;
                                        number is decomposed into three bf16 numbers and six cross
                                        products are accumulated in fp32 (Section II-A of the paper);
                                        used for modes whose shape is a whole number of 128x128 tiles,
-                                       other modes fall back to the fp32 kernels */
+                                       other modes fall back to the fp32 kernels.  With DFT3D_FLAG_3M
+                                       the bf16 kernels use three real products as well */
 #define DFT3D_FLAG_COMPLEX128 16u   /* KDFT: tensors are complex128 (interleaved doubles), matrices are kept
                                        in fp64 and the contractions run on the fp64 matrix cores (the
                                        float64 precision the paper leaves as future work, Section VI).
