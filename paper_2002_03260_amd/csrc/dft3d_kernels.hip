@@ -1299,8 +1299,7 @@ hipError_t launch_fft_z_inst(const float2* in, float2* out, int64_t nrows, const
 
 bool fft_z_supported(int A, int B)
 {
-    return (A == 16 && B == 16) || (A == 16 && B == 32) || (A == 32 && B == 32) ||
-           (A == 32 && B == 64) || (A == 64 && B == 64);
+    return fft_zr_supported(A, B) || (A == 64 && B == 64);
 }
 
 hipError_t launch_fft_z(const float2* in, float2* out, int64_t nrows, int A, int B,
@@ -1308,11 +1307,8 @@ hipError_t launch_fft_z(const float2* in, float2* out, int64_t nrows, int A, int
                         int conj, hipStream_t stream)
 {
     if (nrows <= 0) return hipSuccess;
+    // the register-resident kernels cover every offered split but 64 x 64
     if (fft_zr_supported(A, B)) return launch_fft_zr(in, out, nrows, A, B, FA, FB, Tw, scale, conj, stream);
-    if (A == 16 && B == 16) return launch_fft_z_inst<16, 16, 8, 4, 2, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
-    if (A == 16 && B == 32) return launch_fft_z_inst<16, 32, 4, 8, 4, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
-    if (A == 32 && B == 32) return launch_fft_z_inst<32, 32, 2, 4, 2, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
-    if (A == 32 && B == 64) return launch_fft_z_inst<32, 64, 2, 8, 2, 1>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     if (A == 64 && B == 64) return launch_fft_z_inst<64, 64, 1, 8, 2, 1>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     return hipErrorInvalidValue;
 }

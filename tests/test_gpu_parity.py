@@ -60,7 +60,7 @@ def to_host(t):
 
 # ------------------------------------------------------------------------------------ KDFT
 KDFT_SHAPES = [(4, 4, 4), (5, 7, 3), (1, 1, 9), (9, 1, 1), (17, 33, 20), (32, 32, 32),
-               (64, 48, 80), (130, 20, 258), (24, 200, 36)]
+               (64, 48, 80), (130, 20, 258), (24, 200, 36), (16, 64, 48), (3, 32, 16), (64, 16, 144)]
 
 
 @pytest.mark.parametrize("shape", KDFT_SHAPES)
@@ -288,7 +288,9 @@ def test_generated_matrix_on_device_equals_host_generator(dft):
 
 # ------------------------------------------------------------------------------------ FFT steps
 FFT_CASES = [((16, 16, 16), None), ((8, 12, 30), (2, 3, 5)), ((64, 32, 128), None),
-             ((36, 20, 48), (6, 4, 8)), ((32, 32, 512), (4, 8, 16)), ((6, 5, 7), (3, 1, 7))]
+             ((36, 20, 48), (6, 4, 8)), ((32, 32, 512), (4, 8, 16)), ((6, 5, 7), (3, 1, 7)),
+             # strided stages with 16 / 32 / 64-point matrices and inner extents that are multiples of 16
+             ((4, 2048, 16), None), ((2, 4096, 16), (0, 64, 0)), ((512, 3, 48), (16, 0, 0)), ((1024, 1, 80), (16, 0, 0))]
 
 
 @pytest.mark.parametrize("shape,split", FFT_CASES)
