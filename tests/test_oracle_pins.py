@@ -221,6 +221,19 @@ def test_matches_numpy_fftn(shape):
     assert rel_l2(orc.dft3d(x), want) < 1e-12
 
 
+@pytest.mark.parametrize("shape", [(6, 10, 15), (16, 16, 16), (1, 12, 40)])
+def test_mode_products_on_a_complex128_tensor_match_numpy_fftn(shape):
+    """The composition the complex128 parity tests use as their oracle (matrix per axis, modes
+    z, y, x on a full-precision complex128 tensor), pinned to the library FFT in both directions."""
+    rng = np.random.default_rng(77 + shape[1])
+    x = rng.standard_normal(shape) + 1j * rng.standard_normal(shape)
+    for sign, want in ((orc.FORWARD, np.fft.fftn(x)), (orc.BACKWARD, np.fft.ifftn(x) * x.size)):
+        y = x
+        for axis in (2, 1, 0):
+            y = orc.mode_contract(orc.dft_matrix(shape[axis], None, sign), y, axis)
+        assert rel_l2(y, want) < 1e-13
+
+
 # --------------------------------------------------------------------------- P6: nonuniform closed forms
 def test_nonuniform_delta_dirichlet_sum():
     n = 16
