@@ -21,18 +21,18 @@ pytestmark = pytest.mark.gpu
 
 TOL = 2e-5
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-# progress lines also go to a scratch folder at the repository root when it exists (a file that
-# keeps growing shows a long test is alive even when stdout is captured)
-_PROGRESS = os.path.join(ROOT, os.environ.get("DFT3D_PROGRESS_DIR", "gpurun_out"), "test_progress.log")
+# progress lines also go to the file DFT3D_PROGRESS_DIR/test_progress.log when that variable names an
+# existing folder (a file that keeps growing shows a long test is alive even when stdout is captured)
+_PROGRESS_DIR = os.environ.get("DFT3D_PROGRESS_DIR", "")
 
 
 def say(msg):
-    """Progress line on stdout and, when the folder exists, in a file (long tests stay visibly alive)."""
+    """Progress line on stdout and, when asked for, in a file (long tests stay visibly alive)."""
     line = f"[{time.strftime('%H:%M:%S')}] {msg}"
     print(line, flush=True)
     try:
-        if os.path.isdir(os.path.dirname(_PROGRESS)):
-            with open(_PROGRESS, "a") as f:
+        if _PROGRESS_DIR and os.path.isdir(_PROGRESS_DIR):
+            with open(os.path.join(_PROGRESS_DIR, "test_progress.log"), "a") as f:
                 f.write(line + "\n")
     except OSError:
         pass
