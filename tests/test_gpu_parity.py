@@ -60,7 +60,8 @@ def to_host(t):
 
 # ------------------------------------------------------------------------------------ KDFT
 KDFT_SHAPES = [(4, 4, 4), (5, 7, 3), (1, 1, 9), (9, 1, 1), (17, 33, 20), (32, 32, 32),
-               (64, 48, 80), (130, 20, 258), (24, 200, 36), (16, 64, 48), (3, 32, 16), (64, 16, 144)]
+               (64, 48, 80), (130, 20, 258), (24, 200, 36), (16, 64, 48), (3, 32, 16), (64, 16, 144),
+               (128, 192, 64), (320, 64, 128)]
 
 
 @pytest.mark.parametrize("shape", KDFT_SHAPES)
