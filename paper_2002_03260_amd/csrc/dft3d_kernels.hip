@@ -62,6 +62,7 @@ __device__ __forceinline__ void trace_mark(int slot)
     if (threadIdx.x == 0 && g_trace) {
         const int64_t b = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
         g_trace[b * 8 + slot] = wall_clock64();
+        if (slot == 1 || slot == 2) g_trace[b * 8 + 3 + slot] = clock64();     // shader-clock count
         if (slot == 0) {
             g_trace[b * 8 + 6] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));    // HW_ID
             g_trace[b * 8 + 7] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11));   // XCC_ID
@@ -100,6 +101,26 @@ __device__ __forceinline__ typename CVec<EV>::type cvec_zero();
 template <> __device__ __forceinline__ f32x2 cvec_zero<1>() { return f32x2{0.f, 0.f}; }
 template <> __device__ __forceinline__ f32x4 cvec_zero<2>() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
 
+// B consecutive floats (B = 1, 2, 4; aligned to their total size) in one LDS read
+template <int B>
+__device__ __forceinline__ void load_floats(float* dst, const float* src)
+{
+    static_assert(B == 1 || B == 2 || B == 4, "one, two or four floats");
+    if constexpr (B == 1) {
+        dst[0] = src[0];
+    } else if constexpr (B == 2) {
+        const f32x2 v = *reinterpret_cast<const f32x2*>(src);
+        dst[0] = v.x;
+        dst[1] = v.y;
+    } else {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(src);
+        dst[0] = v.x;
+        dst[1] = v.y;
+        dst[2] = v.z;
+        dst[3] = v.w;
+    }
+}
+
 // store one or two complex numbers to an LDS location that is only 8-byte aligned
 __device__ __forceinline__ void store_cvec(float2* dst, f32x2 v)
 {
@@ -124,6 +145,7 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     static_assert((TM / WM) * NWN == 4, "four waves per workgroup");
     static_assert(!MASKED || EV == 1, "the masked path loads single elements");
     constexpr int BM = WM / 16, BN = WN / 16, KS = KC / 4;
+    static_assert(BN % 2 == 0, "column blocks are read and stored in pairs");
     constexpr int XP = TN + 16;   // float2 pitch: rows n, n+1 land 32 banks apart (b64 reads conflict-free)
     constexpr int VP = TM + 16;   // float pitch: rows n..n+3 land 16 banks apart
     constexpr int TPR = TN / EV;                  // threads per tile row
@@ -180,43 +202,59 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     xvec xreg[XL];
     f32x4 vrreg[VL], vireg[VL];
 
-    auto gload = [&](int n0) {
-#pragma unroll
-        for (int j = 0; j < VL; ++j) {
-            const int f = tid + j * kThreads;
-            if (VV % kThreads == 0 || f < VV) {
-                const int r = f / (TM / 4), c4 = f % (TM / 4);
-                const int64_t off = (int64_t)(n0 + r) * a.M.ld + k0 + c4 * 4;
-                vrreg[j] = *reinterpret_cast<const f32x4*>(a.M.re + off);
-                vireg[j] = *reinterpret_cast<const f32x4*>(a.M.im + off);
+    // Global loads and LDS stores of one chunk come in VL + XL pieces each (piece j < VL: both matrix
+    // planes' j-th vector, piece VL + j: the j-th data vector), so the main loop can spread them
+    // between its MFMAs.
+    // Load addresses are a uniform 64-bit base (tile, chunk, piece: scalar registers and scalar
+    // arithmetic) plus a 32-bit lane offset that never changes, so the main loop spends no vector
+    // instructions on them.  The launcher keeps the fast path to shapes whose lane offsets fit.
+    static_assert(kThreads % (TM / 4) == 0, "a piece covers whole matrix rows");
+    constexpr int VRP = kThreads / (TM / 4);      // matrix rows per piece
+    // (byte offsets, so that the 32-bit value is added to the base as it stands)
+    const unsigned v_lane = ((unsigned)(tid / (TM / 4)) * (unsigned)a.M.ld + (unsigned)(tid % (TM / 4)) * 4u) * 4u;
+    const unsigned x_lane = ((unsigned)xr * (unsigned)I + (unsigned)xc) * 8u;     // fast path only
+    const float2* __restrict__ Xu = a.X + tile_o * (int64_t)N * I + c0;    // fast path only
+    auto gload_piece = [&](int n0, int p) {
+        if (p < VL) {
+            if (VV % kThreads == 0 || tid + p * kThreads < VV) {
+                const int64_t base = (int64_t)(n0 + p * VRP) * a.M.ld + k0;
+                vrreg[p] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(a.M.re + base) + v_lane);
+                vireg[p] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(a.M.im + base) + v_lane);
             }
-        }
-#pragma unroll
-        for (int j = 0; j < XL; ++j) {
-            const int n = n0 + xr + j * XRPP;
+        } else {
+            const int j = p - VL;
             if (MASKED) {
+                const int n = n0 + xr + j * XRPP;
                 const int nn = n < N ? n : N - 1;
                 xvec v = *reinterpret_cast<const xvec*>(Xo + (int64_t)nn * I);
                 xreg[j] = (xcol_ok && n < N) ? v : cvec_zero<EV>();
             } else {
-                xreg[j] = *reinterpret_cast<const xvec*>(Xo + (int64_t)n * I);
+                const float2* row = Xu + (int64_t)(n0 + j * XRPP) * I;
+                xreg[j] = *reinterpret_cast<const xvec*>(reinterpret_cast<const char*>(row) + x_lane);
             }
         }
     };
     const float vsign = a.conj ? -1.0f : 1.0f;
-    auto lstore = [&](int buf) {
-#pragma unroll
-        for (int j = 0; j < VL; ++j) {
-            const int f = tid + j * kThreads;
+    auto lstore_piece = [&](int buf, int p) {
+        if (p < VL) {
+            const int f = tid + p * kThreads;
             if (VV % kThreads == 0 || f < VV) {
                 const int r = f / (TM / 4), c4 = f % (TM / 4);
-                *reinterpret_cast<f32x4*>(&Vr[buf][r][c4 * 4]) = vrreg[j];
-                *reinterpret_cast<f32x4*>(&Vi[buf][r][c4 * 4]) = vireg[j] * vsign;
+                *reinterpret_cast<f32x4*>(&Vr[buf][r][c4 * 4]) = vrreg[p];
+                *reinterpret_cast<f32x4*>(&Vi[buf][r][c4 * 4]) = vireg[p] * vsign;
             }
-        }
-#pragma unroll
-        for (int j = 0; j < XL; ++j)
+        } else {
+            const int j = p - VL;
             *reinterpret_cast<xvec*>(&Xs[buf][xr + j * XRPP][xc]) = xreg[j];
+        }
+    };
+    auto gload = [&](int n0) {
+#pragma unroll
+        for (int p = 0; p < VL + XL; ++p) gload_piece(n0, p);
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < VL + XL; ++p) lstore_piece(buf, p);
     };
 
     // SCHEME 4: accr / acci hold Re / Im.  SCHEME 3 (three real products per complex one):
@@ -243,26 +281,44 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     for (int c = 0; c < nchunks; ++c) {
         const int buf = (NB == 2) ? (c & 1) : 0;
         const bool more = (c + 1) < nchunks;
-        if (NB == 2) {
-            // chunk c+1 was requested one whole chunk ago: move it to the other LDS buffer now
-            // (nobody reads that buffer any more) and request chunk c+2; both overlap the MFMAs
-            if (more) lstore(buf ^ 1);
-            if (c + 2 < nchunks) gload((c + 2) * KC);
-        } else if (more) {
-            gload((c + 1) * KC);
-        }
+        if (NB == 1 && more) gload((c + 1) * KC);
+        // NB == 2: chunk c+1 was requested one whole chunk ago: it moves to the other LDS buffer now
+        // (nobody reads that buffer any more) and chunk c+2 is requested, piece by piece between the
+        // groups of MFMAs below.  The pieces run unconditionally so that they stay in the MFMAs' basic
+        // block: past the end they store stale registers into the buffer nobody reads any more and
+        // load the last chunk again.
+        const int n2 = (c + 2 < nchunks ? c + 2 : nchunks - 1) * KC;
+        constexpr int NPH = (SCHEME == 3) ? 3 : 4;          // MFMA groups per k-step
+        constexpr int NSLOT = KS * NPH, NPIECE = 2 * (VL + XL);
+        auto side = [&](int slot) {
+            if (NB != 2) return;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int p = 0; p < NPIECE; ++p) {
+                if (p * NSLOT / NPIECE != slot) continue;
+                // a piece's store is followed by the load that refills its registers, so every
+                // load has a whole chunk of MFMAs to arrive
+                if (p % 2 == 0) lstore_piece(buf ^ 1, p / 2);
+                else gload_piece(n2, p / 2);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // Which tile row an MFMA row stands for, and which tile column an MFMA column, is free as
+        // long as the epilogue stores by the same rule.  Row i of block bm is tile row BM*i + bm and
+        // columns j of the blocks 2q, 2q+1 are tile columns 32q + 2j, 32q + 2j + 1 of the wave tile,
+        // so a lane's operands for all blocks are contiguous in LDS: one read per plane and column pair.
         float ar[2][BM], ai[2][BM];
         f32x2 bx[2][BN];
         auto read_operands = [&](int slot, int s) {
             const int n = 4 * s + lq;
+            load_floats<BM>(ar[slot], &Vr[buf][n][wm0 + BM * l16]);
+            load_floats<BM>(ai[slot], &Vi[buf][n][wm0 + BM * l16]);
 #pragma unroll
-            for (int bm = 0; bm < BM; ++bm) {
-                ar[slot][bm] = Vr[buf][n][wm0 + bm * 16 + l16];
-                ai[slot][bm] = Vi[buf][n][wm0 + bm * 16 + l16];
+            for (int q = 0; q < BN / 2; ++q) {
+                const f32x4 x = *reinterpret_cast<const f32x4*>(&Xs[buf][n][wn0 + 32 * q + 2 * l16]);
+                bx[slot][2 * q] = f32x2{x.x, x.y};
+                bx[slot][2 * q + 1] = f32x2{x.z, x.w};
             }
-#pragma unroll
-            for (int bn = 0; bn < BN; ++bn)
-                bx[slot][bn] = *reinterpret_cast<const f32x2*>(&Xs[buf][n][wn0 + bn * 16 + l16]);
         };
         read_operands(0, 0);
 #pragma unroll
@@ -280,16 +336,19 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         accr[bm][bn] = mfma16(ar[cur][bm], bx[cur][bn].x, accr[bm][bn]);
+                side(NPH * s);
 #pragma unroll
                 for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         acci[bm][bn] = mfma16(ai[cur][bm], bx[cur][bn].y, acci[bm][bn]);
+                side(NPH * s + 1);
 #pragma unroll
                 for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         acc3[bm % M3][bn % B3] = mfma16(as[bm], bs[bn], acc3[bm % M3][bn % B3]);
+                side(NPH * s + 2);
             } else {
                 float an[BM];
 #pragma unroll
@@ -299,21 +358,25 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         accr[bm][bn] = mfma16(ar[cur][bm], bx[cur][bn].x, accr[bm][bn]);
+                side(NPH * s);
 #pragma unroll
                 for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         acci[bm][bn] = mfma16(ar[cur][bm], bx[cur][bn].y, acci[bm][bn]);
+                side(NPH * s + 1);
 #pragma unroll
                 for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         accr[bm][bn] = mfma16(an[bm], bx[cur][bn].y, accr[bm][bn]);
+                side(NPH * s + 2);
 #pragma unroll
                 for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         acci[bm][bn] = mfma16(ai[cur][bm], bx[cur][bn].x, acci[bm][bn]);
+                side(NPH * s + 3);
             }
         }
         if (NB == 1) {
@@ -325,41 +388,68 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     }
 
     TRACE_MARK(2);
-    // epilogue: scale, optional twiddle, store (16 consecutive columns per quarter-wave)
+    // epilogue: scale, optional twiddle, store.  Accumulator register v of block (bm, bn) is MFMA row
+    // 4 * lq + v, column l16: tile row BM * (4 * lq + v) + bm, and the blocks 2q, 2q+1 hold two
+    // neighbouring columns, stored together (a quarter-wave writes 256 contiguous bytes per row).
     const int K = a.M.K;
+    const bool pair_store = !MASKED && (((a.sYk | a.sYohi | a.sYolo) & 1) == 0) &&
+                            ((reinterpret_cast<uintptr_t>(a.Y) & 15) == 0);
 #pragma unroll
-    for (int bn = 0; bn < BN; ++bn) {
-        int64_t o = tile_o, col = c0 + wn0 + bn * 16 + l16;
-        if (MASKED) {
-            if (col >= a.O * I) continue;
-            o = col / I;
-            col -= o * I;
+    for (int q = 0; q < BN / 2; ++q) {
+        int64_t col[2];
+        bool ok[2];
+        float2* __restrict__ Yo[2];
+        int beta[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            int64_t o = tile_o;
+            col[e] = c0 + wn0 + 32 * q + 2 * l16 + e;
+            ok[e] = true;
+            if (MASKED) {
+                ok[e] = col[e] < a.O * I;
+                const int64_t cc = ok[e] ? col[e] : 0;
+                o = cc / I;
+                col[e] = cc - o * I;
+            }
+            Yo[e] = a.Y + out_offset(a, o);
+            beta[e] = a.Tw ? (int)((uint32_t)col[e] / (uint32_t)a.twInner) : 0;   // col < I < 2^31
         }
-        float2* __restrict__ Yo = a.Y + out_offset(a, o);
-        const int beta = a.Tw ? (int)((uint32_t)col / (uint32_t)a.twInner) : 0;   // col < I < 2^31
 #pragma unroll
         for (int bm = 0; bm < BM; ++bm) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int k = k0 + wm0 + bm * 16 + 4 * lq + v;
+                const int k = k0 + wm0 + BM * (4 * lq + v) + bm;
                 if (MASKED && k >= K) continue;
-                float yr, yi;
-                if (SCHEME == 3) {
-                    yr = (accr[bm][bn][v] - acci[bm][bn][v]) * a.scale;
-                    yi = (acc3[bm % M3][bn % B3][v] - accr[bm][bn][v] - acci[bm][bn][v]) * a.scale;
+                float2 y[2];
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int bn = 2 * q + e;
+                    float yr, yi;
+                    if (SCHEME == 3) {
+                        yr = (accr[bm][bn][v] - acci[bm][bn][v]) * a.scale;
+                        yi = (acc3[bm % M3][bn % B3][v] - accr[bm][bn][v] - acci[bm][bn][v]) * a.scale;
+                    } else {
+                        yr = accr[bm][bn][v] * a.scale;
+                        yi = acci[bm][bn][v] * a.scale;
+                    }
+                    if (a.Tw) {
+                        float2 w = a.Tw[(int64_t)k * a.twB + beta[e]];
+                        if (a.conj) w.y = -w.y;
+                        const float tr = yr * w.x - yi * w.y;
+                        const float ti = yr * w.y + yi * w.x;
+                        yr = tr;
+                        yi = ti;
+                    }
+                    y[e] = make_float2(yr, yi);
+                }
+                if (pair_store) {
+                    *reinterpret_cast<f32x4*>(Yo[0] + (int64_t)k * a.sYk + col[0]) =
+                        f32x4{y[0].x, y[0].y, y[1].x, y[1].y};
                 } else {
-                    yr = accr[bm][bn][v] * a.scale;
-                    yi = acci[bm][bn][v] * a.scale;
+#pragma unroll
+                    for (int e = 0; e < 2; ++e)
+                        if (ok[e]) Yo[e][(int64_t)k * a.sYk + col[e]] = y[e];
                 }
-                if (a.Tw) {
-                    float2 w = a.Tw[(int64_t)k * a.twB + beta];
-                    if (a.conj) w.y = -w.y;
-                    float tr = yr * w.x - yi * w.y;
-                    float ti = yr * w.y + yi * w.x;
-                    yr = tr;
-                    yi = ti;
-                }
-                Yo[(int64_t)k * a.sYk + col] = make_float2(yr, yi);
             }
         }
     }
@@ -491,11 +581,10 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
 #pragma unroll
             for (int bm = 0; bm < BM; ++bm)
                 ax[slot][bm] = *reinterpret_cast<const f32x2*>(&Xs[buf][wo0 + bm * 16 + l16][n]);
-#pragma unroll
-            for (int bn = 0; bn < BN; ++bn) {
-                br[slot][bn] = Vr[buf][n][wk0 + bn * 16 + l16];
-                bi[slot][bn] = Vi[buf][n][wk0 + bn * 16 + l16];
-            }
+            // column j of block bn is tile column BN * j + bn of the wave tile: a lane's matrix
+            // operands for all blocks are contiguous in LDS (the epilogue stores by the same rule)
+            load_floats<BN>(br[slot], &Vr[buf][n][wk0 + BN * l16]);
+            load_floats<BN>(bi[slot], &Vi[buf][n][wk0 + BN * l16]);
         };
         read_operands(0, 0);
 #pragma unroll
@@ -552,17 +641,22 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
         __syncthreads();
     }
 
+    // epilogue: block bn holds tile columns BN * l16 + bn, so a lane owns BN consecutive k of each of
+    // its rows: stored together where the output keeps k contiguous
     const int K = a.M.K;
+    const bool run_store = !MASKED && a.sYk == 1 && (((a.sYohi | a.sYolo) & 1) == 0) &&
+                           ((reinterpret_cast<uintptr_t>(a.Y) & 15) == 0);
 #pragma unroll
-    for (int bn = 0; bn < BN; ++bn) {
-        const int k = k0 + wk0 + bn * 16 + l16;
-        if (MASKED && k >= K) continue;
+    for (int bm = 0; bm < BM; ++bm) {
 #pragma unroll
-        for (int bm = 0; bm < BM; ++bm) {
+        for (int v = 0; v < 4; ++v) {
+            const int64_t orow = o0 + wo0 + bm * 16 + 4 * lq + v;
+            if (MASKED && orow >= O) continue;
+            float2* __restrict__ Yo = a.Y + out_offset(a, orow);
+            float2 y[BN];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int64_t orow = o0 + wo0 + bm * 16 + 4 * lq + v;
-                if (MASKED && orow >= O) continue;
+            for (int bn = 0; bn < BN; ++bn) {
+                const int k = k0 + wk0 + BN * l16 + bn;
                 float yr, yi;
                 if (SCHEME == 3) {
                     yr = (accr[bm][bn][v] - acci[bm][bn][v]) * a.scale;
@@ -571,15 +665,25 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
                     yr = accr[bm][bn][v] * a.scale;
                     yi = acci[bm][bn][v] * a.scale;
                 }
-                if (a.Tw) {   // I == 1 means beta == 0
+                if (a.Tw && (!MASKED || k < K)) {   // I == 1 means beta == 0
                     float2 w = a.Tw[(int64_t)k * a.twB];
                     if (a.conj) w.y = -w.y;
-                    float tr = yr * w.x - yi * w.y;
-                    float ti = yr * w.y + yi * w.x;
+                    const float tr = yr * w.x - yi * w.y;
+                    const float ti = yr * w.y + yi * w.x;
                     yr = tr;
                     yi = ti;
                 }
-                a.Y[out_offset(a, orow) + (int64_t)k * a.sYk] = make_float2(yr, yi);
+                y[bn] = make_float2(yr, yi);
+            }
+            const int kb = k0 + wk0 + BN * l16;
+            if (run_store && BN % 2 == 0) {
+#pragma unroll
+                for (int bn = 0; bn + 1 < BN; bn += 2)
+                    *reinterpret_cast<f32x4*>(Yo + kb + bn) = f32x4{y[bn].x, y[bn].y, y[bn + 1].x, y[bn + 1].y};
+            } else {
+#pragma unroll
+                for (int bn = 0; bn < BN; ++bn)
+                    if (!MASKED || kb + bn < K) Yo[(int64_t)(kb + bn) * a.sYk] = y[bn];
             }
         }
     }
@@ -1209,7 +1313,9 @@ hipError_t launch_s(const ContractArgs& a, hipStream_t stream)
 {
     const int K = a.M.K, N = a.M.N;
     const int tk = (int)cdiv(K, TM);
-    const bool whole = (K % TM == 0) && (N % KC == 0) && (a.I % TN == 0);
+    // (the fast path addresses its loads with 32-bit lane offsets of up to 8 rows of I elements)
+    const bool whole = (K % TM == 0) && (N % KC == 0) && (a.I % TN == 0) && a.I < (1 << 25) &&
+                       a.M.ld < (1 << 21);
     if (whole) {
         const int64_t ti = a.I / TN;
         const int64_t total = (int64_t)tk * ti * a.O;
