@@ -164,8 +164,13 @@ def main() -> int:
         w = wl.WORKLOADS[name]
     form = form_override if form_override is not None else w.formulation
     big = w.elements > (1 << 30)
-    steps = args.steps if args.steps is not None else (3 if (big and form == dft.KDFT) else 20)
-    warmup = args.warmup if args.warmup is not None else (1 if big else 3)
+    steps = args.steps if args.steps is not None else (3 if (big and form == dft.KDFT) else 100)
+    warmup = args.warmup if args.warmup is not None else (1 if big else 10)
+    # The shader clock of an idle MI355X takes some tenths of a second of load to reach its sustained
+    # value (counted inside the 256^3 contraction kernel: 2.09 GHz in the first milliseconds, 2.35 GHz
+    # sustained), so sub-millisecond workloads run the same step untimed for this long before the
+    # warmup steps; the seconds-long workloads need none.
+    settle_s = 0.0 if big else 0.3
 
     coords = wl.make_coords(w)
     split = [a for a, _ in w.splits] if (form == dft.FFT and w.splits) else None
@@ -191,6 +196,11 @@ def main() -> int:
     plan.ensure_workspace()
     stream = torch.cuda.current_stream()
 
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < settle_s:
+        for _ in range(20):
+            plan.exec(x, out, stream=stream)
+        torch.cuda.synchronize()
     for _ in range(warmup):
         plan.exec(x, out, stream=stream)
     torch.cuda.synchronize()
@@ -319,6 +329,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": w.name + ("" if form_override is None else ("_fft" if form == dft.FFT else "_kdft")),
+            "clock_settle_s": settle_s,
             "formulation": "FFT" if form == dft.FFT else "KDFT",
             "complex_scheme": "3M" if (args.three_m and form == dft.KDFT) else "4M",
             "arithmetic": "fp64 MFMA" if c128 else

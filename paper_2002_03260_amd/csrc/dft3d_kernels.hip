@@ -506,47 +506,58 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
     xvec xreg[XL];
     f32x4 vrreg[VL], vireg[VL];
 
-    auto gload = [&](int n0) {
-#pragma unroll
-        for (int j = 0; j < VL; ++j) {
-            const int f = tid + j * kThreads;
-            if (VV % kThreads == 0 || f < VV) {
-                const int r = f / (TK / 4), c4 = f % (TK / 4);
-                const int64_t off = (int64_t)(n0 + r) * a.M.ld + k0 + c4 * 4;
-                vrreg[j] = *reinterpret_cast<const f32x4*>(a.M.re + off);
-                vireg[j] = *reinterpret_cast<const f32x4*>(a.M.im + off);
+    // Loads and LDS stores of one chunk in VL + XL pieces (piece j < VL: both matrix planes' j-th
+    // vector, piece VL + j: the j-th data vector), spread between the MFMAs of the main loop.  Load
+    // addresses: uniform 64-bit base plus a constant 32-bit lane offset in bytes (the launcher keeps
+    // the fast path to shapes whose offsets fit).
+    static_assert(kThreads % (TK / 4) == 0, "a piece covers whole matrix rows");
+    constexpr int VRP = kThreads / (TK / 4);
+    const unsigned v_lane = ((unsigned)(tid / (TK / 4)) * (unsigned)a.M.ld + (unsigned)(tid % (TK / 4)) * 4u) * 4u;
+    const unsigned x_lane = ((unsigned)xr * (unsigned)N + (unsigned)xc) * 8u;     // fast path only
+    auto gload_piece = [&](int n0, int p) {
+        if (p < VL) {
+            if (VV % kThreads == 0 || tid + p * kThreads < VV) {
+                const int64_t base = (int64_t)(n0 + p * VRP) * a.M.ld + k0;
+                vrreg[p] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(a.M.re + base) + v_lane);
+                vireg[p] = *reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(a.M.im + base) + v_lane);
             }
-        }
-#pragma unroll
-        for (int j = 0; j < XL; ++j) {
-            const int64_t orow = o0 + xr + j * XRPP;
-            const int n = n0 + xc;
+        } else {
+            const int j = p - VL;
             if (MASKED) {
+                const int64_t orow = o0 + xr + j * XRPP;
+                const int n = n0 + xc;
                 const int64_t oo = orow < O ? orow : O - 1;
                 const int nn = n < N ? n : N - 1;
                 xvec v = *reinterpret_cast<const xvec*>(a.X + oo * N + nn);
                 xreg[j] = (orow < O && n < N) ? v : cvec_zero<EV>();
             } else {
-                xreg[j] = *reinterpret_cast<const xvec*>(a.X + orow * N + n);
+                const float2* row = a.X + (o0 + j * XRPP) * (int64_t)N + n0;
+                xreg[j] = *reinterpret_cast<const xvec*>(reinterpret_cast<const char*>(row) + x_lane);
             }
         }
     };
     const float vsign = a.conj ? -1.0f : 1.0f;
-    auto lstore = [&](int buf) {
-#pragma unroll
-        for (int j = 0; j < VL; ++j) {
-            const int f = tid + j * kThreads;
+    auto lstore_piece = [&](int buf, int p) {
+        if (p < VL) {
+            const int f = tid + p * kThreads;
             if (VV % kThreads == 0 || f < VV) {
                 const int r = f / (TK / 4), c4 = f % (TK / 4);
-                *reinterpret_cast<f32x4*>(&Vr[buf][r][c4 * 4]) = vrreg[j];
-                *reinterpret_cast<f32x4*>(&Vi[buf][r][c4 * 4]) = vireg[j] * vsign;
+                *reinterpret_cast<f32x4*>(&Vr[buf][r][c4 * 4]) = vrreg[p];
+                *reinterpret_cast<f32x4*>(&Vi[buf][r][c4 * 4]) = vireg[p] * vsign;
             }
-        }
-#pragma unroll
-        for (int j = 0; j < XL; ++j) {
+        } else {
+            const int j = p - VL;
             float2* dst = &Xs[buf][xr + j * XRPP][xc];     // odd pitch: 8-byte aligned only
             store_cvec(dst, xreg[j]);
         }
+    };
+    auto gload = [&](int n0) {
+#pragma unroll
+        for (int p = 0; p < VL + XL; ++p) gload_piece(n0, p);
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < VL + XL; ++p) lstore_piece(buf, p);
     };
 
     // SCHEME 4: accr / acci hold Re / Im.  SCHEME 3 (three real products per complex one):
@@ -571,9 +582,28 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
 
     for (int c = 0; c < nchunks; ++c) {
         const int buf = c & 1;
-        const bool more = (c + 1) < nchunks;
-        if (more) lstore(buf ^ 1);          // chunk c+1, requested one whole chunk ago
-        if (c + 2 < nchunks) gload((c + 2) * KC);
+        // Chunk c+1, requested one whole chunk ago, moves to the other LDS buffer and chunk c+2 is
+        // requested, piece by piece between the groups of MFMAs.  The pieces run unconditionally so that
+        // they stay in the MFMAs' basic block: past the end they store stale registers into the buffer
+        // nobody reads any more and load the last chunk again.
+        const int n2 = (c + 2 < nchunks ? c + 2 : nchunks - 1) * KC;
+        constexpr int NPH = (SCHEME == 3) ? 3 : 4;
+        constexpr int NSLOT = KS * NPH, NPIECE = 2 * (VL + XL);
+        if (MASKED) {          // (the masked version has no registers to spare for the spreading)
+            lstore(buf ^ 1);
+            gload(n2);
+        }
+        auto side = [&](int slot) {
+            if (MASKED) return;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int p = 0; p < NPIECE; ++p) {
+                if (p * NSLOT / NPIECE != slot) continue;
+                if (p % 2 == 0) lstore_piece(buf ^ 1, p / 2);
+                else gload_piece(n2, p / 2);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
         f32x2 ax[2][BM];
         float br[2][BN], bi[2][BN];
         auto read_operands = [&](int slot, int s) {
@@ -602,16 +632,19 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         accr[bm][bn] = mfma16(ax[cur][bm].x, br[cur][bn], accr[bm][bn]);
+                side(NPH * s);
 #pragma unroll
                 for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         acci[bm][bn] = mfma16(ax[cur][bm].y, bi[cur][bn], acci[bm][bn]);
+                side(NPH * s + 1);
 #pragma unroll
                 for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         acc3[bm % M3][bn % B3] = mfma16(as[bm], bs[bn], acc3[bm % M3][bn % B3]);
+                side(NPH * s + 2);
             } else {
                 float bneg[BN];
 #pragma unroll
@@ -621,21 +654,25 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         accr[bm][bn] = mfma16(ax[cur][bm].x, br[cur][bn], accr[bm][bn]);
+                side(NPH * s);
 #pragma unroll
                 for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         acci[bm][bn] = mfma16(ax[cur][bm].x, bi[cur][bn], acci[bm][bn]);
+                side(NPH * s + 1);
 #pragma unroll
                 for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         accr[bm][bn] = mfma16(ax[cur][bm].y, bneg[bn], accr[bm][bn]);
+                side(NPH * s + 2);
 #pragma unroll
                 for (int bm = 0; bm < BM; ++bm)
 #pragma unroll
                     for (int bn = 0; bn < BN; ++bn)
                         acci[bm][bn] = mfma16(ax[cur][bm].y, br[cur][bn], acci[bm][bn]);
+                side(NPH * s + 3);
             }
         }
         __syncthreads();
@@ -1333,7 +1370,8 @@ hipError_t launch_c(const ContractArgs& a, hipStream_t stream)
     const int tk = (int)cdiv(K, TK);
     const int64_t to = cdiv(a.O, TO);
     const int64_t total = (int64_t)tk * to;
-    const bool whole = (K % TK == 0) && (N % KC == 0) && (a.O % TO == 0);
+    // (the fast path addresses its loads with 32-bit lane offsets of up to 64 rows of N elements)
+    const bool whole = (K % TK == 0) && (N % KC == 0) && (a.O % TO == 0) && N < (1 << 22) && a.M.ld < (1 << 21);
     if (whole)
         return launch_tiles(k_contract_c<TO, TK, WO, WK, KC, 2, false, 2, SCHEME>, a, tk, to, total, stream);
     return launch_tiles(k_contract_c<TO, TK, WO, WK, KC, 1, true, 2, SCHEME>, a, tk, to, total, stream);
