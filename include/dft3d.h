@@ -66,6 +66,14 @@ typedef enum { DFT3D_FORWARD = -1, DFT3D_BACKWARD = 1 } dft3d_direction;
                                        float64 precision the paper leaves as future work, Section VI).
                                        Every byte count below doubles (16 bytes per element).  Not
                                        combined with 3M / BF16X3; not offered for FFT or point plans */
+#define DFT3D_FLAG_ADJOINT 32u      /* KDFT: the plan applies the conjugate transpose of the transform its
+                                       other arguments describe, out = (M_x (x) M_y (x) M_z)^H in: from
+                                       integer frequencies back to the (nonuniform) samples, the operation
+                                       an iterative solve of the inverse problem of Section III-A needs
+                                       next to the forward one.  Shapes are unchanged for
+                                       dft3d_plan_create(_ex); a dft3d_plan_create_points plan then takes
+                                       a kx x ky x kz tensor and returns an nx x ny x nz one.  On uniform
+                                       axes it equals BACKWARD without the 1/N factor */
 #define DFT3D_FLAG_3M 4u            /* KDFT: three real products per complex product
                                        (Vr*Xr, Vi*Xi, (Vr+Vi)*(Xr+Xi)) instead of four: 25 % fewer
                                        MFMA operations, slightly larger rounding error in Im */
@@ -85,7 +93,8 @@ typedef enum { DFT3D_FORWARD = -1, DFT3D_BACKWARD = 1 } dft3d_direction;
  *             to sqrt(N) with A <= B.  (512 -> 16*32, 2048 -> 32*64.)
  *   flags     DFT3D_FLAG_* bits
  * Errors: INVALID_ARG (NULL plan pointer, size < 1, bad split, unknown formulation or flag),
- * UNSUPPORTED (FFT with coordinates, COMPLEX128 on an FFT plan or together with 3M / BF16X3),
+ * UNSUPPORTED (FFT with coordinates, COMPLEX128 or ADJOINT on an FFT plan, COMPLEX128 together
+ * with 3M / BF16X3),
  * ALLOC / HIP (device allocation or copy failed).
  */
 dft3d_status dft3d_plan_create(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
@@ -103,9 +112,10 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
  * linear solve, Section III-A).
  *   zx,zy,zz  HOST arrays of 2*k? doubles, (re, im) of each point; points must be non-zero.  NULL =
  *             that axis uses the N-th roots of unity (then k? must equal n?).
- *   flags     0 or DFT3D_FLAG_3M
+ *   flags     DFT3D_FLAG_3M and / or DFT3D_FLAG_ADJOINT (then the roles of n? and k? swap: input
+ *             kx x ky x kz, output nx x ny x nz, matrices V_j^H), or 0
  * exec needs a workspace of dft3d_plan_workspace_bytes = 8*(nx*ny*kz + nx*ky*kz) bytes (the two
- * intermediates).  dft3d_mode_contract on such a plan reads a tensor whose axes after `axis`
+ * intermediates; ADJOINT: 8*(kx*ky*nz + kx*ny*nz)).  dft3d_mode_contract on such a plan reads a tensor whose axes after `axis`
  * already have their output length and writes one whose `axis` has length k (order z, y, x).
  * Errors: INVALID_ARG (sizes, a zero / non-finite point, an entry that overflows fp32).
  */

@@ -119,6 +119,28 @@ def dft3d_points(x: np.ndarray, points) -> np.ndarray:
     return y
 
 
+def dft3d_adjoint(y: np.ndarray, shape=None, coords=(None, None, None), points=None) -> np.ndarray:
+    """Conjugate transpose of the transform of Eq. 10 applied to ``y``:
+
+        out[n1, n2, n3] = sum_{k1,k2,k3} conj(M1[k1,n1]) conj(M2[k2,n2]) conj(M3[k3,n3]) y[k1,k2,k3]
+
+    with the per-axis matrices M_j of the forward transform: sample coordinates ``coords`` (square
+    matrices, Eq. 3 read as in the benchmark configuration) or evaluation ``points`` (K x N matrices,
+    Eq. 3 as printed; then ``shape`` gives the n_j).  One axis at a time, in fp64."""
+    y = _check_input(y)
+    if points is None:
+        shape = y.shape
+        Ms = [dft_matrix(n, coords[j]) for j, n in enumerate(shape)]
+    else:
+        if shape is None:
+            raise ValueError("the adjoint of a point transform needs the shape of the data space")
+        Ms = [dft_matrix(n) if points[j] is None else points_matrix(points[j], n) for j, n in enumerate(shape)]
+    out = y
+    for axis in (2, 1, 0):
+        out = mode_contract(np.ascontiguousarray(Ms[axis].conj().T), out, axis)
+    return out
+
+
 def mode_contract(M: np.ndarray, x: np.ndarray, axis: int) -> np.ndarray:
     """``out[..., k, ...] = sum_n M[k, n] x[..., n, ...]`` along ``axis`` in fp64.
 

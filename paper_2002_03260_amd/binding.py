@@ -23,6 +23,7 @@ FLAG_UNFUSED = 2
 FLAG_3M = 4
 FLAG_BF16X3 = 8
 FLAG_COMPLEX128 = 16
+FLAG_ADJOINT = 32
 
 EXPORTS = [
     "dft3d_plan_create", "dft3d_plan_create_ex", "dft3d_plan_create_points",
@@ -178,6 +179,8 @@ class Plan:
             _check(self._lib.dft3d_plan_create_points(ctypes.byref(self._h), *self.shape, *ks,
                                                       _np_ptr(zs[0]), _np_ptr(zs[1]), _np_ptr(zs[2]), flags))
             self.out_shape = tuple(ks)
+            if flags & FLAG_ADJOINT:      # `shape` describes the forward transform; the adjoint maps back
+                self.shape, self.out_shape = self.out_shape, self.shape
             return
         cs = [_host_coords(c, n) for c, n in zip(coords, self.shape)]
         sp = None

@@ -162,12 +162,27 @@ dft3d_status upload_matrix(const std::vector<float>& re, const std::vector<float
     return DFT3D_OK;
 }
 
+// Row-major K x N planes of a matrix -> row-major N x K planes of its conjugate transpose.
+template <typename T>
+void conjugate_transpose(std::vector<T>& re, std::vector<T>& im, int64_t K, int64_t N)
+{
+    std::vector<T> tr((size_t)(K * N)), ti((size_t)(K * N));
+    for (int64_t k = 0; k < K; ++k)
+        for (int64_t n = 0; n < N; ++n) {
+            tr[(size_t)(n * K + k)] = re[(size_t)(k * N + n)];
+            ti[(size_t)(n * K + k)] = -im[(size_t)(k * N + n)];
+        }
+    re.swap(tr);
+    im.swap(ti);
+}
+
 dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out, bool with_split = false,
-                              bool with_f64 = false, bool split_sum = false)
+                              bool with_f64 = false, bool split_sum = false, bool adjoint = false)
 {
     std::vector<float> re((size_t)n * n), im((size_t)n * n);
     dft3d_status s = dft3d_generate_matrix(n, coords, DFT3D_FORWARD, re.data(), im.data());
     if (s != DFT3D_OK) return s;
+    if (adjoint) conjugate_transpose(re, im, n, n);
     s = upload_matrix(re, im, (int)n, (int)n, out);
     if (s != DFT3D_OK || (!with_split && !with_f64)) return s;
     // the bf16 levels and the fp64 planes are taken from the fp64 entries, not from their fp32 roundings
@@ -177,6 +192,7 @@ dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out
             if (coords) unit_root_turns((double)k * coords[j], DFT3D_FORWARD, &dre[k * n + j], &dim[k * n + j]);
             else unit_root_ratio(k * j, n, DFT3D_FORWARD, &dre[k * n + j], &dim[k * n + j]);
         }
+    if (adjoint) conjugate_transpose(dre, dim, n, n);
     if (with_split) s = upload_split(dre, dim, (int)n, (int)n, split_sum, out);
     if (s == DFT3D_OK && with_f64) s = upload_f64(dre, dim, (int)n, (int)n, out);
     return s;
@@ -503,9 +519,13 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
         return DFT3D_ERR_INVALID_ARG;
     }
     if (flags & ~(DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_UNFUSED | DFT3D_FLAG_3M | DFT3D_FLAG_BF16X3 |
-                  DFT3D_FLAG_COMPLEX128)) {
+                  DFT3D_FLAG_COMPLEX128 | DFT3D_FLAG_ADJOINT)) {
         set_error("plan_create: unknown flag bits 0x%x", flags);
         return DFT3D_ERR_INVALID_ARG;
+    }
+    if ((flags & DFT3D_FLAG_ADJOINT) && f != DFT3D_KDFT) {
+        set_error("plan_create: ADJOINT is offered for KDFT plans (on uniform axes it equals BACKWARD up to the 1/N factor)");
+        return DFT3D_ERR_UNSUPPORTED;
     }
     if ((flags & DFT3D_FLAG_COMPLEX128) &&
         (f != DFT3D_KDFT || (flags & (DFT3D_FLAG_3M | DFT3D_FLAG_BF16X3)))) {
@@ -540,7 +560,8 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
                 if (!c[j] && !c[i] && n[i] == n[j]) { p->M_owner[j] = i; break; }
             if (p->M_owner[j] == j)
                 s = make_axis_matrix(n[j], c[j], &p->M[j], (flags & DFT3D_FLAG_BF16X3) != 0,
-                                     (flags & DFT3D_FLAG_COMPLEX128) != 0, (flags & DFT3D_FLAG_3M) != 0);
+                                     (flags & DFT3D_FLAG_COMPLEX128) != 0, (flags & DFT3D_FLAG_3M) != 0,
+                                     (flags & DFT3D_FLAG_ADJOINT) != 0);
             else p->M[j] = p->M[p->M_owner[j]];
         }
     } else {
@@ -667,12 +688,14 @@ dft3d_status dft3d_plan_create_points(dft3d_plan* plan, int64_t nx, int64_t ny, 
             return DFT3D_ERR_INVALID_ARG;
         }
     }
-    if (flags & ~DFT3D_FLAG_3M) {
-        set_error("plan_create_points: only DFT3D_FLAG_3M is accepted");
+    if (flags & ~(DFT3D_FLAG_3M | DFT3D_FLAG_ADJOINT)) {
+        set_error("plan_create_points: only DFT3D_FLAG_3M and DFT3D_FLAG_ADJOINT are accepted");
         return DFT3D_ERR_INVALID_ARG;
     }
-    if (ky * kz >= (int64_t(1) << 31) || nx * ny >= (int64_t(1) << 31)) {
-        set_error("plan_create_points: ky*kz and nx*ny must be below 2^31");
+    const bool adjoint = (flags & DFT3D_FLAG_ADJOINT) != 0;
+    if (ky * kz >= (int64_t(1) << 31) || nx * ny >= (int64_t(1) << 31) ||
+        (adjoint && (ny * nz >= (int64_t(1) << 31) || kx * ky >= (int64_t(1) << 31)))) {
+        set_error("plan_create_points: ky*kz and nx*ny (ADJOINT: also ny*nz and kx*ky) must be below 2^31");
         return DFT3D_ERR_UNSUPPORTED;
     }
     dft3d_plan_s* p = new (std::nothrow) dft3d_plan_s();
@@ -682,14 +705,16 @@ dft3d_status dft3d_plan_create_points(dft3d_plan* plan, int64_t nx, int64_t ny, 
     p->points = true;
     dft3d_status s = DFT3D_OK;
     for (int j = 0; j < 3 && s == DFT3D_OK; ++j) {
-        p->n[j] = n[j];
-        p->k[j] = k[j];
+        // the adjoint plan contracts the k index: its tensors go from kx x ky x kz to nx x ny x nz
+        p->n[j] = adjoint ? k[j] : n[j];
+        p->k[j] = adjoint ? n[j] : k[j];
         p->nonuniform[j] = z[j] != nullptr;
         p->M_owner[j] = j;
         std::vector<float> re((size_t)(k[j] * n[j])), im((size_t)(k[j] * n[j]));
         s = z[j] ? dft3d_generate_points_matrix(k[j], n[j], z[j], re.data(), im.data())
                  : dft3d_generate_matrix(n[j], nullptr, DFT3D_FORWARD, re.data(), im.data());
-        if (s == DFT3D_OK) s = upload_matrix(re, im, (int)k[j], (int)n[j], &p->M[j]);
+        if (s == DFT3D_OK && adjoint) conjugate_transpose(re, im, k[j], n[j]);
+        if (s == DFT3D_OK) s = upload_matrix(re, im, (int)p->k[j], (int)p->n[j], &p->M[j]);
     }
     if (s != DFT3D_OK) {
         dft3d_plan_destroy(p);

@@ -53,7 +53,7 @@ def test_binding_constants_match_the_header():
     text = open(os.path.join(ROOT, "include", "dft3d.h")).read()
     flags = {m.group(1): int(m.group(2)) for m in re.finditer(r"#define\s+DFT3D_FLAG_(\w+)\s+(\d+)u", text)}
     assert flags == {"CLOBBER_INPUT": dft.FLAG_CLOBBER_INPUT, "UNFUSED": dft.FLAG_UNFUSED, "3M": dft.FLAG_3M,
-                     "BF16X3": dft.FLAG_BF16X3, "COMPLEX128": dft.FLAG_COMPLEX128}
+                     "BF16X3": dft.FLAG_BF16X3, "COMPLEX128": dft.FLAG_COMPLEX128, "ADJOINT": dft.FLAG_ADJOINT}
     assert len(set(flags.values())) == len(flags) and all(v & (v - 1) == 0 for v in flags.values())
     enums = {m.group(1): int(m.group(2)) for m in re.finditer(r"DFT3D_(\w+)\s*=\s*(-?\d+)", text)}
     assert enums["KDFT"] == dft.KDFT and enums["FFT"] == dft.FFT

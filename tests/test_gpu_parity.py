@@ -163,6 +163,46 @@ def test_kdft_arbitrary_evaluation_points(dft, shape, ks):
             assert report(f"points mode {axis}", to_host(yd), y) <= TOL
 
 
+@pytest.mark.parametrize("shape,flags", [((128, 128, 128), 0), ((50, 128, 72), 0), ((128, 256, 128), "3M"),
+                                         ((128, 128, 256), "BF16X3"), ((1, 96, 40), 0)])
+def test_kdft_adjoint_of_nonuniform_transform(dft, shape, flags):
+    """DFT3D_FLAG_ADJOINT on a plan with sample coordinates: out = (M_x (x) M_y (x) M_z)^H in."""
+    say(f"case kdft adjoint {shape} {flags}")
+    fl = dft.FLAG_ADJOINT | {0: 0, "3M": dft.FLAG_3M, "BF16X3": dft.FLAG_BF16X3}[flags]
+    rng = np.random.default_rng(8)
+    coords = tuple(np.sort(rng.random(n)) for n in shape)
+    coords = (coords[0], None, coords[2])              # one uniform axis among them
+    y = wl.draw_complex(shape, "normal", 2650 + sum(shape))
+    want = orc.dft3d_adjoint(y, coords=coords)
+    with dft.Plan(shape, dft.KDFT, coords=coords, flags=fl) as p:
+        yd = to_dev(y)
+        assert report(f"kdft adjoint {shape}", to_host(p.exec(yd)), want) <= TOL
+        with pytest.raises(dft.Dft3dError):
+            p.exec(yd, direction=dft.BACKWARD)
+        for axis in range(3):
+            MH = orc.dft_matrix(shape[axis], coords[axis]).conj().T
+            got = to_host(p.mode_contract(axis, yd))
+            assert report(f"adjoint mode {axis}", got, orc.mode_contract(MH, y, axis)) <= TOL
+    with pytest.raises(dft.Dft3dError):
+        dft.Plan(shape, dft.FFT, flags=dft.FLAG_ADJOINT)
+
+
+@pytest.mark.parametrize("shape,ks", [((6, 10, 12), (4, 10, 20)), ((128, 64, 96), (200, 64, 130))])
+def test_kdft_adjoint_of_point_transform(dft, shape, ks):
+    """ADJOINT of the K x N point matrices: a kx x ky x kz tensor goes back to nx x ny x nz."""
+    say(f"case kdft points adjoint {ks} -> {shape}")
+    rng = np.random.default_rng(10)
+    pts = [(1.0 + (rng.random(k) - 0.5) / n) * np.exp(2j * np.pi * rng.random(k)) for n, k in zip(shape, ks)]
+    pts[1] = None if ks[1] == shape[1] else pts[1]
+    y = wl.draw_complex(ks, "uniform", 2660 + sum(ks))
+    want = orc.dft3d_adjoint(y, shape=shape, points=pts)
+    with dft.Plan(shape, dft.KDFT, points=pts, flags=dft.FLAG_ADJOINT) as p:
+        assert p.shape == tuple(ks) and p.out_shape == tuple(shape)
+        got = to_host(p.exec(to_dev(y)))
+        assert got.shape == tuple(shape)
+        assert report(f"kdft points adjoint {ks}->{shape}", got, want) <= TOL
+
+
 @pytest.mark.parametrize("shape", [(128, 128, 128), (256, 256, 256), (128, 384, 256), (130, 256, 128)])
 @pytest.mark.parametrize("three_m", [False, True])
 def test_kdft_bf16_split_scheme(dft, shape, three_m):

@@ -306,6 +306,50 @@ def test_points_rectangular_output_matches_brute_polynomial():
                 assert abs(X[a, b, c] - np.sum(xc * w)) < 1e-12 * np.sum(np.abs(xc * w))
 
 
+# --------------------------------------------------------------------------- adjoint
+def test_adjoint_on_uniform_axes_is_unscaled_inverse_fft():
+    """On uniform axes M^H = conj(M): the adjoint is numpy's ifftn times the number of points."""
+    shape = (6, 10, 7)
+    y = rand_c64(shape, 23)
+    ref = np.fft.ifftn(y.astype(np.complex128)) * np.prod(shape)
+    assert rel_l2(orc.dft3d_adjoint(y), ref) < 1e-13
+
+
+def test_adjoint_satisfies_the_inner_product_identity():
+    """<A x, y> = <x, A^H y> with A the (pinned) forward transform: nonuniform coordinates, and
+    rectangular point matrices off the unit circle.  A transposed index, a missing conjugate or a
+    wrong axis order breaks the identity."""
+    rng = np.random.default_rng(12)
+    shape = (5, 6, 4)
+    coords = tuple(np.sort(rng.random(n)) for n in shape)
+    x, y = rand_c64(shape, 24), rand_c64(shape, 25)
+    lhs = np.vdot(y.astype(np.complex128), orc.dft3d(x, coords))          # <y, A x>
+    rhs = np.vdot(orc.dft3d_adjoint(y, coords=coords), x.astype(np.complex128))
+    assert abs(lhs - rhs) < 1e-12 * abs(lhs)
+
+    pts = [0.95 * np.exp(2j * np.pi * rng.random(k)) for k in (3, 7, 6)]
+    yk = rand_c64((3, 7, 6), 26)
+    lhs = np.vdot(yk.astype(np.complex128), orc.dft3d_points(x, pts))
+    back = orc.dft3d_adjoint(yk, shape=shape, points=pts)
+    assert back.shape == shape
+    rhs = np.vdot(back, x.astype(np.complex128))
+    assert abs(lhs - rhs) < 1e-12 * abs(lhs)
+
+
+def test_adjoint_of_a_single_frequency_is_the_conjugate_matrix_row():
+    """y = delta at frequency (a, b, c) -> out[n] = conj(M1[a,n1]) conj(M2[b,n2]) conj(M3[c,n3]),
+    written out from the definition M[k, n] = exp(-2 pi i k c[n])."""
+    rng = np.random.default_rng(13)
+    shape = (4, 5, 6)
+    coords = tuple(np.sort(rng.random(n)) for n in shape)
+    y = np.zeros(shape, np.complex64)
+    a, b, c = 3, 1, 4
+    y[a, b, c] = 1.0
+    want = np.exp(2j * np.pi * a * coords[0])[:, None, None] * np.exp(2j * np.pi * b * coords[1])[None, :, None] * \
+        np.exp(2j * np.pi * c * coords[2])[None, None, :]
+    assert np.max(np.abs(orc.dft3d_adjoint(y, coords=coords) - want)) < 1e-13
+
+
 # --------------------------------------------------------------------------- sampled slabs
 def test_sampled_slabs_equal_full():
     shape = (10, 6, 7)
