@@ -106,6 +106,10 @@ def main() -> int:
                     help="KDFT: fp32 accuracy from three bf16 levels on the bf16 matrix cores (DFT3D_FLAG_BF16X3)")
     ap.add_argument("--complex128", action="store_true",
                     help="KDFT: complex128 tensors on the fp64 matrix cores (DFT3D_FLAG_COMPLEX128)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of one HIP graph that holds one exec (for the small, launch-bound "
+                         "workloads); the per-kernel durations of the roofline then come from profiled "
+                         "eager steps run right after the timed region")
     ap.add_argument("--unfused", action="store_true",
                     help="FFT: run the twiddle and the re-ordering as separate memory-bound kernels")
     args = ap.parse_args()
@@ -205,13 +209,35 @@ def main() -> int:
         plan.exec(x, out, stream=stream)
     torch.cuda.synchronize()
 
-    plan.enable_profiling(steps)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        plan.exec(x, out, stream=stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    if args.graph:
+        if big:
+            print("bench.py: --graph is meant for the small workloads", file=sys.stderr)
+            return 2
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            plan.exec(x, out)
+        for _ in range(warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        plan.enable_profiling(steps)
+        for _ in range(steps):
+            plan.exec(x, out, stream=stream)
+        torch.cuda.synchronize()
+    else:
+        plan.enable_profiling(steps)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            plan.exec(x, out, stream=stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
 
     ms_per_step = (t1 - t0) * 1e3 / steps
     E = w.elements
@@ -330,6 +356,7 @@ def main() -> int:
         "config": {
             "workload": w.name + ("" if form_override is None else ("_fft" if form == dft.FFT else "_kdft")),
             "clock_settle_s": settle_s,
+            "launch": "hip graph replay" if args.graph else "eager",
             "formulation": "FFT" if form == dft.FFT else "KDFT",
             "complex_scheme": "3M" if (args.three_m and form == dft.KDFT) else "4M",
             "arithmetic": "fp64 MFMA" if c128 else

@@ -148,6 +148,9 @@ dft3d_status dft3d_plan_get_split(dft3d_plan plan, int axis, int64_t* A, int64_t
  * direction: DFT3D_FORWARD or DFT3D_BACKWARD.  stream: a hipStream_t passed as void* (NULL =
  * the null stream).  Errors: INVALID_ARG (NULL / misaligned / aliased pointers, bad direction,
  * workspace missing or too small), UNSUPPORTED (BACKWARD on a nonuniform plan), HIP (launch).
+ * The call only launches kernels on `stream` (no allocation, copy, memset or synchronisation), so
+ * with per-pass timing off it may be captured into a HIP graph; replaying the graph is what pays
+ * for small tensors, where launch latency exceeds kernel time.
  */
 dft3d_status dft3d_exec(dft3d_plan plan, const void* in, void* out, int direction,
                         void* stream);

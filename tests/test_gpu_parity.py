@@ -515,3 +515,41 @@ def test_exec_argument_errors(dft):
         with pytest.raises(dft.Dft3dError) as ei:
             p.exec(x, direction=dft.BACKWARD)
         assert ei.value.status_name == "DFT3D_ERR_UNSUPPORTED"
+
+
+@pytest.mark.parametrize("form,shape", [("KDFT", (32, 32, 32)), ("KDFT", (128, 128, 128)), ("FFT", (64, 256, 256))])
+def test_exec_replayed_from_a_hip_graph(dft, form, shape):
+    """exec only launches kernels, so a caller may capture it into a HIP graph (what pays for the
+    small, launch-bound sizes).  Several replays, with eager work and synchronisations in between,
+    must each reproduce the eager result bit for bit, and that result is the oracle's."""
+    import torch
+    say(f"case graph replay {form} {shape}")
+    formulation = dft.KDFT if form == "KDFT" else dft.FFT
+    x = wl.draw_complex(shape, "normal", 2900 + sum(shape))
+    want = orc.dft3d(x)
+    with dft.Plan(shape, formulation) as p:
+        xd = to_dev(x)
+        p.ensure_workspace()
+        eager = p.exec(xd).clone()
+        torch.cuda.synchronize()
+        assert report(f"graph eager {form} {shape}", to_host(eager), want) <= TOL
+        out = torch.empty_like(xd)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            p.exec(xd, out)                      # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            p.exec(xd, out)
+        for rep in range(4):
+            out.fill_(0)                          # a fill kernel, not a memset node inside the graph
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager), f"replay {rep} differs from the eager result"
+            other = p.exec(xd)                    # eager work between the replays
+            torch.cuda.synchronize()
+            assert torch.equal(other, eager)
+        del g
