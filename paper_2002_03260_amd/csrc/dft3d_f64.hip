@@ -47,7 +47,9 @@ __device__ __forceinline__ f64x4 mfma_f64(double a, double b, f64x4 c)
     return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
 }
 
-template <bool STRIDED>
+// FAST: the shape is a whole number of tiles and chunks, so loads need no masks and their addresses
+// are a uniform 64-bit base plus a constant 32-bit lane offset in bytes.
+template <bool STRIDED, bool FAST>
 __global__ __launch_bounds__(kT, 2) void k_contract_f64(ContractArgs64 a, int tilesK, int64_t tilesOther,
                                                         int64_t total)
 {
@@ -106,9 +108,26 @@ __global__ __launch_bounds__(kT, 2) void k_contract_f64(ContractArgs64 a, int ti
         xsrc = reinterpret_cast<const f64x2*>(a.X) + (ok ? o0 + xa : 0) * (int64_t)N;
     }
 
+    // FAST: lane offsets in bytes (the launcher checks that they fit 32 bits)
+    const unsigned v_lane = ((unsigned)vn * (unsigned)ld + (unsigned)vk) * 8u;
+    const unsigned x_lane = STRIDED ? ((unsigned)xa * (unsigned)I + (unsigned)xb) * 16u
+                                    : ((unsigned)xa * (unsigned)N + (unsigned)xb) * 16u;
+    const f64x2* xu = STRIDED ? reinterpret_cast<const f64x2*>(a.X) + tile_o * (int64_t)N * I + c0
+                              : reinterpret_cast<const f64x2*>(a.X) + o0 * (int64_t)N;
+
     f64x4 vr, vi;
     f64x2 xreg[4];
     auto gload = [&](int n0) {
+        if (FAST) {
+            const char* vb = reinterpret_cast<const char*>(a.M + (int64_t)n0 * ld + k0);
+            vr = *reinterpret_cast<const f64x4*>(vb + v_lane);
+            vi = *reinterpret_cast<const f64x4*>(vb + plane * 8 + v_lane);
+            // strided: row n0 + xa, columns xb..xb+3;  contiguous: row xa, n = n0 + xb..xb+3
+            const char* xbse = reinterpret_cast<const char*>(STRIDED ? xu + (int64_t)n0 * I : xu + n0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) xreg[e] = *reinterpret_cast<const f64x2*>(xbse + x_lane + 16 * e);
+            return;
+        }
         vr = *reinterpret_cast<const f64x4*>(vsrc + (int64_t)n0 * ld);
         vi = *reinterpret_cast<const f64x4*>(vsrc + plane + (int64_t)n0 * ld);
         if (STRIDED) {
@@ -130,12 +149,11 @@ __global__ __launch_bounds__(kT, 2) void k_contract_f64(ContractArgs64 a, int ti
             }
         }
     };
-    const double isign = a.conj ? -1.0 : 1.0;      // conjugate the matrix
     auto lstore = [&](int buf) {
         double (*Vt)[KC][TM] = STRIDED ? RT[buf] : CT[buf];
         double (*Xt)[KC][TM] = STRIDED ? CT[buf] : RT[buf];
         *reinterpret_cast<f64x4*>(&Vt[0][vn][vk]) = vr;
-        *reinterpret_cast<f64x4*>(&Vt[1][vn][vk]) = vi * isign;
+        *reinterpret_cast<f64x4*>(&Vt[1][vn][vk]) = vi;
         if (STRIDED) {
             *reinterpret_cast<f64x4*>(&Xt[0][xa][xb]) = f64x4{xreg[0].x, xreg[1].x, xreg[2].x, xreg[3].x};
             *reinterpret_cast<f64x4*>(&Xt[1][xa][xb]) = f64x4{xreg[0].y, xreg[1].y, xreg[2].y, xreg[3].y};
@@ -148,13 +166,18 @@ __global__ __launch_bounds__(kT, 2) void k_contract_f64(ContractArgs64 a, int ti
         }
     };
 
-    f64x4 accr[2][2], acci[2][2];
+    // The four real products of the complex product are accumulated apart (rr = Re R * Re C, ii, ri, ir)
+    // and combined with their signs in the epilogue, so the loop neither negates an operand nor
+    // applies the conjugation.
+    f64x4 prr[2][2], pii[2][2], pri[2][2], pir[2][2];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
-            accr[rb][cb] = f64x4{0, 0, 0, 0};
-            acci[rb][cb] = f64x4{0, 0, 0, 0};
+            prr[rb][cb] = f64x4{0, 0, 0, 0};
+            pii[rb][cb] = f64x4{0, 0, 0, 0};
+            pri[rb][cb] = f64x4{0, 0, 0, 0};
+            pir[rb][cb] = f64x4{0, 0, 0, 0};
         }
 
     const int nchunks = (N + KC - 1) / KC;
@@ -165,52 +188,70 @@ __global__ __launch_bounds__(kT, 2) void k_contract_f64(ContractArgs64 a, int ti
 
     for (int c = 0; c < nchunks; ++c) {
         const int buf = c & 1;
-        if (c + 1 < nchunks) lstore(buf ^ 1);          // chunk c+1, requested one chunk ago
-        if (c + 2 < nchunks) gload((c + 2) * KC);
+        // Chunk c+1, requested one chunk ago, moves to the other LDS buffer after the first k-step's
+        // MFMAs and chunk c+2 is requested after the second's.  Both run unconditionally so that they
+        // stay in the MFMAs' basic block: past the end they store stale registers into the buffer
+        // nobody reads any more and load the last chunk again.
+        const int n2 = (c + 2 < nchunks ? c + 2 : nchunks - 1) * KC;
 #pragma unroll
         for (int ks = 0; ks < KC / 4; ++ks) {
             const int n = 4 * ks + lq;
-            double rr[2], ri[2], cr[2], ci[2], nri[2];
+            // MFMA row (column) i of block b stands for tile row (column) 2 * i + b of the wave tile,
+            // so a lane's operands for both blocks sit side by side in LDS: one 16-byte read per plane
+            // (the epilogue stores by the same rule)
+            const f64x2 vrr = *reinterpret_cast<const f64x2*>(&RT[buf][0][n][wr0 + 2 * l16]);
+            const f64x2 vri = *reinterpret_cast<const f64x2*>(&RT[buf][1][n][wr0 + 2 * l16]);
+            const f64x2 vcr = *reinterpret_cast<const f64x2*>(&CT[buf][0][n][wc0 + 2 * l16]);
+            const f64x2 vci = *reinterpret_cast<const f64x2*>(&CT[buf][1][n][wc0 + 2 * l16]);
+            const double rr[2] = {vrr.x, vrr.y}, ri[2] = {vri.x, vri.y};
+            const double cr[2] = {vcr.x, vcr.y}, ci[2] = {vci.x, vci.y};
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                rr[b] = RT[buf][0][n][wr0 + 16 * b + l16];
-                ri[b] = RT[buf][1][n][wr0 + 16 * b + l16];
-                cr[b] = CT[buf][0][n][wc0 + 16 * b + l16];
-                ci[b] = CT[buf][1][n][wc0 + 16 * b + l16];
-                nri[b] = -ri[b];
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) prr[rb][cb] = mfma_f64(rr[rb], cr[cb], prr[rb][cb]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) pri[rb][cb] = mfma_f64(rr[rb], ci[cb], pri[rb][cb]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) pii[rb][cb] = mfma_f64(ri[rb], ci[cb], pii[rb][cb]);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb) pir[rb][cb] = mfma_f64(ri[rb], cr[cb], pir[rb][cb]);
+            if (ks == 0) {
+                __builtin_amdgcn_sched_barrier(0);
+                lstore(buf ^ 1);
+                __builtin_amdgcn_sched_barrier(0);
+            } else if (ks == 1) {
+                __builtin_amdgcn_sched_barrier(0);
+                gload(n2);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            // (rr + i ri)(cr + i ci): four passes over the four blocks, neighbours use different accumulators
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb) accr[rb][cb] = mfma_f64(rr[rb], cr[cb], accr[rb][cb]);
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb) acci[rb][cb] = mfma_f64(rr[rb], ci[cb], acci[rb][cb]);
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb) accr[rb][cb] = mfma_f64(nri[rb], ci[cb], accr[rb][cb]);
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb) acci[rb][cb] = mfma_f64(ri[rb], cr[cb], acci[rb][cb]);
         }
         __syncthreads();
     }
 
-    // epilogue: accumulator register v of a lane is row 4 * v + lane / 16, column lane % 16 of its block
+    // epilogue: accumulator register v of a lane is MFMA row 4 * v + lane / 16, column lane % 16 of its
+    // block, i.e. tile row 2 * (4 * v + lq) + rb and tile columns 2 * l16, 2 * l16 + 1 for cb = 0, 1
     f64x2* Y = reinterpret_cast<f64x2*>(a.Y);
+    const double msign = a.conj ? -1.0 : 1.0;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
+        for (int v = 0; v < 4; ++v)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int row = wr0 + 16 * rb + 4 * v + lq;
-                const int col = wc0 + 16 * cb + l16;
-                const f64x2 y = f64x2{accr[rb][cb][v] * a.scale, acci[rb][cb][v] * a.scale};
+            for (int cb = 0; cb < 2; ++cb) {
+                const int row = wr0 + 2 * (4 * v + lq) + rb;
+                const int col = wc0 + 2 * l16 + cb;
+                // the matrix is the row operand of a strided mode and the column operand of the
+                // contiguous one; conjugating it flips the sign of its imaginary part's products
+                const double re = prr[rb][cb][v] - msign * pii[rb][cb][v];
+                const double im = STRIDED ? pri[rb][cb][v] + msign * pir[rb][cb][v]
+                                          : msign * pri[rb][cb][v] + pir[rb][cb][v];
+                const f64x2 y = f64x2{re * a.scale, im * a.scale};
                 if (STRIDED) {
                     if (k0 + row < K && c0 + col < I)
                         Y[y_offset(a, tile_o) + (int64_t)(k0 + row) * a.sYk + c0 + col] = y;
@@ -236,15 +277,22 @@ hipError_t launch_contract_f64(const ContractArgs64& a, hipStream_t stream)
     // the kernel reads whole 64-wide, 16-deep tiles of the zero-padded planes
     if (a.ld % 64 != 0 || a.ld < a.K || a.rows % KC != 0 || a.rows < a.N) return hipErrorInvalidValue;
     const int tk = (a.K + 63) / 64;
+    const bool whole = a.K % TM == 0 && a.N % KC == 0 && a.ld < (1 << 20);
     if (a.I == 1) {
         // contiguous mode: rows = o, columns = k; the k-tile index runs fastest
         const int64_t to = (a.O + TM - 1) / TM;
         const int64_t total = (int64_t)tk * to;
-        hipLaunchKernelGGL(k_contract_f64<false>, grid_for(total), dim3(kT), 0, stream, a, tk, to, total);
+        if (whole && a.O % TM == 0 && a.N < (1 << 21))
+            hipLaunchKernelGGL((k_contract_f64<false, true>), grid_for(total), dim3(kT), 0, stream, a, tk, to, total);
+        else
+            hipLaunchKernelGGL((k_contract_f64<false, false>), grid_for(total), dim3(kT), 0, stream, a, tk, to, total);
     } else {
         const int64_t ti = (a.I + TN - 1) / TN;
         const int64_t total = (int64_t)tk * ti * a.O;
-        hipLaunchKernelGGL(k_contract_f64<true>, grid_for(total), dim3(kT), 0, stream, a, tk, ti, total);
+        if (whole && a.I % TN == 0 && a.I < (1 << 23))
+            hipLaunchKernelGGL((k_contract_f64<true, true>), grid_for(total), dim3(kT), 0, stream, a, tk, ti, total);
+        else
+            hipLaunchKernelGGL((k_contract_f64<true, false>), grid_for(total), dim3(kT), 0, stream, a, tk, ti, total);
     }
     return hipGetLastError();
 }
