@@ -51,6 +51,7 @@ __device__ __forceinline__ int64_t remap(int64_t wg, int64_t total)
 
 __device__ __forceinline__ int64_t y_offset(const ContractArgs& a, int64_t o)
 {
+    if (a.Olo == 1) return o * a.sYohi;
     return (o / a.Olo) * a.sYohi + (o % a.Olo) * a.sYolo;
 }
 

@@ -76,6 +76,7 @@ __device__ __forceinline__ void trace_mark(int slot)
 
 __device__ __forceinline__ int64_t out_offset(const ContractArgs& a, int64_t o)
 {
+    if (a.Olo == 1) return o * a.sYohi;      // (uniform branch: every KDFT mode; saves two 64-bit divisions)
     return (o / a.Olo) * a.sYohi + (o % a.Olo) * a.sYolo;
 }
 
