@@ -30,12 +30,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC = {
-    "cfg2": 2.80e8,             # strided contraction: 2 * FETCH_SIZE + WRITE_SIZE (calibrated), bytes per launch
-    "cfg2+bf16x3": 2.94e8,      # bf16-split contraction (six bf16 matrix planes instead of two fp32 ones)
-    "cfg2+complex128": 6.05e8,  # fp64 contraction
-    "cfg3": 2.172e9,            # fused strided-axis kernel
-}
+MEASURED_TRAFFIC = {"cfg2": 2.82e8, "cfg2+bf16x3": 2.95e8, "cfg2+complex128": 6.46e8, "cfg3": 2.172e9}
 
 
 def effective_flop(E: int) -> float:
@@ -106,6 +101,9 @@ def main() -> int:
                     help="KDFT: fp32 accuracy from three bf16 levels on the bf16 matrix cores (DFT3D_FLAG_BF16X3)")
     ap.add_argument("--complex128", action="store_true",
                     help="KDFT: complex128 tensors on the fp64 matrix cores (DFT3D_FLAG_COMPLEX128)")
+    ap.add_argument("--settle", type=float, default=None,
+                    help="seconds of untimed steps before the warmup (default 0.3 for the sub-second "
+                         "workloads, 0 for the seconds-long ones; 0 for counter collection runs)")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of one HIP graph that holds one exec (for the small, launch-bound "
                          "workloads); the per-kernel durations of the roofline then come from profiled "
@@ -174,7 +172,7 @@ def main() -> int:
     # value (counted inside the 256^3 contraction kernel: 2.09 GHz in the first milliseconds, 2.35 GHz
     # sustained), so sub-millisecond workloads run the same step untimed for this long before the
     # warmup steps; the seconds-long workloads need none.
-    settle_s = 0.0 if big else 0.3
+    settle_s = args.settle if args.settle is not None else (0.0 if big else 0.3)
 
     coords = wl.make_coords(w)
     split = [a for a, _ in w.splits] if (form == dft.FFT and w.splits) else None
