@@ -6,11 +6,12 @@
 // One kernel serves both contraction types:  out[row, col] = sum_n R[row, n] C[col, n]
 //   strided modes   : R = matrix (rows = k), C = data (cols = the contiguous index i)
 //   contiguous mode : R = data (rows = o),   C = matrix (cols = k)
-// A workgroup is 4 waves on a 64 x 64 tile (each wave 32 x 32 = 2 x 2 MFMA blocks, re and im
-// accumulators), the contracted index advances in chunks of 16 through double-buffered LDS planes
-// [n][row or col] (re and im apart), filled from registers that were loaded one chunk earlier.
-// The complex product takes four real MFMAs per block.  Two workgroups fit a CU (64 KiB LDS each),
-// so one workgroup's staging and barriers hide behind the other's MFMAs.
+// A workgroup is 4 waves on a 64 x 64 tile (each wave 32 x 32 = 2 x 2 MFMA blocks), the contracted
+// index advances in chunks of 16 through double-buffered LDS planes [n][row or col] (re and im apart),
+// filled from registers that were loaded one chunk earlier.  The complex product takes four real
+// MFMAs per block, each into an accumulator of its own; signs and conjugation are applied once, in
+// the epilogue.  Two workgroups fit a CU (64 KiB LDS each), so one workgroup's staging and barriers
+// hide behind the other's MFMAs.  Shapes that are whole tiles take a path without masks (FAST).
 //
 // MFMA operand layout (checked on hardware): A[i = lane % 16][k = lane / 16], B[k = lane / 16][j = lane % 16],
 // D register v of a lane = row 4 * v + lane / 16, column lane % 16.

@@ -89,7 +89,9 @@ __device__ __forceinline__ int64_t out_offset(const ContractArgs& a, int64_t o)
 //              while the MFMAs of k-step s issue); barrier
 //
 // so a global load always has one full chunk of MFMA work to land, and there is one barrier
-// per chunk.  MASKED = false is the fast path for shapes that are whole multiples of the tile:
+// per chunk.  The stores and loads of a chunk are cut into pieces of one vector each that sit
+// between the groups of MFMAs (the fast path; the masked path does them up front where it has
+// no registers to spare).  MASKED = false is the fast path for shapes that are whole multiples of the tile:
 // no bounds logic at all.  MASKED = true clamps addresses and selects zeros (branch-free).
 // EV = complex numbers per global load of the data tile (2 -> 16-byte loads).
 // ------------------------------------------------------------------------------------------
