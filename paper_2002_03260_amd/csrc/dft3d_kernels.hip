@@ -446,8 +446,10 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
                     y[e] = make_float2(yr, yi);
                 }
                 if (pair_store) {
-                    *reinterpret_cast<f32x4*>(Yo[0] + (int64_t)k * a.sYk + col[0]) =
-                        f32x4{y[0].x, y[0].y, y[1].x, y[1].y};
+                    // (streaming store: the output is not read again by this kernel; measured 7 % on
+                    // the 128^3 contraction, ~1 % at 256^3)
+                    __builtin_nontemporal_store(f32x4{y[0].x, y[0].y, y[1].x, y[1].y},
+                                                reinterpret_cast<f32x4*>(Yo[0] + (int64_t)k * a.sYk + col[0]));
                 } else {
 #pragma unroll
                     for (int e = 0; e < 2; ++e)
@@ -719,7 +721,8 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
             if (run_store && BN % 2 == 0) {
 #pragma unroll
                 for (int bn = 0; bn + 1 < BN; bn += 2)
-                    *reinterpret_cast<f32x4*>(Yo + kb + bn) = f32x4{y[bn].x, y[bn].y, y[bn + 1].x, y[bn + 1].y};
+                    __builtin_nontemporal_store(f32x4{y[bn].x, y[bn].y, y[bn + 1].x, y[bn + 1].y},
+                                                reinterpret_cast<f32x4*>(Yo + kb + bn));
             } else {
 #pragma unroll
                 for (int bn = 0; bn < BN; ++bn)
