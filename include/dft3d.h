@@ -211,7 +211,8 @@ dft3d_status dft3d_fft_reorder(dft3d_plan plan, int axes_mask, const void* in, v
 /* Plain device-to-device copy of `bytes` (multiple of 16) with the library's own copy kernel:
  * the achievable-HBM-bandwidth reference for the memory-bound passes and the calibration
  * kernel for hardware byte counters (its traffic is exactly 2*bytes).  variant selects the
- * launch shape (0 = default).  in/out: DEVICE, 16-byte aligned, non-overlapping. */
+ * launch shape (0 = default; +100 = loads and stores with the streaming hint the memory-bound
+ * passes use).  in/out: DEVICE, 16-byte aligned, non-overlapping. */
 dft3d_status dft3d_device_copy(const void* in, void* out, size_t bytes, int variant, void* stream);
 
 /* ---- host-side generator, exposed so its rounding can be tested without a GPU -------------- */

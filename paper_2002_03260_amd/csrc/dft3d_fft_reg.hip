@@ -33,6 +33,10 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
+// The outputs of these passes are not read again by the kernel that writes them: streaming store.
+__device__ __forceinline__ void stream_store(f32x2* dst, f32x2 v) { __builtin_nontemporal_store(v, dst); }
+__device__ __forceinline__ f32x2 stream_load(const f32x2* src) { return __builtin_nontemporal_load(src); }
+
 __device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
@@ -104,7 +108,7 @@ __global__ __launch_bounds__(256, MINW) void k_fft_zr(const float2* __restrict__
 #pragma unroll
         for (int bb = 0; bb < NBB; ++bb)
 #pragma unroll
-            for (int s = 0; s < NS1; ++s) x[bb][s] = src[4 * B * s + 16 * bb];
+            for (int s = 0; s < NS1; ++s) x[bb][s] = stream_load(&src[4 * B * s + 16 * bb]);
     };
     // Three real products per complex product: with P1 = sum a_r b_r, P2 = sum a_i b_i and
     // P3 = sum (a_r + a_i)(b_r + b_i), Re = P1 - P2 and Im = P3 - P1 - P2: 72 instead of 96 MFMAs per
@@ -173,8 +177,9 @@ __global__ __launch_bounds__(256, MINW) void k_fft_zr(const float2* __restrict__
             for (int ab = 0; ab < NAB; ++ab)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    dst[16 * ab + A * (16 * kbb + v)] = f32x2{q1[kbb][ab][v] - q2[kbb][ab][v],
-                                                             q3[kbb][ab][v] - q1[kbb][ab][v] - q2[kbb][ab][v]};
+                    stream_store(&dst[16 * ab + A * (16 * kbb + v)],
+                                 f32x2{q1[kbb][ab][v] - q2[kbb][ab][v],
+                                       q3[kbb][ab][v] - q1[kbb][ab][v] - q2[kbb][ab][v]});
     };
     auto transform_row_4m = [&](const f32x2 (&x)[NBB][NS1], int64_t row) {
         // stage 1
@@ -252,7 +257,7 @@ __global__ __launch_bounds__(256, MINW) void k_fft_zr(const float2* __restrict__
             for (int ab = 0; ab < NAB; ++ab)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    dst[16 * ab + A * (16 * kbb + v)] = f32x2{wr[kbb][ab][v], wi[kbb][ab][v]};
+                    stream_store(&dst[16 * ab + A * (16 * kbb + v)], f32x2{wr[kbb][ab][v], wi[kbb][ab][v]});
     };
 
     f32x2 xa[NBB][NS1], xb[NBB][NS1];
@@ -329,7 +334,7 @@ __global__ __launch_bounds__(512, 2) void k_fft_zl(const float2* __restrict__ in
     auto load_block = [&](f32x2 (&x)[NS1], int64_t row, int bb) {
         const f32x2* src = reinterpret_cast<const f32x2*>(in) + row * N + ld_off + 16 * bb;
 #pragma unroll
-        for (int s = 0; s < NS1; ++s) x[s] = src[4 * B * s];
+        for (int s = 0; s < NS1; ++s) x[s] = stream_load(&src[4 * B * s]);
     };
 
     f32x4 zr[NBB][NAB], zi[NBB][NAB];
@@ -392,7 +397,7 @@ __global__ __launch_bounds__(512, 2) void k_fft_zl(const float2* __restrict__ in
         for (int ab = 0; ab < NAB; ++ab)
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                dst[16 * ab + A * v] = f32x2{q1[ab][v] - q2[ab][v], q3[ab][v] - q1[ab][v] - q2[ab][v]};
+                stream_store(&dst[16 * ab + A * v], f32x2{q1[ab][v] - q2[ab][v], q3[ab][v] - q1[ab][v] - q2[ab][v]});
     };
 
     static_assert(NBB % 2 == 0, "the two data register sets alternate block by block");
@@ -509,7 +514,7 @@ __global__ __launch_bounds__(256, MINW) void k_fft_sr(FftStridedArgs a, DeviceMa
     auto request = [&](int64_t tile, int g) {
         const f32x2* src = reinterpret_cast<const f32x2*>(X) + in_base(tile) + (int64_t)(wave + 4 * g) * inN;
 #pragma unroll
-        for (int s = 0; s < NS1; ++s) xq[g][s] = (src + (int64_t)(4 * B * s) * inN)[ld_lane];
+        for (int s = 0; s < NS1; ++s) xq[g][s] = stream_load(&(src + (int64_t)(4 * B * s) * inN)[ld_lane]);
     };
 
     int64_t tile = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
@@ -587,8 +592,8 @@ __global__ __launch_bounds__(256, MINW) void k_fft_sr(FftStridedArgs a, DeviceMa
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     // row k_a + A*k_b with k_b = 16*kbb + 4*lq + v: the lq part is in st_lane
-                    (dst + (int64_t)(ka + A * (16 * kbb + v)) * outN)[st_lane] =
-                        f32x2{q1[kbb][v] - q2[kbb][v], q3[kbb][v] - q1[kbb][v] - q2[kbb][v]};
+                    stream_store(&(dst + (int64_t)(ka + A * (16 * kbb + v)) * outN)[st_lane],
+                                 f32x2{q1[kbb][v] - q2[kbb][v], q3[kbb][v] - q1[kbb][v] - q2[kbb][v]});
                 }
         }
         __syncthreads();                           // Z is rewritten by the next tile
@@ -643,7 +648,7 @@ __global__ __launch_bounds__(256, MINW) void k_contract_sr(ContractArgs a, int64
 #pragma unroll
         for (int s = 0; s < NS; ++s)
 #pragma unroll
-            for (int g = 0; g < CT; ++g) x[g][s] = src[(int64_t)(4 * s) * I + 16 * g];
+            for (int g = 0; g < CT; ++g) x[g][s] = stream_load(&src[(int64_t)(4 * s) * I + 16 * g]);
     };
     auto transform_tile = [&](const f32x2 (&x)[CT][NS], unsigned tile) {
         f32x4 p1[CT][NB], p2[CT][NB], p3[CT][NB];
@@ -699,7 +704,7 @@ __global__ __launch_bounds__(256, MINW) void k_contract_sr(ContractArgs a, int64
                         yi = yr * w.y + yi * w.x;
                         yr = tr;
                     }
-                    dst[(int64_t)k * a.sYk + 16 * g] = f32x2{yr, yi};
+                    stream_store(&dst[(int64_t)k * a.sYk + 16 * g], f32x2{yr, yi});
                 }
             }
     };

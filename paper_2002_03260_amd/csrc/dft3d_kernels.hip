@@ -1233,7 +1233,7 @@ __global__ __launch_bounds__(kThreads) void k_phase(const float2* __restrict__ i
     const int c = (int)(bid % chunks_per_row) * (kThreads * EV) + threadIdx.x * EV;
     if (r >= rows || c >= cols) return;
     const float s = conj ? -1.0f : 1.0f;
-    const xvec x = *reinterpret_cast<const xvec*>(in + r * cols + c);
+    const xvec x = __builtin_nontemporal_load(reinterpret_cast<const xvec*>(in + r * cols + c));
     float2 wr = make_float2(1.f, 0.f);
     if (BY_ROW) {
         wr = Tw[(int)(r % AB)];
@@ -1250,7 +1250,7 @@ __global__ __launch_bounds__(kThreads) void k_phase(const float2* __restrict__ i
         y[2 * e] = x[2 * e] * w.x - x[2 * e + 1] * w.y;
         y[2 * e + 1] = x[2 * e] * w.y + x[2 * e + 1] * w.x;
     }
-    *reinterpret_cast<xvec*>(out + r * cols + c) = y;
+    __builtin_nontemporal_store(y, reinterpret_cast<xvec*>(out + r * cols + c));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1295,13 +1295,14 @@ __global__ __launch_bounds__(kThreads) void k_reorder_rows(ReorderArgs a, int64_
         // rows keep their content: copy each from its permuted place
         for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
             const int g = e / nz, z = e - g * nz;
-            *reinterpret_cast<xvec*>(dst + e) = *reinterpret_cast<const xvec*>(source_row(r0 + g) + z);
+            __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const xvec*>(source_row(r0 + g) + z)),
+                                        reinterpret_cast<xvec*>(dst + e));
         }
         return;
     }
     for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
         const int g = e / nz, s = e - g * nz;
-        const xvec v = *reinterpret_cast<const xvec*>(source_row(r0 + g) + s);
+        const xvec v = __builtin_nontemporal_load(reinterpret_cast<const xvec*>(source_row(r0 + g) + s));
         store_cvec(&buf[g * pitch + s + s / B], v);   // s and s+1 share a B-row (B even when EV == 2)
     }
     __syncthreads();
@@ -1316,7 +1317,7 @@ __global__ __launch_bounds__(kThreads) void k_reorder_rows(ReorderArgs a, int64_
             v[2 * q] = t.x;
             v[2 * q + 1] = t.y;
         }
-        *reinterpret_cast<xvec*>(dst + e) = v;
+        __builtin_nontemporal_store(v, reinterpret_cast<xvec*>(dst + e));
     }
 }
 
@@ -1410,7 +1411,8 @@ hipError_t launch_contract(const ContractArgs& a, hipStream_t stream)
 namespace {
 // Plain copy, 16 bytes per lane, UNROLL independent accesses per thread: the achievable-bandwidth
 // reference for the memory-bound passes and the calibration kernel for the HBM byte counters.
-template <int UNROLL>
+// STREAM: loads and stores carry the streaming (non-temporal) hint, as in the memory-bound passes.
+template <int UNROLL, bool STREAM>
 __global__ __launch_bounds__(kThreads) void k_copy(const f32x4* __restrict__ in, f32x4* __restrict__ out,
                                                    int64_t nvec)
 {
@@ -1421,12 +1423,15 @@ __global__ __launch_bounds__(kThreads) void k_copy(const f32x4* __restrict__ in,
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int64_t i = base + threadIdx.x + (int64_t)u * kThreads;
-            if (i < nvec) v[u] = in[i];
+            if (i < nvec) v[u] = STREAM ? __builtin_nontemporal_load(in + i) : in[i];
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int64_t i = base + threadIdx.x + (int64_t)u * kThreads;
-            if (i < nvec) out[i] = v[u];
+            if (i < nvec) {
+                if (STREAM) __builtin_nontemporal_store(v[u], out + i);
+                else out[i] = v[u];
+            }
         }
     }
 }
@@ -1508,15 +1513,26 @@ hipError_t launch_copy(const void* in, void* out, size_t bytes, int variant, hip
 {
     const int64_t nvec = (int64_t)(bytes / 16);
     if (nvec <= 0) return hipSuccess;
+    // variant = 100 * streaming + 10 * (workgroups per 256, 0 = one chunk each) + unroll code
+    const bool streaming = variant >= 100;
+    variant %= 100;
     const int unroll = (variant % 10 == 1) ? 1 : ((variant % 10 == 2) ? 2 : 4);
     const int64_t chunk = (int64_t)kThreads * unroll;
     int64_t blocks = cdiv(nvec, chunk);
     const int cap = variant >= 10 ? 256 * (variant / 10) : 0;     // 0: one chunk per workgroup
     if (cap > 0 && blocks > cap) blocks = cap;
     const dim3 grid = grid_for(blocks), block(kThreads);
-    if (unroll == 1) hipLaunchKernelGGL(k_copy<1>, grid, block, 0, stream, (const f32x4*)in, (f32x4*)out, nvec);
-    else if (unroll == 2) hipLaunchKernelGGL(k_copy<2>, grid, block, 0, stream, (const f32x4*)in, (f32x4*)out, nvec);
-    else hipLaunchKernelGGL(k_copy<4>, grid, block, 0, stream, (const f32x4*)in, (f32x4*)out, nvec);
+    const f32x4* src = (const f32x4*)in;
+    f32x4* dst = (f32x4*)out;
+    if (streaming) {
+        if (unroll == 1) hipLaunchKernelGGL((k_copy<1, true>), grid, block, 0, stream, src, dst, nvec);
+        else if (unroll == 2) hipLaunchKernelGGL((k_copy<2, true>), grid, block, 0, stream, src, dst, nvec);
+        else hipLaunchKernelGGL((k_copy<4, true>), grid, block, 0, stream, src, dst, nvec);
+    } else {
+        if (unroll == 1) hipLaunchKernelGGL((k_copy<1, false>), grid, block, 0, stream, src, dst, nvec);
+        else if (unroll == 2) hipLaunchKernelGGL((k_copy<2, false>), grid, block, 0, stream, src, dst, nvec);
+        else hipLaunchKernelGGL((k_copy<4, false>), grid, block, 0, stream, src, dst, nvec);
+    }
     return hipGetLastError();
 }
 
