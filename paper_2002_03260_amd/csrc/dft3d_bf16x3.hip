@@ -316,9 +316,9 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int t
                 const f32x2 y = f32x2{accr[rb][cb][v] * a.scale, acci[rb][cb][v] * a.scale};
                 if (STRIDED) {
                     float2* Yo = a.Y + y_offset(a, tile_o);
-                    *reinterpret_cast<f32x2*>(Yo + (int64_t)(k0 + row) * a.sYk + c0 + col) = y;
+                    __builtin_nontemporal_store(y, reinterpret_cast<f32x2*>(Yo + (int64_t)(k0 + row) * a.sYk + c0 + col));
                 } else {
-                    *reinterpret_cast<f32x2*>(a.Y + y_offset(a, o0 + row) + (int64_t)(k0 + col) * a.sYk) = y;
+                    __builtin_nontemporal_store(y, reinterpret_cast<f32x2*>(a.Y + y_offset(a, o0 + row) + (int64_t)(k0 + col) * a.sYk));
                 }
             }
         }
@@ -551,9 +551,9 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3m(ContractArgs a, int 
                 const f32x2 y = f32x2{(p1 - p2) * a.scale, (p3 - p1 - p2) * (a.scale * xsign)};
                 if (STRIDED) {
                     float2* Yo = a.Y + y_offset(a, tile_o);
-                    *reinterpret_cast<f32x2*>(Yo + (int64_t)(k0 + row) * a.sYk + c0 + col) = y;
+                    __builtin_nontemporal_store(y, reinterpret_cast<f32x2*>(Yo + (int64_t)(k0 + row) * a.sYk + c0 + col));
                 } else {
-                    *reinterpret_cast<f32x2*>(a.Y + y_offset(a, o0 + row) + (int64_t)(k0 + col) * a.sYk) = y;
+                    __builtin_nontemporal_store(y, reinterpret_cast<f32x2*>(a.Y + y_offset(a, o0 + row) + (int64_t)(k0 + col) * a.sYk));
                 }
             }
         }

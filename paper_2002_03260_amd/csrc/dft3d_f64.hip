@@ -256,10 +256,10 @@ __global__ __launch_bounds__(kT, 2) void k_contract_f64(ContractArgs64 a, int ti
                 const f64x2 y = f64x2{re * a.scale, im * a.scale};
                 if (STRIDED) {
                     if (k0 + row < K && c0 + col < I)
-                        Y[y_offset(a, tile_o) + (int64_t)(k0 + row) * a.sYk + c0 + col] = y;
+                        __builtin_nontemporal_store(y, &Y[y_offset(a, tile_o) + (int64_t)(k0 + row) * a.sYk + c0 + col]);
                 } else {
                     if (o0 + row < a.O && k0 + col < K)
-                        Y[y_offset(a, o0 + row) + (int64_t)(k0 + col) * a.sYk] = y;
+                        __builtin_nontemporal_store(y, &Y[y_offset(a, o0 + row) + (int64_t)(k0 + col) * a.sYk]);
                 }
             }
 }
