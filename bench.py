@@ -316,11 +316,12 @@ def main() -> int:
                 per_cmac = 6.0 if three else 8.0
                 flops = (per_cmac * (A + B) + 6.0) * E
             elif "stage1" in dom_name:
-                # strided stages with a 16 / 32 / 64 matrix run the three-product streaming kernel
-                per_cmac = 6.0 if (ax != 2 and A in (16, 32, 64)) else 8.0
+                # strided stages with a 16 / 32 / 64 matrix run the three-product streaming kernel, and
+                # every stage of 128 points or more takes the three-product scheme
+                per_cmac = 6.0 if ((ax != 2 and A in (16, 32, 64)) or A >= 128) else 8.0
                 flops = (per_cmac * A + (0.0 if args.unfused else 6.0)) * E
             elif "stage2" in dom_name:
-                per_cmac = 6.0 if (ax != 2 and B in (16, 32, 64)) else 8.0
+                per_cmac = 6.0 if ((ax != 2 and B in (16, 32, 64)) or B >= 128) else 8.0
                 flops = per_cmac * B * E
         hbm_frac = nbytes / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBS
         mfma_frac = flops / (dom_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS

@@ -337,6 +337,10 @@ hipError_t run_mode(const dft3d_plan_s* p, int axis, const float2* in, float2* o
     return launch_contract(a, st);
 }
 
+// A stage of 128 points or more is bound by the matrix cores (8 * 128 / 16 = 64 flop per byte): it
+// takes the three-product complex scheme, like the fused kernels.  Shorter stages are memory-bound.
+int stage_uses_three_products(const DeviceMatrix& M) { return M.N >= 128 ? 1 : 0; }
+
 // FFT first stage on `axis`: view [outer][A][B*inner], contract the A index.
 hipError_t run_first_stage(const dft3d_plan_s* p, int axis, const float2* in, float2* out, int conj,
                            int fuse_twiddle, hipStream_t st)
@@ -356,6 +360,7 @@ hipError_t run_first_stage(const dft3d_plan_s* p, int axis, const float2* in, fl
     a.twInner = p->inner(axis);
     a.scale = 1.0f;
     a.conj = conj;
+    a.three_m = stage_uses_three_products(a.M);
     return launch_contract(a, st);
 }
 
@@ -385,6 +390,7 @@ hipError_t run_second_stage(const dft3d_plan_s* p, int axis, const float2* in, f
     a.twInner = 1;
     a.scale = scale;
     a.conj = conj;
+    a.three_m = stage_uses_three_products(a.M);
     return launch_contract(a, st);
 }
 
