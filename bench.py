@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 PEAK_MFMA_F32_TFLOPS = 157.3      # 256 CU x 256 flop/clk x 2.4 GHz
 PEAK_MFMA_BF16_TFLOPS = 2500.0    # dense bf16 matrix-core peak
 PEAK_MFMA_F64_TFLOPS = 78.6
+PEAK_VALU_F32_TFLOPS = 157.3      # fp32 vector units: 256 CU x 4 SIMD x 64 flop/clk (two packed FMA lanes x 16) x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
@@ -255,7 +256,18 @@ def main() -> int:
     npass = len(per_exec[0])
     pass_ms = [sum(p[i] for p in per_exec) / steps for i in range(npass)]
 
-    if form == dft.KDFT:
+    if form == dft.KDFT and npass == 1 and max(w.shape) <= 32 and not c128:
+        # every axis at most 32 long: the whole transform is one launch of plain vector arithmetic
+        pass_names = ["whole_transform"]
+        dom_ms = pass_ms[0]
+        flops = 8.0 * (w.shape[0] + w.shape[1] + w.shape[2]) * E
+        roofline = {
+            "bound": "alu", "kernel": "k_kdft_small (all three modes in one launch, fp32 vector arithmetic)",
+            "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": PEAK_VALU_F32_TFLOPS,
+            "unit": "TFLOP/s", "avg_launch_ms": dom_ms, "flop_per_launch": flops,
+            "note": "launch latency, not arithmetic, sets the time at this size",
+        }
+    elif form == dft.KDFT:
         # one pass per axis of length > 1, in the order z, y, x
         live = [ax for ax in (2, 1, 0) if w.shape[ax] > 1] or [2]
         pass_names = [f"mode_{'xyz'[ax]}({'contiguous' if ax == 2 else 'strided'})" for ax in live]

@@ -129,7 +129,10 @@ dft3d_status dft3d_plan_get_output_shape(dft3d_plan plan, int64_t* kx, int64_t* 
 /* Frees the plan and the device memory it owns (not the workspace).  NULL is accepted. */
 dft3d_status dft3d_plan_destroy(dft3d_plan plan);
 
-/* Bytes of caller-provided device workspace dft3d_exec needs: 0 with CLOBBER_INPUT, else the
+/* Bytes of caller-provided device workspace dft3d_exec needs: 0 with CLOBBER_INPUT and for KDFT
+ * plans on complex64 tensors whose axes (input and output) are all at most 32 long -- those run
+ * all three modes in one launch of plain fp32 vector arithmetic, whatever arithmetic flags the
+ * plan carries (at that size the transform is launch latency: Eq. 10 on 32^3 is 2.5e7 flop) -- else the
  * size of one tensor (8 * nx*ny*nz; 16 * nx*ny*nz for a COMPLEX128 plan) or, for FFT plans that
  * keep their intermediate with a padded row pitch, 8 * nx*ny*(nz+16).  Always query; the step
  * calls below need none. */

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdft3d.so")
-SOURCES = ["dft3d_kernels.hip", "dft3d_bf16x3.hip", "dft3d_f64.hip", "dft3d_fft_reg.hip", "dft3d_plan.cpp", "dft3d_generate.cpp"]
+SOURCES = ["dft3d_kernels.hip", "dft3d_bf16x3.hip", "dft3d_f64.hip", "dft3d_fft_reg.hip", "dft3d_small.hip", "dft3d_plan.cpp", "dft3d_generate.cpp"]
 HEADERS = [os.path.join(CSRC, "dft3d_internal.h"), os.path.join(ROOT, "include", "dft3d.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -153,6 +153,12 @@ hipError_t launch_fft_sr(const float2* in, float2* out, int64_t O, int64_t I, in
 // ---- plain copy (bandwidth reference / counter calibration) -------------------------------
 // variant: units digit = accesses in flight per thread (1, 2, else 4); tens digit t > 0 caps the
 // grid at 256*t workgroups (grid-stride), 0 launches one chunk per workgroup.
+// Whole KDFT transform of a tensor whose axes are all at most 32 long (input and output) in one
+// launch: in[Mx.N][My.N][Mz.N] -> out[Mx.K][My.K][Mz.K], scaled, matrices conjugated when conj != 0.
+bool kdft_small_supported(const DeviceMatrix& Mx, const DeviceMatrix& My, const DeviceMatrix& Mz);
+hipError_t launch_kdft_small(const float2* in, float2* out, const DeviceMatrix& Mx, const DeviceMatrix& My,
+                             const DeviceMatrix& Mz, float scale, int conj, hipStream_t stream);
+
 hipError_t launch_copy(const void* in, void* out, size_t bytes, int variant, hipStream_t stream);
 
 // ---- host generator -----------------------------------------------------------------------

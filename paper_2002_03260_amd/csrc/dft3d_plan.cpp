@@ -473,6 +473,13 @@ float axis_scale(const dft3d_plan_s* p, int axis, int direction)
     return direction == DFT3D_BACKWARD ? (float)(1.0 / (double)p->n[axis]) : 1.0f;
 }
 
+// KDFT plans on complex64 tensors whose axes are all at most 32 long run the whole transform in one
+// launch and need no workspace.
+bool single_launch(const dft3d_plan_s* p)
+{
+    return p->form == DFT3D_KDFT && !p->complex128() && kdft_small_supported(p->M[0], p->M[1], p->M[2]);
+}
+
 dft3d_status require_uniform_for_backward(const dft3d_plan_s* p, int direction, const char* who)
 {
     if (direction == DFT3D_BACKWARD && (p->points || p->nonuniform[0] || p->nonuniform[1] || p->nonuniform[2])) {
@@ -759,6 +766,7 @@ dft3d_status dft3d_plan_destroy(dft3d_plan p)
 size_t dft3d_plan_workspace_bytes(dft3d_plan p)
 {
     if (!p) return 0;
+    if (single_launch(p)) return 0;
     if (p->points)   // two intermediates of different shapes: after mode z and after mode y
         return (size_t)(p->stage_out_elements(2) + p->stage_out_elements(1)) * 8;
     if (p->flags & DFT3D_FLAG_CLOBBER_INPUT) return 0;
@@ -918,6 +926,20 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
     if (!valid_direction(direction)) { set_error("exec: bad direction"); return DFT3D_ERR_INVALID_ARG; }
     s = require_uniform_for_backward(p, direction, "exec");
     if (s != DFT3D_OK) return s;
+
+    if (single_launch(p)) {
+        hipStream_t sst = (hipStream_t)stream;
+        const int bw = direction == DFT3D_BACKWARD;
+        const float sc = bw ? axis_scale(p, 0, direction) * axis_scale(p, 1, direction) * axis_scale(p, 2, direction) : 1.0f;
+        const int slot = (p->prof_next < p->prof_capacity) ? p->prof_next++ : -1;
+        if (slot >= 0) (void)hipEventRecord(p->prof_events[(size_t)slot * DFT3D_MAX_PASSES * 2], sst);
+        const hipError_t se = launch_kdft_small((const float2*)in, (float2*)out, p->M[0], p->M[1], p->M[2], sc, bw, sst);
+        if (slot >= 0) {
+            (void)hipEventRecord(p->prof_events[(size_t)slot * DFT3D_MAX_PASSES * 2 + 1], sst);
+            p->prof_npass[(size_t)slot] = 1;
+        }
+        return hip_status(se, "exec");
+    }
 
     if (p->points) {
         // in -> W1 (mode z) -> W2 (mode y) -> out (mode x); the two intermediates live in the workspace

@@ -1,0 +1,111 @@
+// Whole KDFT transform of a small tensor (every axis at most 32 long, on input and on output) in ONE
+// launch.  At these sizes (paper Eq. 10 on a 32^3 tensor is 256 KiB and 2.5e7 flop) three mode
+// kernels are pure launch latency, so one workgroup per output index k_x does all three modes:
+//
+//   1. S[b, c]   = sum_a  Mx[k_x, a] * in[a, b, c]       (mode x, for this workgroup's k_x only;
+//                                                         the input is read by every workgroup, from L2)
+//   2. T[b, k_z] = sum_c  S[b, c] * Mz[k_z, c]            (mode z, in LDS)
+//   3. out[k_x, k_y, k_z] = scale * sum_b My[k_y, b] * T[b, k_z]      (mode y, in LDS)
+//
+// which is Eq. 11's Kronecker factorisation applied in the order x, z, y.  Plain fp32 vector
+// arithmetic: the matrix cores have nothing to amortise here.  The matrices may be rectangular
+// (evaluation-point plans) and are conjugated for BACKWARD.
+#include <hip/hip_runtime.h>
+
+#include "dft3d_internal.h"
+
+namespace dft3d {
+
+namespace {
+
+constexpr int kSmallMax = 32;              // longest axis served
+constexpr int kPitch = kSmallMax + 1;      // odd pitch (in complex numbers): rows land on distinct banks
+constexpr int kSmallThreads = 1024;        // one thread per element of a 32 x 32 slab
+
+__device__ __forceinline__ float2 cmul_add(float2 acc, float2 a, float2 b)
+{
+    acc.x = fmaf(a.x, b.x, acc.x);
+    acc.x = fmaf(-a.y, b.y, acc.x);
+    acc.y = fmaf(a.x, b.y, acc.y);
+    acc.y = fmaf(a.y, b.x, acc.y);
+    return acc;
+}
+
+// Matrix planes are stored transposed, plane[n * ld + k]; sgn = -1 conjugates.
+__device__ __forceinline__ float2 entry(const DeviceMatrix& M, int k, int n, float sgn)
+{
+    const int idx = n * M.ld + k;
+    return make_float2(M.re[idx], sgn * M.im[idx]);
+}
+
+__global__ __launch_bounds__(kSmallThreads) void k_kdft_small(const float2* __restrict__ in, float2* __restrict__ out,
+                                                    DeviceMatrix Mx, DeviceMatrix My, DeviceMatrix Mz,
+                                                    float scale, int conj)
+{
+    __shared__ float2 mx[kSmallMax];                    // Mx[k_x, a] of this workgroup
+    __shared__ float2 my[kSmallMax * kPitch];           // My[k_y, b]
+    __shared__ float2 mz[kSmallMax * kPitch];           // Mz[k_z, c]
+    __shared__ float2 S[kSmallMax * kPitch];            // [b][c]
+    __shared__ float2 T[kSmallMax * kPitch];            // [b][k_z]
+
+    const int nx = Mx.N, ny = My.N, nz = Mz.N;          // input lengths
+    const int ky = My.K, kz = Mz.K;                     // output lengths (kx = gridDim.x)
+    const int kx_i = blockIdx.x;
+    const int tid = threadIdx.x;
+    const float sgn = conj ? -1.0f : 1.0f;
+
+    if (tid < nx) mx[tid] = entry(Mx, kx_i, tid, sgn);
+    // (consecutive threads take consecutive k: the planes are contiguous along k)
+    for (int e = tid; e < ky * ny; e += kSmallThreads) my[(e % ky) * kPitch + e / ky] = entry(My, e % ky, e / ky, sgn);
+    for (int e = tid; e < kz * nz; e += kSmallThreads) mz[(e % kz) * kPitch + e / kz] = entry(Mz, e % kz, e / kz, sgn);
+    __syncthreads();
+
+    // 1. mode x for this k_x: consecutive threads read consecutive elements of each input plane
+    const int plane = ny * nz;
+    for (int e = tid; e < plane; e += kSmallThreads) {
+        float2 acc = make_float2(0.f, 0.f);
+#pragma unroll 8
+        for (int a = 0; a < nx; ++a) acc = cmul_add(acc, mx[a], in[(int64_t)a * plane + e]);   // 8 loads in flight
+        S[(e / nz) * kPitch + e % nz] = acc;
+    }
+    __syncthreads();
+
+    // 2. mode z
+    for (int e = tid; e < ny * kz; e += kSmallThreads) {
+        const int b = e / kz, k = e % kz;
+        float2 acc = make_float2(0.f, 0.f);
+#pragma unroll 8
+        for (int c = 0; c < nz; ++c) acc = cmul_add(acc, S[b * kPitch + c], mz[k * kPitch + c]);
+        T[b * kPitch + k] = acc;
+    }
+    __syncthreads();
+
+    // 3. mode y, scaled, stored in natural order
+    for (int e = tid; e < ky * kz; e += kSmallThreads) {
+        const int k2 = e / kz, k3 = e % kz;
+        float2 acc = make_float2(0.f, 0.f);
+#pragma unroll 8
+        for (int b = 0; b < ny; ++b) acc = cmul_add(acc, my[k2 * kPitch + b], T[b * kPitch + k3]);
+        out[((int64_t)kx_i * ky + k2) * kz + k3] = make_float2(acc.x * scale, acc.y * scale);
+    }
+}
+
+}  // namespace
+
+bool kdft_small_supported(const DeviceMatrix& Mx, const DeviceMatrix& My, const DeviceMatrix& Mz)
+{
+    const DeviceMatrix* m[3] = {&Mx, &My, &Mz};
+    for (const DeviceMatrix* q : m)
+        if (!q->re || q->N < 1 || q->K < 1 || q->N > kSmallMax || q->K > kSmallMax) return false;
+    return true;
+}
+
+hipError_t launch_kdft_small(const float2* in, float2* out, const DeviceMatrix& Mx, const DeviceMatrix& My,
+                             const DeviceMatrix& Mz, float scale, int conj, hipStream_t stream)
+{
+    if (!kdft_small_supported(Mx, My, Mz)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_kdft_small, dim3((unsigned)Mx.K), dim3(kSmallThreads), 0, stream, in, out, Mx, My, Mz, scale, conj);
+    return hipGetLastError();
+}
+
+}  // namespace dft3d

@@ -496,7 +496,7 @@ def test_cfg2_kdft_256(dft):
 def test_exec_argument_errors(dft):
     import torch
 
-    shape = (8, 8, 8)
+    shape = (8, 8, 40)      # (axes of at most 32 points would need no workspace)
     x = to_dev(wl.draw_complex(shape, "normal", 1))
     with dft.Plan(shape, dft.KDFT) as p:
         with pytest.raises(dft.Dft3dError) as ei:      # no workspace set
@@ -553,3 +553,30 @@ def test_exec_replayed_from_a_hip_graph(dft, form, shape):
             torch.cuda.synchronize()
             assert torch.equal(other, eager)
         del g
+
+
+@pytest.mark.parametrize("shape", [(32, 32, 32), (5, 7, 3), (1, 1, 8), (32, 1, 17), (2, 31, 32), (1, 1, 1)])
+def test_kdft_single_launch_small_shapes(dft, shape):
+    """Axes of at most 32 points: exec runs all three modes in one launch (no workspace).  Forward,
+    backward, nonuniform coordinates, adjoint; the arithmetic flags change nothing here."""
+    say(f"case kdft single launch {shape}")
+    x = wl.draw_complex(shape, "normal", 3000 + sum(shape))
+    xd = to_dev(x)
+    with dft.Plan(shape, dft.KDFT) as p:
+        assert p.workspace_bytes() == 0
+        assert report(f"small fwd {shape}", to_host(p.exec(xd)), orc.dft3d(x)) <= TOL
+        assert report(f"small bwd {shape}", to_host(p.exec(xd, direction=dft.BACKWARD)),
+                      orc.dft3d(x, sign=orc.BACKWARD)) <= TOL
+        # the single-launch path and the per-mode kernels are different code: they must agree too
+        y = xd
+        for axis in (2, 1, 0):
+            y = p.mode_contract(axis, y)
+        assert report(f"small exec vs modes {shape}", to_host(p.exec(xd)), to_host(y).astype(np.complex128)) <= TOL
+    with dft.Plan(shape, dft.KDFT, flags=dft.FLAG_3M | dft.FLAG_BF16X3) as p:
+        assert report(f"small flags {shape}", to_host(p.exec(xd)), orc.dft3d(x)) <= TOL
+    rng = np.random.default_rng(14)
+    coords = tuple(np.sort(rng.random(n)) for n in shape)
+    with dft.Plan(shape, dft.KDFT, coords=coords) as p:
+        assert report(f"small nonuniform {shape}", to_host(p.exec(xd)), orc.dft3d(x, coords)) <= TOL
+    with dft.Plan(shape, dft.KDFT, coords=coords, flags=dft.FLAG_ADJOINT) as p:
+        assert report(f"small adjoint {shape}", to_host(p.exec(xd)), orc.dft3d_adjoint(x, coords=coords)) <= TOL
