@@ -514,9 +514,34 @@ dft3d_status dft3d_plan_create(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t
     return dft3d_plan_create_ex(plan, nx, ny, nz, f, cx, cy, cz, nullptr, 0);
 }
 
+// Destroys a half-built plan on every exit but the successful one (early returns and exceptions).
+struct PlanGuard {
+    dft3d_plan_s* p;
+    ~PlanGuard() { if (p) dft3d_plan_destroy(p); }
+};
+
+static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
+                                     dft3d_formulation f, const double* cx, const double* cy,
+                                     const double* cz, const int64_t* split, uint32_t flags);
+
+// No exception may cross the C boundary: host allocations that fail (a matrix of 2^24 x 2^24 entries,
+// say) become DFT3D_ERR_ALLOC.
 dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
                                   dft3d_formulation f, const double* cx, const double* cy,
                                   const double* cz, const int64_t* split, uint32_t flags)
+{
+    try {
+        return plan_create_impl(plan, nx, ny, nz, f, cx, cy, cz, split, flags);
+    } catch (...) {
+        if (plan) *plan = nullptr;
+        set_error("plan_create: out of host memory while building the matrices");
+        return DFT3D_ERR_ALLOC;
+    }
+}
+
+static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
+                                     dft3d_formulation f, const double* cx, const double* cy,
+                                     const double* cz, const int64_t* split, uint32_t flags)
 {
     if (!plan) { set_error("plan_create: plan pointer is NULL"); return DFT3D_ERR_INVALID_ARG; }
     *plan = nullptr;
@@ -557,6 +582,7 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
 
     dft3d_plan_s* p = new (std::nothrow) dft3d_plan_s();
     if (!p) { set_error("plan_create: out of host memory"); return DFT3D_ERR_ALLOC; }
+    PlanGuard guard{p};
     p->form = f;
     p->flags = flags;
     for (int j = 0; j < 3; ++j) {
@@ -621,10 +647,8 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
             }
         }
     }
-    if (s != DFT3D_OK) {
-        dft3d_plan_destroy(p);
-        return s;
-    }
+    if (s != DFT3D_OK) return s;      // (the guard frees the plan)
+    guard.p = nullptr;
     if (f == DFT3D_FFT && !(flags & (DFT3D_FLAG_UNFUSED | DFT3D_FLAG_CLOBBER_INPUT)) && n[0] > 1 && n[1] > 1 &&
         n[2] > 1 && n[2] % 16 == 0 && (n[1] * n[2] * 8) % 8192 == 0 && n[1] * (n[2] + 16) <= (int64_t(1) << 21) &&
         fft_z_supported((int)p->A[2], (int)p->B[2]) && fft_sr_supported((int)p->A[1], (int)p->B[1], n[2]) &&
@@ -682,9 +706,26 @@ dft3d_status dft3d_plan_read_profile(dft3d_plan p, int exec_index, float* ms, in
     return DFT3D_OK;
 }
 
+static dft3d_status plan_create_points_impl(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
+                                            int64_t kx, int64_t ky, int64_t kz, const double* zx,
+                                            const double* zy, const double* zz, uint32_t flags);
+
 dft3d_status dft3d_plan_create_points(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
                                       int64_t kx, int64_t ky, int64_t kz, const double* zx,
                                       const double* zy, const double* zz, uint32_t flags)
+{
+    try {
+        return plan_create_points_impl(plan, nx, ny, nz, kx, ky, kz, zx, zy, zz, flags);
+    } catch (...) {
+        if (plan) *plan = nullptr;
+        set_error("plan_create_points: out of host memory while building the matrices");
+        return DFT3D_ERR_ALLOC;
+    }
+}
+
+static dft3d_status plan_create_points_impl(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
+                                            int64_t kx, int64_t ky, int64_t kz, const double* zx,
+                                            const double* zy, const double* zz, uint32_t flags)
 {
     if (!plan) { set_error("plan_create_points: plan pointer is NULL"); return DFT3D_ERR_INVALID_ARG; }
     *plan = nullptr;
@@ -713,6 +754,7 @@ dft3d_status dft3d_plan_create_points(dft3d_plan* plan, int64_t nx, int64_t ny, 
     }
     dft3d_plan_s* p = new (std::nothrow) dft3d_plan_s();
     if (!p) { set_error("plan_create_points: out of host memory"); return DFT3D_ERR_ALLOC; }
+    PlanGuard guard{p};
     p->form = DFT3D_KDFT;
     p->flags = flags;
     p->points = true;
@@ -729,10 +771,8 @@ dft3d_status dft3d_plan_create_points(dft3d_plan* plan, int64_t nx, int64_t ny, 
         if (s == DFT3D_OK && adjoint) conjugate_transpose(re, im, k[j], n[j]);
         if (s == DFT3D_OK) s = upload_matrix(re, im, (int)p->k[j], (int)p->n[j], &p->M[j]);
     }
-    if (s != DFT3D_OK) {
-        dft3d_plan_destroy(p);
-        return s;
-    }
+    if (s != DFT3D_OK) return s;      // (the guard frees the plan)
+    guard.p = nullptr;
     *plan = p;
     return DFT3D_OK;
 }

@@ -145,6 +145,17 @@ def test_argument_errors_are_status_codes(lib):
     assert lib.dft3d_status_string(99) == b"DFT3D_ERR_UNKNOWN"
 
 
+def test_a_matrix_too_large_for_the_host_is_a_status_code_not_an_abort(lib):
+    """A KDFT axis of 2^24 points needs a 2^48-entry matrix: the failed host allocation must come
+    back as DFT3D_ERR_ALLOC (no C++ exception may cross the C boundary)."""
+    h = ctypes.c_void_p()
+    st = lib.dft3d_plan_create(ctypes.byref(h), 1 << 24, 1, 1, dft.KDFT, None, None, None)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_ALLOC" and not h
+    assert b"memory" in lib.dft3d_last_error()
+    st = lib.dft3d_plan_create_points(ctypes.byref(h), 1 << 24, 1, 1, 1 << 24, 1, 1, None, None, None, 0)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_ALLOC" and not h
+
+
 def test_plan_creation_without_a_gpu_fails_loudly(lib):
     import torch
 
