@@ -1566,8 +1566,9 @@ hipError_t launch_reorder_rows(const ReorderArgs& a, int64_t nrows, hipStream_t 
 {
     const int nz = a.n[2];
     const int pitch = nz + a.A[2];
-    // a batch of about 512 complex numbers (4 KiB, one 16-byte access per thread), whole rows
-    int G = 512 / nz;
+    // a batch of about 1024 complex numbers (8 KiB, two 16-byte accesses per thread in flight), whole
+    // rows: measured on 512^3 0.387 ms with 4 KiB batches, 0.335 ms with 8 KiB, 0.364 ms with 16 KiB
+    int G = 1024 / nz;
     if (G > CAP / pitch) G = CAP / pitch;
     if (G < 1) G = 1;
     const int64_t blocks = (nrows + G - 1) / G;
