@@ -359,6 +359,15 @@ def main() -> int:
         roofline["complex_scheme"] = "3M"
     roofline["passes_ms"] = {(pass_names[i] if i < len(pass_names) else f"pass{i}"): round(pass_ms[i], 5)
                              for i in range(npass)}
+    if args.unfused and form == dft.FFT:
+        # the memory-bound exhibits: every twiddle pass and the re-ordering pass move 16 bytes per element
+        nb = 16.0 * E
+        ph = [pass_ms[i] for i in range(npass) if i < len(pass_names) and pass_names[i].endswith("_phase")]
+        ro = [pass_ms[i] for i in range(npass) if i < len(pass_names) and pass_names[i] == "reorder_xyz"]
+        roofline["memory_bound_passes"] = {
+            name: {"avg_launch_ms": sum(v) / len(v), "achieved_GBs": nb / (sum(v) / len(v) * 1e-3) / 1e9,
+                   "frac_of_hbm_peak": nb / (sum(v) / len(v) * 1e-3) / 1e9 / PEAK_HBM_GBS}
+            for name, v in (("k_phase", ph), ("k_reorder_rows", ro)) if v}
 
     result = {
         "metric": "dft3d_effective_gflops",
