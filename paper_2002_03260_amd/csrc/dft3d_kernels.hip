@@ -1268,8 +1268,9 @@ __device__ __forceinline__ int unswap_slot(int k, int A, int B)
     return (k % A) * B + k / A;
 }
 
-template <int CAP, int EV>
-__global__ __launch_bounds__(kThreads) void k_reorder_rows(ReorderArgs a, int64_t nrows, int G)
+// T = threads per workgroup (long rows take 1024: they are few, large workgroups)
+template <int CAP, int EV, int T>
+__global__ __launch_bounds__(T) void k_reorder_rows(ReorderArgs a, int64_t nrows, int G)
 {
     typedef typename CVec<EV>::type xvec;
     __shared__ __align__(16) float2 buf[CAP];
@@ -1293,20 +1294,20 @@ __global__ __launch_bounds__(kThreads) void k_reorder_rows(ReorderArgs a, int64_
     };
     if (!a.swap[2]) {
         // rows keep their content: copy each from its permuted place
-        for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
+        for (int e = threadIdx.x * EV; e < count; e += T * EV) {
             const int g = e / nz, z = e - g * nz;
             __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const xvec*>(source_row(r0 + g) + z)),
                                         reinterpret_cast<xvec*>(dst + e));
         }
         return;
     }
-    for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
+    for (int e = threadIdx.x * EV; e < count; e += T * EV) {
         const int g = e / nz, s = e - g * nz;
         const xvec v = __builtin_nontemporal_load(reinterpret_cast<const xvec*>(source_row(r0 + g) + s));
         store_cvec(&buf[g * pitch + s + s / B], v);   // s and s+1 share a B-row (B even when EV == 2)
     }
     __syncthreads();
-    for (int e = threadIdx.x * EV; e < count; e += kThreads * EV) {
+    for (int e = threadIdx.x * EV; e < count; e += T * EV) {
         const int g = e / nz, k = e - g * nz;          // natural index k = ka + A*kb
         const int kb = k / A, ka = k - kb * A;
         const float2* p = &buf[g * pitch + ka * (B + 1) + kb];
@@ -1573,10 +1574,11 @@ hipError_t launch_reorder_rows(const ReorderArgs& a, int64_t nrows, hipStream_t 
     if (G < 1) G = 1;
     const int64_t blocks = (nrows + G - 1) / G;
     const bool vec2 = (nz % 2 == 0) && (!a.swap[2] || (a.A[2] % 2 == 0 && a.B[2] % 2 == 0));
+    constexpr int T = CAP > 4096 ? 1024 : kThreads;
     if (vec2)
-        hipLaunchKernelGGL((k_reorder_rows<CAP, 2>), grid_for(blocks), dim3(kThreads), 0, stream, a, nrows, G);
+        hipLaunchKernelGGL((k_reorder_rows<CAP, 2, T>), grid_for(blocks), dim3(T), 0, stream, a, nrows, G);
     else
-        hipLaunchKernelGGL((k_reorder_rows<CAP, 1>), grid_for(blocks), dim3(kThreads), 0, stream, a, nrows, G);
+        hipLaunchKernelGGL((k_reorder_rows<CAP, 1, T>), grid_for(blocks), dim3(T), 0, stream, a, nrows, G);
     return hipGetLastError();
 }
 }  // namespace
