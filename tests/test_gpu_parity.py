@@ -580,3 +580,61 @@ def test_kdft_single_launch_small_shapes(dft, shape):
         assert report(f"small nonuniform {shape}", to_host(p.exec(xd)), orc.dft3d(x, coords)) <= TOL
     with dft.Plan(shape, dft.KDFT, coords=coords, flags=dft.FLAG_ADJOINT) as p:
         assert report(f"small adjoint {shape}", to_host(p.exec(xd)), orc.dft3d_adjoint(x, coords=coords)) <= TOL
+
+
+def _sweep_case(seed):
+    """A seeded random configuration: shape (mixing tiny sizes with sizes next to the tile edges),
+    formulation, flags, direction."""
+    rng = np.random.default_rng(5000 + seed)
+    pool = [1, 2, 3, 5, 8, 15, 16, 17, 24, 31, 32, 33, 48, 63, 64, 65, 80, 96, 127, 128, 129, 130, 160, 192, 256]
+    while True:
+        shape = tuple(int(rng.choice(pool)) for _ in range(3))
+        if np.prod(shape) <= 1_500_000:
+            break
+    form = "FFT" if rng.random() < 0.45 else "KDFT"
+    backward = bool(rng.random() < 0.4)
+    flags = []
+    if rng.random() < 0.3:
+        flags.append("CLOBBER_INPUT")
+    if form == "KDFT":
+        if rng.random() < 0.3:
+            flags.append("3M")
+        if rng.random() < 0.2:
+            flags.append("BF16X3")
+        nonuniform = (not backward) and rng.random() < 0.3
+    else:
+        if rng.random() < 0.25 and "CLOBBER_INPUT" not in flags:
+            flags.append("UNFUSED")
+        nonuniform = False
+    return shape, form, tuple(flags), backward, nonuniform
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_configuration_sweep(dft, seed):
+    """Whole transforms of seeded random shapes / formulations / flags / directions against the oracle:
+    every dispatch decision (fast or masked tiles, fused or staged axes, skipped axes, ping-pong
+    parity with CLOBBER_INPUT, the single-launch path) is taken by some case."""
+    shape, form, flags, backward, nonuniform = _sweep_case(seed)
+    say(f"case sweep {seed}: {shape} {form} {flags} backward={backward} nonuniform={nonuniform}")
+    rng = np.random.default_rng(6000 + seed)
+    coords = tuple(np.sort(rng.random(n)) for n in shape) if nonuniform else (None, None, None)
+    fl = 0
+    for f in flags:
+        fl |= getattr(dft, "FLAG_" + f)
+    x = wl.draw_complex(shape, "normal", 7000 + seed)
+    sign = orc.BACKWARD if backward else orc.FORWARD
+    want = orc.dft3d(x, coords, sign=sign)
+    formulation = dft.FFT if form == "FFT" else dft.KDFT
+    try:
+        plan = dft.Plan(shape, formulation, coords=coords, flags=fl)
+    except dft.Dft3dError as e:
+        assert e.status_name == "DFT3D_ERR_UNSUPPORTED", e
+        pytest.skip(f"combination not offered: {e}")
+    with plan as p:
+        xd = to_dev(x)
+        try:
+            got = to_host(p.exec(xd, direction=dft.BACKWARD if backward else dft.FORWARD))
+        except dft.Dft3dError as e:
+            assert e.status_name == "DFT3D_ERR_UNSUPPORTED", e
+            pytest.skip(f"combination not offered: {e}")
+        assert report(f"sweep {seed} {shape} {form} {flags}", got, want) <= TOL
