@@ -32,10 +32,10 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/); None until measured for a workload.
 MEASURED_TRAFFIC = {
-    "cfg2": 2.82e8,             # strided contraction: 2 * FETCH_SIZE + WRITE_SIZE (calibrated), bytes per launch
-    "cfg2+bf16x3": 2.95e8,      # bf16-split contraction (six bf16 matrix planes instead of two fp32 ones)
+    "cfg2": 2.79e8,             # strided contraction: 2 * FETCH_SIZE + WRITE_SIZE (calibrated), bytes per launch
+    "cfg2+bf16x3": 2.94e8,      # bf16-split contraction (six bf16 matrix planes instead of two fp32 ones)
     "cfg2+complex128": 6.46e8,  # fp64 contraction
-    "cfg3": 2.172e9,            # fused strided-axis kernel
+    "cfg3": 2.18e9,             # fused strided-axis kernel
 }
 
 

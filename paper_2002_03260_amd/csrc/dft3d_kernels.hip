@@ -721,8 +721,9 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_c(ContractArgs a, i
             if (run_store && BN % 2 == 0) {
 #pragma unroll
                 for (int bn = 0; bn + 1 < BN; bn += 2)
-                    __builtin_nontemporal_store(f32x4{y[bn].x, y[bn].y, y[bn + 1].x, y[bn + 1].y},
-                                                reinterpret_cast<f32x4*>(Yo + kb + bn));
+                    // (plain store: one instruction writes 16 of a lane's 32 contiguous bytes, so with the
+                    // streaming hint the halves of a line reach memory separately: 9 % more bytes written)
+                    *reinterpret_cast<f32x4*>(Yo + kb + bn) = f32x4{y[bn].x, y[bn].y, y[bn + 1].x, y[bn + 1].y};
             } else {
 #pragma unroll
                 for (int bn = 0; bn < BN; ++bn)
