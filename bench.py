@@ -193,7 +193,7 @@ def main() -> int:
         flags |= dft.FLAG_3M
     if args.bf16x3 and form == dft.KDFT:
         flags |= dft.FLAG_BF16X3
-    c128 = args.complex128 and form == dft.KDFT
+    c128 = args.complex128
     if c128:
         if big:
             print("bench.py: a complex128 tensor of this workload and its output do not fit one GPU", file=sys.stderr)
@@ -315,8 +315,10 @@ def main() -> int:
         dom = max(range(npass), key=lambda i: pass_ms[i])
         dom_ms = pass_ms[dom]
         dom_name = pass_names[dom] if dom < len(pass_names) else f"pass{dom}"
-        nbytes = 16.0 * E
-        # fp32 flop of that pass: 8 per complex multiply-add of its stage matrices (+6 for a fused twiddle)
+        nbytes = (32.0 if c128 else 16.0) * E
+        mfma_peak = PEAK_MFMA_F64_TFLOPS if c128 else PEAK_MFMA_F32_TFLOPS
+        # flop of that pass: 8 per complex multiply-add of its stage matrices (+6 for a fused twiddle);
+        # complex128 plans run staged passes with four real products throughout
         ax = {"z": 2, "y": 1, "x": 0}.get(dom_name[0])
         flops = 0.0
         if ax is not None and w.splits and "reorder_xyz" not in dom_name and "z_reorder" != dom_name and "phase" not in dom_name:
@@ -330,18 +332,18 @@ def main() -> int:
             elif "stage1" in dom_name:
                 # strided stages with a 16 / 32 / 64 matrix run the three-product streaming kernel, and
                 # every stage of 128 points or more takes the three-product scheme
-                per_cmac = 6.0 if ((ax != 2 and A in (16, 32, 64)) or A >= 128) else 8.0
+                per_cmac = 6.0 if (not c128 and ((ax != 2 and A in (16, 32, 64)) or A >= 128)) else 8.0
                 flops = (per_cmac * A + (0.0 if args.unfused else 6.0)) * E
             elif "stage2" in dom_name:
-                per_cmac = 6.0 if ((ax != 2 and B in (16, 32, 64)) or B >= 128) else 8.0
+                per_cmac = 6.0 if (not c128 and ((ax != 2 and B in (16, 32, 64)) or B >= 128)) else 8.0
                 flops = per_cmac * B * E
         hbm_frac = nbytes / (dom_ms * 1e-3) / 1e9 / PEAK_HBM_GBS
-        mfma_frac = flops / (dom_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS
+        mfma_frac = flops / (dom_ms * 1e-3) / 1e12 / mfma_peak
         # the pass is bound by whichever of the two takes longer at its peak rate
         if mfma_frac > hbm_frac:
             roofline = {
                 "bound": "mfma", "kernel": dom_name,
-                "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+                "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": mfma_peak, "unit": "TFLOP/s",
                 "avg_launch_ms": dom_ms, "flop_per_launch": flops, "bytes_per_launch": nbytes,
                 "hbm_frac": hbm_frac,
             }

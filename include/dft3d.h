@@ -61,11 +61,14 @@ typedef enum { DFT3D_FORWARD = -1, DFT3D_BACKWARD = 1 } dft3d_direction;
                                        used for modes whose shape is a whole number of 128x128 tiles,
                                        other modes fall back to the fp32 kernels.  With DFT3D_FLAG_3M
                                        the bf16 kernels use three real products as well */
-#define DFT3D_FLAG_COMPLEX128 16u   /* KDFT: tensors are complex128 (interleaved doubles), matrices are kept
-                                       in fp64 and the contractions run on the fp64 matrix cores (the
+#define DFT3D_FLAG_COMPLEX128 16u   /* tensors are complex128 (interleaved doubles), matrices and twiddles are
+                                       kept in fp64 and the contractions run on the fp64 matrix cores (the
                                        float64 precision the paper leaves as future work, Section VI).
-                                       Every byte count below doubles (16 bytes per element).  Not
-                                       combined with 3M / BF16X3; not offered for FFT or point plans */
+                                       Every byte count below doubles (16 bytes per element).  KDFT plans,
+                                       and FFT plans as staged passes (first stage with the twiddle in its
+                                       epilogue, second stage, re-ordering: no fused axis kernels, no
+                                       dft3d_fft_phase / dft3d_fft_axis).  Not combined with 3M / BF16X3 /
+                                       UNFUSED; not offered for point plans */
 #define DFT3D_FLAG_ADJOINT 32u      /* KDFT: the plan applies the conjugate transpose of the transform its
                                        other arguments describe, out = (M_x (x) M_y (x) M_z)^H in: from
                                        integer frequencies back to the (nonuniform) samples, the operation
@@ -93,8 +96,8 @@ typedef enum { DFT3D_FORWARD = -1, DFT3D_BACKWARD = 1 } dft3d_direction;
  *             to sqrt(N) with A <= B.  (512 -> 16*32, 2048 -> 32*64.)
  *   flags     DFT3D_FLAG_* bits
  * Errors: INVALID_ARG (NULL plan pointer, size < 1, bad split, unknown formulation or flag),
- * UNSUPPORTED (FFT with coordinates, COMPLEX128 or ADJOINT on an FFT plan, COMPLEX128 together
- * with 3M / BF16X3),
+ * UNSUPPORTED (FFT with coordinates, ADJOINT on an FFT plan, COMPLEX128 together with 3M / BF16X3 /
+ * UNFUSED),
  * ALLOC / HIP (device allocation or copy failed).
  */
 dft3d_status dft3d_plan_create(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,

@@ -255,7 +255,16 @@ __global__ __launch_bounds__(kT, 2) void k_contract_f64(ContractArgs64 a, int ti
                 const double re = prr[rb][cb][v] - msign * pii[rb][cb][v];
                 const double im = STRIDED ? pri[rb][cb][v] + msign * pir[rb][cb][v]
                                           : msign * pri[rb][cb][v] + pir[rb][cb][v];
-                const f64x2 y = f64x2{re * a.scale, im * a.scale};
+                f64x2 y = f64x2{re * a.scale, im * a.scale};
+                if (a.Tw) {      // fused twiddle of the FFT formulation's first stage
+                    const int64_t kk = STRIDED ? k0 + row : k0 + col;
+                    const int64_t ii = STRIDED ? c0 + col : 0;
+                    if (kk < K && (!STRIDED || ii < I)) {
+                        const f64x2 w = reinterpret_cast<const f64x2*>(a.Tw)[kk * a.twB + ii / a.twInner];
+                        const double wi = a.conj ? -w.y : w.y;
+                        y = f64x2{y.x * w.x - y.y * wi, y.x * wi + y.y * w.x};
+                    }
+                }
                 if (STRIDED) {
                     if (k0 + row < K && c0 + col < I)
                         Y[y_offset(a, tile_o) + (int64_t)(k0 + row) * a.sYk + c0 + col] = y;
@@ -264,6 +273,28 @@ __global__ __launch_bounds__(kT, 2) void k_contract_f64(ContractArgs64 a, int ti
                         Y[y_offset(a, o0 + row) + (int64_t)(k0 + col) * a.sYk] = y;
                 }
             }
+}
+
+// Sub-index swap of 16-byte elements: output element e gathers its source (natural index
+// k_a + A*k_b  <-  slot k_a*B + k_b on every swapped axis).
+struct Reorder128 {
+    const f64x2* in;
+    f64x2* out;
+    int n[3], A[3], B[3], swap[3];
+};
+__global__ __launch_bounds__(kT) void k_reorder_c128(Reorder128 a, int64_t total)
+{
+    const int64_t stride = (int64_t)gridDim.x * kT;
+    for (int64_t e = (int64_t)blockIdx.x * kT + threadIdx.x; e < total; e += stride) {
+        const int z = (int)(e % a.n[2]);
+        const int64_t r = e / a.n[2];
+        const int y = (int)(r % a.n[1]);
+        const int x = (int)(r / a.n[1]);
+        const int sx = a.swap[0] ? (x % a.A[0]) * a.B[0] + x / a.A[0] : x;
+        const int sy = a.swap[1] ? (y % a.A[1]) * a.B[1] + y / a.A[1] : y;
+        const int sz = a.swap[2] ? (z % a.A[2]) * a.B[2] + z / a.A[2] : z;
+        a.out[e] = a.in[((int64_t)sx * a.n[1] + sy) * a.n[2] + sz];
+    }
 }
 
 inline dim3 grid_for(int64_t blocks)
@@ -298,6 +329,26 @@ hipError_t launch_contract_f64(const ContractArgs64& a, hipStream_t stream)
         else
             hipLaunchKernelGGL((k_contract_f64<true, false>), grid_for(total), dim3(kT), 0, stream, a, tk, ti, total);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_reorder_c128(const void* in, void* out, const int n[3], const int A[3], const int B[3],
+                               const int swap[3], hipStream_t stream)
+{
+    Reorder128 a{};
+    a.in = reinterpret_cast<const f64x2*>(in);
+    a.out = reinterpret_cast<f64x2*>(out);
+    for (int j = 0; j < 3; ++j) {
+        a.n[j] = n[j];
+        a.A[j] = A[j];
+        a.B[j] = B[j];
+        a.swap[j] = swap[j];
+    }
+    const int64_t total = (int64_t)n[0] * n[1] * n[2];
+    if (total <= 0) return hipSuccess;
+    int64_t blocks = (total + kT - 1) / kT;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(k_reorder_c128, dim3((unsigned)blocks), dim3(kT), 0, stream, a, total);
     return hipGetLastError();
 }
 

@@ -87,8 +87,17 @@ struct ContractArgs64 {
     int64_t Olo, sYohi, sYolo, sYk;
     double scale;
     int conj;
+    // optional twiddle fused into the epilogue: out *= Tw[k * twB + (i / twInner)] (conjugated when conj);
+    // (re, im) pairs of doubles, NULL = none
+    const double* Tw;
+    int twB;
+    int64_t twInner;
 };
 hipError_t launch_contract_f64(const ContractArgs64& a, hipStream_t stream);
+
+// Sub-index swap of a complex128 tensor (same meaning as ReorderArgs, 16-byte elements).
+hipError_t launch_reorder_c128(const void* in, void* out, const int n[3], const int A[3], const int B[3],
+                               const int swap[3], hipStream_t stream);
 
 // ---- twiddle (phase) multiply -------------------------------------------------------------
 // Tensor viewed as [outer][A][B][inner]; out = in * Tw[k_a * B + beta] (conjugated if conj).

@@ -232,6 +232,7 @@ struct dft3d_plan_s {
     int64_t A[3] = {1, 1, 1}, B[3] = {1, 1, 1};
     DeviceMatrix FA[3], FB[3];
     float2* Tw[3] = {nullptr, nullptr, nullptr};
+    double* Tw64[3] = {nullptr, nullptr, nullptr};   // complex128 plans: the same table in fp64, (re, im) pairs
     int F_owner[3] = {0, 1, 2};
 
     void* workspace = nullptr;
@@ -341,10 +342,42 @@ hipError_t run_mode(const dft3d_plan_s* p, int axis, const float2* in, float2* o
 // takes the three-product complex scheme, like the fused kernels.  Shorter stages are memory-bound.
 int stage_uses_three_products(const DeviceMatrix& M) { return M.N >= 128 ? 1 : 0; }
 
+// The complex128 form of a stage contraction: same views and strides, fp64 planes and twiddles.
+hipError_t run_stage_c128(const DeviceMatrix& M, const void* in, void* out, int64_t O, int64_t I, int64_t Olo,
+                          int64_t sYohi, int64_t sYolo, int64_t sYk, const double* Tw, int twB, int64_t twInner,
+                          double scale, int conj, hipStream_t st)
+{
+    ContractArgs64 d{};
+    d.X = in;
+    d.Y = out;
+    d.M = M.f64;
+    d.K = M.K;
+    d.N = M.N;
+    d.ld = M.ld64;
+    d.rows = M.rows64;
+    d.O = O;
+    d.I = I;
+    d.Olo = Olo;
+    d.sYohi = sYohi;
+    d.sYolo = sYolo;
+    d.sYk = sYk;
+    d.scale = scale;
+    d.conj = conj;
+    d.Tw = Tw;
+    d.twB = twB;
+    d.twInner = twInner;
+    return launch_contract_f64(d, st);
+}
+
 // FFT first stage on `axis`: view [outer][A][B*inner], contract the A index.
 hipError_t run_first_stage(const dft3d_plan_s* p, int axis, const float2* in, float2* out, int conj,
                            int fuse_twiddle, hipStream_t st)
 {
+    if (p->complex128()) {
+        const int64_t I = p->B[axis] * p->inner(axis);
+        return run_stage_c128(p->FA[axis], in, out, p->outer(axis), I, 1, (int64_t)p->FA[axis].K * I, 0, I,
+                              fuse_twiddle ? p->Tw64[axis] : nullptr, (int)p->B[axis], p->inner(axis), 1.0, conj, st);
+    }
     ContractArgs a{};
     a.X = in;
     a.Y = out;
@@ -370,6 +403,12 @@ hipError_t run_second_stage(const dft3d_plan_s* p, int axis, const float2* in, f
                             float scale, int reorder, hipStream_t st)
 {
     const int64_t A = p->A[axis], B = p->B[axis], inner = p->inner(axis);
+    if (p->complex128()) {
+        // BACKWARD: the exact fp64 reciprocal of the axis length (the float `scale` is not used)
+        const double sc = conj ? 1.0 / (double)p->n[axis] : 1.0;
+        return run_stage_c128(p->FB[axis], in, out, p->outer(axis) * A, inner, A, A * B * inner,
+                              reorder ? inner : B * inner, reorder ? A * inner : inner, nullptr, 1, 1, sc, conj, st);
+    }
     ContractArgs a{};
     a.X = in;
     a.Y = out;
@@ -397,7 +436,7 @@ hipError_t run_second_stage(const dft3d_plan_s* p, int axis, const float2* in, f
 // FFT, whole z axis in one fused kernel (both stages, twiddle, natural order).
 bool z_axis_fusable(const dft3d_plan_s* p)
 {
-    return p->form == DFT3D_FFT && fft_z_supported((int)p->A[2], (int)p->B[2]);
+    return p->form == DFT3D_FFT && !p->complex128() && fft_z_supported((int)p->A[2], (int)p->B[2]);
 }
 
 hipError_t run_fused_z(const dft3d_plan_s* p, const float2* in, float2* out, int conj, float scale,
@@ -410,7 +449,7 @@ hipError_t run_fused_z(const dft3d_plan_s* p, const float2* in, float2* out, int
 // FFT, whole x or y axis in one fused kernel.
 bool strided_axis_fusable(const dft3d_plan_s* p, int axis)
 {
-    return p->form == DFT3D_FFT && axis != 2 &&
+    return p->form == DFT3D_FFT && axis != 2 && !p->complex128() &&
            fft_s_supported((int)p->A[axis], (int)p->B[axis], p->inner(axis));
 }
 
@@ -456,6 +495,16 @@ hipError_t run_fused_s_padded(const dft3d_plan_s* p, int axis, const float2* in,
 
 hipError_t run_reorder(const dft3d_plan_s* p, int mask, const float2* in, float2* out, hipStream_t st)
 {
+    if (p->complex128()) {
+        int n[3], A[3], B[3], swap[3];
+        for (int j = 0; j < 3; ++j) {
+            n[j] = (int)p->n[j];
+            A[j] = (int)p->A[j];
+            B[j] = (int)p->B[j];
+            swap[j] = (mask >> j) & 1;
+        }
+        return launch_reorder_c128(in, out, n, A, B, swap, st);
+    }
     ReorderArgs r{};
     r.in = in;
     r.out = out;
@@ -565,9 +614,8 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
         set_error("plan_create: ADJOINT is offered for KDFT plans (on uniform axes it equals BACKWARD up to the 1/N factor)");
         return DFT3D_ERR_UNSUPPORTED;
     }
-    if ((flags & DFT3D_FLAG_COMPLEX128) &&
-        (f != DFT3D_KDFT || (flags & (DFT3D_FLAG_3M | DFT3D_FLAG_BF16X3)))) {
-        set_error("plan_create: COMPLEX128 is offered for KDFT plans without 3M / BF16X3");
+    if ((flags & DFT3D_FLAG_COMPLEX128) && (flags & (DFT3D_FLAG_3M | DFT3D_FLAG_BF16X3 | DFT3D_FLAG_UNFUSED))) {
+        set_error("plan_create: COMPLEX128 is not combined with 3M / BF16X3 / UNFUSED");
         return DFT3D_ERR_UNSUPPORTED;
     }
     if (f == DFT3D_FFT && (cx || cy || cz)) {
@@ -622,11 +670,34 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
                 p->FA[j] = p->FA[i];
                 p->FB[j] = p->FB[i];
                 p->Tw[j] = p->Tw[i];
+                p->Tw64[j] = p->Tw64[i];
                 continue;
             }
-            s = make_axis_matrix(p->A[j], nullptr, &p->FA[j]);
-            if (s == DFT3D_OK) s = make_axis_matrix(p->B[j], nullptr, &p->FB[j]);
+            const bool c128 = (flags & DFT3D_FLAG_COMPLEX128) != 0;
+            s = make_axis_matrix(p->A[j], nullptr, &p->FA[j], false, c128);
+            if (s == DFT3D_OK) s = make_axis_matrix(p->B[j], nullptr, &p->FB[j], false, c128);
             if (s != DFT3D_OK) break;
+            if (c128) {
+                // the twiddle table T[k_a * B + beta] = exp(-2 pi i k_a beta / N) in fp64
+                const int64_t A64 = p->A[j], B64 = p->B[j];
+                std::vector<double> tw((size_t)(2 * A64 * B64));
+                for (int64_t ka = 0; ka < A64; ++ka)
+                    for (int64_t be = 0; be < B64; ++be)
+                        unit_root_ratio(ka * be, A64 * B64, DFT3D_FORWARD, &tw[(size_t)(2 * (ka * B64 + be))],
+                                        &tw[(size_t)(2 * (ka * B64 + be) + 1)]);
+                hipError_t e64 = hipMalloc((void**)&p->Tw64[j], tw.size() * sizeof(double));
+                if (e64 != hipSuccess) {
+                    set_error("plan_create: hipMalloc of an fp64 twiddle table failed: %s", hipGetErrorString(e64));
+                    s = DFT3D_ERR_ALLOC;
+                    break;
+                }
+                e64 = hipMemcpy(p->Tw64[j], tw.data(), tw.size() * sizeof(double), hipMemcpyHostToDevice);
+                if (e64 != hipSuccess) {
+                    set_error("plan_create: fp64 twiddle upload failed: %s", hipGetErrorString(e64));
+                    s = DFT3D_ERR_HIP;
+                    break;
+                }
+            }
             const size_t cnt = (size_t)(p->A[j] * p->B[j]);
             std::vector<float> tr(cnt), ti(cnt);
             s = dft3d_generate_twiddle(p->A[j], p->B[j], DFT3D_FORWARD, tr.data(), ti.data());
@@ -649,7 +720,7 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
     }
     if (s != DFT3D_OK) return s;      // (the guard frees the plan)
     guard.p = nullptr;
-    if (f == DFT3D_FFT && !(flags & (DFT3D_FLAG_UNFUSED | DFT3D_FLAG_CLOBBER_INPUT)) && n[0] > 1 && n[1] > 1 &&
+    if (f == DFT3D_FFT && !(flags & (DFT3D_FLAG_UNFUSED | DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_COMPLEX128)) && n[0] > 1 && n[1] > 1 &&
         n[2] > 1 && n[2] % 16 == 0 && (n[1] * n[2] * 8) % 8192 == 0 && n[1] * (n[2] + 16) <= (int64_t(1) << 21) &&
         fft_z_supported((int)p->A[2], (int)p->B[2]) && fft_sr_supported((int)p->A[1], (int)p->B[1], n[2]) &&
         fft_sr_supported((int)p->A[0], (int)p->B[0], n[1] * n[2]))
@@ -797,6 +868,7 @@ dft3d_status dft3d_plan_destroy(dft3d_plan p)
             free_matrix(p->FA[j]);
             free_matrix(p->FB[j]);
             if (p->Tw[j]) (void)hipFree(p->Tw[j]);
+            if (p->Tw64[j]) (void)hipFree(p->Tw64[j]);
         }
     }
     delete p;
@@ -890,6 +962,10 @@ dft3d_status dft3d_fft_phase(dft3d_plan p, int axis, const void* in, void* out, 
         return DFT3D_ERR_INVALID_ARG;
     }
     if (p->form != DFT3D_FFT) { set_error("fft_phase: not an FFT plan"); return DFT3D_ERR_UNSUPPORTED; }
+    if (p->complex128()) {
+        set_error("fft_phase: complex128 plans apply the twiddle in the first stage only");
+        return DFT3D_ERR_UNSUPPORTED;
+    }
     return hip_status(launch_phase((const float2*)in, (float2*)out, p->outer(axis), (int)p->A[axis],
                                    (int)p->B[axis], p->inner(axis), p->Tw[axis],
                                    direction == DFT3D_BACKWARD, (hipStream_t)stream),

@@ -276,9 +276,48 @@ def test_kdft_complex128_nonuniform(dft):
     assert report("kdft complex128 nonuniform", got, _oracle_c128(x, coords)) <= TOL_F64
 
 
+@pytest.mark.parametrize("shape,split", [((8, 12, 30), (2, 3, 5)), ((64, 32, 128), None), ((36, 20, 48), (6, 4, 8)),
+                                         ((1, 256, 512), None), ((128, 64, 64), None), ((6, 5, 7), (3, 1, 7))])
+def test_fft_formulation_complex128(dft, shape, split):
+    """DFT3D_FLAG_COMPLEX128 on an FFT plan: per axis first stage with the fp64 twiddle in its epilogue
+    and second stage (the x / y re-ordering folded into its stores), z re-ordering pass, all in fp64."""
+    import torch
+
+    say(f"case fft complex128 {shape} split {split}")
+    x = wl.draw_complex128(shape, 8300 + sum(shape))
+    want = _oracle_c128(x)
+    xd = torch.from_numpy(x).to("cuda")
+    with dft.Plan(shape, dft.FFT, split=split, flags=dft.FLAG_COMPLEX128) as p:
+        got = p.exec(xd).cpu().numpy()
+        assert got.dtype == np.complex128
+        assert report(f"fft complex128 {shape}", got, want) <= TOL_F64
+        assert np.array_equal(xd.cpu().numpy(), x), "input must be left intact"
+        gotb = p.exec(xd, direction=dft.BACKWARD).cpu().numpy()
+        assert report(f"fft complex128 backward {shape}", gotb, _oracle_c128(x, sign=orc.BACKWARD)) <= TOL_F64
+        back = p.exec(torch.from_numpy(got).to("cuda"), direction=dft.BACKWARD).cpu().numpy()
+        assert report(f"fft complex128 round trip {shape}", back, x) <= TOL_F64
+        # single steps against the oracle's literal steps (fp64 throughout)
+        for axis in range(3):
+            A, B = p.split(axis)
+            z = ff.first_stage(x, axis, A, B)
+            assert report(f"c128 f1 axis {axis}", p.fft_first_stage(axis, xd).cpu().numpy(), z) <= TOL_F64
+            w = ff.second_stage(x, axis, A, B)
+            assert report(f"c128 f2 axis {axis}", p.fft_second_stage(axis, xd, reorder=False).cpu().numpy(), w) <= TOL_F64
+            assert report(f"c128 f2+reorder axis {axis}", p.fft_second_stage(axis, xd, reorder=True).cpu().numpy(),
+                          ff.reorder(w, axis, A, B)) <= TOL_F64
+            moved = p.fft_reorder(1 << axis, xd).cpu().numpy()
+            assert np.array_equal(moved, ff.reorder(x, axis, A, B)), "re-ordering is pure data movement"
+        with pytest.raises(dft.Dft3dError):
+            p.fft_phase(0, xd)
+    with dft.Plan(shape, dft.FFT, split=split, flags=dft.FLAG_COMPLEX128 | dft.FLAG_CLOBBER_INPUT) as p:
+        assert p.workspace_bytes() == 0
+        got = p.exec(torch.from_numpy(x).to("cuda")).cpu().numpy()
+        assert report(f"fft complex128 clobber {shape}", got, want) <= TOL_F64
+
+
 def test_complex128_plan_restrictions(dft):
     with pytest.raises(dft.Dft3dError) as e:
-        dft.Plan((8, 8, 8), dft.FFT, flags=dft.FLAG_COMPLEX128)
+        dft.Plan((8, 8, 8), dft.FFT, flags=dft.FLAG_COMPLEX128 | dft.FLAG_UNFUSED)
     assert e.value.status_name == "DFT3D_ERR_UNSUPPORTED"
     with pytest.raises(dft.Dft3dError):
         dft.Plan((8, 8, 8), dft.KDFT, flags=dft.FLAG_COMPLEX128 | dft.FLAG_3M)
