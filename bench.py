@@ -332,7 +332,8 @@ def main() -> int:
             elif "stage1" in dom_name:
                 # strided stages with a 16 / 32 / 64 matrix run the three-product streaming kernel, and
                 # every stage of 128 points or more takes the three-product scheme
-                per_cmac = 6.0 if (not c128 and ((ax != 2 and A in (16, 32, 64)) or A >= 128)) else 8.0
+                per_cmac = 6.0 if (not c128 and ((ax != 2 and A in (16, 32, 64)) or A >= 128 or
+                                                  (A == 64 and not args.unfused))) else 8.0
                 flops = (per_cmac * A + (0.0 if args.unfused else 6.0)) * E
             elif "stage2" in dom_name:
                 per_cmac = 6.0 if (not c128 and ((ax != 2 and B in (16, 32, 64)) or B >= 128)) else 8.0
