@@ -275,6 +275,60 @@ __global__ __launch_bounds__(kT, 2) void k_contract_f64(ContractArgs64 a, int ti
             }
 }
 
+// Strided contraction with a small square matrix (16 or 32 points: the stages of the FFT formulation)
+// in plain fp64 vector arithmetic.  Such a pass moves 32 bytes per 8 * N flop, below the ridge of the
+// fp64 units (whose vector rate equals the matrix-core rate on this chip), and an N-row matrix would
+// fill a quarter or half of the matrix-core kernel's 64-row tile.  One thread owns one column (o, i):
+// it loads the N points of the column (consecutive threads read consecutive 16-byte elements), forms
+// the N outputs with the matrix broadcast from LDS, applies the optional twiddle and stores them.
+template <int N>
+__global__ __launch_bounds__(kT) void k_stage_f64(ContractArgs64 a, int64_t ncols)
+{
+    __shared__ f64x2 m[N * N];       // M[k][n] as (re, im), conjugated for BACKWARD
+    const int tid = threadIdx.x;
+    const int64_t plane = (int64_t)a.rows * a.ld;
+    for (int e = tid; e < N * N; e += kT) {
+        const int k = e % N, n = e / N;                   // the planes are contiguous along k
+        m[k * N + n] = f64x2{a.M[(int64_t)n * a.ld + k], (a.conj ? -1.0 : 1.0) * a.M[plane + (int64_t)n * a.ld + k]};
+    }
+    __syncthreads();
+    const int64_t I = a.I;
+    const f64x2* X = reinterpret_cast<const f64x2*>(a.X);
+    f64x2* Y = reinterpret_cast<f64x2*>(a.Y);
+    const int64_t stride = (int64_t)gridDim.x * gridDim.y * kT;
+    for (int64_t c = block_id() * kT + tid; c < ncols; c += stride) {
+        const int64_t o = c / I, i = c - o * I;
+        const f64x2* src = X + o * N * I + i;
+        f64x2 x[N];
+#pragma unroll
+        for (int n = 0; n < N; ++n) x[n] = src[(int64_t)n * I];
+        f64x2* dst = Y + y_offset(a, o) + i;
+        const int64_t beta = a.Tw ? i / a.twInner : 0;
+#pragma unroll 2
+        for (int k = 0; k < N; ++k) {
+            double re = 0.0, im = 0.0;
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                const f64x2 w = m[k * N + n];
+                re = fma(w.x, x[n].x, re);
+                re = fma(-w.y, x[n].y, re);
+                im = fma(w.x, x[n].y, im);
+                im = fma(w.y, x[n].x, im);
+            }
+            re *= a.scale;
+            im *= a.scale;
+            if (a.Tw) {
+                const f64x2 t = reinterpret_cast<const f64x2*>(a.Tw)[(int64_t)k * a.twB + beta];
+                const double ti = a.conj ? -t.y : t.y;
+                const double r2 = re * t.x - im * ti;
+                im = re * ti + im * t.x;
+                re = r2;
+            }
+            dst[(int64_t)k * a.sYk] = f64x2{re, im};
+        }
+    }
+}
+
 // Sub-index swap of 16-byte elements: output element e gathers its source (natural index
 // k_a + A*k_b  <-  slot k_a*B + k_b on every swapped axis).
 struct Reorder128 {
@@ -309,6 +363,15 @@ inline dim3 grid_for(int64_t blocks)
 hipError_t launch_contract_f64(const ContractArgs64& a, hipStream_t stream)
 {
     if (a.O < 1 || a.I < 1 || a.N < 1 || a.K < 1) return hipErrorInvalidValue;
+    if (a.I > 1 && a.K == a.N && (a.N == 16 || a.N == 32) && a.ld >= a.K && a.rows >= a.N) {
+        // small strided stage: fp64 vector arithmetic, one column per thread
+        const int64_t ncols = a.O * a.I;
+        int64_t blocks = (ncols + kT - 1) / kT;
+        if (blocks > 256 * 64) blocks = 256 * 64;
+        if (a.N == 16) hipLaunchKernelGGL(k_stage_f64<16>, grid_for(blocks), dim3(kT), 0, stream, a, ncols);
+        else hipLaunchKernelGGL(k_stage_f64<32>, grid_for(blocks), dim3(kT), 0, stream, a, ncols);
+        return hipGetLastError();
+    }
     // the kernel reads whole 64-wide, 16-deep tiles of the zero-padded planes
     if (a.ld % 64 != 0 || a.ld < a.K || a.rows % KC != 0 || a.rows < a.N) return hipErrorInvalidValue;
     const int tk = (a.K + 63) / 64;

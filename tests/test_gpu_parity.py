@@ -236,7 +236,7 @@ def _oracle_c128(x, coords=(None, None, None), sign=None):
 
 
 @pytest.mark.parametrize("shape", [(6, 10, 12), (40, 33, 70), (64, 64, 64), (128, 130, 64), (3, 5, 260),
-                                   (1, 256, 192), (2, 2, 2)])
+                                   (1, 256, 192), (2, 2, 2), (32, 16, 40), (16, 32, 7)])
 def test_kdft_complex128(dft, shape):
     """DFT3D_FLAG_COMPLEX128: complex128 tensors, fp64 matrices, fp64 matrix cores."""
     import torch
