@@ -813,7 +813,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_z(const float2* __restric
 #pragma unroll
         for (int j = 0; j < XL; ++j) {
             const int64_t e = base + 2 * (tid + j * NT);
-            xreg[j] = (e < limit) ? *reinterpret_cast<const f32x4*>(X + e) : f32x4{0.f, 0.f, 0.f, 0.f};
+            xreg[j] = (e < limit) ? __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(X + e))
+                                  : f32x4{0.f, 0.f, 0.f, 0.f};
         }
     };
 
@@ -942,7 +943,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_z(const float2* __restric
                 const float2 p0 = xos[(row * B + kb) * OP + ka];
                 const float2 p1 = xos[(row * B + kb) * OP + ka + 1];
                 if (base + e < limit)
-                    *reinterpret_cast<f32x4*>(Y + base + e) = f32x4{p0.x, p0.y, p1.x, p1.y};
+                    __builtin_nontemporal_store(f32x4{p0.x, p0.y, p1.x, p1.y}, reinterpret_cast<f32x4*>(Y + base + e));
             }
         }
         __syncthreads();
@@ -1045,7 +1046,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
 #pragma unroll
         for (int j = 0; j < XL; ++j)
             if (j * NSLOT / XL == slot)
-                xreg[j] = *reinterpret_cast<const f32x4*>(src + (int64_t)(j * RPP) * I);
+                xreg[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + (int64_t)(j * RPP) * I));
     };
     auto gload = [&](int64_t tile) {
 #pragma unroll
