@@ -375,7 +375,8 @@ hipError_t launch_contract_f64(const ContractArgs64& a, hipStream_t stream)
     // the kernel reads whole 64-wide, 16-deep tiles of the zero-padded planes
     if (a.ld % 64 != 0 || a.ld < a.K || a.rows % KC != 0 || a.rows < a.N) return hipErrorInvalidValue;
     const int tk = (a.K + 63) / 64;
-    const bool whole = a.K % TM == 0 && a.N % KC == 0 && a.ld < (1 << 20);
+    // (K need not fill the tile: the planes are zero-padded to whole tiles and the stores are masked)
+    const bool whole = a.N % KC == 0 && a.ld < (1 << 20);
     if (a.I == 1) {
         // contiguous mode: rows = o, columns = k; the k-tile index runs fastest
         const int64_t to = (a.O + TM - 1) / TM;
