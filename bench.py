@@ -262,7 +262,7 @@ def main() -> int:
         dom_ms = pass_ms[0]
         flops = 8.0 * (w.shape[0] + w.shape[1] + w.shape[2]) * E
         roofline = {
-            "bound": "alu", "kernel": "k_kdft_small (all three modes in one launch, fp32 vector arithmetic)",
+            "bound": "alu", "kernel": "k_kdft_small (all three modes in one launch: x in fp32 vector arithmetic, z and y on fp32 MFMA)",
             "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": PEAK_VALU_F32_TFLOPS,
             "unit": "TFLOP/s", "avg_launch_ms": dom_ms, "flop_per_launch": flops,
             "note": "launch latency, not arithmetic, sets the time at this size",

@@ -7,9 +7,10 @@
 //   2. T[b, k_z] = sum_c  S[b, c] * Mz[k_z, c]            (mode z, in LDS)
 //   3. out[k_x, k_y, k_z] = scale * sum_b My[k_y, b] * T[b, k_z]      (mode y, in LDS)
 //
-// which is Eq. 11's Kronecker factorisation applied in the order x, z, y.  Plain fp32 vector
-// arithmetic: the matrix cores have nothing to amortise here.  The matrices may be rectangular
-// (evaluation-point plans) and are conjugated for BACKWARD.
+// which is Eq. 11's Kronecker factorisation applied in the order x, z, y.  Mode x is plain fp32 vector
+// arithmetic on data streamed from L2; modes z and y are 32 x 32 x 32 products in LDS and run on the
+// matrix cores (as vector code they were bound by LDS bandwidth: 2 us each of a 12 us kernel).  The
+// matrices may be rectangular (evaluation-point plans) and are conjugated for BACKWARD.
 #include <hip/hip_runtime.h>
 
 #include "dft3d_internal.h"
@@ -17,6 +18,8 @@
 namespace dft3d {
 
 namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kSmallMax = 32;              // longest axis served
 constexpr int kPitch = kSmallMax + 1;      // odd pitch (in complex numbers): rows land on distinct banks
@@ -54,6 +57,14 @@ __global__ __launch_bounds__(kSmallThreads) void k_kdft_small(const float2* __re
     const int tid = threadIdx.x;
     const float sgn = conj ? -1.0f : 1.0f;
 
+    // modes z and y run as full 32 x 32 x 32 products: everything beyond the actual lengths is zero
+    for (int e = tid; e < kSmallMax * kPitch; e += kSmallThreads) {
+        my[e] = make_float2(0.f, 0.f);
+        mz[e] = make_float2(0.f, 0.f);
+        S[e] = make_float2(0.f, 0.f);
+        T[e] = make_float2(0.f, 0.f);
+    }
+    __syncthreads();
     if (tid < nx) mx[tid] = entry(Mx, kx_i, tid, sgn);
     // (consecutive threads take consecutive k: the planes are contiguous along k)
     for (int e = tid; e < ky * ny; e += kSmallThreads) my[(e % ky) * kPitch + e / ky] = entry(My, e % ky, e / ky, sgn);
@@ -70,23 +81,48 @@ __global__ __launch_bounds__(kSmallThreads) void k_kdft_small(const float2* __re
     }
     __syncthreads();
 
-    // 2. mode z
-    for (int e = tid; e < ny * kz; e += kSmallThreads) {
-        const int b = e / kz, k = e % kz;
-        float2 acc = make_float2(0.f, 0.f);
-#pragma unroll 8
-        for (int c = 0; c < nz; ++c) acc = cmul_add(acc, S[b * kPitch + c], mz[k * kPitch + c]);
-        T[b * kPitch + k] = acc;
+    // 2. mode z and 3. mode y on the matrix cores: 32 x 32 x 32 complex products (the arrays are zero
+    // beyond the actual lengths), one 16 x 16 output block per wave for the first four waves.
+    // MFMA 16x16x4 operand layout: lane l supplies A[l % 16][l / 16] and B[l / 16][l % 16]; accumulator
+    // register v is D[4 * (l / 16) + v][l % 16].
+    const int wave = tid >> 6, lane = tid & 63;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int bi = (wave >> 1) * 16, bj = (wave & 1) * 16;      // block origin (rows, columns)
+    if (wave < 4) {
+        // T[b, k_z] = sum_c S[b, c] * Mz[k_z, c]:  A = S (rows b), B[c][k_z] = mz[k_z][c]
+        f32x4 pr = {0.f, 0.f, 0.f, 0.f}, pi = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int st = 0; st < kSmallMax / 4; ++st) {
+            const float2 av = S[(bi + l16) * kPitch + 4 * st + lq];
+            const float2 bv = mz[(bj + l16) * kPitch + 4 * st + lq];
+            pr = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.x, pr, 0, 0, 0);
+            pi = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.y, pi, 0, 0, 0);
+            pr = __builtin_amdgcn_mfma_f32_16x16x4f32(-av.y, bv.y, pr, 0, 0, 0);
+            pi = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, bv.x, pi, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) T[(bi + 4 * lq + v) * kPitch + bj + l16] = make_float2(pr[v], pi[v]);
     }
     __syncthreads();
-
-    // 3. mode y, scaled, stored in natural order
-    for (int e = tid; e < ky * kz; e += kSmallThreads) {
-        const int k2 = e / kz, k3 = e % kz;
-        float2 acc = make_float2(0.f, 0.f);
-#pragma unroll 8
-        for (int b = 0; b < ny; ++b) acc = cmul_add(acc, my[k2 * kPitch + b], T[b * kPitch + k3]);
-        out[((int64_t)kx_i * ky + k2) * kz + k3] = make_float2(acc.x * scale, acc.y * scale);
+    if (wave < 4) {
+        // out[k_y, k_z] = sum_b My[k_y, b] * T[b, k_z]:  A = my (rows k_y), B[b][k_z] = T[b][k_z]
+        f32x4 pr = {0.f, 0.f, 0.f, 0.f}, pi = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int st = 0; st < kSmallMax / 4; ++st) {
+            const float2 av = my[(bi + l16) * kPitch + 4 * st + lq];
+            const float2 bv = T[(4 * st + lq) * kPitch + bj + l16];
+            pr = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.x, pr, 0, 0, 0);
+            pi = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.y, pi, 0, 0, 0);
+            pr = __builtin_amdgcn_mfma_f32_16x16x4f32(-av.y, bv.y, pr, 0, 0, 0);
+            pi = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, bv.x, pi, 0, 0, 0);
+        }
+        const int k3 = bj + l16;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int k2 = bi + 4 * lq + v;
+            if (k2 < ky && k3 < kz)
+                out[((int64_t)kx_i * ky + k2) * kz + k3] = make_float2(pr[v] * scale, pi[v] * scale);
+        }
     }
 }
 
