@@ -162,6 +162,24 @@ dft3d_status dft3d_exec(dft3d_plan plan, const void* in, void* out, int directio
                         void* stream);
 
 /*
+ * dft3d_exec for callers that cannot allocate device memory or hand over a workspace: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and bit-identical results; the intermediate tensor that dft3d_exec keeps in the
+ * caller's workspace lives in a static device array of DFT3D_NOALLOC_MAX_BYTES inside the library
+ * (one per GPU, held from the first plan created on that GPU until the process ends), and any
+ * workspace set on the plan is ignored.  The call allocates and frees nothing; the array's address
+ * is looked up once per GPU, during plan creation.
+ * Errors: as dft3d_exec, and UNSUPPORTED when dft3d_plan_workspace_bytes(plan) exceeds
+ * DFT3D_NOALLOC_MAX_BYTES (one complex64 tensor of 128 x 128 x 256, say).
+ * Every pass overwrites the part of the array it uses before reading it, so nothing needs clearing
+ * between calls; but all calls on one GPU share the one array: two calls whose kernels may overlap
+ * in time (different streams, different plans, different threads) race.  Order them on one stream.
+ */
+#define DFT3D_NOALLOC_MAX_BYTES (32u << 20)
+dft3d_status dft3d_exec_noalloc(dft3d_plan plan, const void* in, void* out, int direction,
+                                void* stream);
+
+/*
  * Per-pass timing of dft3d_exec (measurement aid; the analogue of the per-operation breakdown
  * the paper reads from its profiler in Section V).  After enable_profiling(plan, max_execs)
  * the next max_execs calls of dft3d_exec record a HIP event before and after every kernel on

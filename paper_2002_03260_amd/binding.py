@@ -29,7 +29,7 @@ EXPORTS = [
     "dft3d_plan_create", "dft3d_plan_create_ex", "dft3d_plan_create_points",
     "dft3d_plan_get_output_shape", "dft3d_generate_points_matrix", "dft3d_plan_destroy",
     "dft3d_plan_workspace_bytes", "dft3d_plan_set_workspace", "dft3d_plan_get_split",
-    "dft3d_exec", "dft3d_plan_enable_profiling", "dft3d_plan_read_profile", "dft3d_mode_contract", "dft3d_fft_first_stage", "dft3d_fft_phase",
+    "dft3d_exec", "dft3d_exec_noalloc", "dft3d_plan_enable_profiling", "dft3d_plan_read_profile", "dft3d_mode_contract", "dft3d_fft_first_stage", "dft3d_fft_phase",
     "dft3d_fft_second_stage", "dft3d_fft_axis", "dft3d_fft_reorder", "dft3d_device_copy", "dft3d_generate_matrix",
     "dft3d_generate_twiddle", "dft3d_status_string", "dft3d_last_error",
 ]
@@ -71,6 +71,7 @@ def load_library():
     lib.dft3d_plan_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
     lib.dft3d_plan_get_split.argtypes = [vp, ci, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     lib.dft3d_exec.argtypes = [vp, vp, vp, ci, vp]
+    lib.dft3d_exec_noalloc.argtypes = [vp, vp, vp, ci, vp]
     lib.dft3d_plan_enable_profiling.argtypes = [vp, ci]
     lib.dft3d_plan_read_profile.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ci)]
     lib.dft3d_mode_contract.argtypes = [vp, ci, vp, vp, ci, vp]
@@ -275,6 +276,13 @@ class Plan:
         if self.workspace_bytes():
             self.ensure_workspace(x.device)
         _check(self._lib.dft3d_exec(self._h, xi, oi, direction, _stream_handle(stream)))
+        return out
+
+    def exec_noalloc(self, x, out, direction: int = FORWARD, stream=None):
+        """dft3d_exec_noalloc: the intermediate lives in the library's static scratch array; the caller
+        brings the output tensor and nothing is allocated."""
+        xi, oi, out = self._tensors(x, out)
+        _check(self._lib.dft3d_exec_noalloc(self._h, xi, oi, direction, _stream_handle(stream)))
         return out
 
     def mode_contract(self, axis, x, out=None, direction: int = FORWARD, stream=None):

@@ -4,17 +4,20 @@ from __future__ import annotations
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdft3d.so")
-SOURCES = ["dft3d_kernels.hip", "dft3d_bf16x3.hip", "dft3d_f64.hip", "dft3d_fft_reg.hip", "dft3d_small.hip", "dft3d_plan.cpp", "dft3d_generate.cpp"]
+OBJDIR = os.path.join(HERE, "_build")
+SOURCES = ["dft3d_kernels.hip", "dft3d_bf16x3.hip", "dft3d_f64.hip", "dft3d_fft_reg.hip", "dft3d_small.hip",
+           "dft3d_noalloc.hip", "dft3d_plan.cpp", "dft3d_generate.cpp"]
 HEADERS = [os.path.join(CSRC, "dft3d_internal.h"), os.path.join(ROOT, "include", "dft3d.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed-FP32 VALU forms are kept out of all device code of this library
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
@@ -34,21 +37,47 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
-    """Compile every source into libdft3d.so (always recompiles)."""
-    cmd = [HIPCC] + FLAGS + list(extra_flags)
+def _compile(src: str, obj: str, extra_flags, verbose: bool) -> None:
     # hipcc treats .cpp as HIP when -x hip is given; the host files include hip_runtime.h
-    cmd += ["-x", "hip"] + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+    cmd = [HIPCC] + FLAGS + list(extra_flags) + ["-x", "hip", "-c", src, "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         sys.stderr.write(res.stdout + res.stderr)
-        raise RuntimeError("hipcc failed building libdft3d.so")
+        raise RuntimeError(f"hipcc failed compiling {os.path.basename(src)}")
     if verbose and res.stderr:
-        sys.stderr.write(res.stderr)
+        sys.stderr.write("\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l) + "\n")
+
+
+def build(verbose: bool = False, extra_flags=(), incremental: bool = False) -> str:
+    """Compile every source (one object each, in parallel) and link libdft3d.so.  Recompiles
+    everything unless incremental is set, in which case only objects older than their source or a
+    header are rebuilt."""
+    os.makedirs(OBJDIR, exist_ok=True)
+    newest_header = max(os.path.getmtime(h) for h in HEADERS)
+    jobs = []
+    objs = []
+    for s in SOURCES:
+        src = os.path.join(CSRC, s)
+        obj = os.path.join(OBJDIR, s + ".o")
+        objs.append(obj)
+        fresh = (incremental and not extra_flags and os.path.exists(obj)
+                 and os.path.getmtime(obj) >= max(os.path.getmtime(src), newest_header))
+        if not fresh:
+            jobs.append((src, obj))
+    with ThreadPoolExecutor(max_workers=min(8, max(1, len(jobs)))) as pool:
+        for f in [pool.submit(_compile, src, obj, extra_flags, verbose) for src, obj in jobs]:
+            f.result()
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stdout + res.stderr)
+        raise RuntimeError("hipcc failed linking libdft3d.so")
     return LIB
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    print(build(verbose=True, incremental="--incremental" in sys.argv))

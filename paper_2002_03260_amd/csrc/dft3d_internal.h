@@ -177,4 +177,12 @@ void unit_root_turns(double t, int sign, double* re, double* im);
 
 void set_error(const char* fmt, ...);
 
+// dft3d_exec with the intermediate storage given explicitly instead of taken from the plan.
+dft3d_status exec_with_workspace(dft3d_plan p, const void* in, void* out, int direction, void* stream,
+                                 void* workspace, size_t workspace_bytes, const char* who);
+
+// Device address, on the current device, of the library's static scratch array (resolved once per
+// device); nullptr with the error text set on failure.
+void* noalloc_scratch_for_current_device();
+
 }  // namespace dft3d

@@ -725,6 +725,9 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
         fft_z_supported((int)p->A[2], (int)p->B[2]) && fft_sr_supported((int)p->A[1], (int)p->B[1], n[2]) &&
         fft_sr_supported((int)p->A[0], (int)p->B[0], n[1] * n[2]))
         p->ws_pitch = n[2] + 16;
+    // set-up for dft3d_exec_noalloc: look up this GPU's copy of the static scratch array now, so that
+    // the exec call itself never has to (a failure here is reported by that call, not by this one)
+    (void)noalloc_scratch_for_current_device();
     *plan = p;
     return DFT3D_OK;
 }
@@ -844,6 +847,7 @@ static dft3d_status plan_create_points_impl(dft3d_plan* plan, int64_t nx, int64_
     }
     if (s != DFT3D_OK) return s;      // (the guard frees the plan)
     guard.p = nullptr;
+    (void)noalloc_scratch_for_current_device();
     *plan = p;
     return DFT3D_OK;
 }
@@ -1035,12 +1039,19 @@ dft3d_status dft3d_device_copy(const void* in, void* out, size_t bytes, int vari
     return hip_status(launch_copy(in, out, bytes, variant, (hipStream_t)stream), "device_copy");
 }
 
-dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, void* stream)
+}  // extern "C"
+
+namespace dft3d {
+
+// The whole transform with the workspace given explicitly (dft3d_exec passes the plan's own; the
+// entry point for callers that cannot allocate passes the library's static scratch array).
+dft3d_status exec_with_workspace(dft3d_plan p, const void* in, void* out, int direction, void* stream,
+                                 void* workspace, size_t workspace_bytes, const char* who)
 {
-    dft3d_status s = check_buffers(p, in, out, "exec");
+    dft3d_status s = check_buffers(p, in, out, who);
     if (s != DFT3D_OK) return s;
-    if (!valid_direction(direction)) { set_error("exec: bad direction"); return DFT3D_ERR_INVALID_ARG; }
-    s = require_uniform_for_backward(p, direction, "exec");
+    if (!valid_direction(direction)) { set_error("%s: bad direction", who); return DFT3D_ERR_INVALID_ARG; }
+    s = require_uniform_for_backward(p, direction, who);
     if (s != DFT3D_OK) return s;
 
     if (single_launch(p)) {
@@ -1054,29 +1065,29 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
             (void)hipEventRecord(p->prof_events[(size_t)slot * DFT3D_MAX_PASSES * 2 + 1], sst);
             p->prof_npass[(size_t)slot] = 1;
         }
-        return hip_status(se, "exec");
+        return hip_status(se, who);
     }
 
     if (p->points) {
         // in -> W1 (mode z) -> W2 (mode y) -> out (mode x); the two intermediates live in the workspace
         const size_t need = dft3d_plan_workspace_bytes(p);
-        if (!p->workspace || p->workspace_bytes < need) {
-            set_error("exec: a workspace of %zu bytes must be set first", need);
+        if (!workspace || workspace_bytes < need) {
+            set_error("%s: a workspace of %zu bytes must be set first", who, need);
             return DFT3D_ERR_INVALID_ARG;
         }
-        const uintptr_t w = (uintptr_t)p->workspace, a = (uintptr_t)in, b = (uintptr_t)out;
+        const uintptr_t w = (uintptr_t)workspace, a = (uintptr_t)in, b = (uintptr_t)out;
         const uintptr_t abytes = (uintptr_t)p->elements() * 8, bbytes = (uintptr_t)p->out_elements() * 8;
         if ((w < a + abytes && a < w + need) || (w < b + bbytes && b < w + need)) {
-            set_error("exec: the workspace overlaps in or out");
+            set_error("%s: the workspace overlaps in or out", who);
             return DFT3D_ERR_INVALID_ARG;
         }
-        float2* w1 = (float2*)p->workspace;
+        float2* w1 = (float2*)workspace;
         float2* w2 = w1 + p->stage_out_elements(2);
         hipStream_t pst = (hipStream_t)stream;
         hipError_t pe = run_mode(p, 2, (const float2*)in, w1, 0, 1.0f, pst);
         if (pe == hipSuccess) pe = run_mode(p, 1, w1, w2, 0, 1.0f, pst);
         if (pe == hipSuccess) pe = run_mode(p, 0, w2, (float2*)out, 0, 1.0f, pst);
-        return hip_status(pe, "exec");
+        return hip_status(pe, who);
     }
 
     const bool clobber = (p->flags & DFT3D_FLAG_CLOBBER_INPUT) != 0;
@@ -1085,17 +1096,17 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
         other = (float2*)const_cast<void*>(in);
     } else {
         const size_t need = dft3d_plan_workspace_bytes(p);
-        if (!p->workspace || p->workspace_bytes < need) {
-            set_error("exec: a workspace of %zu bytes must be set first", need);
+        if (!workspace || workspace_bytes < need) {
+            set_error("%s: a workspace of %zu bytes must be set first", who, need);
             return DFT3D_ERR_INVALID_ARG;
         }
-        const uintptr_t w = (uintptr_t)p->workspace, bytes = (uintptr_t)need;
+        const uintptr_t w = (uintptr_t)workspace, bytes = (uintptr_t)need;
         const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
         if ((w < a + bytes && a < w + bytes) || (w < b + bytes && b < w + bytes)) {
-            set_error("exec: the workspace overlaps in or out");
+            set_error("%s: the workspace overlaps in or out", who);
             return DFT3D_ERR_INVALID_ARG;
         }
-        other = (float2*)p->workspace;
+        other = (float2*)workspace;
     }
 
     hipStream_t st = (hipStream_t)stream;
@@ -1145,7 +1156,7 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
         }
         npass = count_passes();
         if (npass % 2 == 0) {
-            set_error("exec: CLOBBER_INPUT cannot be combined with this pass structure");
+            set_error("%s: CLOBBER_INPUT cannot be combined with this pass structure", who);
             return DFT3D_ERR_UNSUPPORTED;
         }
     }
@@ -1212,7 +1223,17 @@ dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, 
             advance();
         }
     }
-    return hip_status(e, "exec");
+    return hip_status(e, who);
+}
+
+}  // namespace dft3d
+
+extern "C" {
+
+dft3d_status dft3d_exec(dft3d_plan p, const void* in, void* out, int direction, void* stream)
+{
+    return exec_with_workspace(p, in, out, direction, stream, p ? p->workspace : nullptr,
+                               p ? p->workspace_bytes : 0, "exec");
 }
 
 }  // extern "C"
