@@ -311,11 +311,10 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
             roofline.update({"kernel": "k_contract_f64 (strided mode contraction, fp64 MFMA)",
                              "peak": PEAK_MFMA_F64_TFLOPS})
         elif opts.bf16x3:
-            # each real fp32 product becomes six bf16 products (level pairs of total order <= 2):
-            # priced in bf16 flops against the bf16 peak
-            flops = 6.0 * (6.0 if opts.three_m else 8.0) * n_dom * E
-            roofline.update({"kernel": "k_contract_bf16x3%s (strided mode contraction, bf16 MFMA, 6 level products)"
-                                       % ("m" if opts.three_m else ""),
+            # each real fp32 product becomes six bf16 products (level pairs of total order <= 2) and the
+            # bf16 kernel takes three real products per complex one: priced in bf16 flops against the bf16 peak
+            flops = 6.0 * 6.0 * n_dom * E
+            roofline.update({"kernel": "k_contract_bf16x3 (strided mode contraction, bf16 MFMA, 3 real x 6 level products)",
                              "achieved": flops / (dom_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_BF16_TFLOPS,
                              "flop_per_launch": flops,
                              "fp32_equivalent_tflops": 8.0 * n_dom * E / (dom_ms * 1e-3) / 1e12})
@@ -417,7 +416,7 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
             "clock_settle_s": settle_s,
             "launch": "hip graph replay" if opts.graph else "eager",
             "formulation": "FFT" if form == dft.FFT else "KDFT",
-            "complex_scheme": "3M" if (opts.three_m and form == dft.KDFT) else "4M",
+            "complex_scheme": "3M" if ((opts.three_m or opts.bf16x3) and form == dft.KDFT) else "4M",
             "arithmetic": "fp64 MFMA" if c128 else
                           "bf16x3 split on bf16 MFMA, fp32 accumulate" if (opts.bf16x3 and form == dft.KDFT)
                           else "fp32 MFMA",

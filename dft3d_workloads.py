@@ -94,17 +94,22 @@ def make_coords(w: Workload):
     return tuple(np.sort(rng.random(n)) for n in w.shape)
 
 
-def make_input_device(w: Workload, device="cuda"):
-    """Input generated on the device plane by plane from a seeded torch generator.
+def make_input_device(w: Workload, device="cuda", out=None):
+    """Input generated on the device plane by plane from a seeded torch generator (into the tensor
+    ``out`` when one is given: the same values, no new allocation).
 
     Used for tensors the host cannot hold; whoever needs the values on the host reads them
     back from the device, so the generator need not be reproducible elsewhere."""
     import torch
 
+    n1, n2, n3 = w.shape
+    if out is not None:
+        if tuple(out.shape) != (n1, n2, n3) or out.dtype != torch.complex64 or not out.is_contiguous():
+            raise ValueError("out must be a contiguous complex64 tensor of the workload's shape")
+        device = out.device
     g = torch.Generator(device=device)
     g.manual_seed(w.seed)
-    n1, n2, n3 = w.shape
-    x = torch.empty((n1, n2, n3), dtype=torch.complex64, device=device)
+    x = out if out is not None else torch.empty((n1, n2, n3), dtype=torch.complex64, device=device)
     xr = torch.view_as_real(x)
     chunk = max(1, (1 << 27) // (n2 * n3))
     for a0 in range(0, n1, chunk):

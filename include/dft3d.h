@@ -57,10 +57,11 @@ typedef enum { DFT3D_FORWARD = -1, DFT3D_BACKWARD = 1 } dft3d_direction;
                                        kernels instead of fusing them into the contractions */
 #define DFT3D_FLAG_BF16X3 8u        /* KDFT: float32 accuracy on the bf16 matrix cores -- every fp32
                                        number is decomposed into three bf16 numbers and six cross
-                                       products are accumulated in fp32 (Section II-A of the paper);
+                                       products are accumulated in fp32 (Section II-A of the paper),
+                                       with three real products per complex product;
                                        used for modes whose shape is a whole number of 128x128 tiles,
-                                       other modes fall back to the fp32 kernels.  With DFT3D_FLAG_3M
-                                       the bf16 kernels use three real products as well */
+                                       other modes fall back to the fp32 kernels (which take three
+                                       real products only with DFT3D_FLAG_3M) */
 #define DFT3D_FLAG_COMPLEX128 16u   /* tensors are complex128 (interleaved doubles), matrices and twiddles are
                                        kept in fp64 and the contractions run on the fp64 matrix cores (the
                                        float64 precision the paper leaves as future work, Section VI).
@@ -95,9 +96,11 @@ typedef enum { DFT3D_FORWARD = -1, DFT3D_BACKWARD = 1 } dft3d_direction;
  *             Default: A = 2^floor(log2(N)/2) for powers of two, else the divisor pair closest
  *             to sqrt(N) with A <= B.  (512 -> 16*32, 2048 -> 32*64.)
  *   flags     DFT3D_FLAG_* bits
- * Errors: INVALID_ARG (NULL plan pointer, size < 1, bad split, unknown formulation or flag),
- * UNSUPPORTED (FFT with coordinates, ADJOINT on an FFT plan, COMPLEX128 together with 3M / BF16X3 /
- * UNFUSED),
+ * Errors: INVALID_ARG (NULL plan pointer, size < 1 or > 2^24, bad split, unknown formulation or flag,
+ * a coordinate that is not finite),
+ * UNSUPPORTED (FFT with coordinates, ADJOINT / 3M / BF16X3 on an FFT plan, COMPLEX128 together with
+ * 3M / BF16X3 / UNFUSED, ny*nz or nx*ny of 2^31 or more: the kernels index the extents inside and
+ * outside an axis with 32 bits),
  * ALLOC / HIP (device allocation or copy failed).
  */
 dft3d_status dft3d_plan_create(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
@@ -120,7 +123,8 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
  * exec needs a workspace of dft3d_plan_workspace_bytes = 8*(nx*ny*kz + nx*ky*kz) bytes (the two
  * intermediates; ADJOINT: 8*(kx*ky*nz + kx*ny*nz)).  dft3d_mode_contract on such a plan reads a tensor whose axes after `axis`
  * already have their output length and writes one whose `axis` has length k (order z, y, x).
- * Errors: INVALID_ARG (sizes, a zero / non-finite point, an entry that overflows fp32).
+ * Errors: INVALID_ARG (sizes, a zero / non-finite point, an entry that overflows fp32), UNSUPPORTED
+ * (ky*kz or nx*ny of 2^31 or more; with ADJOINT also ny*nz and kx*ky).
  */
 dft3d_status dft3d_plan_create_points(dft3d_plan* plan, int64_t nx, int64_t ny, int64_t nz,
                                       int64_t kx, int64_t ky, int64_t kz, const double* zx,

@@ -10,14 +10,25 @@
 // all accumulated in the fp32 accumulators of the MFMA.  The matrix is split once at plan time
 // (from its fp64 entries); the data tile is split while it is staged into LDS.
 //
+// The complex product takes three real products, each accumulated on its own:
+//     P1 = sum Vr*Xr,  P2 = sum Vi*Xi,  P3 = sum (Vr+Vi)*(Xr+Xi);   Re = P1 - P2,  Im = P3 - P1 - P2.
+// This is not only 25 % less matrix work than four products.  The 16-term adder inside the bf16 MFMA
+// aligns its addends to the largest one and cuts what falls below about 2^-31 of it towards minus
+// infinity (measured: 2^24 + 1 + 2^-8 comes back as 2^24, 2^24 + 2 + 1 - 2^-8 as 2^24 + 2), so the many
+// small level products of the split give every accumulator a small negative bias that does not
+// depend on the data's signs.  A sum accumulated in one register (Re = sum Vr*Xr + (-Vi)*Xi) keeps that
+// bias, and the next mode's all-ones matrix row (output index 0) adds it up coherently over the whole
+// axis: measured 7e-5 relative at 8192 x 8192, against 2e-6 everywhere else.  In the differences
+// P1 - P2 and P3 - (P1 + P2) the biases of the accumulators cancel (P3's operands are twice as large as
+// those of P1 and P2, and so is its bias); a four-product kernel was built first and removed for this.
+//
 // Kernel shape.  One kernel serves both contraction types:  out[row, col] = sum_n R[row,n] C[col,n]
 //   strided modes   : R = matrix (rows = k), C = data (cols = the contiguous index i)
 //   contiguous mode : R = data (rows = o),   C = matrix (cols = k)
 // Both operands of a 32x32x16 bf16 MFMA hold 8 consecutive n per lane, so the LDS tiles are
-// [plane][row or col][n] with n contiguous: RT and CT, 6 planes each (re, im) x (hi, mid, lo),
-// 128 rows x 16 n per chunk, 48-byte pitch (32 data + 16 pad: 16 consecutive rows hit 16 distinct
-// 16-byte bank groups).  A workgroup is 4 waves (one per SIMD, up to 512 VGPRs each) on a 128x128
-// tile, each wave 64x64 = 2x2 MFMA blocks x (re, im) accumulators; 96 MFMAs per chunk per wave.
+// [plane][row or col][n] with n contiguous: RT and CT, 9 planes each (re, im, re+im) x (hi, mid, lo),
+// 128 rows x 16 n per chunk.  A workgroup is 4 waves (one per SIMD, up to 512 VGPRs each) on a 128x128
+// tile, each wave 64x64 = 2x2 MFMA blocks x three accumulators; 72 MFMAs per chunk per wave.
 // Double-buffered LDS, register-staged prefetch one chunk ahead, one barrier per chunk.
 #include <hip/hip_runtime.h>
 
@@ -38,7 +49,6 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kT = 256;
 constexpr int TM = 128, TN = 128, KC = 16;
-constexpr int kPlanes = 6;                 // (re, im) x (hi, mid, lo); plane = 3*part + level
 
 __device__ __forceinline__ int64_t block_id() { return (int64_t)blockIdx.y * gridDim.x + blockIdx.x; }
 
@@ -81,253 +91,8 @@ __device__ __forceinline__ f32x16 mfma_bf16(u32x4 a, u32x4 b, f32x16 c)
                                                   c, 0, 0, 0);
 }
 
-template <bool STRIDED>
-__global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int tilesK, int64_t tilesOther,
-                                                           int64_t total)
-{
-    // [buffer][plane][row][3 x 16 bytes]: slots 0, 1 hold n = 0..7, 8..15 of the chunk, slot 2 is padding
-    __shared__ u32x4 RT[2][kPlanes][TM][3];
-    __shared__ u32x4 CT[2][kPlanes][TN][3];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wr0 = (wave >> 1) * 64;      // wave tile origin inside the 128 x 128 tile
-    const int wc0 = (wave & 1) * 64;
-    const int l32 = lane & 31;
-    const int kq = lane >> 5;
-
-    int64_t t = block_id();
-    if (t >= total) return;
-    t = remap(t, total);
-    const int kt = (int)(t % tilesK);
-    t /= tilesK;
-    const int k0 = kt * 128;
-
-    const int N = a.M.N;
-    const int64_t I = a.I;
-    // the bf16 planes are stored tile by tile: [k tile of 128][chunk of 16 n][plane][128 k][16 n], so the
-    // 128 x 16 piece of every plane that one chunk needs is 4 KiB of contiguous memory
-    const unsigned short* __restrict__ Vs = a.M.split;
-    const int vchunks = a.M.split_ld / KC;
-
-    // this thread's piece of the matrix tile: row = tid / 2 (k), 8 consecutive n
-    const int vrow = tid >> 1, vhalf = tid & 1;
-    const unsigned short* vsrc = Vs + (int64_t)kt * vchunks * (kPlanes * 2048) + vrow * 16 + 8 * vhalf;
-
-    // this thread's piece of the data tile
-    int64_t tile_o = 0, c0 = 0, o0 = 0;
-    const float2* xsrc;
-    int xrow, xhalf;                       // LDS destination (row or column, which half of the chunk)
-    if (STRIDED) {
-        tile_o = t / tilesOther;
-        c0 = (t % tilesOther) * TN;
-        xrow = tid & 127;                  // column of the tile
-        xhalf = tid >> 7;                  // n = 8*xhalf .. +7, one load per n (stride I)
-        xsrc = a.X + tile_o * (int64_t)N * I + (int64_t)(8 * xhalf) * I + c0 + xrow;
-    } else {
-        o0 = t * TM;
-        xrow = tid >> 1;                   // row o of the tile
-        xhalf = tid & 1;                   // 8 consecutive n, contiguous in memory
-        xsrc = a.X + (o0 + xrow) * (int64_t)N + 8 * xhalf;
-    }
-
-    // Register staging of the global loads: every register is requested again right after the
-    // staging code has consumed it, so a load has almost a whole iteration (~1.5 us of MFMA work)
-    // to arrive.  (Two register sets and a distance of two iterations measured slower.)
-    u32x4 vreg[kPlanes];
-    f32x2 xreg[8];
-    constexpr int kXLoads = STRIDED ? 8 : 4;
-    auto load_v = [&](int n0, int p) {
-        vreg[p] = *reinterpret_cast<const u32x4*>(vsrc + (int64_t)(n0 / KC) * (kPlanes * 2048) + p * 2048);
-    };
-    auto load_x = [&](int n0, int j) {           // j < kXLoads
-        if (STRIDED) {
-            xreg[j] = *reinterpret_cast<const f32x2*>(xsrc + (int64_t)(n0 + j) * I);
-        } else {
-            const f32x4 v = *reinterpret_cast<const f32x4*>(xsrc + n0 + 2 * j);
-            xreg[2 * j] = f32x2{v.x, v.y};
-            xreg[2 * j + 1] = f32x2{v.z, v.w};
-        }
-    };
-    auto gload = [&](int n0) {           // same order as the main loop requests them
-#pragma unroll
-        for (int j = 0; j < kXLoads; ++j) load_x(n0, j);
-#pragma unroll
-        for (int p = 0; p < kPlanes; ++p) load_v(n0, p);
-    };
-
-    // Staging of a chunk into LDS, cut into small steps.  The data values are split into their
-    // three bf16 levels two at a time (pair q = values 2q, 2q+1 of the 8 this thread holds; part 0 =
-    // real, 1 = imaginary); a split takes three steps (one per level).
-    const unsigned vflip = a.conj ? 0x80008000u : 0u;      // conjugate the matrix: flip the sign of Im
-    u32x4 lv[2][3];                 // [part][level], dword q = pair q
-    float res0[2], res1[2];         // residuals carried between the steps of one split, per part
-    auto split_step = [&](int part, int q, int step) {
-        if (step == 0) {
-            const float x0 = part ? xreg[2 * q].y : xreg[2 * q].x;
-            const float x1 = part ? xreg[2 * q + 1].y : xreg[2 * q + 1].x;
-            const unsigned p0 = pack_bf16(x0, x1);
-            res0[part] = x0 - lo_as_float(p0);      // exact
-            res1[part] = x1 - hi_as_float(p0);
-            lv[part][0][q] = p0;
-        } else if (step == 1) {
-            const unsigned p1 = pack_bf16(res0[part], res1[part]);
-            res0[part] -= lo_as_float(p1);          // exact
-            res1[part] -= hi_as_float(p1);
-            lv[part][1][q] = p1;
-        } else {
-            lv[part][2][q] = pack_bf16(res0[part], res1[part]);
-        }
-    };
-    auto store_x = [&](int buf, int part, int level) {
-        u32x4 (*Xt)[TM][3] = STRIDED ? CT[buf] : RT[buf];
-        Xt[3 * part + level][xrow][xhalf] = lv[part][level];
-    };
-    auto store_v = [&](int buf, int p) {
-        u32x4 (*Vt)[TM][3] = STRIDED ? RT[buf] : CT[buf];
-        u32x4 v = vreg[p];
-        if (p >= 3) v ^= vflip;
-        Vt[p][vrow][vhalf] = v;
-    };
-    auto lstore = [&](int buf) {
-#pragma unroll
-        for (int part = 0; part < 2; ++part) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int step = 0; step < 3; ++step) split_step(part, q, step);
-#pragma unroll
-            for (int level = 0; level < 3; ++level) store_x(buf, part, level);
-        }
-#pragma unroll
-        for (int p = 0; p < kPlanes; ++p) store_v(buf, p);
-    };
-
-    f32x16 accr[2][2], acci[2][2];
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                accr[rb][cb][v] = 0.f;
-                acci[rb][cb][v] = 0.f;
-            }
-
-    const int nchunks = N / KC;
-    auto chunk_n0 = [&](int j) { return (j < nchunks ? j : nchunks - 1) * KC; };     // clamped: tail re-reads the last chunk
-    gload(0);
-    lstore(0);
-    gload(chunk_n0(1));
-    __syncthreads();
-
-    // Level pairs of the six cross products.  With R = Rr + i Ri and C = Cr + i Ci,
-    // Im = Ri*Cr + Rr*Ci and Re = Rr*Cr - Ri*Ci: four phases of 24 MFMAs, inside a phase the four
-    // blocks of the wave tile take turns so neighbours never share an accumulator.
-    //
-    // A wave issues in order and only one MFMA (32 cycles) can be in flight ahead of it, so the
-    // wave's other work of the iteration -- converting and storing chunk c+1, requesting chunk
-    // c+2, negating Ri -- is cut into steps of a few instructions and at most one step is placed
-    // in front of each of the 96 MFMAs, where it issues in the shadow of the previous one.
-    constexpr int PL[6] = {1, 2, 0, 1, 0, 0};
-    constexpr int QL[6] = {1, 0, 2, 0, 1, 0};
-    // The steps in order: per pair 3 + 3 split steps and the pair's loads; 6 negations of Ri
-    // operands; 6 stores of the data levels; 6 x (store a matrix plane, request it again).  They are
-    // spread evenly over the 96 MFMA slots.
-    constexpr int kPerPair = 6 + kXLoads / 4;
-    constexpr int kNegAt = 4 * kPerPair;
-    constexpr int kXStoreAt = kNegAt + 6;
-    constexpr int kVAt = kXStoreAt + 6;
-    constexpr int kSteps = kVAt + 12;
-    static_assert(kSteps <= 96, "one step per MFMA at most");
-    // Ri is negated between its positive uses (phase 0, slots < 24) and its negative ones (>= 72)
-    static_assert((kNegAt * 96) / kSteps >= 24 && ((kNegAt + 5) * 96) / kSteps < 72, "negation slots");
-    for (int c = 0; c < nchunks; ++c) {
-        const int buf = c & 1;
-        const int n2 = chunk_n0(c + 2);
-
-        // MFMAs of chunk c from LDS buffer c % 2; chunk c+1 goes to the other buffer (after the last
-        // chunk: a harmless re-store, nobody reads it)
-        u32x4 Rr[2][3], Ri[2][3], Cr[2][3], Ci[2][3];
-#pragma unroll
-        for (int j = 0; j < 3; ++j) {
-            const int lr = PL[j], lc = QL[j];        // (1,1), (2,0), (0,2): each level once, in order of first use
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                Ri[b][lr] = RT[buf][3 + lr][wr0 + b * 32 + l32][kq];
-                Cr[b][lc] = CT[buf][lc][wc0 + b * 32 + l32][kq];
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < 3; ++j) {
-            const int lr = PL[j], lc = QL[j];
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                Rr[b][lr] = RT[buf][lr][wr0 + b * 32 + l32][kq];
-                Ci[b][lc] = CT[buf][3 + lc][wc0 + b * 32 + l32][kq];
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-
-        static_for<0, 96>([&](auto slot) {
-            constexpr int s = decltype(slot)::value;
-            // ---- at most one step of side work: step i sits in slot i * 96 / kSteps
-            constexpr int step = (s * kSteps + 95) / 96;
-            if constexpr (step < kSteps && (step * 96) / kSteps == s) {
-                if constexpr (step < kNegAt) {
-                    constexpr int q = step / kPerPair, w = step % kPerPair;
-                    if constexpr (w < 6) split_step(w / 3, q, w % 3);
-                    else if constexpr (STRIDED) load_x(n2, 2 * q + (w - 6));
-                    else load_x(n2, q);
-                } else if constexpr (step < kXStoreAt) {
-                    constexpr int w = step - kNegAt;
-                    Ri[w & 1][w >> 1] ^= 0x80008000u;
-                } else if constexpr (step < kVAt) {
-                    constexpr int w = step - kXStoreAt;
-                    store_x(buf ^ 1, w / 3, w % 3);
-                } else {
-                    constexpr int w = step - kVAt;
-                    if constexpr ((w & 1) == 0) store_v(buf ^ 1, w >> 1);
-                    else load_v(n2, w >> 1);
-                }
-            }
-            // ---- one MFMA
-            constexpr int phase = s / 24, pq = (s % 24) / 4, rb = (s >> 1) & 1, cb = s & 1;
-            constexpr int lr = PL[pq], lc = QL[pq];
-            if constexpr (phase == 0) acci[rb][cb] = mfma_bf16(Ri[rb][lr], Cr[cb][lc], acci[rb][cb]);
-            else if constexpr (phase == 1) acci[rb][cb] = mfma_bf16(Rr[rb][lr], Ci[cb][lc], acci[rb][cb]);
-            else if constexpr (phase == 2) accr[rb][cb] = mfma_bf16(Rr[rb][lr], Cr[cb][lc], accr[rb][cb]);
-            else accr[rb][cb] = mfma_bf16(Ri[rb][lr], Ci[cb][lc], accr[rb][cb]);      // Ri negated
-            __builtin_amdgcn_sched_barrier(0);
-        });
-        __syncthreads();
-    }
-
-    // epilogue: accumulator register v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-        const int col = wc0 + cb * 32 + l32;
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = wr0 + rb * 32 + 8 * (v / 4) + 4 * kq + (v % 4);
-                const f32x2 y = f32x2{accr[rb][cb][v] * a.scale, acci[rb][cb][v] * a.scale};
-                if (STRIDED) {
-                    float2* Yo = a.Y + y_offset(a, tile_o);
-                    __builtin_nontemporal_store(y, reinterpret_cast<f32x2*>(Yo + (int64_t)(k0 + row) * a.sYk + c0 + col));
-                } else {
-                    __builtin_nontemporal_store(y, reinterpret_cast<f32x2*>(a.Y + y_offset(a, o0 + row) + (int64_t)(k0 + col) * a.sYk));
-                }
-            }
-        }
-    }
-}
-
-// Three-product variant (DFT3D_FLAG_BF16X3 together with DFT3D_FLAG_3M).  With P1 = sum Vr*Xr,
-// P2 = sum Vi*Xi and P3 = sum (Vr+Vi)*(Xr+Xi):  Re = P1 - P2,  Im = P3 - P1 - P2, each real product
-// again as six bf16 level products: 18 instead of 24 MFMAs per complex block and chunk.  The sums
+// With P1 = sum Vr*Xr, P2 = sum Vi*Xi and P3 = sum (Vr+Vi)*(Xr+Xi):  Re = P1 - P2,  Im = P3 - P1 - P2,
+// each real product as six bf16 level products: 18 MFMAs per complex block and chunk.  The sums
 // Vr+Vi (at plan time, from fp64) and Xr+Xi (in fp32 while staging) are split into their own three
 // levels, so each operand has nine planes: (re, im, sum) x (hi, mid, lo), plane = 3*part + level.
 // LDS rows are 32 bytes (two 16-byte slots) without padding; the slot is XOR-ed with bits 2 and 3 of
@@ -337,7 +102,7 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int t
 constexpr int kPlanes3 = 9;
 
 template <bool STRIDED>
-__global__ __launch_bounds__(kT, 1) void k_contract_bf16x3m(ContractArgs a, int tilesK, int64_t tilesOther,
+__global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int tilesK, int64_t tilesOther,
                                                             int64_t total)
 {
     // [buffer][plane][row][2 x 16 bytes]: slots hold n = 0..7 and 8..15 of the chunk, swizzled by row
@@ -411,7 +176,9 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3m(ContractArgs a, int 
         for (int p = 0; p < kPlanes3; ++p) load_v(n0, p);
     };
 
-    // Staging in small steps, as in the four-product kernel; part 0 = real, 1 = imaginary, 2 = their sum.
+    // Staging of a chunk into LDS, cut into small steps.  The data values are split into their three
+    // bf16 levels two at a time (pair q = values 2q, 2q+1 of the 8 this thread holds; part 0 = real,
+    // 1 = imaginary, 2 = their sum); a split takes three steps (one per level).
     // Conjugating the matrix flips the sign of Vi and turns Vr+Vi into Vr-Vi, which is not a stored
     // plane: BACKWARD instead conjugates the data and the result (conj(V) x = conj(V conj(x))).
     const float xsign = a.conj ? -1.0f : 1.0f;
@@ -482,6 +249,11 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3m(ContractArgs a, int 
     gload(chunk_n0(1));
     __syncthreads();
 
+    // Level pairs of the six cross products.
+    // A wave issues in order and only one MFMA (32 cycles) can be in flight ahead of it, so the
+    // wave's other work of the iteration -- converting and storing chunk c+1, requesting chunk
+    // c+2 -- is cut into steps of a few instructions and at most one step is placed in front of
+    // each of the 72 MFMAs, where it issues in the shadow of the previous one.
     constexpr int PL[6] = {1, 2, 0, 1, 0, 0};
     constexpr int QL[6] = {1, 0, 2, 0, 1, 0};
     // the steps of the side work in order: per pair 9 split steps (3 parts x 3 levels) and the pair's
@@ -571,7 +343,7 @@ inline dim3 grid_for(int64_t blocks)
 
 bool contract_bf16x3_supported(const ContractArgs& a)
 {
-    if (!a.M.split || a.Tw) return false;
+    if (!a.M.split || a.M.split_planes != kPlanes3 || a.Tw) return false;
     const int K = a.M.K, N = a.M.N;
     if (K % 128 != 0 || N % KC != 0 || N < KC) return false;
     if (a.I == 1) return a.O % TM == 0;
@@ -581,18 +353,6 @@ bool contract_bf16x3_supported(const ContractArgs& a)
 hipError_t launch_contract_bf16x3(const ContractArgs& a, hipStream_t stream)
 {
     const int tk = a.M.K / 128;
-    if (a.three_m && a.M.split_planes == 9) {
-        if (a.I == 1) {
-            const int64_t to = a.O / TM;
-            const int64_t total = (int64_t)tk * to;
-            hipLaunchKernelGGL(k_contract_bf16x3m<false>, grid_for(total), dim3(kT), 0, stream, a, tk, to, total);
-        } else {
-            const int64_t ti = a.I / TN;
-            const int64_t total = (int64_t)tk * ti * a.O;
-            hipLaunchKernelGGL(k_contract_bf16x3m<true>, grid_for(total), dim3(kT), 0, stream, a, tk, ti, total);
-        }
-        return hipGetLastError();
-    }
     if (a.I == 1) {
         // contiguous mode: rows = o, columns = k; the k-tile index runs fastest
         const int64_t to = a.O / TM;

@@ -72,6 +72,12 @@ extern "C" dft3d_status dft3d_generate_matrix(int64_t n, const double* coords, i
         set_error("dft3d_generate_matrix: invalid argument");
         return DFT3D_ERR_INVALID_ARG;
     }
+    if (coords)
+        for (int64_t j = 0; j < n; ++j)
+            if (!std::isfinite(coords[j])) {
+                set_error("dft3d_generate_matrix: coordinate %lld is not finite", (long long)j);
+                return DFT3D_ERR_INVALID_ARG;
+            }
     for (int64_t k = 0; k < n; ++k) {
         for (int64_t j = 0; j < n; ++j) {
             double cr, ci;

@@ -25,14 +25,14 @@ struct DeviceMatrix {
     int N = 0;     // contracted length (columns of M)
     int ld = 0;    // padded K
     int rows = 0;  // padded N
-    // Optional bf16 decomposition of the same matrix for the bf16-split contraction: six planes
-    // (Re hi, mid, lo, Im hi, mid, lo), zero padded to split_rows x split_ld, stored tile by tile as
+    // Optional bf16 decomposition of the same matrix for the bf16-split contraction: nine planes
+    // (Re, Im, Re + Im) x (hi, mid, lo), zero padded to split_rows x split_ld, stored tile by tile as
     // [k tile of 128][chunk of 16 n][plane][128 k][16 n] (n contiguous: a bf16 MFMA operand lane
     // holds 8 consecutive n; the piece one kernel iteration needs is contiguous).
     unsigned short* split = nullptr;
     int split_ld = 0;     // padded N (multiple of 16)
     int split_rows = 0;   // padded K (multiple of 128)
-    int split_planes = 0; // 6, or 9 with the planes of Re + Im appended (three-product scheme)
+    int split_planes = 0; // 9: three levels each of Re, Im and Re + Im (three-product scheme)
     // Optional fp64 copy for complex128 plans: planes re, im (rows64 * ld64 doubles apart), transposed
     // like the fp32 planes, plane[n * ld64 + k].
     double* f64 = nullptr;
@@ -68,8 +68,8 @@ hipError_t launch_contract(const ContractArgs& a, hipStream_t stream);
 bool contract_sr_supported(const ContractArgs& a);
 hipError_t launch_contract_sr(const ContractArgs& a, hipStream_t stream);
 
-// bf16-split variant (three bf16 levels per fp32 number, six cross products on bf16 MFMA);
-// only whole 128 x 128 tiles, no fused twiddle.
+// bf16-split variant (three bf16 levels per fp32 number, six cross products on bf16 MFMA, three
+// real products per complex product); only whole 128 x 128 tiles, no fused twiddle.
 bool contract_bf16x3_supported(const ContractArgs& a);
 hipError_t launch_contract_bf16x3(const ContractArgs& a, hipStream_t stream);
 

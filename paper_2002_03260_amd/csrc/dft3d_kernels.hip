@@ -54,26 +54,6 @@ inline dim3 grid_for(int64_t blocks)
     return dim3((unsigned)kMaxX, (unsigned)((blocks + kMaxX - 1) / kMaxX));
 }
 
-#ifdef DFT3D_TRACE
-// Diagnostic build only (never compiled into the shipped library): per-workgroup time stamps.
-__device__ unsigned long long* g_trace = nullptr;
-__device__ __forceinline__ void trace_mark(int slot)
-{
-    if (threadIdx.x == 0 && g_trace) {
-        const int64_t b = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
-        g_trace[b * 8 + slot] = wall_clock64();
-        if (slot == 1 || slot == 2) g_trace[b * 8 + 3 + slot] = clock64();     // shader-clock count
-        if (slot == 0) {
-            g_trace[b * 8 + 6] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));    // HW_ID
-            g_trace[b * 8 + 7] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11));   // XCC_ID
-        }
-    }
-}
-#define TRACE_MARK(s) trace_mark(s)
-#else
-#define TRACE_MARK(s)
-#endif
-
 __device__ __forceinline__ int64_t out_offset(const ContractArgs& a, int64_t o)
 {
     if (a.Olo == 1) return o * a.sYohi;      // (uniform branch: every KDFT mode; saves two 64-bit divisions)
@@ -174,7 +154,6 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     int64_t t = linear_block_id();
     if (t >= total) return;
     t = xcd_remap(t, total);
-    TRACE_MARK(0);
     const int kt = (int)(t % tilesK);
     t /= tilesK;
     const int k0 = kt * TM;
@@ -279,8 +258,6 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
     lstore(0);
     if (NB == 2 && nchunks > 1) gload(KC);
     __syncthreads();
-    TRACE_MARK(1);
-
     for (int c = 0; c < nchunks; ++c) {
         const int buf = (NB == 2) ? (c & 1) : 0;
         const bool more = (c + 1) < nchunks;
@@ -389,8 +366,6 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
         }
         __syncthreads();
     }
-
-    TRACE_MARK(2);
     // epilogue: scale, optional twiddle, store.  Accumulator register v of block (bm, bn) is MFMA row
     // 4 * lq + v, column l16: tile row BM * (4 * lq + v) + bm, and the blocks 2q, 2q+1 hold two
     // neighbouring columns, stored together (a quarter-wave writes 256 contiguous bytes per row).
@@ -458,7 +433,6 @@ __global__ __launch_bounds__(kThreads, MINW) void k_contract_s(ContractArgs a, i
             }
         }
     }
-    TRACE_MARK(3);
 }
 
 // Contiguous-mode contraction (I == 1): out[o, k] = sum_n in[o, n] M[k, n].
@@ -1053,16 +1027,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
         for (int sl = 0; sl < NSLOT; ++sl) gload_slice(tile, sl);
     };
 
-#ifdef DFT3D_TRACE
-    unsigned long long tacc[7] = {0, 0, 0, 0, 0, 0, 0}, tprev = wall_clock64();
-#define TRACE_ACC(i) { unsigned long long tn = wall_clock64(); tacc[i] += tn - tprev; tprev = tn; }
-#else
-#define TRACE_ACC(i)
-#endif
     int64_t tile = linear_block_id();
     if (tile < ntiles) gload(tile);
     for (; tile < ntiles; tile += nwg) {
-        TRACE_ACC(6);
         {
             // rows lrow + j*RPP: the swizzle bit ((row / B) & 1) is a per-thread constant when RPP
             // is a multiple of 2B, and known at compile time per j when RPP divides B
@@ -1076,12 +1043,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
                 *reinterpret_cast<f32x4*>(&xs[addr]) = xreg[j];
             }
         }
-        TRACE_ACC(0);
         __syncthreads();
-        TRACE_ACC(1);
         const bool more_tiles = tile + nwg < ntiles;
-        TRACE_ACC(2);
-
         // stage 1, in place; U1 beta groups in flight per wave
         constexpr int BMA = A / 16;
 #pragma unroll
@@ -1143,10 +1106,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
                         *reinterpret_cast<f32x2*>(&xs[wr]) = f32x2{zr, zi};
                     }
         }
-        TRACE_ACC(3);
         __syncthreads();
-        TRACE_ACC(4);
-
         // stage 2: U2 k_a groups at a time per wave (they share the FB operands), all k_b blocks in flight
         constexpr int BMB = B / 16;
         float2* dst = Y + tile_base(tile) + l16;
@@ -1203,15 +1163,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restric
                     }
             }
         }
-        TRACE_ACC(5);
         __syncthreads();
     }
-#ifdef DFT3D_TRACE
-    if (g_trace && (threadIdx.x & 63) == 0) {
-        const int64_t b = linear_block_id() * NW + (threadIdx.x >> 6);
-        for (int i = 0; i < 7; ++i) g_trace[b * 8 + i] = tacc[i];
-    }
-#endif
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1508,13 +1461,6 @@ hipError_t launch_fft_s(const float2* in, float2* out, int64_t O, int64_t I, int
     return hipErrorInvalidValue;
 }
 
-#ifdef DFT3D_TRACE
-extern "C" int dft3d_debug_set_trace(void* dev_ptr)
-{
-    unsigned long long* p = (unsigned long long*)dev_ptr;
-    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &p, sizeof(p));
-}
-#endif
 
 hipError_t launch_copy(const void* in, void* out, size_t bytes, int variant, hipStream_t stream)
 {

@@ -55,13 +55,14 @@ double from_bf16(unsigned short h)
 
 // Build and upload the three-level bf16 decomposition of a K x N complex matrix given as fp64
 // row-major planes: v = v1 + v2 + v3 with vj = bf16(v - v1 - .. - v(j-1)).
-// With with_sum the planes of Re + Im (formed in fp64) follow, for the three-product scheme.
+// The planes of Re + Im (formed in fp64) follow those of Re and Im: the bf16 kernel uses three real
+// products per complex product.
 dft3d_status upload_split(const std::vector<double>& re, const std::vector<double>& im, int K, int N,
-                          bool with_sum, DeviceMatrix* m)
+                          DeviceMatrix* m)
 {
     const int ld = round_up(N, 16), rows = round_up(K, 128);
     const size_t plane = (size_t)ld * rows;
-    const int parts = with_sum ? 3 : 2;
+    const int parts = 3;
     std::vector<unsigned short> host((size_t)(3 * parts) * plane, 0);
     for (int part = 0; part < parts; ++part) {
         for (int k = 0; k < K; ++k)
@@ -177,7 +178,7 @@ void conjugate_transpose(std::vector<T>& re, std::vector<T>& im, int64_t K, int6
 }
 
 dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out, bool with_split = false,
-                              bool with_f64 = false, bool split_sum = false, bool adjoint = false)
+                              bool with_f64 = false, bool adjoint = false)
 {
     std::vector<float> re((size_t)n * n), im((size_t)n * n);
     dft3d_status s = dft3d_generate_matrix(n, coords, DFT3D_FORWARD, re.data(), im.data());
@@ -193,7 +194,7 @@ dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out
             else unit_root_ratio(k * j, n, DFT3D_FORWARD, &dre[k * n + j], &dim[k * n + j]);
         }
     if (adjoint) conjugate_transpose(dre, dim, n, n);
-    if (with_split) s = upload_split(dre, dim, (int)n, (int)n, split_sum, out);
+    if (with_split) s = upload_split(dre, dim, (int)n, (int)n, out);
     if (s == DFT3D_OK && with_f64) s = upload_f64(dre, dim, (int)n, (int)n, out);
     return s;
 }
@@ -605,6 +606,12 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
         set_error("plan_create: unknown formulation %d", (int)f);
         return DFT3D_ERR_INVALID_ARG;
     }
+    for (int j = 0; j < 3; ++j)
+        for (int64_t i = 0; c[j] && i < n[j]; ++i)
+            if (!std::isfinite(c[j][i])) {
+                set_error("plan_create: coordinate %lld of axis %d is not finite", (long long)i, j);
+                return DFT3D_ERR_INVALID_ARG;
+            }
     if (flags & ~(DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_UNFUSED | DFT3D_FLAG_3M | DFT3D_FLAG_BF16X3 |
                   DFT3D_FLAG_COMPLEX128 | DFT3D_FLAG_ADJOINT)) {
         set_error("plan_create: unknown flag bits 0x%x", flags);
@@ -616,6 +623,10 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
     }
     if ((flags & DFT3D_FLAG_COMPLEX128) && (flags & (DFT3D_FLAG_3M | DFT3D_FLAG_BF16X3 | DFT3D_FLAG_UNFUSED))) {
         set_error("plan_create: COMPLEX128 is not combined with 3M / BF16X3 / UNFUSED");
+        return DFT3D_ERR_UNSUPPORTED;
+    }
+    if (f == DFT3D_FFT && (flags & (DFT3D_FLAG_3M | DFT3D_FLAG_BF16X3))) {
+        set_error("plan_create: 3M and BF16X3 select variants of the KDFT mode contraction; an FFT plan has none");
         return DFT3D_ERR_UNSUPPORTED;
     }
     if (f == DFT3D_FFT && (cx || cy || cz)) {
@@ -647,8 +658,7 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
                 if (!c[j] && !c[i] && n[i] == n[j]) { p->M_owner[j] = i; break; }
             if (p->M_owner[j] == j)
                 s = make_axis_matrix(n[j], c[j], &p->M[j], (flags & DFT3D_FLAG_BF16X3) != 0,
-                                     (flags & DFT3D_FLAG_COMPLEX128) != 0, (flags & DFT3D_FLAG_3M) != 0,
-                                     (flags & DFT3D_FLAG_ADJOINT) != 0);
+                                     (flags & DFT3D_FLAG_COMPLEX128) != 0, (flags & DFT3D_FLAG_ADJOINT) != 0);
             else p->M[j] = p->M[p->M_owner[j]];
         }
     } else {

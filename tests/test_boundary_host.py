@@ -145,6 +145,36 @@ def test_argument_errors_are_status_codes(lib):
     assert lib.dft3d_status_string(99) == b"DFT3D_ERR_UNKNOWN"
 
 
+def test_plan_arguments_rejected_before_any_device_work(lib):
+    """Non-finite coordinates, contraction variants on an FFT plan and extents the kernels cannot
+    index come back as status codes from checks that run before the first device call."""
+    h = ctypes.c_void_p()
+    for bad in (float("nan"), float("inf"), -float("inf")):
+        c = (ctypes.c_double * 4)(0.0, 0.1, bad, 0.3)
+        st = lib.dft3d_plan_create(ctypes.byref(h), 4, 4, 4, dft.KDFT, None, ctypes.cast(c, ctypes.c_void_p), None)
+        assert lib.dft3d_status_string(st) == b"DFT3D_ERR_INVALID_ARG" and not h
+        assert b"not finite" in lib.dft3d_last_error()
+        re = np.empty((4, 4), np.float32)
+        im = np.empty((4, 4), np.float32)
+        st = lib.dft3d_generate_matrix(4, ctypes.cast(c, ctypes.c_void_p), dft.FORWARD,
+                                       re.ctypes.data_as(ctypes.c_void_p), im.ctypes.data_as(ctypes.c_void_p))
+        assert lib.dft3d_status_string(st) == b"DFT3D_ERR_INVALID_ARG"
+    for fl in (dft.FLAG_3M, dft.FLAG_BF16X3, dft.FLAG_3M | dft.FLAG_BF16X3):
+        st = lib.dft3d_plan_create_ex(ctypes.byref(h), 8, 8, 8, dft.FFT, None, None, None, None, fl)
+        assert lib.dft3d_status_string(st) == b"DFT3D_ERR_UNSUPPORTED" and not h
+    # ny*nz (and nx*ny) are 32-bit quantities inside the kernels
+    st = lib.dft3d_plan_create(ctypes.byref(h), 1, 1 << 16, 1 << 15, dft.KDFT, None, None, None)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_UNSUPPORTED" and not h
+    assert b"2^31" in lib.dft3d_last_error()
+    st = lib.dft3d_plan_create(ctypes.byref(h), 1 << 16, 1 << 15, 1, dft.FFT, None, None, None)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_UNSUPPORTED" and not h
+    st = lib.dft3d_plan_create(ctypes.byref(h), (1 << 24) + 1, 1, 1, dft.FFT, None, None, None)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_INVALID_ARG" and not h
+    # the entry point that allocates nothing validates like exec
+    st = lib.dft3d_exec_noalloc(None, None, None, dft.FORWARD, None)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_INVALID_ARG"
+
+
 def test_a_matrix_too_large_for_the_host_is_a_status_code_not_an_abort(lib):
     """A KDFT axis of 2^24 points needs a 2^48-entry matrix: the failed host allocation must come
     back as DFT3D_ERR_ALLOC (no C++ exception may cross the C boundary)."""

@@ -83,8 +83,8 @@ def test_2d_8192_sampled_outputs(dft):
     x = wl.draw_complex(shape, "normal", 200203260 + 77)
     xd = torch.from_numpy(x).to("cuda")
     outs = {}
-    for form, name in ((dft.KDFT, "kdft"), (dft.FFT, "fft")):
-        with dft.Plan(shape, form) as p:
+    for form, name, flags in ((dft.KDFT, "kdft", 0), (dft.FFT, "fft", 0), (dft.KDFT, "kdft_bf16x3", dft.FLAG_BF16X3)):
+        with dft.Plan(shape, form, flags=flags) as p:
             outs[name] = p.exec(xd)
             torch.cuda.synchronize()
         say(f"  {name} done")
@@ -198,12 +198,26 @@ def test_cfg5_parseval(cfg5):
 
 
 @pytest.mark.timeout(900)
+def _cfg5_want_slabs(cfg5):
+    if not hasattr(cfg5, "want_slabs"):
+        cfg5.k1s = [0, 1, 1337]
+        say(f"  oracle: output slabs k1 = {cfg5.k1s}")
+        cfg5.want_slabs = orc.dft3d_sampled(cfg5.x_host, cfg5.k1s)
+    return cfg5.k1s, cfg5.want_slabs
+
+
+def _cfg5_want_pencils(cfg5):
+    if not hasattr(cfg5, "want_pencils"):
+        cfg5.k2s, cfg5.k3s = [0, 2047, 777], [5, 1024]
+        say(f"  oracle: output pencils k2 = {cfg5.k2s}, k3 = {cfg5.k3s}")
+        cfg5.want_pencils = orc.dft3d_pencils(cfg5.x_host, cfg5.k2s, cfg5.k3s)
+    return cfg5.k2s, cfg5.k3s, cfg5.want_pencils
+
+
 def test_cfg5_sampled_slabs(cfg5):
     import torch
 
-    k1s = [0, 1, 1337]
-    say(f"  oracle: output slabs k1 = {k1s}")
-    want = orc.dft3d_sampled(cfg5.x_host, k1s)
+    k1s, want = _cfg5_want_slabs(cfg5)
     for name, out in (("kdft", cfg5.out_k), ("fft", cfg5.out_f)):
         got = out[k1s].cpu().numpy()
         r = rel_l2(got, want)
@@ -214,9 +228,7 @@ def test_cfg5_sampled_slabs(cfg5):
 
 @pytest.mark.timeout(900)
 def test_cfg5_sampled_pencils(cfg5):
-    k2s, k3s = [0, 2047, 777], [5, 1024]
-    say(f"  oracle: output pencils k2 = {k2s}, k3 = {k3s}")
-    want = orc.dft3d_pencils(cfg5.x_host, k2s, k3s)
+    k2s, k3s, want = _cfg5_want_pencils(cfg5)
     for name, out in (("kdft", cfg5.out_k), ("fft", cfg5.out_f)):
         got = out[:, k2s][:, :, k3s].cpu().numpy()
         r = rel_l2(got, want)
@@ -259,3 +271,40 @@ def test_cfg5_separable_input_closed_form(dft, cfg5):
         del out
         torch.cuda.empty_cache()
         assert r <= TOL
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("variant", ["3M", "BF16X3", "BF16X3+3M"])
+def test_cfg5_kdft_flag_variants_sampled(dft, cfg5, variant):
+    """The KDFT variants whose speed is quoted at 2048^3 (three real products, the bf16 split, both),
+    against the same oracle slabs and pencils as the default path: accumulation over 2048 terms
+    through six of the nine cross products of the split."""
+    import torch
+
+    w = cfg5.w
+    flags = {"3M": dft.FLAG_3M, "BF16X3": dft.FLAG_BF16X3, "BF16X3+3M": dft.FLAG_BF16X3 | dft.FLAG_3M}[variant]
+    k1s, want_slabs = _cfg5_want_slabs(cfg5)
+    k2s, k3s, want_pencils = _cfg5_want_pencils(cfg5)
+    # the stored FFT-formulation output has served its tests (this file runs in order): its memory
+    # takes the regenerated input, which the transform then overwrites (CLOBBER_INPUT)
+    x = wl.make_input_device(w, out=cfg5.out_f)
+    say(f"  KDFT {variant} exec")
+    with dft.Plan(w.shape, dft.KDFT, flags=flags | dft.FLAG_CLOBBER_INPUT) as p:
+        out = torch.empty_like(x)
+        t0 = time.perf_counter()
+        p.exec(x, out)
+        torch.cuda.synchronize()
+        say(f"  took {time.perf_counter() - t0:.2f} s")
+    got = out[k1s].cpu().numpy()
+    r = rel_l2(got, want_slabs)
+    say(f"[parity] cfg5 kdft {variant} slabs: relL2={r:.3e} max|err|={np.max(np.abs(got - want_slabs)):.3e}")
+    assert r <= TOL
+    got = out[:, k2s][:, :, k3s].cpu().numpy()
+    rp = rel_l2(got, want_pencils)
+    say(f"[parity] cfg5 kdft {variant} pencils: relL2={rp:.3e} max|err|={np.max(np.abs(got - want_pencils)):.3e}")
+    assert rp <= TOL
+    rk = _device_rel_l2(out, cfg5.out_k)
+    say(f"[parity] cfg5 kdft {variant} vs default KDFT, every output: relL2={rk:.3e}")
+    assert rk <= 2 * TOL
+    del out
+    torch.cuda.empty_cache()
