@@ -149,6 +149,13 @@ size_t dft3d_plan_workspace_bytes(dft3d_plan plan);
  * keeps ownership and must keep it alive while exec calls are in flight. */
 dft3d_status dft3d_plan_set_workspace(dft3d_plan plan, void* dev, size_t bytes);
 
+/* Which kernel family contracts mode `axis` (0, 1 or 2) of a KDFT plan in dft3d_exec and
+ * dft3d_mode_contract (Eq. 11, one mode product): writes a NUL-terminated name such as
+ * "k_contract_s", "k_contract_c (3M)", "k_contract_bf16x3", "k_contract_sr", "k_contract_f64" or
+ * "k_kdft_small" (the single launch that runs all three modes) into name[len].  Lets a caller see
+ * whether a flag such as DFT3D_FLAG_BF16X3 takes effect for a shape.  Host only, launches nothing. */
+dft3d_status dft3d_plan_mode_kernel(dft3d_plan plan, int axis, char* name, size_t len);
+
 /* First-stage / second-stage lengths chosen for an axis (0, 1 or 2) of an FFT plan. */
 dft3d_status dft3d_plan_get_split(dft3d_plan plan, int axis, int64_t* A, int64_t* B);
 

@@ -101,7 +101,10 @@ __device__ __forceinline__ f32x16 mfma_bf16(u32x4 a, u32x4 b, f32x16 c)
 // Three accumulator sets (192 AGPRs) and nine operand planes per side (144 VGPRs): one wave per SIMD.
 constexpr int kPlanes3 = 9;
 
-template <bool STRIDED>
+// MASKED: any shape.  The matrix planes are zero padded to whole tiles and chunks, so only the data
+// loads (clamped to the tensor, and zero beyond the contracted length) and the stores (skipped outside
+// the output) know about the edges.
+template <bool STRIDED, bool MASKED>
 __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int tilesK, int64_t tilesOther,
                                                             int64_t total)
 {
@@ -156,12 +159,26 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int t
 
     u32x4 vreg[kPlanes3];
     f32x2 xreg[8];
-    constexpr int kXLoads = STRIDED ? 8 : 4;
+    constexpr bool kByElement = STRIDED || MASKED;      // one load per complex number (else two per load)
+    constexpr int kXLoads = kByElement ? 8 : 4;
     auto load_v = [&](int n0, int p) {
         vreg[p] = *reinterpret_cast<const u32x4*>(vsrc + (int64_t)(n0 / KC) * (kPlanes3 * 2048) + p * 2048);
     };
     auto load_x = [&](int n0, int j) {           // j < kXLoads
-        if (STRIDED) {
+        if (MASKED) {
+            const int n = n0 + 8 * xhalf + j;
+            const int nc = n < N ? n : N - 1;
+            const f32x2* src;
+            if (STRIDED) {
+                const int64_t col = c0 + xrow < I ? c0 + xrow : I - 1;
+                src = reinterpret_cast<const f32x2*>(a.X + tile_o * (int64_t)N * I + (int64_t)nc * I + col);
+            } else {
+                const int64_t row = o0 + xrow < a.O ? o0 + xrow : a.O - 1;
+                src = reinterpret_cast<const f32x2*>(a.X + row * (int64_t)N + nc);
+            }
+            const f32x2 v = *src;
+            xreg[j] = n < N ? v : f32x2{0.f, 0.f};
+        } else if (STRIDED) {
             xreg[j] = *reinterpret_cast<const f32x2*>(xsrc + (int64_t)(n0 + j) * I);
         } else {
             const f32x4 v = *reinterpret_cast<const f32x4*>(xsrc + n0 + 2 * j);
@@ -242,7 +259,7 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int t
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[part][rb][cb][v] = 0.f;
 
-    const int nchunks = N / KC;
+    const int nchunks = vchunks;             // = N / KC for whole chunks; the matrix planes are zero beyond N
     auto chunk_n0 = [&](int j) { return (j < nchunks ? j : nchunks - 1) * KC; };     // clamped: tail re-reads the last chunk
     gload(0);
     lstore(0);
@@ -291,7 +308,7 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int t
                 if constexpr (step < kXStoreAt) {
                     constexpr int q = step / kPerPair, w = step % kPerPair;
                     if constexpr (w < 9) split_step(w / 3, q, w % 3);
-                    else if constexpr (STRIDED) load_x(n2, 2 * q + (w - 9));
+                    else if constexpr (kByElement) load_x(n2, 2 * q + (w - 9));
                     else load_x(n2, q);
                 } else if constexpr (step < kVAt) {
                     constexpr int w = step - kXStoreAt;
@@ -321,6 +338,9 @@ __global__ __launch_bounds__(kT, 1) void k_contract_bf16x3(ContractArgs a, int t
                 const int row = wr0 + rb * 32 + 8 * (v / 4) + 4 * kq + (v % 4);
                 const float p1 = acc[0][rb][cb][v], p2 = acc[1][rb][cb][v], p3 = acc[2][rb][cb][v];
                 const f32x2 y = f32x2{(p1 - p2) * a.scale, (p3 - p1 - p2) * (a.scale * xsign)};
+                if (MASKED) {
+                    if (STRIDED ? (k0 + row >= a.M.K || c0 + col >= I) : (o0 + row >= a.O || k0 + col >= a.M.K)) continue;
+                }
                 if (STRIDED) {
                     float2* Yo = a.Y + y_offset(a, tile_o);
                     __builtin_nontemporal_store(y, reinterpret_cast<f32x2*>(Yo + (int64_t)(k0 + row) * a.sYk + c0 + col));
@@ -344,24 +364,32 @@ inline dim3 grid_for(int64_t blocks)
 bool contract_bf16x3_supported(const ContractArgs& a)
 {
     if (!a.M.split || a.M.split_planes != kPlanes3 || a.Tw) return false;
-    const int K = a.M.K, N = a.M.N;
-    if (K % 128 != 0 || N % KC != 0 || N < KC) return false;
-    if (a.I == 1) return a.O % TM == 0;
-    return a.I % TN == 0;
+    // 32-bit tile counts inside the kernel
+    const int64_t tk = (a.M.K + 127) / 128;
+    const int64_t other = a.I == 1 ? (a.O + TM - 1) / TM : ((a.I + TN - 1) / TN) * a.O;
+    return a.M.K >= 1 && a.M.N >= 1 && tk * other < (int64_t(1) << 31);
 }
 
 hipError_t launch_contract_bf16x3(const ContractArgs& a, hipStream_t stream)
 {
-    const int tk = a.M.K / 128;
+    const int K = a.M.K, N = a.M.N;
+    const int tk = (K + 127) / 128;
+    const bool whole_kn = K % 128 == 0 && N % KC == 0;
     if (a.I == 1) {
         // contiguous mode: rows = o, columns = k; the k-tile index runs fastest
-        const int64_t to = a.O / TM;
+        const int64_t to = (a.O + TM - 1) / TM;
         const int64_t total = (int64_t)tk * to;
-        hipLaunchKernelGGL(k_contract_bf16x3<false>, grid_for(total), dim3(kT), 0, stream, a, tk, to, total);
+        if (whole_kn && a.O % TM == 0)
+            hipLaunchKernelGGL((k_contract_bf16x3<false, false>), grid_for(total), dim3(kT), 0, stream, a, tk, to, total);
+        else
+            hipLaunchKernelGGL((k_contract_bf16x3<false, true>), grid_for(total), dim3(kT), 0, stream, a, tk, to, total);
     } else {
-        const int64_t ti = a.I / TN;
+        const int64_t ti = (a.I + TN - 1) / TN;
         const int64_t total = (int64_t)tk * ti * a.O;
-        hipLaunchKernelGGL(k_contract_bf16x3<true>, grid_for(total), dim3(kT), 0, stream, a, tk, ti, total);
+        if (whole_kn && a.I % TN == 0)
+            hipLaunchKernelGGL((k_contract_bf16x3<true, false>), grid_for(total), dim3(kT), 0, stream, a, tk, ti, total);
+        else
+            hipLaunchKernelGGL((k_contract_bf16x3<true, true>), grid_for(total), dim3(kT), 0, stream, a, tk, ti, total);
     }
     return hipGetLastError();
 }

@@ -62,6 +62,8 @@ struct ContractArgs {
 };
 
 hipError_t launch_contract(const ContractArgs& a, hipStream_t stream);
+// The kernel family launch_contract picks for these arguments (nothing is launched).
+const char* contract_kernel_name(const ContractArgs& a);
 
 // Streaming variant for strided modes with a small square matrix (16, 32 or 64) and an inner
 // extent that is a multiple of 16: one wavefront per 16-column tile, no staging of the data in LDS.

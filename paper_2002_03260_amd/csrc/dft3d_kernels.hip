@@ -1342,30 +1342,50 @@ hipError_t launch_c(const ContractArgs& a, hipStream_t stream)
 
 }  // namespace
 
-hipError_t launch_contract(const ContractArgs& a, hipStream_t stream)
+// One decision procedure serves the launch and the query of which kernel a contraction takes: with
+// `name` set nothing is launched and *name receives the kernel family.
+static hipError_t dispatch_contract(const ContractArgs& a, hipStream_t stream, const char** name)
 {
+#define DFT3D_PICK(family, call)                \
+    do {                                        \
+        if (name) {                             \
+            *name = family;                     \
+            return hipSuccess;                  \
+        }                                       \
+        return call;                            \
+    } while (0)
     const int K = a.M.K, N = a.M.N;
-    if (a.O <= 0 || a.I <= 0 || K <= 0 || N <= 0) return hipSuccess;
-    if (a.bf16x3 && contract_bf16x3_supported(a)) return launch_contract_bf16x3(a, stream);
+    if (a.O <= 0 || a.I <= 0 || K <= 0 || N <= 0) DFT3D_PICK("none", hipSuccess);
+    if (a.bf16x3 && contract_bf16x3_supported(a)) DFT3D_PICK("k_contract_bf16x3", launch_contract_bf16x3(a, stream));
     constexpr int64_t kFillTiles = 512;   // two workgroups on each of the 256 CUs
     if (a.I == 1) {
-        if (N <= 32 && K <= 32) return launch_c<128, 32, 32, 32, 16>(a, stream);
-        if (N <= 64 && K <= 64) return launch_c<128, 64, 32, 64, 16>(a, stream);
-        if (cdiv(K, 128) * cdiv(a.O, 128) < kFillTiles) return launch_c<64, 64, 32, 32, 16>(a, stream);
-        if (a.three_m) return launch_c<128, 64, 64, 32, 16, 3>(a, stream);
-        return launch_c<128, 128, 64, 64, 16>(a, stream);
+        if (N <= 32 && K <= 32) DFT3D_PICK("k_contract_c", (launch_c<128, 32, 32, 32, 16>(a, stream)));
+        if (N <= 64 && K <= 64) DFT3D_PICK("k_contract_c", (launch_c<128, 64, 32, 64, 16>(a, stream)));
+        if (cdiv(K, 128) * cdiv(a.O, 128) < kFillTiles) DFT3D_PICK("k_contract_c", (launch_c<64, 64, 32, 32, 16>(a, stream)));
+        if (a.three_m) DFT3D_PICK("k_contract_c (3M)", (launch_c<128, 64, 64, 32, 16, 3>(a, stream)));
+        DFT3D_PICK("k_contract_c", (launch_c<128, 128, 64, 64, 16>(a, stream)));
     }
     // 64-point first stages of the FFT formulation (24 flop per byte: at the ridge) run faster on the
     // LDS-tiled three-product kernel than on the streaming one (8192 = 64 * 128: 0.39 -> 0.34 ms)
     if (K == 64 && N == 64 && a.Tw && a.Olo == 1 && a.I % 128 == 0)
-        return launch_s<64, 128, 32, 64, 16, 2, 3>(a, stream);
-    if (contract_sr_supported(a)) return launch_contract_sr(a, stream);
-    if (K <= 16 && N <= 16) return launch_s<16, 256, 16, 64, 16, 1>(a, stream);
-    if (K <= 32 && N <= 32) return launch_s<32, 128, 32, 32, 32, 1>(a, stream);
-    if (K <= 64 && N <= 64) return launch_s<64, 128, 64, 32, 16, 2>(a, stream);
-    if (cdiv(K, 128) * cdiv(a.I, 128) * a.O < kFillTiles) return launch_s<64, 64, 32, 32, 16, 2>(a, stream);
-    if (a.three_m) return launch_s<64, 128, 32, 64, 16, 2, 3>(a, stream);
-    return launch_s<128, 128, 64, 64, 16, 2>(a, stream);
+        DFT3D_PICK("k_contract_s (3M)", (launch_s<64, 128, 32, 64, 16, 2, 3>(a, stream)));
+    if (contract_sr_supported(a)) DFT3D_PICK("k_contract_sr", launch_contract_sr(a, stream));
+    if (K <= 16 && N <= 16) DFT3D_PICK("k_contract_s", (launch_s<16, 256, 16, 64, 16, 1>(a, stream)));
+    if (K <= 32 && N <= 32) DFT3D_PICK("k_contract_s", (launch_s<32, 128, 32, 32, 32, 1>(a, stream)));
+    if (K <= 64 && N <= 64) DFT3D_PICK("k_contract_s", (launch_s<64, 128, 64, 32, 16, 2>(a, stream)));
+    if (cdiv(K, 128) * cdiv(a.I, 128) * a.O < kFillTiles) DFT3D_PICK("k_contract_s", (launch_s<64, 64, 32, 32, 16, 2>(a, stream)));
+    if (a.three_m) DFT3D_PICK("k_contract_s (3M)", (launch_s<64, 128, 32, 64, 16, 2, 3>(a, stream)));
+    DFT3D_PICK("k_contract_s", (launch_s<128, 128, 64, 64, 16, 2>(a, stream)));
+#undef DFT3D_PICK
+}
+
+hipError_t launch_contract(const ContractArgs& a, hipStream_t stream) { return dispatch_contract(a, stream, nullptr); }
+
+const char* contract_kernel_name(const ContractArgs& a)
+{
+    const char* name = "none";
+    (void)dispatch_contract(a, nullptr, &name);
+    return name;
 }
 
 namespace {

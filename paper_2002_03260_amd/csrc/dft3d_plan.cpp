@@ -293,6 +293,29 @@ dft3d_status hip_status(hipError_t e, const char* who)
     return DFT3D_ERR_HIP;
 }
 
+// Arguments of the complex64 contraction of one KDFT mode.
+ContractArgs mode_args(const dft3d_plan_s* p, int axis, const float2* in, float2* out, int conj, float scale)
+{
+    ContractArgs a{};
+    a.X = in;
+    a.Y = out;
+    a.M = p->M[axis];
+    a.O = p->outer(axis);
+    a.I = p->inner(axis);
+    a.Olo = 1;
+    a.sYohi = (int64_t)a.M.K * a.I;
+    a.sYolo = 0;
+    a.sYk = a.I;
+    a.Tw = nullptr;
+    a.twB = 1;
+    a.twInner = 1;
+    a.scale = scale;
+    a.conj = conj;
+    a.three_m = (p->flags & DFT3D_FLAG_3M) ? 1 : 0;
+    a.bf16x3 = (p->flags & DFT3D_FLAG_BF16X3) ? 1 : 0;
+    return a;
+}
+
 // out[.., k, ..] = sum_n M[k,n] in[.., n, ..] along `axis`, natural layout.
 hipError_t run_mode(const dft3d_plan_s* p, int axis, const float2* in, float2* out, int conj,
                     float scale, hipStream_t st)
@@ -319,24 +342,7 @@ hipError_t run_mode(const dft3d_plan_s* p, int axis, const float2* in, float2* o
         (void)scale;
         return launch_contract_f64(d, st);
     }
-    ContractArgs a{};
-    a.X = in;
-    a.Y = out;
-    a.M = p->M[axis];
-    a.O = p->outer(axis);
-    a.I = p->inner(axis);
-    a.Olo = 1;
-    a.sYohi = (int64_t)a.M.K * a.I;
-    a.sYolo = 0;
-    a.sYk = a.I;
-    a.Tw = nullptr;
-    a.twB = 1;
-    a.twInner = 1;
-    a.scale = scale;
-    a.conj = conj;
-    a.three_m = (p->flags & DFT3D_FLAG_3M) ? 1 : 0;
-    a.bf16x3 = (p->flags & DFT3D_FLAG_BF16X3) ? 1 : 0;
-    return launch_contract(a, st);
+    return launch_contract(mode_args(p, axis, in, out, conj, scale), st);
 }
 
 // A stage of 128 points or more is bound by the matrix cores (8 * 128 / 16 = 64 flop per byte): it
@@ -928,6 +934,20 @@ dft3d_status dft3d_plan_get_split(dft3d_plan p, int axis, int64_t* A, int64_t* B
     }
     *A = p->A[axis];
     *B = p->B[axis];
+    return DFT3D_OK;
+}
+
+dft3d_status dft3d_plan_mode_kernel(dft3d_plan p, int axis, char* name, size_t len)
+{
+    if (!p || axis < 0 || axis > 2 || !name || len == 0) {
+        set_error("plan_mode_kernel: invalid argument");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    if (p->form != DFT3D_KDFT) { set_error("plan_mode_kernel: not a KDFT plan"); return DFT3D_ERR_UNSUPPORTED; }
+    const char* k = single_launch(p) ? "k_kdft_small"
+                    : p->complex128() ? "k_contract_f64"
+                                      : contract_kernel_name(mode_args(p, axis, nullptr, nullptr, 0, 1.0f));
+    snprintf(name, len, "%s", k);
     return DFT3D_OK;
 }
 

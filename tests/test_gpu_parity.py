@@ -209,15 +209,18 @@ def test_kdft_adjoint_of_point_transform(dft, shape, ks):
         assert report(f"kdft points adjoint {ks}->{shape}", got, want) <= TOL
 
 
-@pytest.mark.parametrize("shape", [(128, 128, 128), (256, 256, 256), (128, 384, 256), (130, 256, 128)])
+@pytest.mark.parametrize("shape", [(128, 128, 128), (256, 256, 256), (128, 384, 256), (130, 256, 128),
+                                   (130, 200, 258), (33, 129, 40), (1, 7, 300), (200, 1, 1)])
 @pytest.mark.parametrize("three_m", [False, True])
 def test_kdft_bf16_split_scheme(dft, shape, three_m):
     """DFT3D_FLAG_BF16X3: three bf16 levels per fp32 number on the bf16 matrix cores; same tolerance.
-    Together with DFT3D_FLAG_3M: three real products per complex product (nine planes per operand)."""
+    Whole 128 x 128 tiles or not, every mode must take the bf16 kernel (edge tiles are masked).
+    DFT3D_FLAG_3M on top changes nothing for these modes (the bf16 kernel always uses three real products)."""
     say(f"case kdft bf16x3 {shape} three_m={three_m}")
     x = wl.draw_complex(shape, "normal", 2700 + sum(shape))
     want = orc.dft3d(x)
     with dft.Plan(shape, dft.KDFT, flags=dft.FLAG_BF16X3 | (dft.FLAG_3M if three_m else 0)) as p:
+        assert [p.mode_kernel(axis) for axis in range(3)] == ["k_contract_bf16x3"] * 3
         xd = to_dev(x)
         got = to_host(p.exec(xd))
         assert report(f"kdft bf16x3 {shape}", got, want) <= TOL
@@ -332,6 +335,20 @@ def test_complex128_plan_restrictions(dft):
     with dft.Plan((8, 8, 8), dft.KDFT, flags=dft.FLAG_COMPLEX128) as p:
         with pytest.raises(ValueError):
             p.exec(torch.zeros((8, 8, 8), dtype=torch.complex64, device="cuda"))
+
+
+def test_plan_reports_the_kernel_of_each_mode(dft):
+    with dft.Plan((256, 256, 256), dft.KDFT) as p:
+        assert [p.mode_kernel(a) for a in range(3)] == ["k_contract_s", "k_contract_s", "k_contract_c"]
+    with dft.Plan((256, 256, 256), dft.KDFT, flags=dft.FLAG_3M) as p:
+        assert [p.mode_kernel(a) for a in range(3)] == ["k_contract_s (3M)", "k_contract_s (3M)", "k_contract_c (3M)"]
+    with dft.Plan((64, 64, 64), dft.KDFT) as p:
+        assert p.mode_kernel(0) == "k_contract_sr" and p.mode_kernel(2) == "k_contract_c"
+    with dft.Plan((64, 64, 64), dft.KDFT, flags=dft.FLAG_COMPLEX128) as p:
+        assert p.mode_kernel(1) == "k_contract_f64"
+    with dft.Plan((64, 64, 64), dft.FFT) as p:
+        with pytest.raises(dft.Dft3dError):
+            p.mode_kernel(0)
 
 
 def test_kdft_clobber_input(dft):
@@ -709,6 +726,7 @@ def test_kdft_single_launch_small_shapes(dft, shape):
             y = p.mode_contract(axis, y)
         assert report(f"small exec vs modes {shape}", to_host(p.exec(xd)), to_host(y).astype(np.complex128)) <= TOL
     with dft.Plan(shape, dft.KDFT, flags=dft.FLAG_3M | dft.FLAG_BF16X3) as p:
+        assert p.mode_kernel(0) == "k_kdft_small"
         assert report(f"small flags {shape}", to_host(p.exec(xd)), orc.dft3d(x)) <= TOL
     rng = np.random.default_rng(14)
     coords = tuple(np.sort(rng.random(n)) for n in shape)
