@@ -352,6 +352,10 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
                 three = (A == 16 and B in (16, 32)) or (ax == 2 and (A, B) == (32, 64))
                 per_cmac = 6.0 if three else 8.0
                 flops = (per_cmac * (A + B) + 6.0) * E
+                if ax != 2 and (A, B) == (32, 64):
+                    # streaming kernel of the strided axes: three real products in the first stage, four
+                    # in the second (whose accumulators are the resident output tile)
+                    flops = (6.0 * A + 8.0 * B + 6.0) * E
             elif "stage1" in dom_name:
                 # strided stages with a 16 / 32 / 64 matrix run the three-product streaming kernel, and
                 # every stage of 128 points or more takes the three-product scheme

@@ -232,7 +232,7 @@ dft3d_status dft3d_fft_second_stage(dft3d_plan plan, int axis, const void* in, v
 /* FFT, one whole axis in a single fused kernel: first stage, twiddle, second stage and natural
  * order (Eq. 13 - Eq. 16 for that axis), one read and one write of the tensor.  Offered for
  * axis 2 (z) with splits 16x16, 16x32, 32x32, 32x64, 64x64 and for axes 0, 1 (x, y) with splits
- * 16x16, 16x32, 32x32 when the extent inside the axis is a multiple of 16; UNSUPPORTED
+ * 16x16, 16x32, 32x32, 32x64 when the extent inside the axis is a multiple of 16; UNSUPPORTED
  * otherwise.  dft3d_exec uses it whenever it applies (unless the plan has DFT3D_FLAG_UNFUSED). */
 dft3d_status dft3d_fft_axis(dft3d_plan plan, int axis, const void* in, void* out, int direction,
                             void* stream);

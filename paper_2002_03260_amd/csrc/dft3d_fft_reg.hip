@@ -600,6 +600,532 @@ __global__ __launch_bounds__(256, MINW) void k_fft_sr(FftStridedArgs a, DeviceMa
     }
 }
 
+// The same pass on tiles of all N positions x 32 contiguous columns: every lane holds two neighbouring
+// columns (16-byte loads and stores, 256 contiguous bytes per row and quarter wave), which the memory
+// system serves faster than 128-byte pieces (measured with a plain tiled copy at 512^3: 5.3 against
+// 4.9 TB/s along y, 5.1 against 3.9 TB/s along x).  The two columns of a lane are two independent sets
+// of MFMA columns.  Z for 32 columns takes 128 KiB of LDS, so one workgroup of eight waves runs per CU:
+// wave w does stage 1 for beta = w, w+8, .. and stage 2 for k_a = w, w+8, ..
+template <int A, int B>
+__global__ __launch_bounds__(512, 1) void k_fft_sw(FftStridedArgs a, DeviceMatrix FA, DeviceMatrix FB,
+                                                    const float2* __restrict__ Tw, float scale, int conj)
+{
+    const float2* __restrict__ X = a.X;
+    float2* __restrict__ Y = a.Y;
+    constexpr int N = A * B;
+    static_assert(A == 16, "one block of k_a per stage-1 product");
+    constexpr int NW = 8;
+    constexpr int NBB = B / 16;      // blocks of k_b
+    constexpr int NS1 = A / 4;       // k-steps of stage 1 (over l)
+    constexpr int NS2 = B / 4;       // k-steps of stage 2 (over beta)
+    constexpr int NG = B / NW;       // beta values per wave
+    constexpr int NH = A / NW;       // k_a values per wave
+    static_assert(NG >= 2 && NG % 2 == 0 && NH >= 1, "work split over eight waves");
+
+    extern __shared__ __align__(16) unsigned char smem_sw[];
+    f32x4* Zs = reinterpret_cast<f32x4*>(smem_sw);                        // [k_a][beta][16 column pairs]
+    float2* tws = reinterpret_cast<float2*>(smem_sw + (size_t)N * 16 * sizeof(f32x4));   // T[k_a][beta]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, lq = lane >> 4;
+    const float isign = conj ? -1.0f : 1.0f;
+
+    for (int e = tid; e < N; e += 512) {
+        float2 t = Tw[e];
+        t.y *= isign;
+        tws[e] = t;
+    }
+    float fa_r[NS1], fa_i[NS1], fa_s[NS1];
+#pragma unroll
+    for (int s = 0; s < NS1; ++s) {
+        const int idx = (4 * s + lq) * FA.ld + l16;
+        fa_r[s] = FA.re[idx];
+        fa_i[s] = FA.im[idx] * isign;
+        fa_s[s] = fa_r[s] + fa_i[s];
+    }
+    float fb_r[NBB][NS2], fb_i[NBB][NS2], fb_s[NBB][NS2];
+#pragma unroll
+    for (int kbb = 0; kbb < NBB; ++kbb)
+#pragma unroll
+        for (int s = 0; s < NS2; ++s) {
+            const int idx = (4 * s + lq) * FB.ld + 16 * kbb + l16;
+            fb_r[kbb][s] = FB.re[idx] * scale;
+            fb_i[kbb][s] = FB.im[idx] * (scale * isign);
+            fb_s[kbb][s] = fb_r[kbb][s] + fb_i[kbb][s];
+        }
+
+    // tile -> (o, y, 32-column group); a.Zt counts groups of 16 columns and is even here
+    const int64_t zt2 = a.Zt / 2;
+    const int64_t per_o = a.Yn * zt2;
+    const int64_t ntiles = a.O * per_o;
+    const int64_t nwg = (int64_t)gridDim.x * gridDim.y;
+    auto in_base = [&](int64_t tile) {
+        const int64_t o = tile / per_o, r = tile % per_o;
+        return o * a.inO + (r / zt2) * a.inY + (r % zt2) * 32;
+    };
+    auto out_base = [&](int64_t tile) {
+        const int64_t o = tile / per_o, r = tile % per_o;
+        return o * a.outO + (r / zt2) * a.outY + (r % zt2) * 32;
+    };
+    const int64_t inN = a.inN, outN = a.outN;
+    const unsigned ld_lane = (unsigned)(B * lq) * (unsigned)inN + 2 * l16;        // row B*lq, columns 2*l16, 2*l16+1
+    const unsigned st_lane = (unsigned)(A * 4 * lq) * (unsigned)outN + 2 * l16;   // row A*4*lq
+
+    // operand registers of the tile: xq[g][s] = x[B*(4*s + lq) + beta_g, columns 2*l16 and 2*l16+1]
+    f32x4 xq[NG][NS1];
+    auto request = [&](int64_t tile, int g) {
+        const float2* src = X + in_base(tile) + (int64_t)(wave + NW * g) * inN;
+#pragma unroll
+        for (int s = 0; s < NS1; ++s)
+            xq[g][s] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(&(src + (int64_t)(4 * B * s) * inN)[ld_lane]));
+    };
+
+    int64_t tile = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    if (tile < ntiles) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) request(tile, g);
+    }
+    __syncthreads();                               // twiddle table
+    for (; tile < ntiles; tile += nwg) {
+        const int64_t next = tile + nwg < ntiles ? tile + nwg : tile;    // past the end: a harmless re-read
+
+        // ---- stage 1: two beta values at a time, two columns per lane
+#pragma unroll
+        for (int g = 0; g < NG; g += 2) {
+            f32x4 p1[2][2], p2[2][2], p3[2][2];     // [beta of the pair][column of the lane]
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    p1[u][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    p2[u][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    p3[u][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+            for (int s = 0; s < NS1; ++s)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const f32x4 x = xq[g + u][s];
+                    p1[u][0] = mfma(fa_r[s], x[0], p1[u][0]);
+                    p2[u][0] = mfma(fa_i[s], x[1], p2[u][0]);
+                    p3[u][0] = mfma(fa_s[s], x[0] + x[1], p3[u][0]);
+                    p1[u][1] = mfma(fa_r[s], x[2], p1[u][1]);
+                    p2[u][1] = mfma(fa_i[s], x[3], p2[u][1]);
+                    p3[u][1] = mfma(fa_s[s], x[2] + x[3], p3[u][1]);
+                }
+            // the registers of these two beta values are free: request them for the next tile
+            request(next, g);
+            request(next, g + 1);
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int beta = wave + NW * (g + u);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int ka = 4 * lq + v;
+                    const float2 t = tws[ka * B + beta];
+                    f32x4 z;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const float re = p1[u][h][v] - p2[u][h][v];
+                        const float im = p3[u][h][v] - p1[u][h][v] - p2[u][h][v];
+                        z[2 * h] = re * t.x - im * t.y;
+                        z[2 * h + 1] = re * t.y + im * t.x;
+                    }
+                    Zs[(ka * B + beta) * 16 + l16] = z;
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- stage 2: one k_a at a time, all blocks of k_b in flight
+        float2* dst = Y + out_base(tile);                                   // uniform
+#pragma unroll
+        for (int hh = 0; hh < NH; ++hh) {
+            const int ka = wave + NW * hh;
+            f32x4 q1[NBB][2], q2[NBB][2], q3[NBB][2];
+#pragma unroll
+            for (int kbb = 0; kbb < NBB; ++kbb)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    q1[kbb][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    q2[kbb][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    q3[kbb][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+            for (int s = 0; s < NS2; ++s) {
+                const f32x4 z = Zs[(ka * B + 4 * s + lq) * 16 + l16];
+                const float zs0 = z[0] + z[1], zs1 = z[2] + z[3];
+#pragma unroll
+                for (int kbb = 0; kbb < NBB; ++kbb) {
+                    q1[kbb][0] = mfma(fb_r[kbb][s], z[0], q1[kbb][0]);
+                    q2[kbb][0] = mfma(fb_i[kbb][s], z[1], q2[kbb][0]);
+                    q3[kbb][0] = mfma(fb_s[kbb][s], zs0, q3[kbb][0]);
+                    q1[kbb][1] = mfma(fb_r[kbb][s], z[2], q1[kbb][1]);
+                    q2[kbb][1] = mfma(fb_i[kbb][s], z[3], q2[kbb][1]);
+                    q3[kbb][1] = mfma(fb_s[kbb][s], zs1, q3[kbb][1]);
+                }
+            }
+#pragma unroll
+            for (int kbb = 0; kbb < NBB; ++kbb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    // row k_a + A*k_b with k_b = 16*kbb + 4*lq + v: the lq part is in st_lane
+                    const f32x4 w = f32x4{q1[kbb][0][v] - q2[kbb][0][v], q3[kbb][0][v] - q1[kbb][0][v] - q2[kbb][0][v],
+                                          q1[kbb][1][v] - q2[kbb][1][v], q3[kbb][1][v] - q1[kbb][1][v] - q2[kbb][1][v]};
+                    __builtin_nontemporal_store(w, reinterpret_cast<f32x4*>(&(dst + (int64_t)(ka + A * (16 * kbb + v)) * outN)[st_lane]));
+                }
+        }
+        __syncthreads();                           // Z is rewritten by the next tile
+    }
+}
+
+// ---- strided axes, streaming form ------------------------------------------------------------------
+// The kernels above keep the whole intermediate Z[k_a][beta][columns] of a tile in LDS, which limits a
+// tile to N * columns * 8 bytes <= 128 KiB: 16 or 32 columns at N = 512, nothing at N = 2048.  Here Z
+// never exists as a whole.  The second stage is a sum over beta, so its RESULT is what stays resident:
+// every wave keeps the accumulators of its share of the output tile W[k_a][k_b][columns] in registers
+// (the whole tile, N * columns complex numbers = 256 KiB, is half of the CU's register file) and the
+// first stage feeds it a slot of SB consecutive beta at a time through a small double-buffered LDS
+// ring:
+//   slot t:  stage 1, wave w = (beta = SB*t + w / CH, column group w % CH):
+//                D[k_a, c] = twiddle * sum_l FA[k_a, l] x[B*l + beta, c]   (data straight from global
+//                memory into the MFMA B operand, requested two slots ahead)  ->  Z ring
+//            one barrier
+//            stage 2, wave w owns the pairs (k_a, column group) p = w, w + 8, ..:
+//                W[k_a, k_b, c] += sum_{beta in slot} FB[k_b, beta] Z[k_a, beta, c]
+//   after the last slot the accumulators are stored to rows k_a + A*k_b and cleared.
+// Stage 1 uses three real products per complex product (its three accumulators live for one slot);
+// stage 2 uses four with two accumulators (re, im), because three resident accumulators per output
+// would not fit.  Per element 6*A + 8*B flop instead of 6*(A + B).
+// A tile is all N positions x 16*CV*CH columns: CV = complex numbers per lane and access (1 or 2),
+// CH = column groups side by side.  N = 512: CV = 2, CH = 2 (64 columns, 512 contiguous bytes per row
+// from two neighbouring waves); N = 2048: CV = 1, CH = 1 (16 columns).  Stage matrices and twiddles
+// sit in LDS in per-lane operand order.  One workgroup of eight waves per CU, one barrier per slot.
+template <int CV>
+struct cvec;
+template <>
+struct cvec<1> { typedef f32x2 type; };
+template <>
+struct cvec<2> { typedef f32x4 type; };
+
+template <int A, int B, int CV, int CH, int SB>
+struct FftSsLayout {
+    static constexpr int N = A * B;
+    static constexpr int NW = 8;
+    static constexpr int NAB = A / 16, NBB = B / 16, NS1 = A / 4, KS = SB / 4, NSLOT = B / SB;
+    static constexpr int PPW = A * CH / NW;                     // (k_a, column group) pairs per wave
+    static constexpr int VB = 8 * CV;                           // bytes of one lane's element
+    static constexpr int PK = CH * SB * 16 + 32 / VB;           // Z ring: elements per k_a (32 bytes of padding)
+    static constexpr size_t z_bytes = (size_t)2 * A * PK * VB;
+    static constexpr size_t fa_bytes = (size_t)NAB * NS1 * 3 * 64 * 4;
+    static constexpr size_t fb_bytes = (size_t)NBB * (B / 4) * 2 * 64 * 4;
+    static constexpr size_t tw_bytes = (size_t)N * 8;
+    static constexpr size_t lds_bytes = z_bytes + fa_bytes + fb_bytes + tw_bytes;
+    static_assert(SB * CH == NW, "one stage-1 unit per wave and slot");
+    static_assert(SB % 4 == 0 && NSLOT % 2 == 0 && PPW >= 1 && (A * CH) % NW == 0, "slot structure");
+};
+
+template <int A, int B, int CV, int CH, int SB>
+__global__ __launch_bounds__(512, 1) void k_fft_ss(FftStridedArgs a, DeviceMatrix FA, DeviceMatrix FB,
+                                                    const float2* __restrict__ Tw, float scale, int conj)
+{
+    typedef FftSsLayout<A, B, CV, CH, SB> L;
+    typedef typename cvec<CV>::type vec;
+    constexpr int NAB = L::NAB, NBB = L::NBB, NS1 = L::NS1, KS = L::KS, NSLOT = L::NSLOT, PPW = L::PPW, PK = L::PK;
+    constexpr int NW = L::NW;
+
+    extern __shared__ __align__(16) unsigned char smem_ss[];
+    // Operand tables in per-lane order, four consecutive k-steps (or all blocks of k_b) side by side, so
+    // that one 16-byte LDS read feeds many matrix instructions:
+    vec* Zs = reinterpret_cast<vec*>(smem_ss);                                   // [2][A][PK]
+    f32x4* faT = reinterpret_cast<f32x4*>(smem_ss + L::z_bytes);                // [NAB][NS1/4][re, im, re+im][lane] x (4 k-steps)
+    f32x4* fbT = reinterpret_cast<f32x4*>(smem_ss + L::z_bytes + L::fa_bytes);  // [B/4][NBB/2][lane] x (re, im of two blocks of k_b)
+    float2* tws = reinterpret_cast<float2*>(smem_ss + L::z_bytes + L::fa_bytes + L::fb_bytes);   // T[beta][k_a]
+
+    const float2* __restrict__ X = a.X;
+    float2* __restrict__ Y = a.Y;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, lq = lane >> 4;
+    const float isign = conj ? -1.0f : 1.0f;
+
+    // ---- tables, once per workgroup ------------------------------------------------------------------
+    {
+        float* faF = reinterpret_cast<float*>(faT);
+        for (int e = tid; e < NAB * NS1 * 64; e += 512) {
+            const int ln = e & 63, s = (e >> 6) % NS1, ab = (e >> 6) / NS1;
+            const int idx = (4 * s + (ln >> 4)) * FA.ld + 16 * ab + (ln & 15);    // FA[k_a][l] at plane[l * ld + k_a]
+            const float r = FA.re[idx], i = FA.im[idx] * isign;
+            float* t = faF + (((ab * (NS1 / 4) + s / 4) * 3) * 64 + ln) * 4 + (s & 3);
+            t[0] = r;
+            t[64 * 4] = i;
+            t[128 * 4] = r + i;
+        }
+        float* fbF = reinterpret_cast<float*>(fbT);
+        for (int e = tid; e < NBB * (B / 4) * 64; e += 512) {
+            const int ln = e & 63, bq = (e >> 6) % (B / 4), kbb = (e >> 6) / (B / 4);
+            const int idx = (4 * bq + (ln >> 4)) * FB.ld + 16 * kbb + (ln & 15);  // FB[k_b][beta]
+            float* t = fbF + ((bq * (NBB / 2) + kbb / 2) * 64 + ln) * 4 + 2 * (kbb & 1);
+            t[0] = FB.re[idx] * scale;
+            t[1] = FB.im[idx] * (scale * isign);
+        }
+        for (int e = tid; e < A * B; e += 512) {        // Tw is T[k_a][beta]: transposed here
+            float2 t = Tw[e];
+            t.y *= isign;
+            tws[(e % B) * A + e / B] = t;
+        }
+    }
+
+    // ---- geometry --------------------------------------------------------------------------------------
+    // tile -> (o, y, column block): tiles are visited first, first + nwg, ..; the position is advanced
+    // with carries instead of being divided out of the tile index every time (64-bit divisions in the
+    // loop cost more issue slots than the matrix instructions)
+    constexpr int TG = CV * CH;                        // 16-column groups per tile
+    const int64_t ztt = a.Zt / TG;
+    const int64_t per_o = a.Yn * ztt;
+    const int64_t ntiles = a.O * per_o;
+    const int64_t nwg = (int64_t)gridDim.x * gridDim.y;
+    const int64_t first = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    struct Pos {
+        int o, y, zt;                                  // (the host side keeps all three below 2^31)
+    };
+    const int ztt32 = (int)ztt, yn32 = (int)a.Yn;
+    const Pos step = {(int)(nwg / per_o), (int)((nwg % per_o) / ztt), (int)(nwg % ztt)};
+    auto advance = [&](Pos& p) {
+        p.zt += step.zt;
+        if (p.zt >= ztt32) {
+            p.zt -= ztt32;
+            p.y += 1;
+        }
+        p.y += step.y;
+        if (p.y >= yn32) {
+            p.y -= yn32;
+            p.o += 1;
+        }
+        p.o += step.o;
+    };
+    Pos rq = {(int)(first / per_o), (int)((first % per_o) / ztt), (int)(first % ztt)};   // tile of the slot requested next
+    Pos st = rq;                                                                          // tile being accumulated
+    const int64_t inN = a.inN, outN = a.outN;
+    // stage-1 unit of this wave: beta = SB*slot + ub, column group ug
+    const int ub = wave / CH, ug = wave % CH;
+    const unsigned ld_lane = (unsigned)(B * lq) * (unsigned)inN + (unsigned)(16 * CV * ug + CV * l16);
+    const unsigned st_lane = (unsigned)(A * 4 * lq) * (unsigned)outN + (unsigned)(CV * l16);
+
+    vec xs[2][NS1];                                    // two register sets: slots alternate
+    const int64_t in_step = (int64_t)(4 * B) * inN;     // rows between the k-steps of stage 1
+    const int64_t out_stepA = (int64_t)A * outN, out_step16A = 16 * out_stepA;
+    auto request = [&](int set, int slot) {            // of the tile at rq
+        const float2* src = X + ((int64_t)rq.o * a.inO + (int64_t)rq.y * a.inY + (int64_t)rq.zt * (16 * TG)) +
+                            (int64_t)(SB * slot + ub) * inN;
+#pragma unroll
+        for (int s = 0; s < NS1; ++s) {
+            xs[set][s] = __builtin_nontemporal_load(reinterpret_cast<const vec*>(&src[ld_lane]));
+            src += in_step;
+        }
+    };
+
+    // stage-2 accumulators of this wave: pair j = (k_a, column group) of p = wave + NW*j
+    f32x4 wr[PPW][CV][NBB], wi[PPW][CV][NBB];
+    auto clear_acc = [&]() {
+#pragma unroll
+        for (int j = 0; j < PPW; ++j)
+#pragma unroll
+            for (int h = 0; h < CV; ++h)
+#pragma unroll
+                for (int kbb = 0; kbb < NBB; ++kbb) {
+                    wr[j][h][kbb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    wi[j][h][kbb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+    };
+
+    auto stage1 = [&](int set, int slot, int buf) {      // set: compile-time constant at every call
+        f32x4 p1[NAB][CV], p2[NAB][CV], p3[NAB][CV];
+#pragma unroll
+        for (int ab = 0; ab < NAB; ++ab)
+#pragma unroll
+            for (int h = 0; h < CV; ++h) {
+                p1[ab][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+                p2[ab][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+                p3[ab][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+        for (int sq = 0; sq < NS1 / 4; ++sq)
+#pragma unroll
+            for (int ab = 0; ab < NAB; ++ab) {
+                const f32x4* t = faT + ((ab * (NS1 / 4) + sq) * 3) * 64 + lane;
+                const f32x4 fr = t[0], fi = t[64], fs = t[128];
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4) {
+                    const vec x = xs[set][4 * sq + s4];
+#pragma unroll
+                    for (int h = 0; h < CV; ++h) {
+                        p1[ab][h] = mfma(fr[s4], x[2 * h], p1[ab][h]);
+                        p2[ab][h] = mfma(fi[s4], x[2 * h + 1], p2[ab][h]);
+                        p3[ab][h] = mfma(fs[s4], x[2 * h] + x[2 * h + 1], p3[ab][h]);
+                    }
+                }
+            }
+        const int beta = SB * slot + ub;
+        vec* zw = Zs + (size_t)buf * (A * PK) + (ug * SB + ub) * 16 + l16;
+#pragma unroll
+        for (int ab = 0; ab < NAB; ++ab) {
+            // the twiddles of this lane's four k_a are 32 contiguous bytes of T[beta][k_a]
+            const f32x4* tq = reinterpret_cast<const f32x4*>(tws + beta * A + 16 * ab + 4 * lq);
+            const f32x4 t01 = tq[0], t23 = tq[1];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int ka = 16 * ab + 4 * lq + v;
+                const float2 t = v == 0 ? make_float2(t01[0], t01[1]) : v == 1 ? make_float2(t01[2], t01[3])
+                               : v == 2 ? make_float2(t23[0], t23[1]) : make_float2(t23[2], t23[3]);
+                vec z;
+#pragma unroll
+                for (int h = 0; h < CV; ++h) {
+                    const float re = p1[ab][h][v] - p2[ab][h][v];
+                    const float im = p3[ab][h][v] - p1[ab][h][v] - p2[ab][h][v];
+                    z[2 * h] = re * t.x - im * t.y;
+                    z[2 * h + 1] = re * t.y + im * t.x;
+                }
+                zw[ka * PK] = z;
+            }
+        }
+    };
+
+    auto stage2 = [&](int slot, int buf) {
+        const vec* zr = Zs + (size_t)buf * (A * PK) + lq * 16 + l16;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            vec z[PPW];
+            float zn[PPW][CV];
+#pragma unroll
+            for (int j = 0; j < PPW; ++j) {
+                const int p = wave + NW * j;
+                z[j] = zr[(p / CH) * PK + ((p % CH) * SB + 4 * ks) * 16];
+#pragma unroll
+                for (int h = 0; h < CV; ++h) zn[j][h] = -z[j][2 * h + 1];
+            }
+            const f32x4* t = fbT + (size_t)(slot * KS + ks) * (NBB / 2) * 64 + lane;
+            f32x4 fq[NBB / 2];
+#pragma unroll
+            for (int q = 0; q < NBB / 2; ++q) fq[q] = t[q * 64];
+#pragma unroll
+            for (int kbb = 0; kbb < NBB; ++kbb) {
+                const float fr = fq[kbb / 2][2 * (kbb & 1)], fi = fq[kbb / 2][2 * (kbb & 1) + 1];
+#pragma unroll
+                for (int j = 0; j < PPW; ++j)
+#pragma unroll
+                    for (int h = 0; h < CV; ++h) wr[j][h][kbb] = mfma(fr, z[j][2 * h], wr[j][h][kbb]);
+#pragma unroll
+                for (int j = 0; j < PPW; ++j)
+#pragma unroll
+                    for (int h = 0; h < CV; ++h) wi[j][h][kbb] = mfma(fr, z[j][2 * h + 1], wi[j][h][kbb]);
+#pragma unroll
+                for (int j = 0; j < PPW; ++j)
+#pragma unroll
+                    for (int h = 0; h < CV; ++h) wr[j][h][kbb] = mfma(fi, zn[j][h], wr[j][h][kbb]);
+#pragma unroll
+                for (int j = 0; j < PPW; ++j)
+#pragma unroll
+                    for (int h = 0; h < CV; ++h) wi[j][h][kbb] = mfma(fi, z[j][2 * h], wi[j][h][kbb]);
+            }
+        }
+    };
+
+    auto store_tile = [&]() {                          // the tile at st
+        float2* dst = Y + ((int64_t)st.o * a.outO + (int64_t)st.y * a.outY + (int64_t)st.zt * (16 * TG));
+#pragma unroll
+        for (int j = 0; j < PPW; ++j) {
+            const int p = wave + NW * j;
+            const int ka = p / CH, cg = p % CH;
+            float2* blk = dst + (int64_t)ka * outN + 16 * CV * cg;       // row k_a, this pair's columns
+#pragma unroll
+            for (int kbb = 0; kbb < NBB; ++kbb) {
+                // rows k_a + A*k_b with k_b = 16*kbb + 4*lq + v: the lq part is in st_lane
+                float2* row = blk;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    vec w;
+#pragma unroll
+                    for (int h = 0; h < CV; ++h) {
+                        w[2 * h] = wr[j][h][kbb][v];
+                        w[2 * h + 1] = wi[j][h][kbb][v];
+                    }
+                    __builtin_nontemporal_store(w, reinterpret_cast<vec*>(&row[st_lane]));
+                    row += out_stepA;
+                }
+                blk += out_step16A;
+            }
+        }
+    };
+
+    // Slots are numbered g = 0, 1, .. across the tiles of this workgroup; barrier B_g separates the ring
+    // writes of slot g from its reads.  Between B_g and B_(g+1) a wave has two independent pieces of
+    // work: stage 2 of slot g and stage 1 of slot g + 1 (which fills the other ring buffer, last read
+    // before B_g).  The two waves of a SIMD (w and w + 4) take them in opposite order, so that one of
+    // them has matrix work while the other waits for its data, applies the twiddles and writes the ring:
+    //   waves 0..3:  S1(0) | B_0 S2(0) S1(1) | B_1 S2(1) S1(2) | ..        body(g) = B_g, S2(g), S1(g+1)
+    //   waves 4..7:  S1(0) B_0 S1(1) | S2(0) B_1 S1(2) | S2(1) B_2 S1(3) | ..   body(g) = S2(g), B_(g+1), S1(g+2)
+    // One loop body serves both (the barrier sits before or after stage 2, stage 1 looks one or two
+    // slots ahead); waves 4..7 keep slot g's data in register set (g + 1) % 2 instead of g % 2, which
+    // makes the set index of the body the same compile-time number for both.
+    const bool late = wave >= 4;
+    const int ahead = late ? 2 : 1;
+    const int64_t mine = first < ntiles ? (ntiles - first + nwg - 1) / nwg : 0;      // tiles of this workgroup
+    const int64_t G = mine * NSLOT;
+    // Requests and stage-1 steps past the last slot are not skipped: they re-read the last tile and
+    // write ring buffers nobody reads (every access in bounds).  With unconditional loads the compiler
+    // can count how many younger requests may still be in flight when a register set is used; a
+    // conditional request made it wait for all of them, the one issued a moment ago included.
+    auto request_slot = [&](int set, int64_t g) {      // called with g = 0, 1, 2, .. in this order
+        const int slot = (int)(g % NSLOT);
+        if (slot == 0 && g != 0 && g < G) advance(rq);
+        request(set, slot);
+    };
+    if (G == 0) return;                            // (whole workgroup, before any barrier)
+    clear_acc();
+    if (!late) {
+        request_slot(0, 0);
+        request_slot(1, 1);
+    } else {
+        request_slot(1, 0);
+        request_slot(0, 1);
+    }
+    __syncthreads();                               // tables
+    if (!late) {
+        stage1(0, 0, 0);
+        request_slot(0, 2);
+    } else {
+        stage1(1, 0, 0);
+        request_slot(1, 2);
+        __syncthreads();                           // B_0
+        stage1(0, 1, 1);
+        request_slot(0, 3);
+    }
+    auto body = [&](int set, int64_t g) {
+        if (!late) __syncthreads();                // B_g
+        stage2((int)(g % NSLOT), (int)(g & 1));
+        if (late) __syncthreads();                 // B_(g+1)
+        const int64_t g1 = g + ahead;
+        stage1(set, (int)(g1 % NSLOT), (int)(g1 & 1));
+        request_slot(set, g1 + 2);
+        // (after stage 1, so that its wait for the data requested two slots ago does not have to count
+        // these stores)
+        if (g % NSLOT == NSLOT - 1) {
+            store_tile();
+            clear_acc();
+            advance(st);
+        }
+    };
+    for (int64_t g = 0; g < G; g += 2) {
+        body(1, g);
+        body(0, g + 1);
+    }
+    if (!late) __syncthreads();                    // B_G, which waves 4..7 passed inside their last body
+}
+
 // ---- strided contraction with a small square matrix ----------------------------------------------
 // out[o, k, i] = scale * tw * sum_n M[k, n] in[o, n, i] for NK x NK matrices, NK = 16, 32 or 64 (the
 // single stages of the FFT formulation when an axis has no fused kernel, and small KDFT modes).
@@ -751,6 +1277,29 @@ hipError_t launch_inst(const float2* in, float2* out, int64_t nrows, const Devic
     return hipGetLastError();
 }
 
+template <int A, int B, int CV, int CH, int SB>
+hipError_t launch_ss_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw,
+                          float scale, int conj, hipStream_t stream)
+{
+    typedef FftSsLayout<A, B, CV, CH, SB> L;
+    const int64_t ntiles = a.O * a.Yn * (a.Zt / (CV * CH));
+    const int64_t blocks = ntiles < 256 ? ntiles : 256;          // one persistent workgroup per CU
+    hipLaunchKernelGGL((k_fft_ss<A, B, CV, CH, SB>), dim3((unsigned)blocks), dim3(512), L::lds_bytes, stream, a, FA, FB,
+                       Tw, scale, conj);
+    return hipGetLastError();
+}
+
+template <int A, int B>
+hipError_t launch_sw_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw,
+                          float scale, int conj, hipStream_t stream)
+{
+    constexpr size_t lds = (size_t)A * B * 16 * sizeof(f32x4) + (size_t)A * B * sizeof(float2);
+    const int64_t ntiles = a.O * a.Yn * (a.Zt / 2);
+    const int64_t blocks = ntiles < 256 ? ntiles : 256;          // one persistent workgroup per CU
+    hipLaunchKernelGGL((k_fft_sw<A, B>), dim3((unsigned)blocks), dim3(512), lds, stream, a, FA, FB, Tw, scale, conj);
+    return hipGetLastError();
+}
+
 template <int A, int B, int MINW>
 hipError_t launch_s_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw,
                          float scale, int conj, hipStream_t stream)
@@ -795,22 +1344,44 @@ hipError_t launch_contract_sr(const ContractArgs& a, hipStream_t stream)
     return launch_csr_inst<64, 1, 2>(a, stream);
 }
 
+hipError_t configure_fft_kernels()
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sw<16, 32>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)((size_t)512 * 16 * sizeof(f32x4) + (size_t)512 * sizeof(float2)));
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_ss<32, 64, 1, 1, 8>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)FftSsLayout<32, 64, 1, 1, 8>::lds_bytes);
+}
+
 bool fft_sr_supported(int A, int B, int64_t I)
 {
-    // 32-bit lane offsets inside the kernel: (12*A + 1) rows must stay below 2^32 bytes
-    return I % 16 == 0 && I <= (int64_t(1) << 21) && A == 16 && (B == 16 || B == 32);
+    // 32-bit lane offsets inside the kernels: up to 12*A rows (and 3*B rows) of I elements
+    if (I % 16 != 0) return false;
+    if (A == 32 && B == 64) return I <= (int64_t(1) << 23);
+    return I <= (int64_t(1) << 21) && A == 16 && (B == 16 || B == 32);
 }
 
 hipError_t launch_fft_sr_ex(const FftStridedArgs& a, int A, int B, const DeviceMatrix& FA,
                             const DeviceMatrix& FB, const float2* Tw, float scale, int conj, hipStream_t stream)
 {
     if (a.O <= 0 || a.Yn <= 0 || a.Zt <= 0) return hipSuccess;
-    const int64_t lim = int64_t(1) << 21;
+    const int64_t lim = int64_t(1) << ((A == 32 && B == 64) ? 23 : 21);
     if (a.inN < 16 || a.outN < 16 || a.inN > lim || a.outN > lim || FA.K != A || FA.N != A || FB.K != B ||
         FB.N != B || !Tw)
         return hipErrorInvalidValue;
+    // 16-byte accesses (two columns per lane) need rows that start on 16-byte boundaries on both sides
+    const bool even = a.inN % 2 == 0 && a.outN % 2 == 0 && a.inY % 2 == 0 && a.outY % 2 == 0 && a.inO % 2 == 0 &&
+                      a.outO % 2 == 0 && ((uintptr_t)a.X & 15) == 0 && ((uintptr_t)a.Y & 15) == 0;
+    if (A == 32 && B == 64) return launch_ss_inst<32, 64, 1, 1, 8>(a, FA, FB, Tw, scale, conj, stream);
     if (A == 16 && B == 16) return launch_s_inst<16, 16, 4>(a, FA, FB, Tw, scale, conj, stream);
-    if (A == 16 && B == 32) return launch_s_inst<16, 32, 2>(a, FA, FB, Tw, scale, conj, stream);
+    if (A == 16 && B == 32) {
+        // tiles of 32 columns where the layout allows (measured at 512^3: y 0.446 -> 0.449 ms, x 0.512 ->
+        // 0.475 ms; the streaming kernel with 64-column tiles measured 0.495 / 0.509 ms there)
+        if (even && a.Zt % 2 == 0) return launch_sw_inst<16, 32>(a, FA, FB, Tw, scale, conj, stream);
+        return launch_s_inst<16, 32, 2>(a, FA, FB, Tw, scale, conj, stream);
+    }
     return hipErrorInvalidValue;
 }
 

@@ -157,6 +157,9 @@ struct FftStridedArgs {
 hipError_t launch_fft_sr_ex(const FftStridedArgs& a, int A, int B, const DeviceMatrix& FA,
                             const DeviceMatrix& FB, const float2* Tw, float scale, int conj, hipStream_t stream);
 bool fft_sr_supported(int A, int B, int64_t I);
+// One-time set-up of the strided-axis kernels that use more LDS than a launch gets by default
+// (idempotent; called at plan creation).
+hipError_t configure_fft_kernels();
 hipError_t launch_fft_sr(const float2* in, float2* out, int64_t O, int64_t I, int A, int B,
                          const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
                          int conj, hipStream_t stream);

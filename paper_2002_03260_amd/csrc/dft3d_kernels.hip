@@ -1466,7 +1466,7 @@ hipError_t launch_fft_s_inst(const float2* in, float2* out, int64_t O, int64_t I
 bool fft_s_supported(int A, int B, int64_t I)
 {
     if (I % 16 != 0) return false;
-    return (A == 16 && B == 16) || (A == 16 && B == 32) || (A == 32 && B == 32);
+    return (A == 16 && B == 16) || (A == 16 && B == 32) || (A == 32 && B == 32) || fft_sr_supported(A, B, I);
 }
 
 hipError_t launch_fft_s(const float2* in, float2* out, int64_t O, int64_t I, int A, int B,

@@ -744,6 +744,9 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
     // set-up for dft3d_exec_noalloc: look up this GPU's copy of the static scratch array now, so that
     // the exec call itself never has to (a failure here is reported by that call, not by this one)
     (void)noalloc_scratch_for_current_device();
+    // kernels that need more than the default LDS size are told so now, not at their first launch
+    // (which could be inside a graph capture)
+    (void)configure_fft_kernels();
     *plan = p;
     return DFT3D_OK;
 }

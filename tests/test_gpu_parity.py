@@ -451,7 +451,13 @@ def test_fft_fused_axis_kernel(dft, shape, split):
 
 
 @pytest.mark.parametrize("shape,split", [((256, 3, 16), None), ((2, 512, 48), None), ((1024, 1, 32), None),
-                                         ((3, 256, 160), None), ((512, 5, 16), (16, 1, 4))])
+                                         ((3, 256, 160), None), ((512, 5, 16), (16, 1, 4)),
+                                         # inner extents that are multiples of 32: tiles of 32 columns
+                                         ((512, 2, 32), None), ((3, 512, 96), None), ((512, 1, 352), None),
+                                         # multiples of 64: the streaming kernel with 64-column tiles
+                                         ((512, 1, 64), None), ((2, 512, 192), None), ((512, 3, 64), None),
+                                         # 2048 = 32 x 64 on a strided axis (streaming kernel, 16-column tiles)
+                                         ((2048, 1, 16), None), ((2, 2048, 48), None), ((2048, 3, 16), None)])
 def test_fft_fused_strided_axis_kernel(dft, shape, split):
     """The single-kernel x / y pass equals first stage + twiddle + second stage + re-ordering."""
     say(f"case fft fused strided axis {shape} split {split}")
@@ -459,6 +465,7 @@ def test_fft_fused_strided_axis_kernel(dft, shape, split):
     xd = to_dev(x)
     with dft.Plan(shape, dft.FFT, split=split) as p:
         axis = 0 if shape[0] >= 256 else 1
+        say(f"  kernel split {p.split(axis)}")
         A, B = p.split(axis)
         want = ff.fft_axis(x, axis, A, B)
         got = to_host(p.fft_axis(axis, xd))
