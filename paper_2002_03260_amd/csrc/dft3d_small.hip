@@ -3,7 +3,8 @@
 // kernels are pure launch latency, so one workgroup per output index k_x does all three modes:
 //
 //   1. S[b, c]   = sum_a  Mx[k_x, a] * in[a, b, c]       (mode x, for this workgroup's k_x only;
-//                                                         the input is read by every workgroup, from L2)
+//                                                         the input is read by every workgroup, from L2;
+//                                                         all of a thread's loads are in flight at once)
 //   2. T[b, k_z] = sum_c  S[b, c] * Mz[k_z, c]            (mode z, in LDS)
 //   3. out[k_x, k_y, k_z] = scale * sum_b My[k_y, b] * T[b, k_z]      (mode y, in LDS)
 //
@@ -57,27 +58,34 @@ __global__ __launch_bounds__(kSmallThreads) void k_kdft_small(const float2* __re
     const int tid = threadIdx.x;
     const float sgn = conj ? -1.0f : 1.0f;
 
-    // modes z and y run as full 32 x 32 x 32 products: everything beyond the actual lengths is zero
-    for (int e = tid; e < kSmallMax * kPitch; e += kSmallThreads) {
-        my[e] = make_float2(0.f, 0.f);
-        mz[e] = make_float2(0.f, 0.f);
-        S[e] = make_float2(0.f, 0.f);
-        T[e] = make_float2(0.f, 0.f);
-    }
-    __syncthreads();
-    if (tid < nx) mx[tid] = entry(Mx, kx_i, tid, sgn);
-    // (consecutive threads take consecutive k: the planes are contiguous along k)
-    for (int e = tid; e < ky * ny; e += kSmallThreads) my[(e % ky) * kPitch + e / ky] = entry(My, e % ky, e / ky, sgn);
-    for (int e = tid; e < kz * nz; e += kSmallThreads) mz[(e % kz) * kPitch + e / kz] = entry(Mz, e % kz, e / kz, sgn);
+    // The kernel is a chain of memory latencies, so everything it reads from global memory is
+    // requested first, in one go: this thread's entry of My and of Mz, its entry of the Mx row and the
+    // whole column in[:, b, c] of its slab element (b, c) -- up to 32 independent loads in flight.
+    // Thread t is element (b, c) = (t / 32, t % 32) of the zero-padded 32 x 32 slab and entry
+    // (k, n) = (t % 32, t / 32) of the zero-padded matrices (consecutive threads, consecutive k: the
+    // planes are contiguous along k).
+    const int b = tid >> 5, c = tid & 31;
+    const bool live = b < ny && c < nz;
+    const int64_t plane = (int64_t)ny * nz;
+    const float2* col = in + (live ? (int64_t)b * nz + c : 0);
+    float2 xin[kSmallMax];
+#pragma unroll
+    for (int a = 0; a < kSmallMax; ++a) xin[a] = col[(int64_t)(a < nx ? a : nx - 1) * plane];     // (rows past nx: re-read, weight 0)
+    const int mk = tid & 31, mn = tid >> 5;
+    const float2 ey = (mk < ky && mn < ny) ? entry(My, mk, mn, sgn) : make_float2(0.f, 0.f);
+    const float2 ez = (mk < kz && mn < nz) ? entry(Mz, mk, mn, sgn) : make_float2(0.f, 0.f);
+    if (tid < kSmallMax) mx[tid] = tid < nx ? entry(Mx, kx_i, tid, sgn) : make_float2(0.f, 0.f);
+    my[mk * kPitch + mn] = ey;
+    mz[mk * kPitch + mn] = ez;
     __syncthreads();
 
-    // 1. mode x for this k_x: consecutive threads read consecutive elements of each input plane
-    const int plane = ny * nz;
-    for (int e = tid; e < plane; e += kSmallThreads) {
+    // 1. mode x for this k_x, from the registers; elements outside the tensor are the zero padding that
+    // the 32 x 32 x 32 products below rely on
+    {
         float2 acc = make_float2(0.f, 0.f);
-#pragma unroll 8
-        for (int a = 0; a < nx; ++a) acc = cmul_add(acc, mx[a], in[(int64_t)a * plane + e]);   // 8 loads in flight
-        S[(e / nz) * kPitch + e % nz] = acc;
+#pragma unroll
+        for (int a = 0; a < kSmallMax; ++a) acc = cmul_add(acc, mx[a], xin[a]);
+        S[b * kPitch + c] = live ? acc : make_float2(0.f, 0.f);
     }
     __syncthreads();
 
