@@ -942,7 +942,17 @@ __global__ __launch_bounds__(512, 1) void k_fft_ss(FftStridedArgs a, DeviceMatri
                 }
     };
 
-    auto stage1 = [&](int set, int slot, int buf) {      // set: compile-time constant at every call
+    // ---- one barrier interval: stage 2 of slot g interleaved with stage 1 of slot g + 1 ----------------
+    // The two are independent (different accumulators, different ring buffers), and each alone leaves
+    // the matrix pipe idle while it waits for LDS operands (stage 1: twelve MFMAs per operand read, then
+    // the twiddles and the ring writes without any).  So they are issued as one stream: a group of
+    // stage-2 MFMAs, then the stage-1 group whose operands were requested one group earlier, and so on;
+    // sched_barrier keeps the compiler from undoing the order.
+    constexpr int G1 = NAB * (NS1 / 4);                // stage-1 groups: 12 * CV MFMAs each
+    constexpr int G2 = KS * NBB;                       // stage-2 groups: 4 * PPW * CV MFMAs each
+    static_assert(G2 >= G1 + 2, "enough stage-2 groups to interleave stage 1 and its tail");
+    auto interval = [&](int set, int slot2, int buf2, int slot1, int buf1) {      // set: compile-time constant
+        // stage 1 state
         f32x4 p1[NAB][CV], p2[NAB][CV], p3[NAB][CV];
 #pragma unroll
         for (int ab = 0; ab < NAB; ++ab)
@@ -952,84 +962,117 @@ __global__ __launch_bounds__(512, 1) void k_fft_ss(FftStridedArgs a, DeviceMatri
                 p2[ab][h] = f32x4{0.f, 0.f, 0.f, 0.f};
                 p3[ab][h] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
+        f32x4 fr, fi, fs;                              // stage-1 operands of the next group
+        auto read_fa = [&](int g1) {
+            const int sq = g1 / NAB, ab = g1 % NAB;
+            const f32x4* t = faT + ((ab * (NS1 / 4) + sq) * 3) * 64 + lane;
+            fr = t[0], fi = t[64], fs = t[128];
+        };
+        auto group1 = [&](int g1) {
+            const int sq = g1 / NAB, ab = g1 % NAB;
+            const f32x4 r = fr, i = fi, q = fs;
 #pragma unroll
-        for (int sq = 0; sq < NS1 / 4; ++sq)
+            for (int s4 = 0; s4 < 4; ++s4) {
+                const vec x = xs[set][4 * sq + s4];
 #pragma unroll
-            for (int ab = 0; ab < NAB; ++ab) {
-                const f32x4* t = faT + ((ab * (NS1 / 4) + sq) * 3) * 64 + lane;
-                const f32x4 fr = t[0], fi = t[64], fs = t[128];
-#pragma unroll
-                for (int s4 = 0; s4 < 4; ++s4) {
-                    const vec x = xs[set][4 * sq + s4];
-#pragma unroll
-                    for (int h = 0; h < CV; ++h) {
-                        p1[ab][h] = mfma(fr[s4], x[2 * h], p1[ab][h]);
-                        p2[ab][h] = mfma(fi[s4], x[2 * h + 1], p2[ab][h]);
-                        p3[ab][h] = mfma(fs[s4], x[2 * h] + x[2 * h + 1], p3[ab][h]);
-                    }
+                for (int h = 0; h < CV; ++h) {
+                    p1[ab][h] = mfma(r[s4], x[2 * h], p1[ab][h]);
+                    p2[ab][h] = mfma(i[s4], x[2 * h + 1], p2[ab][h]);
+                    p3[ab][h] = mfma(q[s4], x[2 * h] + x[2 * h + 1], p3[ab][h]);
                 }
             }
-        const int beta = SB * slot + ub;
-        vec* zw = Zs + (size_t)buf * (A * PK) + (ug * SB + ub) * 16 + l16;
+        };
+        const int beta = SB * slot1 + ub;
+        f32x4 tq[NAB][2];                              // twiddles of this lane's k_a: 32 contiguous bytes of T[beta][k_a] per block
+        auto read_tw = [&]() {
 #pragma unroll
-        for (int ab = 0; ab < NAB; ++ab) {
-            // the twiddles of this lane's four k_a are 32 contiguous bytes of T[beta][k_a]
-            const f32x4* tq = reinterpret_cast<const f32x4*>(tws + beta * A + 16 * ab + 4 * lq);
-            const f32x4 t01 = tq[0], t23 = tq[1];
+            for (int ab = 0; ab < NAB; ++ab) {
+                const f32x4* t = reinterpret_cast<const f32x4*>(tws + beta * A + 16 * ab + 4 * lq);
+                tq[ab][0] = t[0];
+                tq[ab][1] = t[1];
+            }
+        };
+        vec* zw = Zs + (size_t)buf1 * (A * PK) + (ug * SB + ub) * 16 + l16;
+        auto tail1 = [&](int ab) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int ka = 16 * ab + 4 * lq + v;
-                const float2 t = v == 0 ? make_float2(t01[0], t01[1]) : v == 1 ? make_float2(t01[2], t01[3])
-                               : v == 2 ? make_float2(t23[0], t23[1]) : make_float2(t23[2], t23[3]);
+                const float tx = tq[ab][v / 2][2 * (v & 1)], ty = tq[ab][v / 2][2 * (v & 1) + 1];
                 vec z;
 #pragma unroll
                 for (int h = 0; h < CV; ++h) {
                     const float re = p1[ab][h][v] - p2[ab][h][v];
                     const float im = p3[ab][h][v] - p1[ab][h][v] - p2[ab][h][v];
-                    z[2 * h] = re * t.x - im * t.y;
-                    z[2 * h + 1] = re * t.y + im * t.x;
+                    z[2 * h] = re * tx - im * ty;
+                    z[2 * h + 1] = re * ty + im * tx;
                 }
                 zw[ka * PK] = z;
             }
-        }
-    };
-
-    auto stage2 = [&](int slot, int buf) {
-        const vec* zr = Zs + (size_t)buf * (A * PK) + lq * 16 + l16;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            vec z[PPW];
-            float zn[PPW][CV];
+        };
+        // stage 2 state
+        const vec* zr = Zs + (size_t)buf2 * (A * PK) + lq * 16 + l16;
+        vec z[PPW];
+        float zn[PPW][CV];
+        f32x4 fq[NBB / 2];
+        auto read_z = [&](int ks) {
 #pragma unroll
             for (int j = 0; j < PPW; ++j) {
                 const int p = wave + NW * j;
                 z[j] = zr[(p / CH) * PK + ((p % CH) * SB + 4 * ks) * 16];
-#pragma unroll
-                for (int h = 0; h < CV; ++h) zn[j][h] = -z[j][2 * h + 1];
             }
-            const f32x4* t = fbT + (size_t)(slot * KS + ks) * (NBB / 2) * 64 + lane;
-            f32x4 fq[NBB / 2];
+            const f32x4* t = fbT + (size_t)(slot2 * KS + ks) * (NBB / 2) * 64 + lane;
 #pragma unroll
             for (int q = 0; q < NBB / 2; ++q) fq[q] = t[q * 64];
-#pragma unroll
-            for (int kbb = 0; kbb < NBB; ++kbb) {
-                const float fr = fq[kbb / 2][2 * (kbb & 1)], fi = fq[kbb / 2][2 * (kbb & 1) + 1];
-#pragma unroll
-                for (int j = 0; j < PPW; ++j)
-#pragma unroll
-                    for (int h = 0; h < CV; ++h) wr[j][h][kbb] = mfma(fr, z[j][2 * h], wr[j][h][kbb]);
+        };
+        auto group2 = [&](int g2) {
+            const int kbb = g2 % NBB;
+            if (kbb == 0) {
 #pragma unroll
                 for (int j = 0; j < PPW; ++j)
 #pragma unroll
-                    for (int h = 0; h < CV; ++h) wi[j][h][kbb] = mfma(fr, z[j][2 * h + 1], wi[j][h][kbb]);
+                    for (int h = 0; h < CV; ++h) zn[j][h] = -z[j][2 * h + 1];
+            }
+            const float r = fq[kbb / 2][2 * (kbb & 1)], i = fq[kbb / 2][2 * (kbb & 1) + 1];
 #pragma unroll
-                for (int j = 0; j < PPW; ++j)
+            for (int j = 0; j < PPW; ++j)
 #pragma unroll
-                    for (int h = 0; h < CV; ++h) wr[j][h][kbb] = mfma(fi, zn[j][h], wr[j][h][kbb]);
+                for (int h = 0; h < CV; ++h) wr[j][h][kbb] = mfma(r, z[j][2 * h], wr[j][h][kbb]);
 #pragma unroll
-                for (int j = 0; j < PPW; ++j)
+            for (int j = 0; j < PPW; ++j)
 #pragma unroll
-                    for (int h = 0; h < CV; ++h) wi[j][h][kbb] = mfma(fi, z[j][2 * h], wi[j][h][kbb]);
+                for (int h = 0; h < CV; ++h) wi[j][h][kbb] = mfma(r, z[j][2 * h + 1], wi[j][h][kbb]);
+#pragma unroll
+            for (int j = 0; j < PPW; ++j)
+#pragma unroll
+                for (int h = 0; h < CV; ++h) wr[j][h][kbb] = mfma(i, zn[j][h], wr[j][h][kbb]);
+#pragma unroll
+            for (int j = 0; j < PPW; ++j)
+#pragma unroll
+                for (int h = 0; h < CV; ++h) wi[j][h][kbb] = mfma(i, z[j][2 * h], wi[j][h][kbb]);
+        };
+
+        read_z(0);
+        read_fa(0);
+        __builtin_amdgcn_sched_barrier(0);
+        // groups of stage 2 in order; after group n (n < G1) the stage-1 group n, whose operands were
+        // requested before stage-2 group n; then the twiddle reads, and the tail split over NAB groups
+#pragma unroll
+        for (int g2 = 0; g2 < G2; ++g2) {
+            if (g2 % NBB == 0 && g2 > 0) {
+                // (the previous k-step's last group has been issued: its operands may be replaced)
+                read_z(g2 / NBB);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            group2(g2);
+            __builtin_amdgcn_sched_barrier(0);
+            if (g2 < G1) {
+                group1(g2);
+                if (g2 + 1 < G1) read_fa(g2 + 1);
+                else read_tw();
+                __builtin_amdgcn_sched_barrier(0);
+            } else if (g2 - G1 < NAB) {
+                tail1(g2 - G1);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
@@ -1061,22 +1104,13 @@ __global__ __launch_bounds__(512, 1) void k_fft_ss(FftStridedArgs a, DeviceMatri
         }
     };
 
-    // Slots are numbered g = 0, 1, .. across the tiles of this workgroup; barrier B_g separates the ring
-    // writes of slot g from its reads.  Between B_g and B_(g+1) a wave has two independent pieces of
-    // work: stage 2 of slot g and stage 1 of slot g + 1 (which fills the other ring buffer, last read
-    // before B_g).  The two waves of a SIMD (w and w + 4) take them in opposite order, so that one of
-    // them has matrix work while the other waits for its data, applies the twiddles and writes the ring:
-    //   waves 0..3:  S1(0) | B_0 S2(0) S1(1) | B_1 S2(1) S1(2) | ..        body(g) = B_g, S2(g), S1(g+1)
-    //   waves 4..7:  S1(0) B_0 S1(1) | S2(0) B_1 S1(2) | S2(1) B_2 S1(3) | ..   body(g) = S2(g), B_(g+1), S1(g+2)
-    // One loop body serves both (the barrier sits before or after stage 2, stage 1 looks one or two
-    // slots ahead); waves 4..7 keep slot g's data in register set (g + 1) % 2 instead of g % 2, which
-    // makes the set index of the body the same compile-time number for both.
-    const bool late = wave >= 4;
-    const int ahead = late ? 2 : 1;
+    // Slots are numbered g = 0, 1, .. across the tiles of this workgroup.  One barrier per slot: before
+    // it every wave has written slot g into ring buffer g % 2 (stage 1) and finished reading that buffer
+    // for slot g - 2; after it, stage 2 of slot g runs interleaved with stage 1 of slot g + 1.
     const int64_t mine = first < ntiles ? (ntiles - first + nwg - 1) / nwg : 0;      // tiles of this workgroup
     const int64_t G = mine * NSLOT;
-    // Requests and stage-1 steps past the last slot are not skipped: they re-read the last tile and
-    // write ring buffers nobody reads (every access in bounds).  With unconditional loads the compiler
+    // Requests and the stage-1 step past the last slot are not skipped: they re-read the last tile and
+    // write a ring buffer nobody reads (every access in bounds).  With unconditional loads the compiler
     // can count how many younger requests may still be in flight when a register set is used; a
     // conditional request made it wait for all of them, the one issued a moment ago included.
     auto request_slot = [&](int set, int64_t g) {      // called with g = 0, 1, 2, .. in this order
@@ -1086,33 +1120,65 @@ __global__ __launch_bounds__(512, 1) void k_fft_ss(FftStridedArgs a, DeviceMatri
     };
     if (G == 0) return;                            // (whole workgroup, before any barrier)
     clear_acc();
-    if (!late) {
-        request_slot(0, 0);
-        request_slot(1, 1);
-    } else {
-        request_slot(1, 0);
-        request_slot(0, 1);
-    }
+    request_slot(0, 0);
+    request_slot(1, 1);
     __syncthreads();                               // tables
-    if (!late) {
-        stage1(0, 0, 0);
+    {
+        // slot 0 alone: stage 1 with nothing to interleave (a zero-weight stage 2 on the empty ring would
+        // need the ring cleared); the same code as in `interval`, without the stage-2 pieces
+        f32x4 p1[NAB][CV], p2[NAB][CV], p3[NAB][CV];
+#pragma unroll
+        for (int ab = 0; ab < NAB; ++ab)
+#pragma unroll
+            for (int h = 0; h < CV; ++h) {
+                p1[ab][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+                p2[ab][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+                p3[ab][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+        for (int sq = 0; sq < NS1 / 4; ++sq)
+#pragma unroll
+            for (int ab = 0; ab < NAB; ++ab) {
+                const f32x4* t = faT + ((ab * (NS1 / 4) + sq) * 3) * 64 + lane;
+                const f32x4 fr = t[0], fi = t[64], fs = t[128];
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4) {
+                    const vec x = xs[0][4 * sq + s4];
+#pragma unroll
+                    for (int h = 0; h < CV; ++h) {
+                        p1[ab][h] = mfma(fr[s4], x[2 * h], p1[ab][h]);
+                        p2[ab][h] = mfma(fi[s4], x[2 * h + 1], p2[ab][h]);
+                        p3[ab][h] = mfma(fs[s4], x[2 * h] + x[2 * h + 1], p3[ab][h]);
+                    }
+                }
+            }
+        vec* zw = Zs + (ug * SB + ub) * 16 + l16;
+#pragma unroll
+        for (int ab = 0; ab < NAB; ++ab) {
+            const f32x4* t = reinterpret_cast<const f32x4*>(tws + ub * A + 16 * ab + 4 * lq);
+            const f32x4 t01 = t[0], t23 = t[1];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int ka = 16 * ab + 4 * lq + v;
+                const float tx = (v < 2 ? t01 : t23)[2 * (v & 1)], ty = (v < 2 ? t01 : t23)[2 * (v & 1) + 1];
+                vec z;
+#pragma unroll
+                for (int h = 0; h < CV; ++h) {
+                    const float re = p1[ab][h][v] - p2[ab][h][v];
+                    const float im = p3[ab][h][v] - p1[ab][h][v] - p2[ab][h][v];
+                    z[2 * h] = re * tx - im * ty;
+                    z[2 * h + 1] = re * ty + im * tx;
+                }
+                zw[ka * PK] = z;
+            }
+        }
         request_slot(0, 2);
-    } else {
-        stage1(1, 0, 0);
-        request_slot(1, 2);
-        __syncthreads();                           // B_0
-        stage1(0, 1, 1);
-        request_slot(0, 3);
     }
-    auto body = [&](int set, int64_t g) {
-        if (!late) __syncthreads();                // B_g
-        stage2((int)(g % NSLOT), (int)(g & 1));
-        if (late) __syncthreads();                 // B_(g+1)
-        const int64_t g1 = g + ahead;
-        stage1(set, (int)(g1 % NSLOT), (int)(g1 & 1));
+    auto body = [&](int set, int64_t g) {          // set: register set of slot g + 1
+        __syncthreads();
+        const int64_t g1 = g + 1;
+        interval(set, (int)(g % NSLOT), (int)(g & 1), (int)(g1 % NSLOT), (int)(g1 & 1));
         request_slot(set, g1 + 2);
-        // (after stage 1, so that its wait for the data requested two slots ago does not have to count
-        // these stores)
         if (g % NSLOT == NSLOT - 1) {
             store_tile();
             clear_acc();
@@ -1123,7 +1189,6 @@ __global__ __launch_bounds__(512, 1) void k_fft_ss(FftStridedArgs a, DeviceMatri
         body(1, g);
         body(0, g + 1);
     }
-    if (!late) __syncthreads();                    // B_G, which waves 4..7 passed inside their last body
 }
 
 // ---- strided contraction with a small square matrix ----------------------------------------------
