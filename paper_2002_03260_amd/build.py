@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdft3d.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["dft3d_kernels.hip", "dft3d_bf16x3.hip", "dft3d_f64.hip", "dft3d_fft_reg.hip", "dft3d_small.hip",
+SOURCES = ["dft3d_kernels.hip", "dft3d_bf16x3.hip", "dft3d_f64.hip", "dft3d_fft_reg.hip", "dft3d_fft_nested.hip", "dft3d_small.hip",
            "dft3d_noalloc.hip", "dft3d_plan.cpp", "dft3d_generate.cpp"]
 HEADERS = [os.path.join(CSRC, "dft3d_internal.h"), os.path.join(ROOT, "include", "dft3d.h")]
 

@@ -1,0 +1,247 @@
+// FFT formulation with the second factor split once more: N = 16 * B with B = C * 16, C = 2, 4 or 8
+// (512 = 16 * 32, 1024 = 16 * 64, 2048 = 16 * 128).
+//
+// Eq. 13 - 16 for one axis with n = B*l + b, k = k_a + 16*k2 read
+//     Z[k_a, b]  = T[k_a, b] * sum_l F16[k_a, l] x[B*l + b]
+//     X[k_a + 16*k2] = sum_b FB[k2, b] Z[k_a, b]
+// and cost 6 * (16 + B) matrix-core flop per point.  The B-point transform of the second line is a
+// DFT like the whole one, so the same split applies to it: b = 16*c + beta, k2 = k_c + C*k_b gives
+//     FB[k2, b] = w_C^(c k_c) * w_B^(k_c beta) * F16[k_b, beta]
+//     Y[k_a, k_c, beta] = w_B^(k_c beta) * sum_c w_C^(c k_c) Z[k_a, 16*c + beta]      (C-point butterflies)
+//     X[k_a + 16*(k_c + C*k_b)] = sum_beta F16[k_b, beta] Y[k_a, k_c, beta]
+// Both matrix stages are 16-point now (6 * 32 flop per point on the matrix cores, a third of the
+// 32 x 64 split at N = 2048) and the C-point stage in the middle is plain vector arithmetic on values a
+// lane already holds.  Every table the kernel needs is part of the plan of a 16 x B split: F16 is its
+// first-stage matrix, T its twiddle table, w_B^(k_c beta) = FB[k_c, beta].
+//
+// BACKWARD runs the forward transform on data with real and imaginary parts exchanged, and exchanges
+// them again in the result: with s(z) = i * conj(z), DFT(s(x)) = s(IDFT(x)).  The exchange is a choice
+// of register names, so the inverse costs exactly what the forward transform costs.
+#include <hip/hip_runtime.h>
+
+#include "dft3d_internal.h"
+
+namespace dft3d {
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// In-place C-point forward DFT (w = exp(-2 pi i / C)) of C complex values held as separate real and
+// imaginary parts; T is float or a vector of floats (element-wise).  Output k at index k.
+template <int C, typename T>
+__device__ __forceinline__ void small_dft(T (&r)[C], T (&i)[C])
+{
+    static_assert(C == 1 || C == 2 || C == 4 || C == 8, "radix");
+    if constexpr (C == 2) {
+        const T r0 = r[0] + r[1], i0 = i[0] + i[1], r1 = r[0] - r[1], i1 = i[0] - i[1];
+        r[0] = r0, i[0] = i0, r[1] = r1, i[1] = i1;
+    } else if constexpr (C == 4) {
+        const T t0r = r[0] + r[2], t0i = i[0] + i[2], t1r = r[0] - r[2], t1i = i[0] - i[2];
+        const T t2r = r[1] + r[3], t2i = i[1] + i[3], t3r = r[1] - r[3], t3i = i[1] - i[3];
+        r[0] = t0r + t2r, i[0] = t0i + t2i;
+        r[2] = t0r - t2r, i[2] = t0i - t2i;
+        r[1] = t1r + t3i, i[1] = t1i - t3r;        // t1 + (-i) t3
+        r[3] = t1r - t3i, i[3] = t1i + t3r;
+    } else if constexpr (C == 8) {
+        T er[4] = {r[0], r[2], r[4], r[6]}, ei[4] = {i[0], i[2], i[4], i[6]};
+        T orr[4] = {r[1], r[3], r[5], r[7]}, oi[4] = {i[1], i[3], i[5], i[7]};
+        small_dft<4>(er, ei);
+        small_dft<4>(orr, oi);
+        constexpr float h = 0.70710678118654752440f;
+        // w^k o[k]:  w^1 = (1 - i) h,  w^2 = -i,  w^3 = (-1 - i) h
+        const T p0r = orr[0], p0i = oi[0];
+        const T p1r = (orr[1] + oi[1]) * h, p1i = (oi[1] - orr[1]) * h;
+        const T p2r = oi[2], p2i = -orr[2];
+        const T p3r = (oi[3] - orr[3]) * h, p3i = -(orr[3] + oi[3]) * h;
+        r[0] = er[0] + p0r, i[0] = ei[0] + p0i, r[4] = er[0] - p0r, i[4] = ei[0] - p0i;
+        r[1] = er[1] + p1r, i[1] = ei[1] + p1i, r[5] = er[1] - p1r, i[5] = ei[1] - p1i;
+        r[2] = er[2] + p2r, i[2] = ei[2] + p2i, r[6] = er[2] - p2r, i[6] = ei[2] - p2i;
+        r[3] = er[3] + p3r, i[3] = ei[3] + p3i, r[7] = er[3] - p3r, i[7] = ei[3] - p3i;
+    }
+}
+
+// ---- contiguous axis -------------------------------------------------------------------------------
+// ONE wavefront transforms one row of N points in registers, with no barrier in the row loop; the
+// operand layouts of v_mfma_f32_16x16x4_f32 do the transposition between the two matrix stages:
+//   stage 1, transposed:  D[beta, k_a] = sum_l x[B*l + 16*c + beta] F16[l, k_a]  for each c,
+//     A operand = data straight from global memory (lane: beta = lane % 16, l = 4*s + lane / 16),
+//     D register v of a lane = (beta = 4*(lane/16) + v, k_a = lane % 16); twiddle on D;
+//   C-point butterflies across the C accumulators of a lane, then w_B^(k_c beta);
+//   stage 3:  D[k_b, k_a] = sum_beta F16[k_b, beta] Y[k_a, k_c, beta] for each k_c: register v of the
+//     butterfly output is the B operand of k-step v as it stands (lane group g stands for
+//     beta = 4*g + v; a sum does not care about the order of its terms), the A operand is F16 loaded
+//     once in that order.  D register v = (k_b = 4*(lane/16) + v, k_a = lane % 16): the output index
+//     k_a + 16*k_c + 16*C*k_b runs along the lanes, so loads and stores are 128-byte segments.
+// Three real products per complex product in both matrix stages: 24 * C matrix instructions per row.
+template <int C, bool SWAP, int WPC>
+__global__ __launch_bounds__(256, WPC) void k_fft_zn(const float2* __restrict__ in, float2* __restrict__ out,
+                                                    int64_t nrows, DeviceMatrix FA, DeviceMatrix FB,
+                                                    const float2* __restrict__ Tw, float scale)
+{
+    constexpr int B = 16 * C, N = 16 * B;
+    __shared__ float2 tw1s[C * 4 * 64];      // [c][v][lane]: T[k_a = lane%16][16*c + 4*(lane/16) + v]
+    __shared__ __align__(16) float2 tw2s[C * 16];         // [k_c][beta]: w_B^(k_c beta)
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int l16 = lane & 15, lq = lane >> 4;
+
+    for (int e = tid; e < C * 4 * 64; e += 256) {
+        const int ln = e & 63, v = (e >> 6) & 3, c = e >> 8;
+        tw1s[e] = Tw[(ln & 15) * B + 16 * c + 4 * (ln >> 4) + v];
+    }
+    for (int e = tid; e < C * 16; e += 256) {
+        const int beta = e & 15, kc = e >> 4;
+        tw2s[e] = make_float2(FB.re[beta * FB.ld + kc], FB.im[beta * FB.ld + kc]);    // FB[k][n] at plane[n * ld + k]
+    }
+    __syncthreads();
+
+    // (wave-uniform, and told so: row addresses are then a scalar base plus a 32-bit lane offset)
+    const int64_t wave = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    if (wave >= nrows) return;                    // after the only barrier
+
+    // stage-1 B operand F16[k_a = l16][l = 4*s + lq]; stage-3 A operand scale * F16[k_b = l16][beta = 4*lq + v]
+    float fa_r[4], fa_i[4], fa_s[4], fb_r[4], fb_i[4], fb_s[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int ia = (4 * s + lq) * FA.ld + l16;
+        fa_r[s] = FA.re[ia];
+        fa_i[s] = FA.im[ia];
+        fa_s[s] = fa_r[s] + fa_i[s];
+        const int ib = (4 * lq + s) * FA.ld + l16;
+        fb_r[s] = FA.re[ib] * scale;
+        fb_i[s] = FA.im[ib] * scale;
+        fb_s[s] = fb_r[s] + fb_i[s];
+    }
+
+    const unsigned ld_off = B * lq + l16;         // + 4*B*s + 16*c
+    const unsigned st_off = l16 + 16 * C * 4 * lq;     // + 16*k_c + 16*C*v
+    f32x2 x[C][4];
+    auto load_block = [&](int64_t row, int c) {
+        const f32x2* src = reinterpret_cast<const f32x2*>(in) + row * N + 16 * c;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) x[c][s] = __builtin_nontemporal_load(&(src + 4 * B * s)[ld_off]);
+    };
+#pragma unroll
+    for (int c = 0; c < C; ++c) load_block(wave, c);
+
+    // Order of the memory instructions of a row: the requests for the wave's NEXT row (each block as soon
+    // as the first stage has consumed it), then the stores of this row.  The counter a wave waits on
+    // retires loads and stores in issue order, so data that was requested before the stores can be waited
+    // for without waiting for a single store; requested after them (where more registers would be free)
+    // every row would begin with the wave idle until all its stores had been acknowledged by memory.
+    auto transform_row = [&](int64_t row) {
+        const int64_t next = row + nwaves < nrows ? row + nwaves : row;    // past the end: a harmless re-read
+        // the tables are loop invariant, but keeping them in registers across rows is exactly what does
+        // not fit: make the compiler read them again in every row
+        asm volatile("" ::: "memory");
+        f32x4 zr[C], zi[C];
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            f32x4 p1 = {0.f, 0.f, 0.f, 0.f}, p2 = p1, p3 = p1;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const float xr = SWAP ? x[c][s].y : x[c][s].x, xi = SWAP ? x[c][s].x : x[c][s].y;
+                p1 = mfma(xr, fa_r[s], p1);
+                p2 = mfma(xi, fa_i[s], p2);
+                p3 = mfma(xr + xi, fa_s[s], p3);
+            }
+            load_block(next, c);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float2 t = tw1s[(c * 4 + v) * 64 + lane];
+                const float a = p1[v] - p2[v], b = p3[v] - p1[v] - p2[v];
+                zr[c][v] = a * t.x - b * t.y;
+                zi[c][v] = a * t.y + b * t.x;
+            }
+            __builtin_amdgcn_sched_barrier(0);     // keeps the requests where they are
+        }
+        small_dft<C>(zr, zi);
+#pragma unroll
+        for (int kc = 1; kc < C; ++kc) {
+            const f32x4* t4 = reinterpret_cast<const f32x4*>(&tw2s[kc * 16 + 4 * lq]);   // four twiddles: beta = 4*lq + v
+            const f32x4 t01 = t4[0], t23 = t4[1];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float tx = (v < 2 ? t01 : t23)[2 * (v & 1)], ty = (v < 2 ? t01 : t23)[2 * (v & 1) + 1];
+                const float a = zr[kc][v], b = zi[kc][v];
+                zr[kc][v] = a * tx - b * ty;
+                zi[kc][v] = a * ty + b * tx;
+            }
+        }
+        f32x2* dst = reinterpret_cast<f32x2*>(out) + row * N;
+#pragma unroll
+        for (int kc = 0; kc < C; ++kc) {
+            f32x4 q1 = {0.f, 0.f, 0.f, 0.f}, q2 = q1, q3 = q1;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                q1 = mfma(fb_r[v], zr[kc][v], q1);
+                q2 = mfma(fb_i[v], zi[kc][v], q2);
+                q3 = mfma(fb_s[v], zr[kc][v] + zi[kc][v], q3);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float re = q1[v] - q2[v], im = q3[v] - q1[v] - q2[v];
+                __builtin_nontemporal_store(SWAP ? f32x2{im, re} : f32x2{re, im}, &(dst + 16 * kc + 16 * C * v)[st_off]);
+            }
+        }
+    };
+    // The first row runs outside the loop so that the loop is entered in the state every iteration leaves
+    // behind (requests, then stores): with the prologue's requests as a second way in, the waits at the
+    // top of the loop would have to cover that case too and would wait for stores.
+    transform_row(wave);
+    // (the requests of that first row must stay where they are, in front of its stores: an empty
+    // statement that names their registers keeps the compiler from moving them behind the stores into
+    // the path that enters the loop)
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) asm volatile("" : "+v"(x[c][s]));
+    for (int64_t row = wave + nwaves; row < nrows; row += nwaves) transform_row(row);
+}
+
+template <int C, int WPC>
+hipError_t launch_zn_inst(const float2* in, float2* out, int64_t nrows, const DeviceMatrix& FA, const DeviceMatrix& FB,
+                          const float2* Tw, float scale, int conj, hipStream_t stream)
+{
+    // persistent waves: WPC workgroups of four per CU, fewer when there are fewer rows
+    const int64_t want = (nrows + 3) / 4;
+    const int64_t blocks = want < 256 * WPC ? want : 256 * WPC;
+    if (conj)
+        hipLaunchKernelGGL((k_fft_zn<C, true, WPC>), dim3((unsigned)blocks), dim3(256), 0, stream, in, out, nrows, FA, FB, Tw,
+                           scale);
+    else
+        hipLaunchKernelGGL((k_fft_zn<C, false, WPC>), dim3((unsigned)blocks), dim3(256), 0, stream, in, out, nrows, FA, FB, Tw,
+                           scale);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool fft_zn_supported(int A, int B)
+{
+    return A == 16 && (B == 32 || B == 64 || B == 128);
+}
+
+hipError_t launch_fft_zn(const float2* in, float2* out, int64_t nrows, int A, int B, const DeviceMatrix& FA,
+                         const DeviceMatrix& FB, const float2* Tw, float scale, int conj, hipStream_t stream)
+{
+    if (nrows <= 0) return hipSuccess;
+    // the kernel indexes the stage matrices and the twiddle table without bounds checks
+    if (A != 16 || FA.K != 16 || FA.N != 16 || FB.K != B || FB.N != B || !Tw) return hipErrorInvalidValue;
+    // three workgroups per CU where the registers allow (512^3: 0.383 -> 0.375 ms)
+    if (B == 32) return launch_zn_inst<2, 3>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (B == 64) return launch_zn_inst<4, 3>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (B == 128) return launch_zn_inst<8, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace dft3d

@@ -133,6 +133,13 @@ hipError_t launch_fft_zr(const float2* in, float2* out, int64_t nrows, int A, in
                          const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
                          int conj, hipStream_t stream);
 
+// The same pass with the second factor split once more (16 x (C*16): two 16-point matrix stages around
+// C-point butterflies), one wavefront per row; launch_fft_z uses it for the splits it covers.
+bool fft_zn_supported(int A, int B);
+hipError_t launch_fft_zn(const float2* in, float2* out, int64_t nrows, int A, int B,
+                         const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
+                         int conj, hipStream_t stream);
+
 // ---- fused strided-axis FFT-formulation pass ------------------------------------------------
 // Tensor viewed as [O][A*B][I]; one launch = both stages, twiddle and natural order along the
 // middle index.  I must be a multiple of 16; available for a fixed set of (A, B).

@@ -1434,7 +1434,7 @@ hipError_t launch_fft_z_inst(const float2* in, float2* out, int64_t nrows, const
 
 bool fft_z_supported(int A, int B)
 {
-    return fft_zr_supported(A, B) || (A == 64 && B == 64);
+    return fft_zr_supported(A, B) || fft_zn_supported(A, B) || (A == 64 && B == 64);
 }
 
 hipError_t launch_fft_z(const float2* in, float2* out, int64_t nrows, int A, int B,
@@ -1443,6 +1443,7 @@ hipError_t launch_fft_z(const float2* in, float2* out, int64_t nrows, int A, int
 {
     if (nrows <= 0) return hipSuccess;
     // the register-resident kernels cover every offered split but 64 x 64
+    if (fft_zn_supported(A, B)) return launch_fft_zn(in, out, nrows, A, B, FA, FB, Tw, scale, conj, stream);
     if (fft_zr_supported(A, B)) return launch_fft_zr(in, out, nrows, A, B, FA, FB, Tw, scale, conj, stream);
     if (A == 64 && B == 64) return launch_fft_z_inst<64, 64, 1, 8, 2, 1>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     return hipErrorInvalidValue;

@@ -199,8 +199,11 @@ dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out
     return s;
 }
 
-int64_t default_split(int64_t n)
+int64_t default_split(int64_t n, int axis)
 {
+    // contiguous axis of 1024 or 2048 points: 16 x (C*16), the split whose second factor the fused
+    // kernel splits once more (2048: a third of the matrix-core work of 32 x 64)
+    if (axis == 2 && (n == 1024 || n == 2048)) return 16;
     if ((n & (n - 1)) == 0) {
         int lg = 0;
         while ((int64_t(1) << (lg + 1)) <= n) ++lg;
@@ -669,7 +672,7 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
         }
     } else {
         for (int j = 0; j < 3 && s == DFT3D_OK; ++j) {
-            int64_t A = (split && split[j] > 0) ? split[j] : default_split(n[j]);
+            int64_t A = (split && split[j] > 0) ? split[j] : default_split(n[j], j);
             if (A < 1 || n[j] % A != 0) {
                 set_error("plan_create: split %lld does not divide axis length %lld", (long long)A,
                           (long long)n[j]);

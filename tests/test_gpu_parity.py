@@ -431,7 +431,12 @@ def test_fft_steps_match_oracle_steps(dft, shape, split):
 
 @pytest.mark.parametrize("shape,split", [((5, 7, 256), None), ((16, 9, 512), None), ((3, 3, 1024), None),
                                          ((2, 5, 2048), None), ((1, 3, 4096), None),
-                                         ((4, 4, 512), (2, 2, 16)), ((33, 1, 256), None)])
+                                         ((4, 4, 512), (2, 2, 16)), ((33, 1, 256), None),
+                                         # 512, 1024 and 2048 default to 16 x (C*16) with the second factor split
+                                         # once more inside the kernel; the last case has more rows than the
+                                         # launch has waves.  32 x 32 and 32 x 64 are the kernels without that.
+                                         ((9, 250, 2048), None), ((40, 100, 512), None),
+                                         ((3, 3, 1024), (1, 1, 32)), ((2, 5, 2048), (1, 1, 32))])
 def test_fft_fused_axis_kernel(dft, shape, split):
     """The single-kernel z-axis pass equals first stage + twiddle + second stage + re-ordering."""
     say(f"case fft fused axis {shape} split {split}")
