@@ -373,7 +373,16 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
                 three = (A == 16 and B in (16, 32)) or (ax == 2 and (A, B) == (32, 64))
                 per_cmac = 6.0 if three else 8.0
                 flops = (per_cmac * (A + B) + 6.0) * E
-                if ax != 2 and (A, B) == (32, 64):
+                if ax == 2 and A == 16 and B in (32, 64, 128):
+                    # second factor split once more inside the kernel (B = C*16): two 16-point matrix stages
+                    # with three real products each; the C-point butterflies and both twiddles are vector
+                    # arithmetic and are not counted as matrix-core work
+                    flops = 6.0 * 32 * E
+                elif ax != 2 and (A, B) == (16, 128):
+                    # the same on a strided axis: three real products in the first stage, four in the last
+                    # (whose accumulators are the resident output tile)
+                    flops = (6.0 * 16 + 8.0 * 16) * E
+                elif ax != 2 and (A, B) == (32, 64):
                     # streaming kernel of the strided axes: three real products in the first stage, four
                     # in the second (whose accumulators are the resident output tile)
                     flops = (6.0 * A + 8.0 * B + 6.0) * E

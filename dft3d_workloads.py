@@ -48,7 +48,7 @@ WORKLOADS = {
     "cfg4": Workload("cfg4_kdft_nonuniform_128", 4, (128, 128, 128), KDFT, "uniform",
                      nonuniform=True),
     "cfg5": Workload("cfg5_2048", 5, (2048, 2048, 2048), KDFT, "normal",
-                     splits=((32, 64),) * 3),
+                     splits=((16, 128),) * 3),
 }
 
 # Beyond the five configurations: the paper's two-dimensional size (Section IV, strong-scaling

@@ -224,6 +224,306 @@ hipError_t launch_zn_inst(const float2* in, float2* out, int64_t nrows, const De
     return hipGetLastError();
 }
 
+// ---- strided axes ------------------------------------------------------------------------------------
+// Tensor viewed as [O][N][I]; a tile is all N positions x 16 contiguous columns, the columns being the
+// MFMA column index of both matrix stages (data = B operand, 16 lanes = one 128-byte segment).  Between
+// two matrix stages with the data as B operand the row index of the first result has to become the
+// contraction index of the second, which takes a trip through LDS; and a whole tile of intermediates
+// (N * 16 complex numbers, 256 KiB at N = 2048) does not fit there.  So, as in the streaming kernel of
+// the plain split, what stays resident is the RESULT: each of the eight waves keeps the accumulators of
+// two k_a (all k_c, k_b and columns: 16*C registers of four) and the other stages feed them one slot of
+// four beta at a time through a double-buffered LDS ring:
+//   producer, wave w = (beta = 4*slot + w / 2, half h = w % 2), for c = h, h + 2, ..:
+//       D[k_a, col] = T[k_a, 16*c + beta] * sum_l F16[k_a, l] x[B*l + 16*c + beta, col]
+//       (data straight from global memory, requested one slot ahead into the registers the matrix
+//       instructions have just read), then the (C/2)-point butterflies over its own c:
+//       E_h[m] = sum_c' w_(C/2)^(c' m) D[c = h + 2*c']   ->  ring[h][m][k_a][beta][col]
+//   one barrier
+//   consumer, wave w, k_a = 2*w, 2*w + 1:  reads E_0[m], E_1[m] at (beta = lane / 16, col = lane % 16),
+//       U[m] = E_0[m] + w_C^m E_1[m],  U[m + C/2] = E_0[m] - w_C^m E_1[m]      (the last butterfly level)
+//       Y[k_c] = w_B^(k_c beta) U[k_c]
+//       W[k_a, k_c][k_b, col] += sum_(beta in slot) F16[k_b, beta] Y[k_c][beta, col]   (one k-step, four
+//       real products: two accumulators per output, which is what fits)
+//   after the fourth slot the accumulators are stored to rows k_a + 16*k_c + 16*C*k_b and cleared.
+// Matrix-core work per point: 6*16 (first stage) + 8*16 (last stage) flop, against 6*32 + 8*64 of the
+// streaming kernel for 32 x 64.  One workgroup of eight waves per CU at C = 8.
+template <int C>
+struct FftSnLayout {
+    static constexpr int B = 16 * C, N = 16 * B, CP = C / 2;
+    static constexpr size_t ring_elems = (size_t)2 * CP * 16 * 64;            // one buffer: [h][m][k_a][beta 4][col 16]
+    static constexpr size_t ring_bytes = 2 * ring_elems * 8;
+    static constexpr size_t fa_bytes = 3 * 64 * 16;                            // [re, im, re+im][lane] x (4 k-steps)
+    static constexpr size_t tw1_bytes = (size_t)B * 16 * 8;                    // T[b][k_a]
+    static constexpr size_t tw2_bytes = (size_t)16 * C * 8;                    // w_B^(k_c beta) as [beta][k_c]
+    static constexpr size_t fb_bytes = 4 * 64 * 16;                            // [slot][lane] x (re, im, -im, 0)
+    static constexpr size_t lds_bytes = ring_bytes + fa_bytes + tw1_bytes + tw2_bytes + fb_bytes;
+};
+
+template <int C, bool SWAP, int WPC>
+__global__ __launch_bounds__(512, WPC) void k_fft_sn(FftStridedArgs a, DeviceMatrix FA, DeviceMatrix FB,
+                                                      const float2* __restrict__ Tw, float scale)
+{
+    typedef FftSnLayout<C> L;
+    constexpr int B = L::B, CP = L::CP;
+    static_assert(C == 2 || C == 4 || C == 8, "second factor 32, 64 or 128");
+
+    extern __shared__ __align__(16) unsigned char smem_sn[];
+    f32x2* ring = reinterpret_cast<f32x2*>(smem_sn);
+    f32x4* faT = reinterpret_cast<f32x4*>(smem_sn + L::ring_bytes);
+    float2* tw1 = reinterpret_cast<float2*>(smem_sn + L::ring_bytes + L::fa_bytes);
+    float2* tw2 = reinterpret_cast<float2*>(smem_sn + L::ring_bytes + L::fa_bytes + L::tw1_bytes);
+    f32x4* fbT = reinterpret_cast<f32x4*>(smem_sn + L::ring_bytes + L::fa_bytes + L::tw1_bytes + L::tw2_bytes);
+
+    const float2* __restrict__ X = a.X;
+    float2* __restrict__ Y = a.Y;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, lq = lane >> 4;
+
+    // ---- tables, once per workgroup ------------------------------------------------------------------
+    {
+        float* faF = reinterpret_cast<float*>(faT);
+        for (int e = tid; e < 4 * 64; e += 512) {
+            const int ln = e & 63, s = e >> 6;
+            const int idx = (4 * s + (ln >> 4)) * FA.ld + (ln & 15);         // F16[k_a = ln%16][l = 4*s + ln/16]
+            const float r = FA.re[idx], i = FA.im[idx];
+            faF[(0 * 64 + ln) * 4 + s] = r;
+            faF[(1 * 64 + ln) * 4 + s] = i;
+            faF[(2 * 64 + ln) * 4 + s] = r + i;
+        }
+        for (int e = tid; e < B * 16; e += 512) tw1[(e % B) * 16 + e / B] = Tw[e];      // Tw is T[k_a][b]: transposed here
+        for (int e = tid; e < 16 * C; e += 512) {
+            const int kc = e % C, beta = e / C;
+            tw2[e] = make_float2(FB.re[beta * FB.ld + kc], FB.im[beta * FB.ld + kc]);   // FB[k][n] at plane[n * ld + k]
+        }
+        for (int e = tid; e < 4 * 64; e += 512) {
+            const int ln = e & 63, t = e >> 6;
+            const int idx = (4 * t + (ln >> 4)) * FA.ld + (ln & 15);         // F16[k_b = ln%16][beta = 4*t + ln/16]
+            const float r = FA.re[idx] * scale, i = FA.im[idx] * scale;
+            fbT[e] = f32x4{r, i, -i, 0.f};
+        }
+    }
+
+    // ---- geometry --------------------------------------------------------------------------------------
+    // tile -> (o, y, column block): tiles are visited first, first + nwg, ..; the position is advanced with
+    // carries instead of being divided out of the tile index every time
+    const int64_t ztt = a.Zt;
+    const int64_t per_o = a.Yn * ztt;
+    const int64_t ntiles = a.O * per_o;
+    const int64_t nwg = (int64_t)gridDim.x * gridDim.y;
+    const int64_t first = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    struct Pos {
+        int o, y, zt;                                  // (the host side keeps all three below 2^31)
+    };
+    const int ztt32 = (int)ztt, yn32 = (int)a.Yn;
+    const Pos step = {(int)(nwg / per_o), (int)((nwg % per_o) / ztt), (int)(nwg % ztt)};
+    auto advance = [&](Pos& p) {
+        p.zt += step.zt;
+        if (p.zt >= ztt32) {
+            p.zt -= ztt32;
+            p.y += 1;
+        }
+        p.y += step.y;
+        if (p.y >= yn32) {
+            p.y -= yn32;
+            p.o += 1;
+        }
+        p.o += step.o;
+    };
+    Pos rq = {(int)(first / per_o), (int)((first % per_o) / ztt), (int)(first % ztt)};   // tile of the slot requested next
+    Pos st = rq;                                                                          // tile being accumulated
+    const int64_t inN = a.inN, outN = a.outN;
+    const int64_t mine = first < ntiles ? (ntiles - first + nwg - 1) / nwg : 0;          // tiles of this workgroup
+    const int64_t G = mine * 4;                                                           // slots of this workgroup
+    if (G == 0) return;                                // (whole workgroup, before any barrier)
+
+    // producer unit of this wave
+    const int pb = wave >> 1, ph = wave & 1;
+    const unsigned ld_lane = (unsigned)(B * lq) * (unsigned)inN + (unsigned)l16;
+    f32x2 xs[CP][4];
+    auto request = [&](int slot) {                     // of the tile at rq
+        const float2* src = X + ((int64_t)rq.o * a.inO + (int64_t)rq.y * a.inY + (int64_t)rq.zt * 16) +
+                            (int64_t)(4 * slot + pb + 16 * ph) * inN;
+#pragma unroll
+        for (int cp = 0; cp < CP; ++cp)
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                xs[cp][s] = __builtin_nontemporal_load(
+                    reinterpret_cast<const f32x2*>(&(src + (int64_t)(4 * B * s + 32 * cp) * inN)[ld_lane]));
+    };
+    // Requests past the last slot are not skipped: they re-read the last tile (every access in bounds) and
+    // the producer step that uses them writes a ring buffer nobody reads.  With unconditional loads the
+    // compiler can count how many younger requests may be in flight when the registers are used.
+    auto request_slot = [&](int64_t g) {               // called with g = 0, 1, 2, .. in this order
+        const int slot = (int)(g & 3);
+        if (slot == 0 && g != 0 && g < G) advance(rq);
+        request(slot);
+    };
+
+    f32x4 wr[2][C], wi[2][C];                           // accumulators: [k_a = 2*wave + j][k_c], register v = k_b = 4*lq + v
+    auto clear_acc = [&]() {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int kc = 0; kc < C; ++kc) {
+                wr[j][kc] = f32x4{0.f, 0.f, 0.f, 0.f};
+                wi[j][kc] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+    };
+
+    // ---- producer: slot `slot` (0..3) of the tile whose data sits in xs -> ring buffer `buf`; then the
+    // request for global slot g_next into the same registers
+    auto produce = [&](int slot, int buf, int64_t g_next) {
+        f32x4 zr[CP], zi[CP];
+        const f32x4 fr = faT[lane], fi = faT[64 + lane], fs = faT[128 + lane];
+        f32x4 p1[CP], p2[CP], p3[CP];
+#pragma unroll
+        for (int cp = 0; cp < CP; ++cp) {
+            p1[cp] = f32x4{0.f, 0.f, 0.f, 0.f};
+            p2[cp] = p1[cp];
+            p3[cp] = p1[cp];
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int cp = 0; cp < CP; ++cp) {
+                const float xr = SWAP ? xs[cp][s].y : xs[cp][s].x, xi = SWAP ? xs[cp][s].x : xs[cp][s].y;
+                p1[cp] = mfma(fr[s], xr, p1[cp]);
+                p2[cp] = mfma(fi[s], xi, p2[cp]);
+                p3[cp] = mfma(fs[s], xr + xi, p3[cp]);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        request_slot(g_next);
+        __builtin_amdgcn_sched_barrier(0);
+        const int beta = 4 * slot + pb;
+#pragma unroll
+        for (int cp = 0; cp < CP; ++cp) {
+            // twiddles of this lane's four k_a = 4*lq + v: 32 contiguous bytes of T[b = 16*c + beta][k_a]
+            const f32x4* t = reinterpret_cast<const f32x4*>(tw1 + (16 * (ph + 2 * cp) + beta) * 16 + 4 * lq);
+            const f32x4 t01 = t[0], t23 = t[1];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float tx = (v < 2 ? t01 : t23)[2 * (v & 1)], ty = (v < 2 ? t01 : t23)[2 * (v & 1) + 1];
+                const float re = p1[cp][v] - p2[cp][v], im = p3[cp][v] - p1[cp][v] - p2[cp][v];
+                zr[cp][v] = re * tx - im * ty;
+                zi[cp][v] = re * ty + im * tx;
+            }
+        }
+        if constexpr (CP > 1) small_dft<CP>(zr, zi);
+        f32x2* zw = ring + (size_t)buf * L::ring_elems + (size_t)(ph * CP) * 1024 + pb * 16 + l16;
+#pragma unroll
+        for (int m = 0; m < CP; ++m)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) zw[m * 1024 + (4 * lq + v) * 64] = f32x2{zr[m][v], zi[m][v]};
+    };
+
+    // ---- consumer: slot `slot` of the tile at st from ring buffer `buf`
+    auto consume = [&](int slot, int buf) {
+        __builtin_amdgcn_sched_barrier(0);             // the two steps one after the other: their temporaries share registers
+        const f32x4 f = fbT[slot * 64 + lane];          // F16[k_b = l16][beta = 4*slot + lq]: re, im, -im
+        // w_B^(k_c beta) for this lane's beta: C contiguous complex numbers
+        f32x4 tq[CP];
+        {
+            const f32x4* t = reinterpret_cast<const f32x4*>(tw2 + (4 * slot + lq) * C);
+#pragma unroll
+            for (int q = 0; q < CP; ++q) tq[q] = t[q];
+        }
+        const f32x2* zr0 = ring + (size_t)buf * L::ring_elems + lq * 16 + l16;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const f32x2* zp = zr0 + (2 * wave + j) * 64;
+            float ur[C], ui[C];
+#pragma unroll
+            for (int m = 0; m < CP; ++m) {
+                const f32x2 e0 = zp[m * 1024], e1 = zp[(CP + m) * 1024];
+                // w_C^m e1 (forward): C = 2: 1;  C = 4: 1, -i;  C = 8: 1, (1 - i) h, -i, (-1 - i) h
+                float qr, qi;
+                constexpr float h = 0.70710678118654752440f;
+                const int k8 = m * (8 / C);
+                if (k8 == 0) qr = e1.x, qi = e1.y;
+                else if (k8 == 1) qr = (e1.x + e1.y) * h, qi = (e1.y - e1.x) * h;
+                else if (k8 == 2) qr = e1.y, qi = -e1.x;
+                else qr = (e1.y - e1.x) * h, qi = -(e1.x + e1.y) * h;
+                ur[m] = e0.x + qr, ui[m] = e0.y + qi;
+                ur[m + CP] = e0.x - qr, ui[m + CP] = e0.y - qi;
+            }
+#pragma unroll
+            for (int kc = 1; kc < C; ++kc) {
+                const float tx = tq[kc / 2][2 * (kc & 1)], ty = tq[kc / 2][2 * (kc & 1) + 1];
+                const float re = ur[kc], im = ui[kc];
+                ur[kc] = re * tx - im * ty;
+                ui[kc] = re * ty + im * tx;
+            }
+#pragma unroll
+            for (int kc = 0; kc < C; ++kc) wr[j][kc] = mfma(f[0], ur[kc], wr[j][kc]);
+#pragma unroll
+            for (int kc = 0; kc < C; ++kc) wi[j][kc] = mfma(f[0], ui[kc], wi[j][kc]);
+#pragma unroll
+            for (int kc = 0; kc < C; ++kc) wr[j][kc] = mfma(f[2], ui[kc], wr[j][kc]);
+#pragma unroll
+            for (int kc = 0; kc < C; ++kc) wi[j][kc] = mfma(f[1], ur[kc], wi[j][kc]);
+        }
+    };
+
+    auto store_tile = [&]() {                          // the tile at st
+        // rows k_a + 16*k_c + 16*C*k_b with k_b = 4*lq + v; the lane part needs 64 bits at N = 2048
+        float2* dst = Y + ((int64_t)st.o * a.outO + (int64_t)st.y * a.outY + (int64_t)st.zt * 16) +
+                      ((int64_t)(16 * C * 4 * lq) * outN + l16);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int kc = 0; kc < C; ++kc)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float re = wr[j][kc][v], im = wi[j][kc][v];
+                    __builtin_nontemporal_store(
+                        SWAP ? f32x2{im, re} : f32x2{re, im},
+                        reinterpret_cast<f32x2*>(dst + (int64_t)(2 * wave + j + 16 * kc + 16 * C * v) * outN));
+                }
+    };
+
+    // Slots are numbered g = 0, 1, .. across the tiles of this workgroup.  One barrier per slot: before it
+    // every wave has written slot g into ring buffer g % 2 and finished reading that buffer for slot g - 2;
+    // after it the producer step of slot g + 1 and the consumer step of slot g run.
+    clear_acc();
+    request_slot(0);
+    __syncthreads();                                   // tables
+    produce(0, 0, 1);
+    for (int64_t g = 0; g < G; g += 4) {
+        __syncthreads();
+        produce(1, 1, g + 2);
+        consume(0, 0);
+        __syncthreads();
+        produce(2, 0, g + 3);
+        consume(1, 1);
+        __syncthreads();
+        produce(3, 1, g + 4);
+        consume(2, 0);
+        __syncthreads();
+        produce(0, 0, g + 5);
+        consume(3, 1);
+        store_tile();
+        clear_acc();
+        advance(st);
+    }
+}
+
+template <int C, int WPC>
+hipError_t launch_sn_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw,
+                          float scale, int conj, hipStream_t stream)
+{
+    const int64_t ntiles = a.O * a.Yn * a.Zt;
+    const int64_t blocks = ntiles < 256 * WPC ? ntiles : 256 * WPC;      // persistent workgroups
+    if (conj)
+        hipLaunchKernelGGL((k_fft_sn<C, true, WPC>), dim3((unsigned)blocks), dim3(512), FftSnLayout<C>::lds_bytes, stream,
+                           a, FA, FB, Tw, scale);
+    else
+        hipLaunchKernelGGL((k_fft_sn<C, false, WPC>), dim3((unsigned)blocks), dim3(512), FftSnLayout<C>::lds_bytes, stream,
+                           a, FA, FB, Tw, scale);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 bool fft_zn_supported(int A, int B)
@@ -242,6 +542,32 @@ hipError_t launch_fft_zn(const float2* in, float2* out, int64_t nrows, int A, in
     if (B == 64) return launch_zn_inst<4, 3>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     if (B == 128) return launch_zn_inst<8, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     return hipErrorInvalidValue;
+}
+
+bool fft_sn_supported(int A, int B, int64_t I)
+{
+    // 32-bit lane offsets of the loads: up to 3*B rows of I elements
+    return A == 16 && B == 128 && I % 16 == 0 && I <= (int64_t(1) << 23);
+}
+
+hipError_t configure_fft_nested_kernels()
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<8, false, 1>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<8>::lds_bytes);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<8, true, 1>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<8>::lds_bytes);
+}
+
+hipError_t launch_fft_sn(const FftStridedArgs& a, int A, int B, const DeviceMatrix& FA, const DeviceMatrix& FB,
+                         const float2* Tw, float scale, int conj, hipStream_t stream)
+{
+    if (a.O <= 0 || a.Yn <= 0 || a.Zt <= 0) return hipSuccess;
+    const int64_t lim = int64_t(1) << 23;
+    if (A != 16 || B != 128 || a.inN < 16 || a.outN < 16 || a.inN > lim || a.outN > lim || FA.K != 16 || FA.N != 16 ||
+        FB.K != B || FB.N != B || !Tw)
+        return hipErrorInvalidValue;
+    return launch_sn_inst<8, 1>(a, FA, FB, Tw, scale, conj, stream);
 }
 
 }  // namespace dft3d

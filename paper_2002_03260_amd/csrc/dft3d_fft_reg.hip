@@ -1415,15 +1415,17 @@ hipError_t configure_fft_kernels()
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)((size_t)512 * 16 * sizeof(f32x4) + (size_t)512 * sizeof(float2)));
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_ss<32, 64, 1, 1, 8>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)FftSsLayout<32, 64, 1, 1, 8>::lds_bytes);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_ss<32, 64, 1, 1, 8>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSsLayout<32, 64, 1, 1, 8>::lds_bytes);
+    if (e != hipSuccess) return e;
+    return configure_fft_nested_kernels();
 }
 
 bool fft_sr_supported(int A, int B, int64_t I)
 {
     // 32-bit lane offsets inside the kernels: up to 12*A rows (and 3*B rows) of I elements
     if (I % 16 != 0) return false;
+    if (fft_sn_supported(A, B, I)) return true;
     if (A == 32 && B == 64) return I <= (int64_t(1) << 23);
     return I <= (int64_t(1) << 21) && A == 16 && (B == 16 || B == 32);
 }
@@ -1432,6 +1434,7 @@ hipError_t launch_fft_sr_ex(const FftStridedArgs& a, int A, int B, const DeviceM
                             const DeviceMatrix& FB, const float2* Tw, float scale, int conj, hipStream_t stream)
 {
     if (a.O <= 0 || a.Yn <= 0 || a.Zt <= 0) return hipSuccess;
+    if (A == 16 && B == 128) return launch_fft_sn(a, A, B, FA, FB, Tw, scale, conj, stream);
     const int64_t lim = int64_t(1) << ((A == 32 && B == 64) ? 23 : 21);
     if (a.inN < 16 || a.outN < 16 || a.inN > lim || a.outN > lim || FA.K != A || FA.N != A || FB.K != B ||
         FB.N != B || !Tw)

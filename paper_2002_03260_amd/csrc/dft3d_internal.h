@@ -167,6 +167,12 @@ bool fft_sr_supported(int A, int B, int64_t I);
 // One-time set-up of the strided-axis kernels that use more LDS than a launch gets by default
 // (idempotent; called at plan creation).
 hipError_t configure_fft_kernels();
+// Strided-axis pass with the second factor split once more (16 x 128); launch_fft_sr_ex uses it for the
+// split it covers.
+bool fft_sn_supported(int A, int B, int64_t I);
+hipError_t launch_fft_sn(const FftStridedArgs& a, int A, int B, const DeviceMatrix& FA, const DeviceMatrix& FB,
+                         const float2* Tw, float scale, int conj, hipStream_t stream);
+hipError_t configure_fft_nested_kernels();
 hipError_t launch_fft_sr(const float2* in, float2* out, int64_t O, int64_t I, int A, int B,
                          const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
                          int conj, hipStream_t stream);

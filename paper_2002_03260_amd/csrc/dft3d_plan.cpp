@@ -201,9 +201,9 @@ dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out
 
 int64_t default_split(int64_t n, int axis)
 {
-    // contiguous axis of 1024 or 2048 points: 16 x (C*16), the split whose second factor the fused
-    // kernel splits once more (2048: a third of the matrix-core work of 32 x 64)
-    if (axis == 2 && (n == 1024 || n == 2048)) return 16;
+    // 16 x (C*16), the split whose second factor the fused kernels split once more (2048: a third of the
+    // matrix-core work of 32 x 64): 2048 points on any axis, 1024 points on the contiguous one
+    if (n == 2048 || (axis == 2 && n == 1024)) return 16;
     if ((n & (n - 1)) == 0) {
         int lg = 0;
         while ((int64_t(1) << (lg + 1)) <= n) ++lg;
