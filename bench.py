@@ -349,14 +349,15 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
         elif npass == 5:
             pass_names = ["z_fused_axis"] + pass_names[2:6]
         elif npass == 3:
-            pass_names = ["z_fused_axis", "y_fused_axis", "x_fused_axis"]
+            # (plans with 2048 points along x run the x pass first)
+            pass_names = [f"{'xyz'[ax]}_fused_axis" for ax in plan.axis_order()]
         dom = max(range(npass), key=lambda i: pass_ms[i])
         dom_ms = pass_ms[dom]
         dom_name = pass_names[dom] if dom < len(pass_names) else f"pass{dom}"
-        if (npass == 3 and not c128 and w.splits and w.splits[0] == w.splits[1] and dom in (1, 2)):
+        if (npass == 3 and not c128 and w.splits and w.splits[0] == w.splits[1] and pass_names[dom][0] in "xy"):
             # the y and the x pass are two launches of one kernel: the roofline of that kernel
             # uses its average launch duration, which is what a per-kernel profile reports
-            dom_ms = 0.5 * (pass_ms[1] + pass_ms[2])
+            dom_ms = 0.5 * sum(pass_ms[i] for i in range(3) if pass_names[i][0] in "xy")
             dom_name = "y_and_x_fused_axis"
             kernel_note = "fused strided-axis kernel, average of its two launches (y pass and x pass)"
         nbytes = (32.0 if c128 else 16.0) * E

@@ -28,7 +28,7 @@ FLAG_ADJOINT = 32
 EXPORTS = [
     "dft3d_plan_create", "dft3d_plan_create_ex", "dft3d_plan_create_points",
     "dft3d_plan_get_output_shape", "dft3d_generate_points_matrix", "dft3d_plan_destroy",
-    "dft3d_plan_workspace_bytes", "dft3d_plan_set_workspace", "dft3d_plan_get_split", "dft3d_plan_mode_kernel",
+    "dft3d_plan_workspace_bytes", "dft3d_plan_set_workspace", "dft3d_plan_get_split", "dft3d_plan_axis_order", "dft3d_plan_mode_kernel",
     "dft3d_exec", "dft3d_exec_noalloc", "dft3d_plan_enable_profiling", "dft3d_plan_read_profile", "dft3d_mode_contract", "dft3d_fft_first_stage", "dft3d_fft_phase",
     "dft3d_fft_second_stage", "dft3d_fft_axis", "dft3d_fft_reorder", "dft3d_device_copy", "dft3d_generate_matrix",
     "dft3d_generate_twiddle", "dft3d_status_string", "dft3d_last_error",
@@ -70,6 +70,7 @@ def load_library():
     lib.dft3d_plan_workspace_bytes.restype = ctypes.c_size_t
     lib.dft3d_plan_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
     lib.dft3d_plan_get_split.argtypes = [vp, ci, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.dft3d_plan_axis_order.argtypes = [vp, ctypes.POINTER(ci)]
     lib.dft3d_plan_mode_kernel.argtypes = [vp, ci, ctypes.c_char_p, ctypes.c_size_t]
     lib.dft3d_exec.argtypes = [vp, vp, vp, ci, vp]
     lib.dft3d_exec_noalloc.argtypes = [vp, vp, vp, ci, vp]
@@ -234,6 +235,12 @@ class Plan:
         a, b = ctypes.c_int64(), ctypes.c_int64()
         _check(self._lib.dft3d_plan_get_split(self._h, axis, ctypes.byref(a), ctypes.byref(b)))
         return int(a.value), int(b.value)
+
+    def axis_order(self):
+        """Axes in the order dft3d_exec transforms them."""
+        order = (ctypes.c_int * 3)()
+        _check(self._lib.dft3d_plan_axis_order(self._h, order))
+        return tuple(int(v) for v in order)
 
     def mode_kernel(self, axis: int) -> str:
         """Name of the kernel family that contracts mode ``axis`` of this KDFT plan."""

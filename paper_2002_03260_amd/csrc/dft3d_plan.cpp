@@ -247,6 +247,7 @@ struct dft3d_plan_s {
     // channels, and 16 elements of padding per z row spread them (measured: x pass 8 % faster with
     // its reads padded; padding its writes instead, by running it second, gains less).
     int64_t ws_pitch = 0;
+    bool x_first = false;          // passes x, y, z with the tensor between x and y stored as [y][k_x][z]
 
     // optional per-pass event timing of exec
     std::vector<hipEvent_t> prof_events;   // [exec][pass][begin,end]
@@ -503,6 +504,42 @@ hipError_t run_fused_s_padded(const dft3d_plan_s* p, int axis, const float2* in,
                             conj, st);
 }
 
+// The x and y passes of a plan that transforms x first and keeps the tensor between them transposed,
+// [y][k_x][z]: x pass [1][nx][ny][nz] -> rows k_x of one (y, 16 z) tile nz apart; y pass reads rows
+// nx*nz apart and writes the natural layout [k_x][k_y][z], rows nz apart again.  Both passes then read
+// with the long stride and write with the short one.  (Measured at 2048^3: a pass that writes rows
+// ny*nz = 32 MiB apart takes 45 ms, one that writes rows 16 KiB apart 32 ms, whatever it reads.)
+hipError_t run_fused_s_xfirst(const dft3d_plan_s* p, int axis, const float2* in, float2* out, int conj,
+                              float scale, hipStream_t st)
+{
+    const int64_t nx = p->n[0], ny = p->n[1], nz = p->n[2];
+    FftStridedArgs a{};
+    a.X = in;
+    a.Y = out;
+    a.Zt = nz / 16;
+    if (axis == 0) {
+        a.O = 1;
+        a.Yn = ny;
+        a.inO = 0;
+        a.inN = ny * nz;
+        a.inY = nz;
+        a.outO = 0;
+        a.outN = nz;
+        a.outY = nx * nz;
+    } else {
+        a.O = nx;
+        a.Yn = 1;
+        a.inO = nz;
+        a.inN = nx * nz;
+        a.inY = 0;
+        a.outO = ny * nz;
+        a.outN = nz;
+        a.outY = 0;
+    }
+    return launch_fft_sr_ex(a, (int)p->A[axis], (int)p->B[axis], p->FA[axis], p->FB[axis], p->Tw[axis], scale,
+                            conj, st);
+}
+
 hipError_t run_reorder(const dft3d_plan_s* p, int mask, const float2* in, float2* out, hipStream_t st)
 {
     if (p->complex128()) {
@@ -739,10 +776,19 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
     }
     if (s != DFT3D_OK) return s;      // (the guard frees the plan)
     guard.p = nullptr;
-    if (f == DFT3D_FFT && !(flags & (DFT3D_FLAG_UNFUSED | DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_COMPLEX128)) && n[0] > 1 && n[1] > 1 &&
-        n[2] > 1 && n[2] % 16 == 0 && (n[1] * n[2] * 8) % 8192 == 0 && n[1] * (n[2] + 16) <= (int64_t(1) << 21) &&
-        fft_z_supported((int)p->A[2], (int)p->B[2]) && fft_sr_supported((int)p->A[1], (int)p->B[1], n[2]) &&
+    // Plans whose three axes all fuse.  Where both strided axes run on kernels that take separate input
+    // and output strides and the x axis has 2048 points, the x pass comes first and writes a transposed
+    // intermediate (see run_fused_s_xfirst); otherwise passes z, y, x, with padded rows in the workspace
+    // intermediate between y and x where they help.
+    const bool all_fused_candidate = f == DFT3D_FFT &&
+                                     !(flags & (DFT3D_FLAG_UNFUSED | DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_COMPLEX128)) &&
+                                     n[0] > 1 && n[1] > 1 && n[2] > 1 && n[2] % 16 == 0 &&
+                                     fft_z_supported((int)p->A[2], (int)p->B[2]);
+    if (all_fused_candidate && n[0] == 2048 && fft_sr_supported((int)p->A[1], (int)p->B[1], n[0] * n[2]) &&
         fft_sr_supported((int)p->A[0], (int)p->B[0], n[1] * n[2]))
+        p->x_first = true;
+    else if (all_fused_candidate && (n[1] * n[2] * 8) % 8192 == 0 && n[1] * (n[2] + 16) <= (int64_t(1) << 21) &&
+             fft_sr_supported((int)p->A[1], (int)p->B[1], n[2]) && fft_sr_supported((int)p->A[0], (int)p->B[0], n[1] * n[2]))
         p->ws_pitch = n[2] + 16;
     // set-up for dft3d_exec_noalloc: look up this GPU's copy of the static scratch array now, so that
     // the exec call itself never has to (a failure here is reported by that call, not by this one)
@@ -925,6 +971,16 @@ dft3d_status dft3d_plan_set_workspace(dft3d_plan p, void* dev, size_t bytes)
     }
     p->workspace = dev;
     p->workspace_bytes = dev ? bytes : 0;
+    return DFT3D_OK;
+}
+
+dft3d_status dft3d_plan_axis_order(dft3d_plan p, int order[3])
+{
+    if (!p || !order) {
+        set_error("axis_order: invalid argument");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    for (int step = 0; step < 3; ++step) order[step] = p->x_first ? step : 2 - step;
     return DFT3D_OK;
 }
 
@@ -1136,9 +1192,10 @@ dft3d_status exec_with_workspace(dft3d_plan p, const void* in, void* out, int di
             set_error("%s: a workspace of %zu bytes must be set first", who, need);
             return DFT3D_ERR_INVALID_ARG;
         }
+        // (the workspace may be larger than a tensor: padded rows)
         const uintptr_t w = (uintptr_t)workspace, bytes = (uintptr_t)need;
-        const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out;
-        if ((w < a + bytes && a < w + bytes) || (w < b + bytes && b < w + bytes)) {
+        const uintptr_t a = (uintptr_t)in, b = (uintptr_t)out, tbytes = (uintptr_t)p->elements() * p->elem_bytes();
+        if ((w < a + tbytes && a < w + bytes) || (w < b + tbytes && b < w + bytes)) {
             set_error("%s: the workspace overlaps in or out", who);
             return DFT3D_ERR_INVALID_ARG;
         }
@@ -1221,7 +1278,8 @@ dft3d_status exec_with_workspace(dft3d_plan p, const void* in, void* out, int di
             advance();
         }
     } else {
-        for (int axis = 2; axis >= 0 && e == hipSuccess; --axis) {
+        for (int step = 0; step < 3 && e == hipSuccess; ++step) {
+            const int axis = p->x_first ? step : 2 - step;
             if (skip[axis]) continue;
             if (axis == 2 && zfused) {
                 mark(0);
@@ -1233,8 +1291,9 @@ dft3d_status exec_with_workspace(dft3d_plan p, const void* in, void* out, int di
                 mark(0);
                 // ws_pitch is only set for plans whose passes are z: in -> out, y: out -> workspace,
                 // x: workspace -> out
-                e = p->ws_pitch ? run_fused_s_padded(p, axis, src, dst, conj, axis_scale(p, axis, direction), st)
-                                : run_fused_s(p, axis, src, dst, conj, axis_scale(p, axis, direction), st);
+                e = p->ws_pitch  ? run_fused_s_padded(p, axis, src, dst, conj, axis_scale(p, axis, direction), st)
+                    : p->x_first ? run_fused_s_xfirst(p, axis, src, dst, conj, axis_scale(p, axis, direction), st)
+                                 : run_fused_s(p, axis, src, dst, conj, axis_scale(p, axis, direction), st);
                 advance();
                 continue;
             }

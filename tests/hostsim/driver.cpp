@@ -238,6 +238,12 @@ int main()
         {{2048, 2048, 2048}, DFT3D_KDFT, DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_3M, false, {0, 0, 0}},
         {{2048, 2048, 2048}, DFT3D_FFT, 0, false, {32, 32, 32}},
         {{2048, 2048, 2048}, DFT3D_FFT, DFT3D_FLAG_CLOBBER_INPUT, false, {32, 32, 32}},
+        // default split of 2048: 16 x 128 with the second factor split again; x pass first, transposed intermediate
+        {{2048, 2048, 2048}, DFT3D_FFT, 0, false, {0, 0, 0}},
+        {{2048, 2048, 2048}, DFT3D_FFT, DFT3D_FLAG_CLOBBER_INPUT, false, {0, 0, 0}},
+        {{2048, 48, 1024}, DFT3D_FFT, 0, false, {0, 0, 0}},
+        {{2048, 512, 2048}, DFT3D_FFT, 0, false, {0, 0, 0}},
+        {{32, 2048, 16}, DFT3D_FFT, 0, false, {0, 0, 0}},
         {{1, 8192, 8192}, DFT3D_KDFT, 0, false, {0, 0, 0}},
         {{1, 8192, 8192}, DFT3D_FFT, DFT3D_FLAG_CLOBBER_INPUT, false, {0, 0, 0}},
     };

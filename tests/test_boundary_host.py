@@ -145,6 +145,13 @@ def test_argument_errors_are_status_codes(lib):
     assert lib.dft3d_status_string(99) == b"DFT3D_ERR_UNKNOWN"
 
 
+def test_axis_order_query_rejects_null(lib):
+    """The plan query for the order of the passes is host code: NULL arguments come back as a status."""
+    order = (ctypes.c_int * 3)()
+    st = lib.dft3d_plan_axis_order(None, order)
+    assert lib.dft3d_status_string(st) == b"DFT3D_ERR_INVALID_ARG"
+
+
 def test_plan_arguments_rejected_before_any_device_work(lib):
     """Non-finite coordinates, contraction variants on an FFT plan and extents the kernels cannot
     index come back as status codes from checks that run before the first device call."""

@@ -106,6 +106,48 @@ def test_2d_8192_sampled_outputs(dft):
     assert abs(e_out / e_in - 1) <= 1e-5
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("shape", [(2048, 256, 256), (2048, 512, 512)])
+def test_fft_x_first_plan_sampled(dft, shape):
+    """FFT plans whose x axis has 2048 points transform x first and keep the tensor between the x and
+    the y pass transposed.  The plan with a workspace takes that path, the same plan with CLOBBER_INPUT
+    runs z, y, x in natural layout: both against oracle pencils and slabs, against each other everywhere,
+    forward and backward."""
+    import torch
+
+    say(f"case fft x-first plan {shape}: drawing input")
+    x = wl.draw_complex(shape, "normal", 200203260 + sum(shape))
+    xd = torch.from_numpy(x).to("cuda")
+    with dft.Plan(shape, dft.FFT) as p:
+        say(f"  splits {[p.split(a) for a in range(3)]}")
+        assert p.split(0) == (16, 128) and p.axis_order() == (0, 1, 2)
+        got = p.exec(xd)
+        back = p.exec(got, direction=dft.BACKWARD)
+        torch.cuda.synchronize()
+    with dft.Plan(shape, dft.FFT, flags=dft.FLAG_CLOBBER_INPUT) as p:
+        assert p.axis_order() == (2, 1, 0)
+        ref = p.exec(xd.clone())
+        torch.cuda.synchronize()
+    r = _device_rel_l2(got, ref)
+    say(f"[parity] x-first vs in-place plan: relL2={r:.3e}")
+    assert r <= TOL
+    r = _device_rel_l2(back, xd)
+    say(f"[parity] backward(forward(x)) vs x: relL2={r:.3e}")
+    assert r <= TOL
+    k1s, k2s, k3s = [0, 17, 2047], [0, shape[1] - 1, 100], [3, shape[2] // 2]
+    say(f"  oracle: slabs k1 = {k1s}, pencils k2 = {k2s}, k3 = {k3s}")
+    want = orc.dft3d_sampled(x, k1s)
+    g = got[k1s].cpu().numpy()
+    r = rel_l2(g, want)
+    say(f"[parity] slabs: relL2={r:.3e} max|err|={np.max(np.abs(g - want)):.3e}")
+    assert r <= TOL
+    want = orc.dft3d_pencils(x, k2s, k3s)
+    g = got[:, k2s][:, :, k3s].cpu().numpy()
+    r = rel_l2(g, want)
+    say(f"[parity] pencils: relL2={r:.3e} max|err|={np.max(np.abs(g - want)):.3e}")
+    assert r <= TOL
+
+
 # ----------------------------------------------------------------------------- 2048^3
 def _device_rel_l2(a, b, chunk=64):
     """relative L2 distance of two huge device tensors, reduced in fp64 plane-chunk by chunk."""
