@@ -161,7 +161,7 @@ dft3d_status dft3d_plan_get_split(dft3d_plan plan, int axis, int64_t* A, int64_t
 
 /* Order in which dft3d_exec transforms the axes (Eq. 10: the three modes commute): order[0..2] receives
  * the axis of the first, second and third mode.  2, 1, 0 (z, y, x) for every plan except FFT plans that
- * run the x pass first (all three axes on fused kernels, 2048 points along x, a workspace: 0, 1, 2).
+ * run the x pass first (all three axes on fused kernels, 2048 points or more along x, a workspace: 0, 1, 2).
  * The single-pass entry points below are not affected.  Host only.  INVALID_ARG for NULL arguments. */
 dft3d_status dft3d_plan_axis_order(dft3d_plan plan, int order[3]);
 

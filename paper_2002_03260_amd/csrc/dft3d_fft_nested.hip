@@ -260,7 +260,7 @@ struct FftSnLayout {
 };
 
 template <int C, bool SWAP, int WPC>
-__global__ __launch_bounds__(512, WPC) void k_fft_sn(FftStridedArgs a, DeviceMatrix FA, DeviceMatrix FB,
+__global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, DeviceMatrix FA, DeviceMatrix FB,
                                                       const float2* __restrict__ Tw, float scale)
 {
     typedef FftSnLayout<C> L;
@@ -547,16 +547,28 @@ hipError_t launch_fft_zn(const float2* in, float2* out, int64_t nrows, int A, in
 bool fft_sn_supported(int A, int B, int64_t I)
 {
     // 32-bit lane offsets of the loads: up to 3*B rows of I elements
-    return A == 16 && B == 128 && I % 16 == 0 && I <= (int64_t(1) << 23);
+    return A == 16 && (B == 32 || B == 64 || B == 128) && I % 16 == 0 && I <= (int64_t(1) << 23);
 }
+
+namespace {
+template <int C, int WPC>
+hipError_t configure_sn()
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<C, false, WPC>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<C>::lds_bytes);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<C, true, WPC>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<C>::lds_bytes);
+}
+}  // namespace
 
 hipError_t configure_fft_nested_kernels()
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<8, false, 1>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<8>::lds_bytes);
+    hipError_t e = configure_sn<8, 1>();
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<8, true, 1>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<8>::lds_bytes);
+    e = configure_sn<4, 2>();
+    if (e != hipSuccess) return e;
+    return configure_sn<2, 2>();
 }
 
 hipError_t launch_fft_sn(const FftStridedArgs& a, int A, int B, const DeviceMatrix& FA, const DeviceMatrix& FB,
@@ -564,10 +576,13 @@ hipError_t launch_fft_sn(const FftStridedArgs& a, int A, int B, const DeviceMatr
 {
     if (a.O <= 0 || a.Yn <= 0 || a.Zt <= 0) return hipSuccess;
     const int64_t lim = int64_t(1) << 23;
-    if (A != 16 || B != 128 || a.inN < 16 || a.outN < 16 || a.inN > lim || a.outN > lim || FA.K != 16 || FA.N != 16 ||
+    if (A != 16 || a.inN < 16 || a.outN < 16 || a.inN > lim || a.outN > lim || FA.K != 16 || FA.N != 16 ||
         FB.K != B || FB.N != B || !Tw)
         return hipErrorInvalidValue;
-    return launch_sn_inst<8, 1>(a, FA, FB, Tw, scale, conj, stream);
+    if (B == 128) return launch_sn_inst<8, 1>(a, FA, FB, Tw, scale, conj, stream);
+    if (B == 64) return launch_sn_inst<4, 2>(a, FA, FB, Tw, scale, conj, stream);
+    if (B == 32) return launch_sn_inst<2, 2>(a, FA, FB, Tw, scale, conj, stream);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace dft3d

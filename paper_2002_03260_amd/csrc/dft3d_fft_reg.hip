@@ -600,187 +600,6 @@ __global__ __launch_bounds__(256, MINW) void k_fft_sr(FftStridedArgs a, DeviceMa
     }
 }
 
-// The same pass on tiles of all N positions x 32 contiguous columns: every lane holds two neighbouring
-// columns (16-byte loads and stores, 256 contiguous bytes per row and quarter wave), which the memory
-// system serves faster than 128-byte pieces (measured with a plain tiled copy at 512^3: 5.3 against
-// 4.9 TB/s along y, 5.1 against 3.9 TB/s along x).  The two columns of a lane are two independent sets
-// of MFMA columns.  Z for 32 columns takes 128 KiB of LDS, so one workgroup of eight waves runs per CU:
-// wave w does stage 1 for beta = w, w+8, .. and stage 2 for k_a = w, w+8, ..
-template <int A, int B>
-__global__ __launch_bounds__(512, 1) void k_fft_sw(FftStridedArgs a, DeviceMatrix FA, DeviceMatrix FB,
-                                                    const float2* __restrict__ Tw, float scale, int conj)
-{
-    const float2* __restrict__ X = a.X;
-    float2* __restrict__ Y = a.Y;
-    constexpr int N = A * B;
-    static_assert(A == 16, "one block of k_a per stage-1 product");
-    constexpr int NW = 8;
-    constexpr int NBB = B / 16;      // blocks of k_b
-    constexpr int NS1 = A / 4;       // k-steps of stage 1 (over l)
-    constexpr int NS2 = B / 4;       // k-steps of stage 2 (over beta)
-    constexpr int NG = B / NW;       // beta values per wave
-    constexpr int NH = A / NW;       // k_a values per wave
-    static_assert(NG >= 2 && NG % 2 == 0 && NH >= 1, "work split over eight waves");
-
-    extern __shared__ __align__(16) unsigned char smem_sw[];
-    f32x4* Zs = reinterpret_cast<f32x4*>(smem_sw);                        // [k_a][beta][16 column pairs]
-    float2* tws = reinterpret_cast<float2*>(smem_sw + (size_t)N * 16 * sizeof(f32x4));   // T[k_a][beta]
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int l16 = lane & 15, lq = lane >> 4;
-    const float isign = conj ? -1.0f : 1.0f;
-
-    for (int e = tid; e < N; e += 512) {
-        float2 t = Tw[e];
-        t.y *= isign;
-        tws[e] = t;
-    }
-    float fa_r[NS1], fa_i[NS1], fa_s[NS1];
-#pragma unroll
-    for (int s = 0; s < NS1; ++s) {
-        const int idx = (4 * s + lq) * FA.ld + l16;
-        fa_r[s] = FA.re[idx];
-        fa_i[s] = FA.im[idx] * isign;
-        fa_s[s] = fa_r[s] + fa_i[s];
-    }
-    float fb_r[NBB][NS2], fb_i[NBB][NS2], fb_s[NBB][NS2];
-#pragma unroll
-    for (int kbb = 0; kbb < NBB; ++kbb)
-#pragma unroll
-        for (int s = 0; s < NS2; ++s) {
-            const int idx = (4 * s + lq) * FB.ld + 16 * kbb + l16;
-            fb_r[kbb][s] = FB.re[idx] * scale;
-            fb_i[kbb][s] = FB.im[idx] * (scale * isign);
-            fb_s[kbb][s] = fb_r[kbb][s] + fb_i[kbb][s];
-        }
-
-    // tile -> (o, y, 32-column group); a.Zt counts groups of 16 columns and is even here
-    const int64_t zt2 = a.Zt / 2;
-    const int64_t per_o = a.Yn * zt2;
-    const int64_t ntiles = a.O * per_o;
-    const int64_t nwg = (int64_t)gridDim.x * gridDim.y;
-    auto in_base = [&](int64_t tile) {
-        const int64_t o = tile / per_o, r = tile % per_o;
-        return o * a.inO + (r / zt2) * a.inY + (r % zt2) * 32;
-    };
-    auto out_base = [&](int64_t tile) {
-        const int64_t o = tile / per_o, r = tile % per_o;
-        return o * a.outO + (r / zt2) * a.outY + (r % zt2) * 32;
-    };
-    const int64_t inN = a.inN, outN = a.outN;
-    const unsigned ld_lane = (unsigned)(B * lq) * (unsigned)inN + 2 * l16;        // row B*lq, columns 2*l16, 2*l16+1
-    const unsigned st_lane = (unsigned)(A * 4 * lq) * (unsigned)outN + 2 * l16;   // row A*4*lq
-
-    // operand registers of the tile: xq[g][s] = x[B*(4*s + lq) + beta_g, columns 2*l16 and 2*l16+1]
-    f32x4 xq[NG][NS1];
-    auto request = [&](int64_t tile, int g) {
-        const float2* src = X + in_base(tile) + (int64_t)(wave + NW * g) * inN;
-#pragma unroll
-        for (int s = 0; s < NS1; ++s)
-            xq[g][s] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(&(src + (int64_t)(4 * B * s) * inN)[ld_lane]));
-    };
-
-    int64_t tile = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
-    if (tile < ntiles) {
-#pragma unroll
-        for (int g = 0; g < NG; ++g) request(tile, g);
-    }
-    __syncthreads();                               // twiddle table
-    for (; tile < ntiles; tile += nwg) {
-        const int64_t next = tile + nwg < ntiles ? tile + nwg : tile;    // past the end: a harmless re-read
-
-        // ---- stage 1: two beta values at a time, two columns per lane
-#pragma unroll
-        for (int g = 0; g < NG; g += 2) {
-            f32x4 p1[2][2], p2[2][2], p3[2][2];     // [beta of the pair][column of the lane]
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    p1[u][h] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    p2[u][h] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    p3[u][h] = f32x4{0.f, 0.f, 0.f, 0.f};
-                }
-#pragma unroll
-            for (int s = 0; s < NS1; ++s)
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const f32x4 x = xq[g + u][s];
-                    p1[u][0] = mfma(fa_r[s], x[0], p1[u][0]);
-                    p2[u][0] = mfma(fa_i[s], x[1], p2[u][0]);
-                    p3[u][0] = mfma(fa_s[s], x[0] + x[1], p3[u][0]);
-                    p1[u][1] = mfma(fa_r[s], x[2], p1[u][1]);
-                    p2[u][1] = mfma(fa_i[s], x[3], p2[u][1]);
-                    p3[u][1] = mfma(fa_s[s], x[2] + x[3], p3[u][1]);
-                }
-            // the registers of these two beta values are free: request them for the next tile
-            request(next, g);
-            request(next, g + 1);
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int beta = wave + NW * (g + u);
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int ka = 4 * lq + v;
-                    const float2 t = tws[ka * B + beta];
-                    f32x4 z;
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const float re = p1[u][h][v] - p2[u][h][v];
-                        const float im = p3[u][h][v] - p1[u][h][v] - p2[u][h][v];
-                        z[2 * h] = re * t.x - im * t.y;
-                        z[2 * h + 1] = re * t.y + im * t.x;
-                    }
-                    Zs[(ka * B + beta) * 16 + l16] = z;
-                }
-            }
-        }
-        __syncthreads();
-
-        // ---- stage 2: one k_a at a time, all blocks of k_b in flight
-        float2* dst = Y + out_base(tile);                                   // uniform
-#pragma unroll
-        for (int hh = 0; hh < NH; ++hh) {
-            const int ka = wave + NW * hh;
-            f32x4 q1[NBB][2], q2[NBB][2], q3[NBB][2];
-#pragma unroll
-            for (int kbb = 0; kbb < NBB; ++kbb)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    q1[kbb][h] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    q2[kbb][h] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    q3[kbb][h] = f32x4{0.f, 0.f, 0.f, 0.f};
-                }
-#pragma unroll
-            for (int s = 0; s < NS2; ++s) {
-                const f32x4 z = Zs[(ka * B + 4 * s + lq) * 16 + l16];
-                const float zs0 = z[0] + z[1], zs1 = z[2] + z[3];
-#pragma unroll
-                for (int kbb = 0; kbb < NBB; ++kbb) {
-                    q1[kbb][0] = mfma(fb_r[kbb][s], z[0], q1[kbb][0]);
-                    q2[kbb][0] = mfma(fb_i[kbb][s], z[1], q2[kbb][0]);
-                    q3[kbb][0] = mfma(fb_s[kbb][s], zs0, q3[kbb][0]);
-                    q1[kbb][1] = mfma(fb_r[kbb][s], z[2], q1[kbb][1]);
-                    q2[kbb][1] = mfma(fb_i[kbb][s], z[3], q2[kbb][1]);
-                    q3[kbb][1] = mfma(fb_s[kbb][s], zs1, q3[kbb][1]);
-                }
-            }
-#pragma unroll
-            for (int kbb = 0; kbb < NBB; ++kbb)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    // row k_a + A*k_b with k_b = 16*kbb + 4*lq + v: the lq part is in st_lane
-                    const f32x4 w = f32x4{q1[kbb][0][v] - q2[kbb][0][v], q3[kbb][0][v] - q1[kbb][0][v] - q2[kbb][0][v],
-                                          q1[kbb][1][v] - q2[kbb][1][v], q3[kbb][1][v] - q1[kbb][1][v] - q2[kbb][1][v]};
-                    __builtin_nontemporal_store(w, reinterpret_cast<f32x4*>(&(dst + (int64_t)(ka + A * (16 * kbb + v)) * outN)[st_lane]));
-                }
-        }
-        __syncthreads();                           // Z is rewritten by the next tile
-    }
-}
-
 // ---- strided axes, streaming form ------------------------------------------------------------------
 // The kernels above keep the whole intermediate Z[k_a][beta][columns] of a tile in LDS, which limits a
 // tile to N * columns * 8 bytes <= 128 KiB: 16 or 32 columns at N = 512, nothing at N = 2048.  Here Z
@@ -1354,17 +1173,6 @@ hipError_t launch_ss_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const
     return hipGetLastError();
 }
 
-template <int A, int B>
-hipError_t launch_sw_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw,
-                          float scale, int conj, hipStream_t stream)
-{
-    constexpr size_t lds = (size_t)A * B * 16 * sizeof(f32x4) + (size_t)A * B * sizeof(float2);
-    const int64_t ntiles = a.O * a.Yn * (a.Zt / 2);
-    const int64_t blocks = ntiles < 256 ? ntiles : 256;          // one persistent workgroup per CU
-    hipLaunchKernelGGL((k_fft_sw<A, B>), dim3((unsigned)blocks), dim3(512), lds, stream, a, FA, FB, Tw, scale, conj);
-    return hipGetLastError();
-}
-
 template <int A, int B, int MINW>
 hipError_t launch_s_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw,
                          float scale, int conj, hipStream_t stream)
@@ -1411,10 +1219,7 @@ hipError_t launch_contract_sr(const ContractArgs& a, hipStream_t stream)
 
 hipError_t configure_fft_kernels()
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sw<16, 32>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)((size_t)512 * 16 * sizeof(f32x4) + (size_t)512 * sizeof(float2)));
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_ss<32, 64, 1, 1, 8>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSsLayout<32, 64, 1, 1, 8>::lds_bytes);
     if (e != hipSuccess) return e;
@@ -1427,29 +1232,20 @@ bool fft_sr_supported(int A, int B, int64_t I)
     if (I % 16 != 0) return false;
     if (fft_sn_supported(A, B, I)) return true;
     if (A == 32 && B == 64) return I <= (int64_t(1) << 23);
-    return I <= (int64_t(1) << 21) && A == 16 && (B == 16 || B == 32);
+    return I <= (int64_t(1) << 21) && A == 16 && B == 16;
 }
 
 hipError_t launch_fft_sr_ex(const FftStridedArgs& a, int A, int B, const DeviceMatrix& FA,
                             const DeviceMatrix& FB, const float2* Tw, float scale, int conj, hipStream_t stream)
 {
     if (a.O <= 0 || a.Yn <= 0 || a.Zt <= 0) return hipSuccess;
-    if (A == 16 && B == 128) return launch_fft_sn(a, A, B, FA, FB, Tw, scale, conj, stream);
+    if (fft_sn_supported(A, B, 16)) return launch_fft_sn(a, A, B, FA, FB, Tw, scale, conj, stream);
     const int64_t lim = int64_t(1) << ((A == 32 && B == 64) ? 23 : 21);
     if (a.inN < 16 || a.outN < 16 || a.inN > lim || a.outN > lim || FA.K != A || FA.N != A || FB.K != B ||
         FB.N != B || !Tw)
         return hipErrorInvalidValue;
-    // 16-byte accesses (two columns per lane) need rows that start on 16-byte boundaries on both sides
-    const bool even = a.inN % 2 == 0 && a.outN % 2 == 0 && a.inY % 2 == 0 && a.outY % 2 == 0 && a.inO % 2 == 0 &&
-                      a.outO % 2 == 0 && ((uintptr_t)a.X & 15) == 0 && ((uintptr_t)a.Y & 15) == 0;
     if (A == 32 && B == 64) return launch_ss_inst<32, 64, 1, 1, 8>(a, FA, FB, Tw, scale, conj, stream);
     if (A == 16 && B == 16) return launch_s_inst<16, 16, 4>(a, FA, FB, Tw, scale, conj, stream);
-    if (A == 16 && B == 32) {
-        // tiles of 32 columns where the layout allows (measured at 512^3: y 0.446 -> 0.449 ms, x 0.512 ->
-        // 0.475 ms; the streaming kernel with 64-column tiles measured 0.495 / 0.509 ms there)
-        if (even && a.Zt % 2 == 0) return launch_sw_inst<16, 32>(a, FA, FB, Tw, scale, conj, stream);
-        return launch_s_inst<16, 32, 2>(a, FA, FB, Tw, scale, conj, stream);
-    }
     return hipErrorInvalidValue;
 }
 
@@ -1474,7 +1270,7 @@ hipError_t launch_fft_sr(const float2* in, float2* out, int64_t O, int64_t I, in
 
 bool fft_zr_supported(int A, int B)
 {
-    return (A == 16 && B == 16) || (A == 16 && B == 32) || (A == 32 && B == 32) || (A == 32 && B == 64);
+    return (A == 16 && B == 16) || (A == 32 && B == 32) || (A == 32 && B == 64);
 }
 
 hipError_t launch_fft_zr(const float2* in, float2* out, int64_t nrows, int A, int B, const DeviceMatrix& FA,
@@ -1483,10 +1279,9 @@ hipError_t launch_fft_zr(const float2* in, float2* out, int64_t nrows, int A, in
     if (nrows <= 0) return hipSuccess;
     // the kernel indexes the stage matrices and the twiddle table without bounds checks
     if (FA.K != A || FA.N != A || FB.K != B || FB.N != B || !Tw) return hipErrorInvalidValue;
-    // three-product scheme where its registers still allow three waves per SIMD (measured 15 % faster
-    // at 16 x 32); 32 x 32 would spill with it and runs the four-product scheme
+    // three-product scheme where its registers allow; 32 x 32 would spill with it and runs the
+    // four-product scheme
     if (A == 16 && B == 16) return launch_inst<16, 16, 6, true>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
-    if (A == 16 && B == 32) return launch_inst<16, 32, 3, true>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     if (A == 32 && B == 32) return launch_inst<32, 32, 2, false>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     if (A == 32 && B == 64) {
         // eight waves per workgroup, one workgroup per CU

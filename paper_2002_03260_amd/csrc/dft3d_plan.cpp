@@ -199,11 +199,11 @@ dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out
     return s;
 }
 
-int64_t default_split(int64_t n, int axis)
+int64_t default_split(int64_t n)
 {
     // 16 x (C*16), the split whose second factor the fused kernels split once more (2048: a third of the
-    // matrix-core work of 32 x 64): 2048 points on any axis, 1024 points on the contiguous one
-    if (n == 2048 || (axis == 2 && n == 1024)) return 16;
+    // matrix-core work of 32 x 64)
+    if (n == 2048 || n == 1024) return 16;
     if ((n & (n - 1)) == 0) {
         int lg = 0;
         while ((int64_t(1) << (lg + 1)) <= n) ++lg;
@@ -709,7 +709,7 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
         }
     } else {
         for (int j = 0; j < 3 && s == DFT3D_OK; ++j) {
-            int64_t A = (split && split[j] > 0) ? split[j] : default_split(n[j], j);
+            int64_t A = (split && split[j] > 0) ? split[j] : default_split(n[j]);
             if (A < 1 || n[j] % A != 0) {
                 set_error("plan_create: split %lld does not divide axis length %lld", (long long)A,
                           (long long)n[j]);
@@ -777,14 +777,14 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
     if (s != DFT3D_OK) return s;      // (the guard frees the plan)
     guard.p = nullptr;
     // Plans whose three axes all fuse.  Where both strided axes run on kernels that take separate input
-    // and output strides and the x axis has 2048 points, the x pass comes first and writes a transposed
+    // and output strides and the x axis has 2048 points or more, the x pass comes first and writes a transposed
     // intermediate (see run_fused_s_xfirst); otherwise passes z, y, x, with padded rows in the workspace
     // intermediate between y and x where they help.
     const bool all_fused_candidate = f == DFT3D_FFT &&
                                      !(flags & (DFT3D_FLAG_UNFUSED | DFT3D_FLAG_CLOBBER_INPUT | DFT3D_FLAG_COMPLEX128)) &&
                                      n[0] > 1 && n[1] > 1 && n[2] > 1 && n[2] % 16 == 0 &&
                                      fft_z_supported((int)p->A[2], (int)p->B[2]);
-    if (all_fused_candidate && n[0] == 2048 && fft_sr_supported((int)p->A[1], (int)p->B[1], n[0] * n[2]) &&
+    if (all_fused_candidate && n[0] >= 2048 && fft_sr_supported((int)p->A[1], (int)p->B[1], n[0] * n[2]) &&
         fft_sr_supported((int)p->A[0], (int)p->B[0], n[1] * n[2]))
         p->x_first = true;
     else if (all_fused_candidate && (n[1] * n[2] * 8) % 8192 == 0 && n[1] * (n[2] + 16) <= (int64_t(1) << 21) &&
