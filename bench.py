@@ -369,9 +369,9 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
         if ax is not None and w.splits and "reorder_xyz" not in dom_name and "z_reorder" != dom_name and "phase" not in dom_name:
             A, B = w.splits[ax]
             if "fused" in dom_name:
-                # fused kernels with three real products per complex product: 16x16 and 16x32 on every
-                # axis, 32x64 on the contiguous axis; the others use four
-                three = (A == 16 and B in (16, 32)) or (ax == 2 and (A, B) == (32, 64))
+                # fused kernels with three real products per complex product: 16x16 on every axis, 32x64 on
+                # the contiguous axis; the others use four
+                three = (A == 16 and B == 16) or (ax == 2 and (A, B) == (32, 64))
                 per_cmac = 6.0 if three else 8.0
                 flops = (per_cmac * (A + B) + 6.0) * E
                 if ax == 2 and A == 16 and B in (32, 64, 128):
@@ -379,7 +379,7 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
                     # with three real products each; the C-point butterflies and both twiddles are vector
                     # arithmetic and are not counted as matrix-core work
                     flops = 6.0 * 32 * E
-                elif ax != 2 and (A, B) == (16, 128):
+                elif ax != 2 and A == 16 and B in (32, 64, 128):
                     # the same on a strided axis: three real products in the first stage, four in the last
                     # (whose accumulators are the resident output tile)
                     flops = (6.0 * 16 + 8.0 * 16) * E
