@@ -247,10 +247,11 @@ hipError_t launch_zn_inst(const float2* in, float2* out, int64_t nrows, const De
 //   after the fourth slot the accumulators are stored to rows k_a + 16*k_c + 16*C*k_b and cleared.
 // Matrix-core work per point: 6*16 (first stage) + 8*16 (last stage) flop, against 6*32 + 8*64 of the
 // streaming kernel for 32 x 64.  One workgroup of eight waves per CU at C = 8.
-template <int C>
+template <int C, int CH>
 struct FftSnLayout {
     static constexpr int B = 16 * C, N = 16 * B, CP = C / 2;
-    static constexpr size_t ring_elems = (size_t)2 * CP * 16 * 64;            // one buffer: [h][m][k_a][beta 4][col 16]
+    static constexpr int KP = 64 * CH;                                         // elements per (h, m, k_a): [column group][beta 4][col 16]
+    static constexpr size_t ring_elems = (size_t)2 * CP * 16 * KP;            // one buffer: [h][m][k_a][column group][beta][col]
     static constexpr size_t ring_bytes = 2 * ring_elems * 8;
     static constexpr size_t fa_bytes = 3 * 64 * 16;                            // [re, im, re+im][lane] x (4 k-steps)
     static constexpr size_t tw1_bytes = (size_t)B * 16 * 8;                    // T[b][k_a]
@@ -259,12 +260,12 @@ struct FftSnLayout {
     static constexpr size_t lds_bytes = ring_bytes + fa_bytes + tw1_bytes + tw2_bytes + fb_bytes;
 };
 
-template <int C, bool SWAP, int WPC>
+template <int C, int CH, bool SWAP, int WPC>
 __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, DeviceMatrix FA, DeviceMatrix FB,
                                                       const float2* __restrict__ Tw, float scale)
 {
-    typedef FftSnLayout<C> L;
-    constexpr int B = L::B, CP = L::CP;
+    typedef FftSnLayout<C, CH> L;
+    constexpr int B = L::B, CP = L::CP, KP = L::KP;
     static_assert(C == 2 || C == 4 || C == 8, "second factor 32, 64 or 128");
 
     extern __shared__ __align__(16) unsigned char smem_sn[];
@@ -308,7 +309,7 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
     // ---- geometry --------------------------------------------------------------------------------------
     // tile -> (o, y, column block): tiles are visited first, first + nwg, ..; the position is advanced with
     // carries instead of being divided out of the tile index every time
-    const int64_t ztt = a.Zt;
+    const int64_t ztt = a.Zt / CH;                     // tiles along the columns (the host checks that CH divides Zt)
     const int64_t per_o = a.Yn * ztt;
     const int64_t ntiles = a.O * per_o;
     const int64_t nwg = (int64_t)gridDim.x * gridDim.y;
@@ -341,16 +342,18 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
     // producer unit of this wave
     const int pb = wave >> 1, ph = wave & 1;
     const unsigned ld_lane = (unsigned)(B * lq) * (unsigned)inN + (unsigned)l16;
-    f32x2 xs[CP][4];
+    f32x2 xs[CP][4][CH];
     auto request = [&](int slot) {                     // of the tile at rq
-        const float2* src = X + ((int64_t)rq.o * a.inO + (int64_t)rq.y * a.inY + (int64_t)rq.zt * 16) +
+        const float2* src = X + ((int64_t)rq.o * a.inO + (int64_t)rq.y * a.inY + (int64_t)rq.zt * (16 * CH)) +
                             (int64_t)(4 * slot + pb + 16 * ph) * inN;
 #pragma unroll
         for (int cp = 0; cp < CP; ++cp)
 #pragma unroll
             for (int s = 0; s < 4; ++s)
-                xs[cp][s] = __builtin_nontemporal_load(
-                    reinterpret_cast<const f32x2*>(&(src + (int64_t)(4 * B * s + 32 * cp) * inN)[ld_lane]));
+#pragma unroll
+                for (int cg = 0; cg < CH; ++cg)          // neighbouring 128-byte pieces of the same rows
+                    xs[cp][s][cg] = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(
+                        &(src + (int64_t)(4 * B * s + 32 * cp) * inN + 16 * cg)[ld_lane]));
     };
     // Requests past the last slot are not skipped: they re-read the last tile (every access in bounds) and
     // the producer step that uses them writes a ring buffer nobody reads.  With unconditional loads the
@@ -361,10 +364,11 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
         request(slot);
     };
 
-    f32x4 wr[2][C], wi[2][C];                           // accumulators: [k_a = 2*wave + j][k_c], register v = k_b = 4*lq + v
+    // accumulators: [k_a = 2*wave + j, column group][k_c], register v = k_b = 4*lq + v
+    f32x4 wr[2 * CH][C], wi[2 * CH][C];
     auto clear_acc = [&]() {
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 2 * CH; ++j)
 #pragma unroll
             for (int kc = 0; kc < C; ++kc) {
                 wr[j][kc] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -375,47 +379,55 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
     // ---- producer: slot `slot` (0..3) of the tile whose data sits in xs -> ring buffer `buf`; then the
     // request for global slot g_next into the same registers
     auto produce = [&](int slot, int buf, int64_t g_next) {
-        f32x4 zr[CP], zi[CP];
         const f32x4 fr = faT[lane], fi = faT[64 + lane], fs = faT[128 + lane];
-        f32x4 p1[CP], p2[CP], p3[CP];
+        f32x4 p1[CH][CP], p2[CH][CP], p3[CH][CP];
 #pragma unroll
-        for (int cp = 0; cp < CP; ++cp) {
-            p1[cp] = f32x4{0.f, 0.f, 0.f, 0.f};
-            p2[cp] = p1[cp];
-            p3[cp] = p1[cp];
-        }
+        for (int cg = 0; cg < CH; ++cg)
+#pragma unroll
+            for (int cp = 0; cp < CP; ++cp) {
+                p1[cg][cp] = f32x4{0.f, 0.f, 0.f, 0.f};
+                p2[cg][cp] = p1[cg][cp];
+                p3[cg][cp] = p1[cg][cp];
+            }
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
-            for (int cp = 0; cp < CP; ++cp) {
-                const float xr = SWAP ? xs[cp][s].y : xs[cp][s].x, xi = SWAP ? xs[cp][s].x : xs[cp][s].y;
-                p1[cp] = mfma(fr[s], xr, p1[cp]);
-                p2[cp] = mfma(fi[s], xi, p2[cp]);
-                p3[cp] = mfma(fs[s], xr + xi, p3[cp]);
-            }
+            for (int cg = 0; cg < CH; ++cg)
+#pragma unroll
+                for (int cp = 0; cp < CP; ++cp) {
+                    const f32x2 x = xs[cp][s][cg];
+                    const float xr = SWAP ? x.y : x.x, xi = SWAP ? x.x : x.y;
+                    p1[cg][cp] = mfma(fr[s], xr, p1[cg][cp]);
+                    p2[cg][cp] = mfma(fi[s], xi, p2[cg][cp]);
+                    p3[cg][cp] = mfma(fs[s], xr + xi, p3[cg][cp]);
+                }
         __builtin_amdgcn_sched_barrier(0);
         request_slot(g_next);
         __builtin_amdgcn_sched_barrier(0);
         const int beta = 4 * slot + pb;
 #pragma unroll
-        for (int cp = 0; cp < CP; ++cp) {
-            // twiddles of this lane's four k_a = 4*lq + v: 32 contiguous bytes of T[b = 16*c + beta][k_a]
-            const f32x4* t = reinterpret_cast<const f32x4*>(tw1 + (16 * (ph + 2 * cp) + beta) * 16 + 4 * lq);
-            const f32x4 t01 = t[0], t23 = t[1];
+        for (int cg = 0; cg < CH; ++cg) {
+            f32x4 zr[CP], zi[CP];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float tx = (v < 2 ? t01 : t23)[2 * (v & 1)], ty = (v < 2 ? t01 : t23)[2 * (v & 1) + 1];
-                const float re = p1[cp][v] - p2[cp][v], im = p3[cp][v] - p1[cp][v] - p2[cp][v];
-                zr[cp][v] = re * tx - im * ty;
-                zi[cp][v] = re * ty + im * tx;
+            for (int cp = 0; cp < CP; ++cp) {
+                // twiddles of this lane's four k_a = 4*lq + v: 32 contiguous bytes of T[b = 16*c + beta][k_a]
+                const f32x4* t = reinterpret_cast<const f32x4*>(tw1 + (16 * (ph + 2 * cp) + beta) * 16 + 4 * lq);
+                const f32x4 t01 = t[0], t23 = t[1];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float tx = (v < 2 ? t01 : t23)[2 * (v & 1)], ty = (v < 2 ? t01 : t23)[2 * (v & 1) + 1];
+                    const float re = p1[cg][cp][v] - p2[cg][cp][v], im = p3[cg][cp][v] - p1[cg][cp][v] - p2[cg][cp][v];
+                    zr[cp][v] = re * tx - im * ty;
+                    zi[cp][v] = re * ty + im * tx;
+                }
             }
+            if constexpr (CP > 1) small_dft<CP>(zr, zi);
+            f32x2* zw = ring + (size_t)buf * L::ring_elems + (size_t)(ph * CP) * (16 * KP) + cg * 64 + pb * 16 + l16;
+#pragma unroll
+            for (int m = 0; m < CP; ++m)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) zw[m * (16 * KP) + (4 * lq + v) * KP] = f32x2{zr[m][v], zi[m][v]};
         }
-        if constexpr (CP > 1) small_dft<CP>(zr, zi);
-        f32x2* zw = ring + (size_t)buf * L::ring_elems + (size_t)(ph * CP) * 1024 + pb * 16 + l16;
-#pragma unroll
-        for (int m = 0; m < CP; ++m)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) zw[m * 1024 + (4 * lq + v) * 64] = f32x2{zr[m][v], zi[m][v]};
     };
 
     // ---- consumer: slot `slot` of the tile at st from ring buffer `buf`
@@ -431,12 +443,12 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
         }
         const f32x2* zr0 = ring + (size_t)buf * L::ring_elems + lq * 16 + l16;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const f32x2* zp = zr0 + (2 * wave + j) * 64;
+        for (int j = 0; j < 2 * CH; ++j) {             // j = 2 * column group + (k_a & 1)
+            const f32x2* zp = zr0 + (2 * wave + (j & 1)) * KP + (j >> 1) * 64;
             float ur[C], ui[C];
 #pragma unroll
             for (int m = 0; m < CP; ++m) {
-                const f32x2 e0 = zp[m * 1024], e1 = zp[(CP + m) * 1024];
+                const f32x2 e0 = zp[m * (16 * KP)], e1 = zp[(CP + m) * (16 * KP)];
                 // w_C^m e1 (forward): C = 2: 1;  C = 4: 1, -i;  C = 8: 1, (1 - i) h, -i, (-1 - i) h
                 float qr, qi;
                 constexpr float h = 0.70710678118654752440f;
@@ -468,19 +480,21 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
 
     auto store_tile = [&]() {                          // the tile at st
         // rows k_a + 16*k_c + 16*C*k_b with k_b = 4*lq + v; the lane part needs 64 bits at N = 2048
-        float2* dst = Y + ((int64_t)st.o * a.outO + (int64_t)st.y * a.outY + (int64_t)st.zt * 16) +
+        float2* dst = Y + ((int64_t)st.o * a.outO + (int64_t)st.y * a.outY + (int64_t)st.zt * (16 * CH)) +
                       ((int64_t)(16 * C * 4 * lq) * outN + l16);
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int ja = 0; ja < 2; ++ja)
 #pragma unroll
             for (int kc = 0; kc < C; ++kc)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float re = wr[j][kc][v], im = wi[j][kc][v];
-                    __builtin_nontemporal_store(
-                        SWAP ? f32x2{im, re} : f32x2{re, im},
-                        reinterpret_cast<f32x2*>(dst + (int64_t)(2 * wave + j + 16 * kc + 16 * C * v) * outN));
-                }
+                for (int v = 0; v < 4; ++v)
+#pragma unroll
+                    for (int cg = 0; cg < CH; ++cg) {     // neighbouring 128-byte pieces of one row
+                        const float re = wr[2 * cg + ja][kc][v], im = wi[2 * cg + ja][kc][v];
+                        __builtin_nontemporal_store(
+                            SWAP ? f32x2{im, re} : f32x2{re, im},
+                            reinterpret_cast<f32x2*>(dst + (int64_t)(2 * wave + ja + 16 * kc + 16 * C * v) * outN + 16 * cg));
+                    }
     };
 
     // Slots are numbered g = 0, 1, .. across the tiles of this workgroup.  One barrier per slot: before it
@@ -509,18 +523,19 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
     }
 }
 
-template <int C, int WPC>
+template <int C, int CH, int WPC>
 hipError_t launch_sn_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw,
                           float scale, int conj, hipStream_t stream)
 {
-    const int64_t ntiles = a.O * a.Yn * a.Zt;
+    const int64_t ntiles = a.O * a.Yn * (a.Zt / CH);
     const int64_t blocks = ntiles < 256 * WPC ? ntiles : 256 * WPC;      // persistent workgroups
+    constexpr size_t lds = FftSnLayout<C, CH>::lds_bytes;
     if (conj)
-        hipLaunchKernelGGL((k_fft_sn<C, true, WPC>), dim3((unsigned)blocks), dim3(512), FftSnLayout<C>::lds_bytes, stream,
-                           a, FA, FB, Tw, scale);
+        hipLaunchKernelGGL((k_fft_sn<C, CH, true, WPC>), dim3((unsigned)blocks), dim3(512), lds, stream, a, FA, FB, Tw,
+                           scale);
     else
-        hipLaunchKernelGGL((k_fft_sn<C, false, WPC>), dim3((unsigned)blocks), dim3(512), FftSnLayout<C>::lds_bytes, stream,
-                           a, FA, FB, Tw, scale);
+        hipLaunchKernelGGL((k_fft_sn<C, CH, false, WPC>), dim3((unsigned)blocks), dim3(512), lds, stream, a, FA, FB, Tw,
+                           scale);
     return hipGetLastError();
 }
 
@@ -551,24 +566,25 @@ bool fft_sn_supported(int A, int B, int64_t I)
 }
 
 namespace {
-template <int C, int WPC>
+template <int C, int CH, int WPC>
 hipError_t configure_sn()
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<C, false, WPC>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<C>::lds_bytes);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<C, CH, false, WPC>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<C, CH>::lds_bytes);
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<C, true, WPC>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<C>::lds_bytes);
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<C, CH, true, WPC>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<C, CH>::lds_bytes);
 }
 }  // namespace
 
 hipError_t configure_fft_nested_kernels()
 {
-    hipError_t e = configure_sn<8, 1>();
-    if (e != hipSuccess) return e;
-    e = configure_sn<4, 2>();
-    if (e != hipSuccess) return e;
-    return configure_sn<2, 2>();
+    hipError_t e = configure_sn<8, 1, 1>();
+    if (e == hipSuccess) e = configure_sn<4, 1, 2>();
+    if (e == hipSuccess) e = configure_sn<4, 2, 1>();
+    if (e == hipSuccess) e = configure_sn<2, 1, 2>();
+    if (e == hipSuccess) e = configure_sn<2, 4, 1>();
+    return e;
 }
 
 hipError_t launch_fft_sn(const FftStridedArgs& a, int A, int B, const DeviceMatrix& FA, const DeviceMatrix& FB,
@@ -579,9 +595,20 @@ hipError_t launch_fft_sn(const FftStridedArgs& a, int A, int B, const DeviceMatr
     if (A != 16 || a.inN < 16 || a.outN < 16 || a.inN > lim || a.outN > lim || FA.K != 16 || FA.N != 16 ||
         FB.K != B || FB.N != B || !Tw)
         return hipErrorInvalidValue;
-    if (B == 128) return launch_sn_inst<8, 1>(a, FA, FB, Tw, scale, conj, stream);
-    if (B == 64) return launch_sn_inst<4, 2>(a, FA, FB, Tw, scale, conj, stream);
-    if (B == 32) return launch_sn_inst<2, 2>(a, FA, FB, Tw, scale, conj, stream);
+    // Wider tiles mean longer contiguous pieces per row (128 bytes per 16 columns) but one workgroup per CU
+    // instead of two once the accumulators of N * columns outputs fill its registers.  Measured: 1024 points,
+    // 32 columns: 3.74 -> 3.48 ms (y) and 4.55 -> 3.91 ms (x) at 1024^3; 512 points, 64 columns: 0.474 ->
+    // 0.448 ms for the x pass of 512^3 (rows 2 MiB apart) but 0.426 -> 0.442 ms for its y pass (rows 4 KiB
+    // apart), so the wide tile is taken for rows at least 32 KiB apart.
+    if (B == 128) return launch_sn_inst<8, 1, 1>(a, FA, FB, Tw, scale, conj, stream);
+    if (B == 64) {
+        if (a.Zt % 2 == 0) return launch_sn_inst<4, 2, 1>(a, FA, FB, Tw, scale, conj, stream);
+        return launch_sn_inst<4, 1, 2>(a, FA, FB, Tw, scale, conj, stream);
+    }
+    if (B == 32) {
+        if (a.Zt % 4 == 0 && a.inN >= 4096) return launch_sn_inst<2, 4, 1>(a, FA, FB, Tw, scale, conj, stream);
+        return launch_sn_inst<2, 1, 2>(a, FA, FB, Tw, scale, conj, stream);
+    }
     return hipErrorInvalidValue;
 }
 

@@ -459,8 +459,9 @@ def test_fft_fused_axis_kernel(dft, shape, split):
                                          ((3, 256, 160), None), ((512, 5, 16), (16, 1, 4)),
                                          # inner extents that are multiples of 32: tiles of 32 columns
                                          ((512, 2, 32), None), ((3, 512, 96), None), ((512, 1, 352), None),
-                                         # multiples of 64: the streaming kernel with 64-column tiles
+                                         # multiples of 64 with rows at least 32 KiB apart: 64-column tiles
                                          ((512, 1, 64), None), ((2, 512, 192), None), ((512, 3, 64), None),
+                                         ((512, 64, 64), None), ((512, 3, 2112), None),
                                          # 2048 = 32 x 64 on a strided axis (streaming kernel, 16-column tiles)
                                          ((2048, 1, 16), None), ((2, 2048, 48), None), ((2048, 3, 16), None),
                                          # 2048 = 16 x (8*16): second factor split once more inside the kernel
@@ -468,7 +469,7 @@ def test_fft_fused_axis_kernel(dft, shape, split):
                                          ((2048, 3, 32), (16, 1, 1)), ((2048, 2, 4112), (16, 1, 1)),
                                          # 1024 = 16 x (4*16), against 32 x 32 by default
                                          ((1024, 1, 32), (16, 1, 1)), ((2, 1024, 48), (1, 16, 1)),
-                                         ((1024, 5, 1040), (16, 1, 1))])
+                                         ((1024, 5, 1040), (16, 1, 1)), ((1024, 3, 1056), (16, 1, 1))])
 def test_fft_fused_strided_axis_kernel(dft, shape, split):
     """The single-kernel x / y pass equals first stage + twiddle + second stage + re-ordering."""
     say(f"case fft fused strided axis {shape} split {split}")
