@@ -554,8 +554,28 @@ def run_all(args, opts, mods):
     if parity_on:
         a, b = table[HEADLINE]["parity"], table["cfg5-fft"]["parity"]
         a["note"] = b["note"] = "the two formulations are compared on the same outputs of the same input"
+    # the opt-in arithmetic variants of the contraction, on the same buffers and the same oracle sample
+    variants = {}
+
+    def with_flag(**kw):
+        o = argparse.Namespace(**vars(opts))
+        for key, val in kw.items():
+            setattr(o, key, val)
+        return o
+
+    for label, kw in (("cfg5-kdft+3m", {"three_m": True}), ("cfg5-kdft+bf16x3", {"bf16x3": True})):
+        log(label)
+        r = measure(HEADLINE, 5, 1, 0.0, with_flag(**kw), mods, buffers=(x, out, ws),
+                    want_parity=ref5 if parity_on else False)
+        variants[label] = table_entry(r)
     del x, out, ws, ref5
     torch.cuda.empty_cache()
+    for label, kw in (("cfg2+3m", {"three_m": True}), ("cfg2+bf16x3", {"bf16x3": True}),
+                      ("cfg2+complex128", {"complex128": True})):
+        log(label)
+        r = measure("cfg2", 100, 10, 0.3 if args.settle is None else args.settle, with_flag(**kw), mods,
+                    want_parity=parity_on and "complex128" not in kw)
+        variants[label] = table_entry(r)
     for name, k, wu in TABLE_RUNS:
         if name == "cfg5-fft":
             continue
@@ -563,6 +583,7 @@ def run_all(args, opts, mods):
         r = measure(name, k, wu, 0.3 if args.settle is None else args.settle, opts, mods, want_parity=parity_on)
         table[name] = table_entry(r)
     head["configs"] = {k: table[k] for k in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5-kdft", "cfg5-fft")}
+    head["variants"] = variants
     head["paper_context"] = PAPER_CONTEXT
     if not args.no_cpu_baseline:
         log("cpu_baseline: the oracle on line samples of the 2048^3 workload")
