@@ -504,22 +504,16 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
     request_slot(0);
     __syncthreads();                                   // tables
     produce(0, 0, 1);
-    for (int64_t g = 0; g < G; g += 4) {
+    for (int64_t g = 0; g < G; ++g) {
         __syncthreads();
-        produce(1, 1, g + 2);
-        consume(0, 0);
-        __syncthreads();
-        produce(2, 0, g + 3);
-        consume(1, 1);
-        __syncthreads();
-        produce(3, 1, g + 4);
-        consume(2, 0);
-        __syncthreads();
-        produce(0, 0, g + 5);
-        consume(3, 1);
-        store_tile();
-        clear_acc();
-        advance(st);
+        const int slot = (int)(g & 3), buf = (int)(g & 1);
+        produce((slot + 1) & 3, buf ^ 1, g + 2);
+        consume(slot, buf);
+        if (slot == 3) {
+            store_tile();
+            clear_acc();
+            advance(st);
+        }
     }
 }
 
