@@ -191,7 +191,12 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
     w, form, named_form = resolve(name, wl, dft)
     big = w.elements > (1 << 30)
     coords = wl.make_coords(w)
-    split = [a for a, _ in w.splits] if (form == dft.FFT and w.splits) else None
+    # (opts.split_first: first-stage lengths that replace the workload's own split, e.g. the 32 x 64 split the
+    # 2048^3 configuration is named with, next to the library's default 16 x 128)
+    splits = w.splits
+    if getattr(opts, "split_first", None) and form == dft.FFT:
+        splits = tuple((a, n // a) for a, n in zip(opts.split_first, w.shape))
+    split = [a for a, _ in splits] if (form == dft.FFT and splits) else None
     flags = 0
     if opts.unfused and form == dft.FFT:
         flags = dft.FLAG_UNFUSED     # 10 passes
@@ -368,7 +373,7 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
         dom = max(range(npass), key=lambda i: pass_ms[i])
         dom_ms = pass_ms[dom]
         dom_name = pass_names[dom] if dom < len(pass_names) else f"pass{dom}"
-        if (npass == 3 and not c128 and w.splits and w.splits[0] == w.splits[1] and pass_names[dom][0] in "xy"):
+        if (npass == 3 and not c128 and splits and splits[0] == splits[1] and pass_names[dom][0] in "xy"):
             # the y and the x pass are two launches of one kernel: the roofline of that kernel
             # uses its average launch duration, which is what a per-kernel profile reports
             dom_ms = 0.5 * sum(pass_ms[i] for i in range(3) if pass_names[i][0] in "xy")
@@ -380,8 +385,8 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
         # complex128 plans run staged passes with four real products throughout
         ax = {"z": 2, "y": 1, "x": 0}.get(dom_name[0])
         flops = 0.0
-        if ax is not None and w.splits and "reorder_xyz" not in dom_name and "z_reorder" != dom_name and "phase" not in dom_name:
-            A, B = w.splits[ax]
+        if ax is not None and splits and "reorder_xyz" not in dom_name and "z_reorder" != dom_name and "phase" not in dom_name:
+            A, B = splits[ax]
             if "fused" in dom_name:
                 # fused kernels with three real products per complex product: 16x16 on every axis, 32x64 on
                 # the contiguous axis; the others use four
@@ -474,7 +479,7 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
                           else "fp32 MFMA",
             "shape": list(w.shape), "input": f"{'complex128' if c128 else 'complex64'}, iid {w.dist}, seed {w.seed}",
             "nonuniform": w.nonuniform,
-            "split": [list(s) for s in w.splits] if (form == dft.FFT and w.splits) else None,
+            "split": [list(s) for s in splits] if (form == dft.FFT and splits) else None,
         },
         "roofline": roofline,
     }
@@ -507,6 +512,8 @@ def table_entry(r):
         "achieved": ro["achieved"], "peak": ro["peak"], "unit": ro["unit"], "frac": ro["frac"],
         "traffic": ro["traffic"], "passes_ms": ro["passes_ms"],
     }
+    if r["config"].get("split"):
+        e["split"] = r["config"]["split"]
     for k in ("hbm_frac", "mfma_frac", "note", "kernel_note"):
         if k in ro:
             e[k] = ro[k]
@@ -568,6 +575,12 @@ def run_all(args, opts, mods):
         r = measure(HEADLINE, 5, 1, 0.0, with_flag(**kw), mods, buffers=(x, out, ws),
                     want_parity=ref5 if parity_on else False)
         variants[label] = table_entry(r)
+    # the FFT formulation with the split the configuration is named with (2048 = 32 x 64); the library's own
+    # default, 16 x 128 with the second factor split once more inside the kernels, is the cfg5-fft entry
+    log("cfg5-fft, split 32 x 64")
+    r = measure("cfg5-fft", 10, 2, 0.0, with_flag(split_first=(32, 32, 32)), mods, buffers=(x, out, ws),
+                want_parity=ref5 if parity_on else False)
+    variants["cfg5-fft, split 32x64"] = table_entry(r)
     del x, out, ws, ref5
     torch.cuda.empty_cache()
     for label, kw in (("cfg2+3m", {"three_m": True}), ("cfg2+bf16x3", {"bf16x3": True}),
