@@ -390,22 +390,19 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
             if "fused" in dom_name:
                 # fused kernels with three real products per complex product: 16x16 on every axis, 32x64 on
                 # the contiguous axis; the others use four
-                three = (A == 16 and B == 16) or (ax == 2 and (A, B) == (32, 64))
+                three = (A == 16 and B == 16)
                 per_cmac = 6.0 if three else 8.0
                 flops = (per_cmac * (A + B) + 6.0) * E
-                if ax == 2 and A == 16 and B in (32, 64, 128):
-                    # second factor split once more inside the kernel (B = C*16): two 16-point matrix stages
-                    # with three real products each; the C-point butterflies and both twiddles are vector
-                    # arithmetic and are not counted as matrix-core work
-                    flops = 6.0 * 32 * E
-                elif ax != 2 and A == 16 and B in (32, 64, 128):
+                nested = (A == 16 and B in (32, 64, 128)) or (A, B) == (32, 64)
+                if ax == 2 and nested:
+                    # second factor split once more inside the kernel (B = C*16): an A-point and a 16-point
+                    # matrix stage with three real products each; the C-point butterflies and both twiddles
+                    # are vector arithmetic and are not counted as matrix-core work
+                    flops = 6.0 * (A + 16) * E
+                elif ax != 2 and nested:
                     # the same on a strided axis: three real products in the first stage, four in the last
                     # (whose accumulators are the resident output tile)
-                    flops = (6.0 * 16 + 8.0 * 16) * E
-                elif ax != 2 and (A, B) == (32, 64):
-                    # streaming kernel of the strided axes: three real products in the first stage, four
-                    # in the second (whose accumulators are the resident output tile)
-                    flops = (6.0 * A + 8.0 * B + 6.0) * E
+                    flops = (6.0 * A + 8.0 * 16) * E
             elif "stage1" in dom_name:
                 # strided stages with a 16 / 32 / 64 matrix run the three-product streaming kernel, and
                 # every stage of 128 points or more takes the three-product scheme

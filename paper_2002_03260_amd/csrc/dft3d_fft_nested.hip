@@ -1,18 +1,19 @@
-// FFT formulation with the second factor split once more: N = 16 * B with B = C * 16, C = 2, 4 or 8
-// (512 = 16 * 32, 1024 = 16 * 64, 2048 = 16 * 128).
+// FFT formulation with the second factor split once more: N = A * B with A = 16 and B = C * 16, C = 2, 4
+// or 8 (512 = 16 * 32, 1024 = 16 * 64, 2048 = 16 * 128), or A = 32 and B = 4 * 16 (2048 = 32 * 64).
 //
-// Eq. 13 - 16 for one axis with n = B*l + b, k = k_a + 16*k2 read
-//     Z[k_a, b]  = T[k_a, b] * sum_l F16[k_a, l] x[B*l + b]
-//     X[k_a + 16*k2] = sum_b FB[k2, b] Z[k_a, b]
-// and cost 6 * (16 + B) matrix-core flop per point.  The B-point transform of the second line is a
+// Eq. 13 - 16 for one axis with n = B*l + b, k = k_a + A*k2 read
+//     Z[k_a, b]  = T[k_a, b] * sum_l FA[k_a, l] x[B*l + b]
+//     X[k_a + A*k2] = sum_b FB[k2, b] Z[k_a, b]
+// and cost 6 * (A + B) matrix-core flop per point.  The B-point transform of the second line is a
 // DFT like the whole one, so the same split applies to it: b = 16*c + beta, k2 = k_c + C*k_b gives
 //     FB[k2, b] = w_C^(c k_c) * w_B^(k_c beta) * F16[k_b, beta]
 //     Y[k_a, k_c, beta] = w_B^(k_c beta) * sum_c w_C^(c k_c) Z[k_a, 16*c + beta]      (C-point butterflies)
-//     X[k_a + 16*(k_c + C*k_b)] = sum_beta F16[k_b, beta] Y[k_a, k_c, beta]
-// Both matrix stages are 16-point now (6 * 32 flop per point on the matrix cores, a third of the
-// 32 x 64 split at N = 2048) and the C-point stage in the middle is plain vector arithmetic on values a
-// lane already holds.  Every table the kernel needs is part of the plan of a 16 x B split: F16 is its
-// first-stage matrix, T its twiddle table, w_B^(k_c beta) = FB[k_c, beta].
+//     X[k_a + A*(k_c + C*k_b)] = sum_beta F16[k_b, beta] Y[k_a, k_c, beta]
+// The last matrix stage is 16-point now (6 * (A + 16) flop per point on the matrix cores: a third of the
+// plain 32 x 64 split at N = 2048 with A = 16, less than half with A = 32) and the C-point stage in the
+// middle is plain vector arithmetic on values a lane already holds.  Every table the kernels need is part
+// of the plan of an A x B split: FA is its first-stage matrix, T its twiddle table,
+// w_B^(k_c beta) = FB[k_c, beta] and F16[k_b, beta] = FB[C*k_b, beta].
 //
 // BACKWARD runs the forward transform on data with real and imaginary parts exchanged, and exchanges
 // them again in the result: with s(z) = i * conj(z), DFT(s(x)) = s(IDFT(x)).  The exchange is a choice
@@ -80,22 +81,23 @@ __device__ __forceinline__ void small_dft(T (&r)[C], T (&i)[C])
 //     once in that order.  D register v = (k_b = 4*(lane/16) + v, k_a = lane % 16): the output index
 //     k_a + 16*k_c + 16*C*k_b runs along the lanes, so loads and stores are 128-byte segments.
 // Three real products per complex product in both matrix stages: 24 * C matrix instructions per row.
-template <int C, bool SWAP, int WPC>
+// NAB = A / 16: first stage of 16 or 32 points (32 x (C*16): two blocks of k_a, eight k-steps).
+template <int NAB, int C, bool SWAP, int WPC>
 __global__ __launch_bounds__(256, WPC) void k_fft_zn(const float2* __restrict__ in, float2* __restrict__ out,
                                                     int64_t nrows, DeviceMatrix FA, DeviceMatrix FB,
                                                     const float2* __restrict__ Tw, float scale)
 {
-    constexpr int B = 16 * C, N = 16 * B;
-    __shared__ float2 tw1s[C * 4 * 64];      // [c][v][lane]: T[k_a = lane%16][16*c + 4*(lane/16) + v]
+    constexpr int A = 16 * NAB, NS1 = A / 4, B = 16 * C, N = A * B;
+    __shared__ float2 tw1s[C * NAB * 4 * 64];    // [c][ab][v][lane]: T[k_a = 16*ab + lane%16][16*c + 4*(lane/16) + v]
     __shared__ __align__(16) float2 tw2s[C * 16];         // [k_c][beta]: w_B^(k_c beta)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int l16 = lane & 15, lq = lane >> 4;
 
-    for (int e = tid; e < C * 4 * 64; e += 256) {
-        const int ln = e & 63, v = (e >> 6) & 3, c = e >> 8;
-        tw1s[e] = Tw[(ln & 15) * B + 16 * c + 4 * (ln >> 4) + v];
+    for (int e = tid; e < C * NAB * 4 * 64; e += 256) {
+        const int ln = e & 63, v = (e >> 6) & 3, ab = (e >> 8) % NAB, c = (e >> 8) / NAB;
+        tw1s[e] = Tw[(16 * ab + (ln & 15)) * B + 16 * c + 4 * (ln >> 4) + v];
     }
     for (int e = tid; e < C * 16; e += 256) {
         const int beta = e & 15, kc = e >> 4;
@@ -108,27 +110,33 @@ __global__ __launch_bounds__(256, WPC) void k_fft_zn(const float2* __restrict__ 
     const int64_t nwaves = (int64_t)gridDim.x * 4;
     if (wave >= nrows) return;                    // after the only barrier
 
-    // stage-1 B operand F16[k_a = l16][l = 4*s + lq]; stage-3 A operand scale * F16[k_b = l16][beta = 4*lq + v]
-    float fa_r[4], fa_i[4], fa_s[4], fb_r[4], fb_i[4], fb_s[4];
+    // stage-1 B operand FA[k_a = 16*ab + l16][l = 4*s + lq]; stage-3 A operand scale * F16[k_b = l16][beta = 4*lq + v]
+    // with F16[k_b, beta] = w_16^(k_b beta) = FB[C*k_b, beta]
+    float fa_r[NAB][NS1], fa_i[NAB][NS1], fa_s[NAB][NS1], fb_r[4], fb_i[4], fb_s[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const int ia = (4 * s + lq) * FA.ld + l16;
-        fa_r[s] = FA.re[ia];
-        fa_i[s] = FA.im[ia];
-        fa_s[s] = fa_r[s] + fa_i[s];
-        const int ib = (4 * lq + s) * FA.ld + l16;
-        fb_r[s] = FA.re[ib] * scale;
-        fb_i[s] = FA.im[ib] * scale;
-        fb_s[s] = fb_r[s] + fb_i[s];
+    for (int ab = 0; ab < NAB; ++ab)
+#pragma unroll
+        for (int s = 0; s < NS1; ++s) {
+            const int ia = (4 * s + lq) * FA.ld + 16 * ab + l16;
+            fa_r[ab][s] = FA.re[ia];
+            fa_i[ab][s] = FA.im[ia];
+            fa_s[ab][s] = fa_r[ab][s] + fa_i[ab][s];
+        }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int ib = (4 * lq + v) * FB.ld + C * l16;
+        fb_r[v] = FB.re[ib] * scale;
+        fb_i[v] = FB.im[ib] * scale;
+        fb_s[v] = fb_r[v] + fb_i[v];
     }
 
     const unsigned ld_off = B * lq + l16;         // + 4*B*s + 16*c
-    const unsigned st_off = l16 + 16 * C * 4 * lq;     // + 16*k_c + 16*C*v
-    f32x2 x[C][4];
+    const unsigned st_off = l16 + A * C * 4 * lq;      // + 16*ab + A*k_c + A*C*v
+    f32x2 x[C][NS1];
     auto load_block = [&](int64_t row, int c) {
         const f32x2* src = reinterpret_cast<const f32x2*>(in) + row * N + 16 * c;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) x[c][s] = __builtin_nontemporal_load(&(src + 4 * B * s)[ld_off]);
+        for (int s = 0; s < NS1; ++s) x[c][s] = __builtin_nontemporal_load(&(src + 4 * B * s)[ld_off]);
     };
 #pragma unroll
     for (int c = 0; c < C; ++c) load_block(wave, c);
@@ -143,28 +151,40 @@ __global__ __launch_bounds__(256, WPC) void k_fft_zn(const float2* __restrict__ 
         // the tables are loop invariant, but keeping them in registers across rows is exactly what does
         // not fit: make the compiler read them again in every row
         asm volatile("" ::: "memory");
-        f32x4 zr[C], zi[C];
+        f32x4 zr[NAB][C], zi[NAB][C];
 #pragma unroll
         for (int c = 0; c < C; ++c) {
-            f32x4 p1 = {0.f, 0.f, 0.f, 0.f}, p2 = p1, p3 = p1;
+            f32x4 p1[NAB], p2[NAB], p3[NAB];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
+            for (int ab = 0; ab < NAB; ++ab) {
+                p1[ab] = f32x4{0.f, 0.f, 0.f, 0.f};
+                p2[ab] = p1[ab];
+                p3[ab] = p1[ab];
+            }
+#pragma unroll
+            for (int s = 0; s < NS1; ++s) {
                 const float xr = SWAP ? x[c][s].y : x[c][s].x, xi = SWAP ? x[c][s].x : x[c][s].y;
-                p1 = mfma(xr, fa_r[s], p1);
-                p2 = mfma(xi, fa_i[s], p2);
-                p3 = mfma(xr + xi, fa_s[s], p3);
+#pragma unroll
+                for (int ab = 0; ab < NAB; ++ab) {
+                    p1[ab] = mfma(xr, fa_r[ab][s], p1[ab]);
+                    p2[ab] = mfma(xi, fa_i[ab][s], p2[ab]);
+                    p3[ab] = mfma(xr + xi, fa_s[ab][s], p3[ab]);
+                }
             }
             load_block(next, c);
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float2 t = tw1s[(c * 4 + v) * 64 + lane];
-                const float a = p1[v] - p2[v], b = p3[v] - p1[v] - p2[v];
-                zr[c][v] = a * t.x - b * t.y;
-                zi[c][v] = a * t.y + b * t.x;
-            }
+            for (int ab = 0; ab < NAB; ++ab)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float2 t = tw1s[((c * NAB + ab) * 4 + v) * 64 + lane];
+                    const float a = p1[ab][v] - p2[ab][v], b = p3[ab][v] - p1[ab][v] - p2[ab][v];
+                    zr[ab][c][v] = a * t.x - b * t.y;
+                    zi[ab][c][v] = a * t.y + b * t.x;
+                }
             __builtin_amdgcn_sched_barrier(0);     // keeps the requests where they are
         }
-        small_dft<C>(zr, zi);
+#pragma unroll
+        for (int ab = 0; ab < NAB; ++ab) small_dft<C>(zr[ab], zi[ab]);
 #pragma unroll
         for (int kc = 1; kc < C; ++kc) {
             const f32x4* t4 = reinterpret_cast<const f32x4*>(&tw2s[kc * 16 + 4 * lq]);   // four twiddles: beta = 4*lq + v
@@ -172,27 +192,33 @@ __global__ __launch_bounds__(256, WPC) void k_fft_zn(const float2* __restrict__ 
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const float tx = (v < 2 ? t01 : t23)[2 * (v & 1)], ty = (v < 2 ? t01 : t23)[2 * (v & 1) + 1];
-                const float a = zr[kc][v], b = zi[kc][v];
-                zr[kc][v] = a * tx - b * ty;
-                zi[kc][v] = a * ty + b * tx;
+#pragma unroll
+                for (int ab = 0; ab < NAB; ++ab) {
+                    const float a = zr[ab][kc][v], b = zi[ab][kc][v];
+                    zr[ab][kc][v] = a * tx - b * ty;
+                    zi[ab][kc][v] = a * ty + b * tx;
+                }
             }
         }
         f32x2* dst = reinterpret_cast<f32x2*>(out) + row * N;
 #pragma unroll
-        for (int kc = 0; kc < C; ++kc) {
-            f32x4 q1 = {0.f, 0.f, 0.f, 0.f}, q2 = q1, q3 = q1;
+        for (int kc = 0; kc < C; ++kc)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                q1 = mfma(fb_r[v], zr[kc][v], q1);
-                q2 = mfma(fb_i[v], zi[kc][v], q2);
-                q3 = mfma(fb_s[v], zr[kc][v] + zi[kc][v], q3);
-            }
+            for (int ab = 0; ab < NAB; ++ab) {
+                f32x4 q1 = {0.f, 0.f, 0.f, 0.f}, q2 = q1, q3 = q1;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float re = q1[v] - q2[v], im = q3[v] - q1[v] - q2[v];
-                __builtin_nontemporal_store(SWAP ? f32x2{im, re} : f32x2{re, im}, &(dst + 16 * kc + 16 * C * v)[st_off]);
+                for (int v = 0; v < 4; ++v) {
+                    q1 = mfma(fb_r[v], zr[ab][kc][v], q1);
+                    q2 = mfma(fb_i[v], zi[ab][kc][v], q2);
+                    q3 = mfma(fb_s[v], zr[ab][kc][v] + zi[ab][kc][v], q3);
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float re = q1[v] - q2[v], im = q3[v] - q1[v] - q2[v];
+                    __builtin_nontemporal_store(SWAP ? f32x2{im, re} : f32x2{re, im},
+                                                &(dst + 16 * ab + A * kc + A * C * v)[st_off]);
+                }
             }
-        }
     };
     // The first row runs outside the loop so that the loop is entered in the state every iteration leaves
     // behind (requests, then stores): with the prologue's requests as a second way in, the waits at the
@@ -204,11 +230,11 @@ __global__ __launch_bounds__(256, WPC) void k_fft_zn(const float2* __restrict__ 
 #pragma unroll
     for (int c = 0; c < C; ++c)
 #pragma unroll
-        for (int s = 0; s < 4; ++s) asm volatile("" : "+v"(x[c][s]));
+        for (int s = 0; s < NS1; ++s) asm volatile("" : "+v"(x[c][s]));
     for (int64_t row = wave + nwaves; row < nrows; row += nwaves) transform_row(row);
 }
 
-template <int C, int WPC>
+template <int NAB, int C, int WPC>
 hipError_t launch_zn_inst(const float2* in, float2* out, int64_t nrows, const DeviceMatrix& FA, const DeviceMatrix& FB,
                           const float2* Tw, float scale, int conj, hipStream_t stream)
 {
@@ -216,10 +242,10 @@ hipError_t launch_zn_inst(const float2* in, float2* out, int64_t nrows, const De
     const int64_t want = (nrows + 3) / 4;
     const int64_t blocks = want < 256 * WPC ? want : 256 * WPC;
     if (conj)
-        hipLaunchKernelGGL((k_fft_zn<C, true, WPC>), dim3((unsigned)blocks), dim3(256), 0, stream, in, out, nrows, FA, FB, Tw,
+        hipLaunchKernelGGL((k_fft_zn<NAB, C, true, WPC>), dim3((unsigned)blocks), dim3(256), 0, stream, in, out, nrows, FA, FB, Tw,
                            scale);
     else
-        hipLaunchKernelGGL((k_fft_zn<C, false, WPC>), dim3((unsigned)blocks), dim3(256), 0, stream, in, out, nrows, FA, FB, Tw,
+        hipLaunchKernelGGL((k_fft_zn<NAB, C, false, WPC>), dim3((unsigned)blocks), dim3(256), 0, stream, in, out, nrows, FA, FB, Tw,
                            scale);
     return hipGetLastError();
 }
@@ -247,25 +273,29 @@ hipError_t launch_zn_inst(const float2* in, float2* out, int64_t nrows, const De
 //   after the fourth slot the accumulators are stored to rows k_a + 16*k_c + 16*C*k_b and cleared.
 // Matrix-core work per point: 6*16 (first stage) + 8*16 (last stage) flop, against 6*32 + 8*64 of the
 // streaming kernel for 32 x 64.  One workgroup of eight waves per CU at C = 8.
-template <int C, int CH>
+// NAB = A / 16: first stage of 16 or 32 points (32 x (C*16): two blocks of k_a, eight k-steps; a wave then
+// keeps the accumulators of four k_a).
+template <int NAB, int C, int CH>
 struct FftSnLayout {
-    static constexpr int B = 16 * C, N = 16 * B, CP = C / 2;
+    static constexpr int A = 16 * NAB, NS1 = A / 4, B = 16 * C, N = A * B, CP = C / 2;
     static constexpr int KP = 64 * CH;                                         // elements per (h, m, k_a): [column group][beta 4][col 16]
-    static constexpr size_t ring_elems = (size_t)2 * CP * 16 * KP;            // one buffer: [h][m][k_a][column group][beta][col]
+    static constexpr size_t ring_elems = (size_t)2 * CP * A * KP;             // one buffer: [h][m][k_a][column group][beta][col]
     static constexpr size_t ring_bytes = 2 * ring_elems * 8;
-    static constexpr size_t fa_bytes = 3 * 64 * 16;                            // [re, im, re+im][lane] x (4 k-steps)
-    static constexpr size_t tw1_bytes = (size_t)B * 16 * 8;                    // T[b][k_a]
+    static constexpr size_t fa_bytes = (size_t)NAB * (NS1 / 4) * 3 * 64 * 16;  // [ab][4 k-steps][re, im, re+im][lane] x (4 k-steps)
+    static constexpr size_t tw1_bytes = (size_t)B * A * 8;                     // T[b][k_a]
     static constexpr size_t tw2_bytes = (size_t)16 * C * 8;                    // w_B^(k_c beta) as [beta][k_c]
-    static constexpr size_t fb_bytes = 4 * 64 * 16;                            // [slot][lane] x (re, im, -im, 0)
+    static constexpr size_t fb_bytes = 4 * 64 * 8;                             // [slot][lane] x (re, im)
     static constexpr size_t lds_bytes = ring_bytes + fa_bytes + tw1_bytes + tw2_bytes + fb_bytes;
+    static_assert(lds_bytes <= 160 * 1024, "LDS of one CU");
 };
 
-template <int C, int CH, bool SWAP, int WPC>
+template <int NAB, int C, int CH, bool SWAP, int WPC>
 __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, DeviceMatrix FA, DeviceMatrix FB,
                                                       const float2* __restrict__ Tw, float scale)
 {
-    typedef FftSnLayout<C, CH> L;
-    constexpr int B = L::B, CP = L::CP, KP = L::KP;
+    typedef FftSnLayout<NAB, C, CH> L;
+    constexpr int A = L::A, NS1 = L::NS1, B = L::B, CP = L::CP, KP = L::KP;
+    constexpr int KW = A / 8;                          // k_a per wave
     static_assert(C == 2 || C == 4 || C == 8, "second factor 32, 64 or 128");
 
     extern __shared__ __align__(16) unsigned char smem_sn[];
@@ -273,7 +303,7 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
     f32x4* faT = reinterpret_cast<f32x4*>(smem_sn + L::ring_bytes);
     float2* tw1 = reinterpret_cast<float2*>(smem_sn + L::ring_bytes + L::fa_bytes);
     float2* tw2 = reinterpret_cast<float2*>(smem_sn + L::ring_bytes + L::fa_bytes + L::tw1_bytes);
-    f32x4* fbT = reinterpret_cast<f32x4*>(smem_sn + L::ring_bytes + L::fa_bytes + L::tw1_bytes + L::tw2_bytes);
+    f32x2* fbT = reinterpret_cast<f32x2*>(smem_sn + L::ring_bytes + L::fa_bytes + L::tw1_bytes + L::tw2_bytes);
 
     const float2* __restrict__ X = a.X;
     float2* __restrict__ Y = a.Y;
@@ -285,24 +315,25 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
     // ---- tables, once per workgroup ------------------------------------------------------------------
     {
         float* faF = reinterpret_cast<float*>(faT);
-        for (int e = tid; e < 4 * 64; e += 512) {
-            const int ln = e & 63, s = e >> 6;
-            const int idx = (4 * s + (ln >> 4)) * FA.ld + (ln & 15);         // F16[k_a = ln%16][l = 4*s + ln/16]
+        for (int e = tid; e < NAB * NS1 * 64; e += 512) {
+            const int ln = e & 63, s = (e >> 6) % NS1, ab = (e >> 6) / NS1;
+            const int idx = (4 * s + (ln >> 4)) * FA.ld + 16 * ab + (ln & 15);   // FA[k_a = 16*ab + ln%16][l = 4*s + ln/16]
             const float r = FA.re[idx], i = FA.im[idx];
-            faF[(0 * 64 + ln) * 4 + s] = r;
-            faF[(1 * 64 + ln) * 4 + s] = i;
-            faF[(2 * 64 + ln) * 4 + s] = r + i;
+            float* t = faF + ((((ab * (NS1 / 4) + s / 4) * 3) * 64 + ln) * 4 + (s & 3));
+            t[0] = r;
+            t[64 * 4] = i;
+            t[128 * 4] = r + i;
         }
-        for (int e = tid; e < B * 16; e += 512) tw1[(e % B) * 16 + e / B] = Tw[e];      // Tw is T[k_a][b]: transposed here
+        for (int e = tid; e < B * A; e += 512) tw1[(e % B) * A + e / B] = Tw[e];        // Tw is T[k_a][b]: transposed here
         for (int e = tid; e < 16 * C; e += 512) {
             const int kc = e % C, beta = e / C;
             tw2[e] = make_float2(FB.re[beta * FB.ld + kc], FB.im[beta * FB.ld + kc]);   // FB[k][n] at plane[n * ld + k]
         }
         for (int e = tid; e < 4 * 64; e += 512) {
             const int ln = e & 63, t = e >> 6;
-            const int idx = (4 * t + (ln >> 4)) * FA.ld + (ln & 15);         // F16[k_b = ln%16][beta = 4*t + ln/16]
-            const float r = FA.re[idx] * scale, i = FA.im[idx] * scale;
-            fbT[e] = f32x4{r, i, -i, 0.f};
+            // F16[k_b = ln%16][beta = 4*t + ln/16] = w_16^(k_b beta) = FB[C*k_b, beta]
+            const int idx = (4 * t + (ln >> 4)) * FB.ld + C * (ln & 15);
+            fbT[e] = f32x2{FB.re[idx] * scale, FB.im[idx] * scale};
         }
     }
 
@@ -342,14 +373,14 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
     // producer unit of this wave
     const int pb = wave >> 1, ph = wave & 1;
     const unsigned ld_lane = (unsigned)(B * lq) * (unsigned)inN + (unsigned)l16;
-    f32x2 xs[CP][4][CH];
+    f32x2 xs[CP][NS1][CH];
     auto request = [&](int slot) {                     // of the tile at rq
         const float2* src = X + ((int64_t)rq.o * a.inO + (int64_t)rq.y * a.inY + (int64_t)rq.zt * (16 * CH)) +
                             (int64_t)(4 * slot + pb + 16 * ph) * inN;
 #pragma unroll
         for (int cp = 0; cp < CP; ++cp)
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+            for (int s = 0; s < NS1; ++s)
 #pragma unroll
                 for (int cg = 0; cg < CH; ++cg)          // neighbouring 128-byte pieces of the same rows
                     xs[cp][s][cg] = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(
@@ -364,11 +395,11 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
         request(slot);
     };
 
-    // accumulators: [k_a = 2*wave + j, column group][k_c], register v = k_b = 4*lq + v
-    f32x4 wr[2 * CH][C], wi[2 * CH][C];
+    // accumulators: [k_a = KW*wave + j % KW, column group j / KW][k_c], register v = k_b = 4*lq + v
+    f32x4 wr[KW * CH][C], wi[KW * CH][C];
     auto clear_acc = [&]() {
 #pragma unroll
-        for (int j = 0; j < 2 * CH; ++j)
+        for (int j = 0; j < KW * CH; ++j)
 #pragma unroll
             for (int kc = 0; kc < C; ++kc) {
                 wr[j][kc] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -379,61 +410,74 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
     // ---- producer: slot `slot` (0..3) of the tile whose data sits in xs -> ring buffer `buf`; then the
     // request for global slot g_next into the same registers
     auto produce = [&](int slot, int buf, int64_t g_next) {
-        const f32x4 fr = faT[lane], fi = faT[64 + lane], fs = faT[128 + lane];
-        f32x4 p1[CH][CP], p2[CH][CP], p3[CH][CP];
+        f32x4 p1[CH][CP][NAB], p2[CH][CP][NAB], p3[CH][CP][NAB];
 #pragma unroll
         for (int cg = 0; cg < CH; ++cg)
 #pragma unroll
-            for (int cp = 0; cp < CP; ++cp) {
-                p1[cg][cp] = f32x4{0.f, 0.f, 0.f, 0.f};
-                p2[cg][cp] = p1[cg][cp];
-                p3[cg][cp] = p1[cg][cp];
-            }
+            for (int cp = 0; cp < CP; ++cp)
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int cg = 0; cg < CH; ++cg)
-#pragma unroll
-                for (int cp = 0; cp < CP; ++cp) {
-                    const f32x2 x = xs[cp][s][cg];
-                    const float xr = SWAP ? x.y : x.x, xi = SWAP ? x.x : x.y;
-                    p1[cg][cp] = mfma(fr[s], xr, p1[cg][cp]);
-                    p2[cg][cp] = mfma(fi[s], xi, p2[cg][cp]);
-                    p3[cg][cp] = mfma(fs[s], xr + xi, p3[cg][cp]);
+                for (int ab = 0; ab < NAB; ++ab) {
+                    p1[cg][cp][ab] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    p2[cg][cp][ab] = p1[cg][cp][ab];
+                    p3[cg][cp][ab] = p1[cg][cp][ab];
                 }
+#pragma unroll
+        for (int ab = 0; ab < NAB; ++ab)
+#pragma unroll
+            for (int sq = 0; sq < NS1 / 4; ++sq) {
+                const f32x4* t = faT + ((ab * (NS1 / 4) + sq) * 3) * 64 + lane;
+                const f32x4 fr = t[0], fi = t[64], fs = t[128];
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+                    for (int cg = 0; cg < CH; ++cg)
+#pragma unroll
+                        for (int cp = 0; cp < CP; ++cp) {
+                            const f32x2 x = xs[cp][4 * sq + s4][cg];
+                            const float xr = SWAP ? x.y : x.x, xi = SWAP ? x.x : x.y;
+                            p1[cg][cp][ab] = mfma(fr[s4], xr, p1[cg][cp][ab]);
+                            p2[cg][cp][ab] = mfma(fi[s4], xi, p2[cg][cp][ab]);
+                            p3[cg][cp][ab] = mfma(fs[s4], xr + xi, p3[cg][cp][ab]);
+                        }
+            }
         __builtin_amdgcn_sched_barrier(0);
         request_slot(g_next);
         __builtin_amdgcn_sched_barrier(0);
         const int beta = 4 * slot + pb;
 #pragma unroll
-        for (int cg = 0; cg < CH; ++cg) {
-            f32x4 zr[CP], zi[CP];
+        for (int cg = 0; cg < CH; ++cg)
 #pragma unroll
-            for (int cp = 0; cp < CP; ++cp) {
-                // twiddles of this lane's four k_a = 4*lq + v: 32 contiguous bytes of T[b = 16*c + beta][k_a]
-                const f32x4* t = reinterpret_cast<const f32x4*>(tw1 + (16 * (ph + 2 * cp) + beta) * 16 + 4 * lq);
-                const f32x4 t01 = t[0], t23 = t[1];
+            for (int ab = 0; ab < NAB; ++ab) {
+                f32x4 zr[CP], zi[CP];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float tx = (v < 2 ? t01 : t23)[2 * (v & 1)], ty = (v < 2 ? t01 : t23)[2 * (v & 1) + 1];
-                    const float re = p1[cg][cp][v] - p2[cg][cp][v], im = p3[cg][cp][v] - p1[cg][cp][v] - p2[cg][cp][v];
-                    zr[cp][v] = re * tx - im * ty;
-                    zi[cp][v] = re * ty + im * tx;
+                for (int cp = 0; cp < CP; ++cp) {
+                    // twiddles of this lane's four k_a = 16*ab + 4*lq + v: 32 contiguous bytes of T[b = 16*c + beta][k_a]
+                    const f32x4* t = reinterpret_cast<const f32x4*>(tw1 + (16 * (ph + 2 * cp) + beta) * A + 16 * ab + 4 * lq);
+                    const f32x4 t01 = t[0], t23 = t[1];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const float tx = (v < 2 ? t01 : t23)[2 * (v & 1)], ty = (v < 2 ? t01 : t23)[2 * (v & 1) + 1];
+                        const float re = p1[cg][cp][ab][v] - p2[cg][cp][ab][v];
+                        const float im = p3[cg][cp][ab][v] - p1[cg][cp][ab][v] - p2[cg][cp][ab][v];
+                        zr[cp][v] = re * tx - im * ty;
+                        zi[cp][v] = re * ty + im * tx;
+                    }
                 }
+                if constexpr (CP > 1) small_dft<CP>(zr, zi);
+                f32x2* zw = ring + (size_t)buf * L::ring_elems + (size_t)(ph * CP) * (A * KP) + (16 * ab) * KP + cg * 64 +
+                            pb * 16 + l16;
+#pragma unroll
+                for (int m = 0; m < CP; ++m)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) zw[m * (A * KP) + (4 * lq + v) * KP] = f32x2{zr[m][v], zi[m][v]};
             }
-            if constexpr (CP > 1) small_dft<CP>(zr, zi);
-            f32x2* zw = ring + (size_t)buf * L::ring_elems + (size_t)(ph * CP) * (16 * KP) + cg * 64 + pb * 16 + l16;
-#pragma unroll
-            for (int m = 0; m < CP; ++m)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) zw[m * (16 * KP) + (4 * lq + v) * KP] = f32x2{zr[m][v], zi[m][v]};
-        }
     };
 
     // ---- consumer: slot `slot` of the tile at st from ring buffer `buf`
     auto consume = [&](int slot, int buf) {
         __builtin_amdgcn_sched_barrier(0);             // the two steps one after the other: their temporaries share registers
-        const f32x4 f = fbT[slot * 64 + lane];          // F16[k_b = l16][beta = 4*slot + lq]: re, im, -im
+        const f32x2 f2 = fbT[slot * 64 + lane];         // F16[k_b = l16][beta = 4*slot + lq]
+        const float f[3] = {f2.x, f2.y, -f2.y};
         // w_B^(k_c beta) for this lane's beta: C contiguous complex numbers
         f32x4 tq[CP];
         {
@@ -443,12 +487,12 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
         }
         const f32x2* zr0 = ring + (size_t)buf * L::ring_elems + lq * 16 + l16;
 #pragma unroll
-        for (int j = 0; j < 2 * CH; ++j) {             // j = 2 * column group + (k_a & 1)
-            const f32x2* zp = zr0 + (2 * wave + (j & 1)) * KP + (j >> 1) * 64;
+        for (int j = 0; j < KW * CH; ++j) {            // j = KW * column group + (k_a % KW)
+            const f32x2* zp = zr0 + (KW * wave + j % KW) * KP + (j / KW) * 64;
             float ur[C], ui[C];
 #pragma unroll
             for (int m = 0; m < CP; ++m) {
-                const f32x2 e0 = zp[m * (16 * KP)], e1 = zp[(CP + m) * (16 * KP)];
+                const f32x2 e0 = zp[m * (A * KP)], e1 = zp[(CP + m) * (A * KP)];
                 // w_C^m e1 (forward): C = 2: 1;  C = 4: 1, -i;  C = 8: 1, (1 - i) h, -i, (-1 - i) h
                 float qr, qi;
                 constexpr float h = 0.70710678118654752440f;
@@ -479,21 +523,21 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
     };
 
     auto store_tile = [&]() {                          // the tile at st
-        // rows k_a + 16*k_c + 16*C*k_b with k_b = 4*lq + v; the lane part needs 64 bits at N = 2048
+        // rows k_a + A*k_c + A*C*k_b with k_b = 4*lq + v; the lane part needs 64 bits at N = 2048
         float2* dst = Y + ((int64_t)st.o * a.outO + (int64_t)st.y * a.outY + (int64_t)st.zt * (16 * CH)) +
-                      ((int64_t)(16 * C * 4 * lq) * outN + l16);
+                      ((int64_t)(A * C * 4 * lq) * outN + l16);
 #pragma unroll
-        for (int ja = 0; ja < 2; ++ja)
+        for (int ja = 0; ja < KW; ++ja)
 #pragma unroll
             for (int kc = 0; kc < C; ++kc)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
 #pragma unroll
                     for (int cg = 0; cg < CH; ++cg) {     // neighbouring 128-byte pieces of one row
-                        const float re = wr[2 * cg + ja][kc][v], im = wi[2 * cg + ja][kc][v];
+                        const float re = wr[KW * cg + ja][kc][v], im = wi[KW * cg + ja][kc][v];
                         __builtin_nontemporal_store(
                             SWAP ? f32x2{im, re} : f32x2{re, im},
-                            reinterpret_cast<f32x2*>(dst + (int64_t)(2 * wave + ja + 16 * kc + 16 * C * v) * outN + 16 * cg));
+                            reinterpret_cast<f32x2*>(dst + (int64_t)(KW * wave + ja + A * kc + A * C * v) * outN + 16 * cg));
                     }
     };
 
@@ -517,18 +561,18 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
     }
 }
 
-template <int C, int CH, int WPC>
+template <int NAB, int C, int CH, int WPC>
 hipError_t launch_sn_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw,
                           float scale, int conj, hipStream_t stream)
 {
     const int64_t ntiles = a.O * a.Yn * (a.Zt / CH);
     const int64_t blocks = ntiles < 256 * WPC ? ntiles : 256 * WPC;      // persistent workgroups
-    constexpr size_t lds = FftSnLayout<C, CH>::lds_bytes;
+    constexpr size_t lds = FftSnLayout<NAB, C, CH>::lds_bytes;
     if (conj)
-        hipLaunchKernelGGL((k_fft_sn<C, CH, true, WPC>), dim3((unsigned)blocks), dim3(512), lds, stream, a, FA, FB, Tw,
+        hipLaunchKernelGGL((k_fft_sn<NAB, C, CH, true, WPC>), dim3((unsigned)blocks), dim3(512), lds, stream, a, FA, FB, Tw,
                            scale);
     else
-        hipLaunchKernelGGL((k_fft_sn<C, CH, false, WPC>), dim3((unsigned)blocks), dim3(512), lds, stream, a, FA, FB, Tw,
+        hipLaunchKernelGGL((k_fft_sn<NAB, C, CH, false, WPC>), dim3((unsigned)blocks), dim3(512), lds, stream, a, FA, FB, Tw,
                            scale);
     return hipGetLastError();
 }
@@ -537,7 +581,7 @@ hipError_t launch_sn_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const
 
 bool fft_zn_supported(int A, int B)
 {
-    return A == 16 && (B == 32 || B == 64 || B == 128);
+    return (A == 16 && (B == 32 || B == 64 || B == 128)) || (A == 32 && B == 64);
 }
 
 hipError_t launch_fft_zn(const float2* in, float2* out, int64_t nrows, int A, int B, const DeviceMatrix& FA,
@@ -545,39 +589,42 @@ hipError_t launch_fft_zn(const float2* in, float2* out, int64_t nrows, int A, in
 {
     if (nrows <= 0) return hipSuccess;
     // the kernel indexes the stage matrices and the twiddle table without bounds checks
-    if (A != 16 || FA.K != 16 || FA.N != 16 || FB.K != B || FB.N != B || !Tw) return hipErrorInvalidValue;
+    if (!fft_zn_supported(A, B) || FA.K != A || FA.N != A || FB.K != B || FB.N != B || !Tw) return hipErrorInvalidValue;
+    if (A == 32) return launch_zn_inst<2, 4, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     // three workgroups per CU where the registers allow (512^3: 0.383 -> 0.375 ms)
-    if (B == 32) return launch_zn_inst<2, 3>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
-    if (B == 64) return launch_zn_inst<4, 3>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
-    if (B == 128) return launch_zn_inst<8, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (B == 32) return launch_zn_inst<1, 2, 3>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (B == 64) return launch_zn_inst<1, 4, 3>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (B == 128) return launch_zn_inst<1, 8, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     return hipErrorInvalidValue;
 }
 
 bool fft_sn_supported(int A, int B, int64_t I)
 {
     // 32-bit lane offsets of the loads: up to 3*B rows of I elements
-    return A == 16 && (B == 32 || B == 64 || B == 128) && I % 16 == 0 && I <= (int64_t(1) << 23);
+    return ((A == 16 && (B == 32 || B == 64 || B == 128)) || (A == 32 && B == 64)) && I % 16 == 0 &&
+           I <= (int64_t(1) << 23);
 }
 
 namespace {
-template <int C, int CH, int WPC>
+template <int NAB, int C, int CH, int WPC>
 hipError_t configure_sn()
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<C, CH, false, WPC>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<C, CH>::lds_bytes);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<NAB, C, CH, false, WPC>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<NAB, C, CH>::lds_bytes);
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<C, CH, true, WPC>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<C, CH>::lds_bytes);
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fft_sn<NAB, C, CH, true, WPC>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)FftSnLayout<NAB, C, CH>::lds_bytes);
 }
 }  // namespace
 
 hipError_t configure_fft_nested_kernels()
 {
-    hipError_t e = configure_sn<8, 1, 1>();
-    if (e == hipSuccess) e = configure_sn<4, 1, 2>();
-    if (e == hipSuccess) e = configure_sn<4, 2, 1>();
-    if (e == hipSuccess) e = configure_sn<2, 1, 2>();
-    if (e == hipSuccess) e = configure_sn<2, 4, 1>();
+    hipError_t e = configure_sn<1, 8, 1, 1>();
+    if (e == hipSuccess) e = configure_sn<1, 4, 1, 2>();
+    if (e == hipSuccess) e = configure_sn<1, 4, 2, 1>();
+    if (e == hipSuccess) e = configure_sn<1, 2, 1, 2>();
+    if (e == hipSuccess) e = configure_sn<1, 2, 4, 1>();
+    if (e == hipSuccess) e = configure_sn<2, 4, 1, 1>();
     return e;
 }
 
@@ -586,22 +633,23 @@ hipError_t launch_fft_sn(const FftStridedArgs& a, int A, int B, const DeviceMatr
 {
     if (a.O <= 0 || a.Yn <= 0 || a.Zt <= 0) return hipSuccess;
     const int64_t lim = int64_t(1) << 23;
-    if (A != 16 || a.inN < 16 || a.outN < 16 || a.inN > lim || a.outN > lim || FA.K != 16 || FA.N != 16 ||
-        FB.K != B || FB.N != B || !Tw)
+    if (!fft_sn_supported(A, B, 16) || a.inN < 16 || a.outN < 16 || a.inN > lim || a.outN > lim || FA.K != A ||
+        FA.N != A || FB.K != B || FB.N != B || !Tw)
         return hipErrorInvalidValue;
+    if (A == 32) return launch_sn_inst<2, 4, 1, 1>(a, FA, FB, Tw, scale, conj, stream);
     // Wider tiles mean longer contiguous pieces per row (128 bytes per 16 columns) but one workgroup per CU
     // instead of two once the accumulators of N * columns outputs fill its registers.  Measured: 1024 points,
     // 32 columns: 3.74 -> 3.48 ms (y) and 4.55 -> 3.91 ms (x) at 1024^3; 512 points, 64 columns: 0.474 ->
     // 0.448 ms for the x pass of 512^3 (rows 2 MiB apart) but 0.426 -> 0.442 ms for its y pass (rows 4 KiB
     // apart), so the wide tile is taken for rows at least 32 KiB apart.
-    if (B == 128) return launch_sn_inst<8, 1, 1>(a, FA, FB, Tw, scale, conj, stream);
+    if (B == 128) return launch_sn_inst<1, 8, 1, 1>(a, FA, FB, Tw, scale, conj, stream);
     if (B == 64) {
-        if (a.Zt % 2 == 0) return launch_sn_inst<4, 2, 1>(a, FA, FB, Tw, scale, conj, stream);
-        return launch_sn_inst<4, 1, 2>(a, FA, FB, Tw, scale, conj, stream);
+        if (a.Zt % 2 == 0) return launch_sn_inst<1, 4, 2, 1>(a, FA, FB, Tw, scale, conj, stream);
+        return launch_sn_inst<1, 4, 1, 2>(a, FA, FB, Tw, scale, conj, stream);
     }
     if (B == 32) {
-        if (a.Zt % 4 == 0 && a.inN >= 4096) return launch_sn_inst<2, 4, 1>(a, FA, FB, Tw, scale, conj, stream);
-        return launch_sn_inst<2, 1, 2>(a, FA, FB, Tw, scale, conj, stream);
+        if (a.Zt % 4 == 0 && a.inN >= 4096) return launch_sn_inst<1, 2, 4, 1>(a, FA, FB, Tw, scale, conj, stream);
+        return launch_sn_inst<1, 2, 1, 2>(a, FA, FB, Tw, scale, conj, stream);
     }
     return hipErrorInvalidValue;
 }

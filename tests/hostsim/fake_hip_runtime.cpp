@@ -311,18 +311,18 @@ hipError_t hipLaunchKernel(const void* func, dim3 grid, dim3 block, void** args,
         L.dst_bytes = ((a.O - 1) * a.outO + (N - 1) * a.outN + (a.Yn - 1) * a.outY + 16 * a.Zt) * 8;
         if (N <= 0) fail(name + ": cannot read the split from the kernel name");
     } else if (starts("k_fft_sn<")) {
-        // 16 x (C*16) on a strided axis
+        // (16*NAB) x (C*16) on a strided axis
         const FftStridedArgs& a = *(const FftStridedArgs*)args[0];
         const std::vector<long> t = template_ints(name);
-        const int64_t N = t.size() >= 1 ? 256 * t[0] : 0;
+        const int64_t N = t.size() >= 2 ? 256 * t[0] * t[1] : 0;
         L.src = a.X, L.dst = a.Y;
         L.src_bytes = ((a.O - 1) * a.inO + (N - 1) * a.inN + (a.Yn - 1) * a.inY + 16 * a.Zt) * 8;
         L.dst_bytes = ((a.O - 1) * a.outO + (N - 1) * a.outN + (a.Yn - 1) * a.outY + 16 * a.Zt) * 8;
         if (N <= 0) fail(name + ": cannot read the split from the kernel name");
-        if (3 * (N / 16) * a.inN + 16 > 0xffffffffll) fail(name + ": 32-bit lane offsets of the loads overflow");
+        if (t.size() >= 2 && 3 * 16 * t[1] * a.inN + 16 > 0xffffffffll) fail(name + ": 32-bit lane offsets of the loads overflow");
     } else if (starts("k_fft_zn<")) {
         const std::vector<long> t = template_ints(name);
-        const int64_t N = t.size() >= 1 ? 256 * t[0] : 0;
+        const int64_t N = t.size() >= 2 ? 256 * t[0] * t[1] : 0;
         const int64_t nrows = *(const int64_t*)args[2];
         L.src = *(const void* const*)args[0], L.dst = *(void* const*)args[1];
         L.src_bytes = L.dst_bytes = nrows * N * 8;

@@ -462,8 +462,9 @@ def test_fft_fused_axis_kernel(dft, shape, split):
                                          # multiples of 64 with rows at least 32 KiB apart: 64-column tiles
                                          ((512, 1, 64), None), ((2, 512, 192), None), ((512, 3, 64), None),
                                          ((512, 64, 64), None), ((512, 3, 2112), None),
-                                         # 2048 = 32 x 64 on a strided axis (streaming kernel, 16-column tiles)
-                                         ((2048, 1, 16), None), ((2, 2048, 48), None), ((2048, 3, 16), None),
+                                         # 2048 = 32 x (4*16) on a strided axis: first stage of 32 points
+                                         ((2048, 1, 16), (32, 1, 1)), ((2, 2048, 48), (1, 32, 1)), ((2048, 3, 16), (32, 1, 1)),
+                                         ((2048, 2, 4112), (32, 1, 1)),
                                          # 2048 = 16 x (8*16): second factor split once more inside the kernel
                                          ((2048, 1, 16), (16, 1, 1)), ((2, 2048, 48), (1, 16, 1)),
                                          ((2048, 3, 32), (16, 1, 1)), ((2048, 2, 4112), (16, 1, 1)),
