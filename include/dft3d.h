@@ -239,9 +239,9 @@ dft3d_status dft3d_fft_second_stage(dft3d_plan plan, int axis, const void* in, v
  * order (Eq. 13 - Eq. 16 for that axis), one read and one write of the tensor.  Offered for
  * axis 2 (z) with splits 16x16, 16x32, 16x64, 16x128, 32x32, 32x64, 64x64 and for axes 0, 1 (x, y)
  * with splits 16x16, 16x32, 16x64, 16x128, 32x32, 32x64 when the extent inside the axis is a multiple
- * of 16; UNSUPPORTED otherwise.  For 16 x (C*16) the kernels evaluate the second stage of Eq. 16 with its
- * own factor split once more (C-point butterflies and a 16-point matrix stage): the same sums in another
- * order of evaluation.  dft3d_exec uses the fused kernel whenever it applies (unless the plan has
+ * of 16; UNSUPPORTED otherwise.  For A x (C*16) with A = 16 or 32 the kernels evaluate the second stage of
+ * Eq. 16 with its own factor split once more (C-point butterflies and a 16-point matrix stage): the same
+ * sums in another order of evaluation.  dft3d_exec uses the fused kernel whenever it applies (unless the plan has
  * DFT3D_FLAG_UNFUSED).  The default split of 1024 and 2048 points is 16 x 64 and 16 x 128. */
 dft3d_status dft3d_fft_axis(dft3d_plan plan, int axis, const void* in, void* out, int direction,
                             void* stream);

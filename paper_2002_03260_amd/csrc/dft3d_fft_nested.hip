@@ -581,7 +581,7 @@ hipError_t launch_sn_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const
 
 bool fft_zn_supported(int A, int B)
 {
-    return (A == 16 && (B == 32 || B == 64 || B == 128)) || (A == 32 && B == 64);
+    return (A == 16 && (B == 32 || B == 64 || B == 128)) || (A == 32 && (B == 32 || B == 64));
 }
 
 hipError_t launch_fft_zn(const float2* in, float2* out, int64_t nrows, int A, int B, const DeviceMatrix& FA,
@@ -590,7 +590,8 @@ hipError_t launch_fft_zn(const float2* in, float2* out, int64_t nrows, int A, in
     if (nrows <= 0) return hipSuccess;
     // the kernel indexes the stage matrices and the twiddle table without bounds checks
     if (!fft_zn_supported(A, B) || FA.K != A || FA.N != A || FB.K != B || FB.N != B || !Tw) return hipErrorInvalidValue;
-    if (A == 32) return launch_zn_inst<2, 4, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (A == 32 && B == 64) return launch_zn_inst<2, 4, 2>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (A == 32 && B == 32) return launch_zn_inst<2, 2, 3>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     // three workgroups per CU where the registers allow (512^3: 0.383 -> 0.375 ms)
     if (B == 32) return launch_zn_inst<1, 2, 3>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     if (B == 64) return launch_zn_inst<1, 4, 3>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
@@ -601,7 +602,7 @@ hipError_t launch_fft_zn(const float2* in, float2* out, int64_t nrows, int A, in
 bool fft_sn_supported(int A, int B, int64_t I)
 {
     // 32-bit lane offsets of the loads: up to 3*B rows of I elements
-    return ((A == 16 && (B == 32 || B == 64 || B == 128)) || (A == 32 && B == 64)) && I % 16 == 0 &&
+    return ((A == 16 && (B == 32 || B == 64 || B == 128)) || (A == 32 && (B == 32 || B == 64))) && I % 16 == 0 &&
            I <= (int64_t(1) << 23);
 }
 
@@ -625,6 +626,8 @@ hipError_t configure_fft_nested_kernels()
     if (e == hipSuccess) e = configure_sn<1, 2, 1, 2>();
     if (e == hipSuccess) e = configure_sn<1, 2, 4, 1>();
     if (e == hipSuccess) e = configure_sn<2, 4, 1, 1>();
+    if (e == hipSuccess) e = configure_sn<2, 2, 2, 1>();
+    if (e == hipSuccess) e = configure_sn<2, 2, 1, 2>();
     return e;
 }
 
@@ -636,7 +639,11 @@ hipError_t launch_fft_sn(const FftStridedArgs& a, int A, int B, const DeviceMatr
     if (!fft_sn_supported(A, B, 16) || a.inN < 16 || a.outN < 16 || a.inN > lim || a.outN > lim || FA.K != A ||
         FA.N != A || FB.K != B || FB.N != B || !Tw)
         return hipErrorInvalidValue;
-    if (A == 32) return launch_sn_inst<2, 4, 1, 1>(a, FA, FB, Tw, scale, conj, stream);
+    if (A == 32 && B == 64) return launch_sn_inst<2, 4, 1, 1>(a, FA, FB, Tw, scale, conj, stream);
+    if (A == 32 && B == 32) {
+        if (a.Zt % 2 == 0) return launch_sn_inst<2, 2, 2, 1>(a, FA, FB, Tw, scale, conj, stream);
+        return launch_sn_inst<2, 2, 1, 2>(a, FA, FB, Tw, scale, conj, stream);
+    }
     // Wider tiles mean longer contiguous pieces per row (128 bytes per 16 columns) but one workgroup per CU
     // instead of two once the accumulators of N * columns outputs fill its registers.  Measured: 1024 points,
     // 32 columns: 3.74 -> 3.48 ms (y) and 4.55 -> 3.91 ms (x) at 1024^3; 512 points, 64 columns: 0.474 ->

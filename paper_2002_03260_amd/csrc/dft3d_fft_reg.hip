@@ -18,10 +18,10 @@
 //   D of stage 2 has rows k_b = 16*kbb + 4*(lane/16) + v and columns k_a: the output index
 //     k = k_a + A*k_b runs along the lanes, so the stores are 128-byte segments as well.
 //
-// Every row costs (A + B) * (A*B / 256) MFMAs with four real products per complex product (96 for
-// 16 x 32), three quarters of that with three (the M3 variant), and nothing else but a few VALU
-// operations per point for the twiddle and the sums.  With no LDS and no barriers, three to eight
-// waves per SIMD overlap each other's loads, stores and MFMAs.
+// Every row costs three quarters of (A + B) * (A*B / 256) MFMAs (three real products per complex
+// product) and nothing else but a few VALU operations per point for the twiddle and the sums.  With
+// no LDS and no barriers, six waves per SIMD overlap each other's loads, stores and MFMAs.  In the
+// library this kernel serves 16 x 16; the larger splits run the kernels of dft3d_fft_nested.hip.
 #include <hip/hip_runtime.h>
 
 #include "dft3d_internal.h"
@@ -42,7 +42,7 @@ __device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-template <int A, int B, int MINW, bool M3>
+template <int A, int B, int MINW>
 __global__ __launch_bounds__(256, MINW) void k_fft_zr(const float2* __restrict__ in, float2* __restrict__ out,
                                                        int64_t nrows, DeviceMatrix FA, DeviceMatrix FB,
                                                        const float2* __restrict__ Tw, float scale, int conj)
@@ -181,85 +181,6 @@ __global__ __launch_bounds__(256, MINW) void k_fft_zr(const float2* __restrict__
                                  f32x2{q1[kbb][ab][v] - q2[kbb][ab][v],
                                        q3[kbb][ab][v] - q1[kbb][ab][v] - q2[kbb][ab][v]});
     };
-    auto transform_row_4m = [&](const f32x2 (&x)[NBB][NS1], int64_t row) {
-        // stage 1
-        f32x4 zr[NBB][NAB], zi[NBB][NAB];
-#pragma unroll
-        for (int bb = 0; bb < NBB; ++bb)
-#pragma unroll
-            for (int ab = 0; ab < NAB; ++ab) {
-                zr[bb][ab] = f32x4{0.f, 0.f, 0.f, 0.f};
-                zi[bb][ab] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-#pragma unroll
-        for (int s = 0; s < NS1; ++s) {
-#pragma unroll
-            for (int bb = 0; bb < NBB; ++bb)
-#pragma unroll
-                for (int ab = 0; ab < NAB; ++ab) {
-                    zr[bb][ab] = mfma(x[bb][s].x, fa_r[ab][s], zr[bb][ab]);
-                    zi[bb][ab] = mfma(x[bb][s].x, fa_i[ab][s], zi[bb][ab]);
-                }
-#pragma unroll
-            for (int bb = 0; bb < NBB; ++bb)
-#pragma unroll
-                for (int ab = 0; ab < NAB; ++ab) {
-                    zr[bb][ab] = mfma(-x[bb][s].y, fa_i[ab][s], zr[bb][ab]);
-                    zi[bb][ab] = mfma(x[bb][s].y, fa_r[ab][s], zi[bb][ab]);
-                }
-        }
-        // twiddle; zn = -Im is what the real part of stage 2 multiplies
-        f32x4 zn[NBB][NAB];
-#pragma unroll
-        for (int bb = 0; bb < NBB; ++bb)
-#pragma unroll
-            for (int ab = 0; ab < NAB; ++ab)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const float a = zr[bb][ab][v], b = zi[bb][ab][v];
-                    zr[bb][ab][v] = a * tw_r[bb][ab][v] - b * tw_i[bb][ab][v];
-                    zi[bb][ab][v] = a * tw_i[bb][ab][v] + b * tw_r[bb][ab][v];
-                    zn[bb][ab][v] = -zi[bb][ab][v];
-                }
-        // stage 2
-        f32x4 wr[NBB][NAB], wi[NBB][NAB];
-#pragma unroll
-        for (int kbb = 0; kbb < NBB; ++kbb)
-#pragma unroll
-            for (int ab = 0; ab < NAB; ++ab) {
-                wr[kbb][ab] = f32x4{0.f, 0.f, 0.f, 0.f};
-                wi[kbb][ab] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-#pragma unroll
-        for (int bb = 0; bb < NBB; ++bb)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-#pragma unroll
-                for (int kbb = 0; kbb < NBB; ++kbb)
-#pragma unroll
-                    for (int ab = 0; ab < NAB; ++ab) {
-                        wr[kbb][ab] = mfma(fb_r[kbb][bb][v], zr[bb][ab][v], wr[kbb][ab]);
-                        wi[kbb][ab] = mfma(fb_r[kbb][bb][v], zi[bb][ab][v], wi[kbb][ab]);
-                    }
-#pragma unroll
-                for (int kbb = 0; kbb < NBB; ++kbb)
-#pragma unroll
-                    for (int ab = 0; ab < NAB; ++ab) {
-                        wr[kbb][ab] = mfma(fb_i[kbb][bb][v], zn[bb][ab][v], wr[kbb][ab]);
-                        wi[kbb][ab] = mfma(fb_i[kbb][bb][v], zr[bb][ab][v], wi[kbb][ab]);
-                    }
-            }
-        // natural order: k = k_a + A * k_b
-        f32x2* dst = reinterpret_cast<f32x2*>(out) + row * N + l16 + A * 4 * lq;
-#pragma unroll
-        for (int kbb = 0; kbb < NBB; ++kbb)
-#pragma unroll
-            for (int ab = 0; ab < NAB; ++ab)
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    stream_store(&dst[16 * ab + A * (16 * kbb + v)], f32x2{wr[kbb][ab][v], wi[kbb][ab][v]});
-    };
-
     f32x2 xa[NBB][NS1], xb[NBB][NS1];
     load_row(xa, wave);
     for (int64_t row = wave; row < nrows; row += 2 * nwaves) {
@@ -267,14 +188,12 @@ __global__ __launch_bounds__(256, MINW) void k_fft_zr(const float2* __restrict__
         const int64_t row1 = row + nwaves, row2 = row + 2 * nwaves;
         load_row(xb, row1 < nrows ? row1 : row);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (M3) transform_row_3m(xa, row);
-        else transform_row_4m(xa, row);
+        transform_row_3m(xa, row);
         __builtin_amdgcn_sched_barrier(0);
         if (row1 >= nrows) break;
         load_row(xa, row2 < nrows ? row2 : row);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (M3) transform_row_3m(xb, row1);
-        else transform_row_4m(xb, row1);
+        transform_row_3m(xb, row1);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -589,7 +508,7 @@ hipError_t launch_csr_inst(const ContractArgs& a, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <int A, int B, int MINW, bool M3>
+template <int A, int B, int MINW>
 hipError_t launch_inst(const float2* in, float2* out, int64_t nrows, const DeviceMatrix& FA,
                        const DeviceMatrix& FB, const float2* Tw, float scale, int conj, hipStream_t stream)
 {
@@ -597,7 +516,7 @@ hipError_t launch_inst(const float2* in, float2* out, int64_t nrows, const Devic
     const int64_t resident = 256 * MINW;                 // workgroups of 4 waves
     const int64_t want = (nrows + 3) / 4;
     const int64_t blocks = want < resident ? want : resident;
-    hipLaunchKernelGGL((k_fft_zr<A, B, MINW, M3>), dim3((unsigned)blocks), dim3(256), 0, stream, in, out, nrows, FA, FB,
+    hipLaunchKernelGGL((k_fft_zr<A, B, MINW>), dim3((unsigned)blocks), dim3(256), 0, stream, in, out, nrows, FA, FB,
                        Tw, scale, conj);
     return hipGetLastError();
 }
@@ -693,7 +612,7 @@ hipError_t launch_fft_sr(const float2* in, float2* out, int64_t O, int64_t I, in
 
 bool fft_zr_supported(int A, int B)
 {
-    return (A == 16 && B == 16) || (A == 32 && B == 32);
+    return A == 16 && B == 16;
 }
 
 hipError_t launch_fft_zr(const float2* in, float2* out, int64_t nrows, int A, int B, const DeviceMatrix& FA,
@@ -702,10 +621,7 @@ hipError_t launch_fft_zr(const float2* in, float2* out, int64_t nrows, int A, in
     if (nrows <= 0) return hipSuccess;
     // the kernel indexes the stage matrices and the twiddle table without bounds checks
     if (FA.K != A || FA.N != A || FB.K != B || FB.N != B || !Tw) return hipErrorInvalidValue;
-    // three-product scheme where its registers allow; 32 x 32 would spill with it and runs the
-    // four-product scheme
-    if (A == 16 && B == 16) return launch_inst<16, 16, 6, true>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
-    if (A == 32 && B == 32) return launch_inst<32, 32, 2, false>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
+    if (A == 16 && B == 16) return launch_inst<16, 16, 6>(in, out, nrows, FA, FB, Tw, scale, conj, stream);
     return hipErrorInvalidValue;
 }
 

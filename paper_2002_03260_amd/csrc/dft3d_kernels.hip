@@ -925,249 +925,6 @@ __global__ __launch_bounds__(NW * 64, MINW) void k_fft_z(const float2* __restric
 }
 
 // ------------------------------------------------------------------------------------------
-// Fused FFT-formulation pass for a strided axis (x or y): the tensor is viewed as
-// [o][pos = 0..A*B-1][c = 0..I-1] with c contiguous; a workgroup tile is ALL positions of the axis
-// for 16 neighbouring columns (A*B rows of 128 bytes), kept in LDS as xs[pos][16].
-//   stage 1 (in place): for every beta,  Z[k_a][beta][c] = T[k_a][beta] sum_l FA[k_a][l] xs[l][beta][c]
-//   stage 2: for every k_a,  W[k_b][c] = sum_beta FB[k_b][beta] Z[k_a][beta][c], stored straight from
-//            the accumulators to row k_a + A*k_b of the output (natural order).
-// Both stages use the data as the MFMA B operand (lanes walk the 16 columns), so no transposition
-// is needed.  A wave owns whole beta (stage 1) or whole k_a (stage 2) groups, which makes the
-// in-place stage 1 free of cross-wave hazards.  Rows are XOR-swizzled (the lowest bit of beta is
-// flipped when l is odd) so the two rows a half-wave reads lie in different bank halves.
-// The next tile's global loads are issued before the MFMA work of the current one.
-// ------------------------------------------------------------------------------------------
-template <int A, int B, int NW, int MINW>
-__global__ __launch_bounds__(NW * 64, MINW) void k_fft_s(const float2* __restrict__ X, float2* __restrict__ Y,
-                                                   int64_t O, int64_t I, DeviceMatrix FA, DeviceMatrix FB,
-                                                   const float2* __restrict__ Tw, float scale, int conj)
-{
-    constexpr int NT = NW * 64;
-    constexpr int N = A * B;
-    constexpr int TC = 16;
-    // Stage-matrix planes are stored unpadded, [n][k] with pitch = dimension, and the column is
-    // XOR-swizzled by plane_swz so that the four rows a wave reads together (n = 4s + lq) fall on
-    // four distinct 16-bank groups.  The swizzle of row 4s + lq depends on lq only.
-    static_assert(A <= 64 && B <= 64, "plane swizzle is defined for dimensions 16, 32, 64");
-    constexpr int FAP = A, FBP = B;
-    constexpr int RPP = NT / 8;                    // tile rows fetched per pass (8 threads x 16 B per row)
-    static_assert(N % RPP == 0, "axis length must be a multiple of the rows per pass");
-    constexpr int XL = N / RPP;                    // 16-byte loads per thread per tile
-    static_assert(A % 16 == 0 && B % 16 == 0 && B % NW == 0 && A % NW == 0, "unsupported split");
-
-    __shared__ __align__(16) float2 xs[N * TC];
-    __shared__ __align__(16) float far[A * FAP], fai[A * FAP];
-    __shared__ __align__(16) float fbr[B * FBP], fbi[B * FBP];
-    __shared__ __align__(16) float2 tws[A * B];     // twiddles T[k_a][beta]
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int l16 = lane & 15;
-    const int lq = lane >> 4;
-    const float isign = conj ? -1.0f : 1.0f;
-
-    for (int e = tid; e < A * A; e += NT) {
-        const int n = e / A, k = e % A;
-        far[n * FAP + (k ^ plane_swz<A>(n))] = FA.re[(int64_t)n * FA.ld + k];
-        fai[n * FAP + (k ^ plane_swz<A>(n))] = FA.im[(int64_t)n * FA.ld + k] * isign;
-    }
-    for (int e = tid; e < B * B; e += NT) {
-        const int n = e / B, k = e % B;
-        fbr[n * FBP + (k ^ plane_swz<B>(n))] = FB.re[(int64_t)n * FB.ld + k];
-        fbi[n * FBP + (k ^ plane_swz<B>(n))] = FB.im[(int64_t)n * FB.ld + k] * isign;
-    }
-    for (int e = tid; e < A * B; e += NT) {
-        float2 w = Tw[e];
-        w.y *= isign;
-        tws[e] = w;
-    }
-    // per-lane operand columns of the planes (block bm, lane column l16, row swizzle of lq)
-    int fa_col[A / 16], fb_col[B / 16];
-#pragma unroll
-    for (int bm = 0; bm < A / 16; ++bm) fa_col[bm] = lq * FAP + ((bm * 16 + l16) ^ plane_swz<A>(lq));
-#pragma unroll
-    for (int bm = 0; bm < B / 16; ++bm) fb_col[bm] = lq * FBP + ((bm * 16 + l16) ^ plane_swz<B>(lq));
-    const int tw_rd = 4 * lq * B + wave;            // + ((16bm + v)*B + g*NW)
-
-    // Swizzled LDS row of position pos = hi*B + beta is hi*B + (beta ^ (hi & 1)).  Every access
-    // below is written as a per-lane base plus a compile-time offset so the addresses need no
-    // registers of their own:
-    //   stage-1 reads : hi = l = 4s + lq        -> bit = lq & 1, beta = wave + g*NW (parity = wave & 1)
-    //   stage-1 writes: hi = k_a = 16bm + 4lq+v -> bit = v & 1
-    //   stage-2 reads : hi = k_a = wave + g*NW  -> bit = wave & 1, beta = 4s + lq
-    static_assert(NW % 2 == 0, "an even number of waves keeps the parity of beta fixed per wave");
-    const int flip = (wave & 1) ? -1 : 1;                                   // beta ^ 1 == beta + flip
-    const int s1_rd = (lq * B + wave + ((lq & 1) ? flip : 0)) * TC + l16;   // + (g*NW + 4s*B)*TC
-    const int s1_wr_even = (4 * lq * B + wave) * TC + l16;                  // + ((16bm + v)*B + g*NW)*TC
-    const int s1_wr_odd = s1_wr_even + flip * TC;
-    const int s2_rd = (wave * B + (lq ^ (wave & 1))) * TC + l16;            // + (g*NW*B + 4s)*TC
-
-    const int64_t ctiles = I / TC;                 // column tiles per o (I is a multiple of 16)
-    const int64_t ntiles = O * ctiles;
-    const int64_t nwg = (int64_t)gridDim.x * gridDim.y;
-    const int lrow = tid / 8, lcol = (tid % 8) * 2;
-
-    f32x4 xreg[XL];
-    auto tile_base = [&](int64_t tile) { return (tile / ctiles) * (int64_t)N * I + (tile % ctiles) * TC; };
-    // The prefetch of the next tile is issued in NSLOT slices spread over the MFMA work of the
-    // current tile: a burst of all XL loads fills the memory pipeline and blocks the wave at issue.
-    constexpr int U1 = ((B / NW) % 4 == 0) ? 4 : (((B / NW) % 2 == 0) ? 2 : 1);
-    constexpr int U2 = ((A / NW) % 2 == 0 && B / 16 <= 2) ? 2 : 1;
-    constexpr int NSLOT = (B / NW) / U1 + (A / NW) / U2;
-    auto gload_slice = [&](int64_t tile, int slot) {
-        const float2* src = X + tile_base(tile) + (int64_t)lrow * I + lcol;
-#pragma unroll
-        for (int j = 0; j < XL; ++j)
-            if (j * NSLOT / XL == slot)
-                xreg[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + (int64_t)(j * RPP) * I));
-    };
-    auto gload = [&](int64_t tile) {
-#pragma unroll
-        for (int sl = 0; sl < NSLOT; ++sl) gload_slice(tile, sl);
-    };
-
-    int64_t tile = linear_block_id();
-    if (tile < ntiles) gload(tile);
-    for (; tile < ntiles; tile += nwg) {
-        {
-            // rows lrow + j*RPP: the swizzle bit ((row / B) & 1) is a per-thread constant when RPP
-            // is a multiple of 2B, and known at compile time per j when RPP divides B
-            static_assert(RPP % B == 0 || B % RPP == 0, "rows per pass and B must nest");
-            const int base0 = lrow * TC + lcol;
-            const int rb = (RPP % B == 0) ? ((lrow / B) & 1) : 0;
-#pragma unroll
-            for (int j = 0; j < XL; ++j) {
-                const int jb = (RPP % B == 0) ? ((j * (RPP / B)) & 1) : (((j * RPP) / B) & 1);
-                const int addr = (base0 ^ ((rb ^ jb) << 4)) + j * RPP * TC;
-                *reinterpret_cast<f32x4*>(&xs[addr]) = xreg[j];
-            }
-        }
-        __syncthreads();
-        const bool more_tiles = tile + nwg < ntiles;
-        // stage 1, in place; U1 beta groups in flight per wave
-        constexpr int BMA = A / 16;
-#pragma unroll
-        for (int g = 0; g < B / NW; g += U1) {
-            if (more_tiles) gload_slice(tile + nwg, g / U1);
-            f32x4 cr[U1][BMA], ci[U1][BMA];
-            float2 tw[U1][BMA][4];
-            int beta[U1];
-#pragma unroll
-            for (int u = 0; u < U1; ++u) {
-                beta[u] = wave + (g + u) * NW;
-#pragma unroll
-                for (int bm = 0; bm < BMA; ++bm) {
-                    cr[u][bm] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    ci[u][bm] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) tw[u][bm][v] = tws[tw_rd + (bm * 16 + v) * B + (g + u) * NW];
-                }
-            }
-#pragma unroll 4
-            for (int s = 0; s < A / 4; ++s) {
-                float ar[BMA], ai[BMA];
-                f32x2 x[U1];
-#pragma unroll
-                for (int bm = 0; bm < BMA; ++bm) {
-                    ar[bm] = far[fa_col[bm] + 4 * s * FAP];
-                    ai[bm] = fai[fa_col[bm] + 4 * s * FAP];
-                }
-#pragma unroll
-                for (int u = 0; u < U1; ++u)
-                    x[u] = *reinterpret_cast<const f32x2*>(&xs[s1_rd + ((g + u) * NW + 4 * s * B) * TC]);
-#pragma unroll
-                for (int u = 0; u < U1; ++u)
-#pragma unroll
-                    for (int bm = 0; bm < BMA; ++bm) cr[u][bm] = mfma16(ar[bm], x[u].x, cr[u][bm]);
-#pragma unroll
-                for (int u = 0; u < U1; ++u)
-#pragma unroll
-                    for (int bm = 0; bm < BMA; ++bm) ci[u][bm] = mfma16(ar[bm], x[u].y, ci[u][bm]);
-#pragma unroll
-                for (int u = 0; u < U1; ++u)
-#pragma unroll
-                    for (int bm = 0; bm < BMA; ++bm) cr[u][bm] = mfma16(-ai[bm], x[u].y, cr[u][bm]);
-#pragma unroll
-                for (int u = 0; u < U1; ++u)
-#pragma unroll
-                    for (int bm = 0; bm < BMA; ++bm) ci[u][bm] = mfma16(ai[bm], x[u].x, ci[u][bm]);
-            }
-#pragma unroll
-            for (int u = 0; u < U1; ++u)
-#pragma unroll
-                for (int bm = 0; bm < BMA; ++bm)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const float wx = tw[u][bm][v].x, wy = tw[u][bm][v].y;   // k_a = 16bm + 4lq + v (sign applied at load)
-                        const float zr = cr[u][bm][v] * wx - ci[u][bm][v] * wy;
-                        const float zi = cr[u][bm][v] * wy + ci[u][bm][v] * wx;
-                        const int wr = ((v & 1) ? s1_wr_odd : s1_wr_even) + ((bm * 16 + v) * B + (g + u) * NW) * TC;
-                        *reinterpret_cast<f32x2*>(&xs[wr]) = f32x2{zr, zi};
-                    }
-        }
-        __syncthreads();
-        // stage 2: U2 k_a groups at a time per wave (they share the FB operands), all k_b blocks in flight
-        constexpr int BMB = B / 16;
-        float2* dst = Y + tile_base(tile) + l16;
-#pragma unroll
-        for (int g = 0; g < A / NW; g += U2) {
-            if (more_tiles) gload_slice(tile + nwg, (B / NW) / U1 + g / U2);
-            f32x4 cr[U2][BMB], ci[U2][BMB];
-#pragma unroll
-            for (int u = 0; u < U2; ++u)
-#pragma unroll
-                for (int bm = 0; bm < BMB; ++bm) {
-                    cr[u][bm] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    ci[u][bm] = f32x4{0.f, 0.f, 0.f, 0.f};
-                }
-#pragma unroll 4
-            for (int s = 0; s < B / 4; ++s) {
-                f32x2 z[U2];
-#pragma unroll
-                for (int u = 0; u < U2; ++u)
-                    z[u] = *reinterpret_cast<const f32x2*>(&xs[s2_rd + ((g + u) * NW * B + 4 * s) * TC]);
-                float ar[BMB], ai[BMB];
-#pragma unroll
-                for (int bm = 0; bm < BMB; ++bm) {
-                    ar[bm] = fbr[fb_col[bm] + 4 * s * FBP];
-                    ai[bm] = fbi[fb_col[bm] + 4 * s * FBP];
-                }
-#pragma unroll
-                for (int u = 0; u < U2; ++u)
-#pragma unroll
-                    for (int bm = 0; bm < BMB; ++bm) cr[u][bm] = mfma16(ar[bm], z[u].x, cr[u][bm]);
-#pragma unroll
-                for (int u = 0; u < U2; ++u)
-#pragma unroll
-                    for (int bm = 0; bm < BMB; ++bm) ci[u][bm] = mfma16(ar[bm], z[u].y, ci[u][bm]);
-#pragma unroll
-                for (int u = 0; u < U2; ++u)
-#pragma unroll
-                    for (int bm = 0; bm < BMB; ++bm) cr[u][bm] = mfma16(-ai[bm], z[u].y, cr[u][bm]);
-#pragma unroll
-                for (int u = 0; u < U2; ++u)
-#pragma unroll
-                    for (int bm = 0; bm < BMB; ++bm) ci[u][bm] = mfma16(ai[bm], z[u].x, ci[u][bm]);
-            }
-#pragma unroll
-            for (int u = 0; u < U2; ++u) {
-                const int ka = wave + (g + u) * NW;
-#pragma unroll
-                for (int bm = 0; bm < BMB; ++bm)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int kb = bm * 16 + 4 * lq + v;
-                        *reinterpret_cast<f32x2*>(dst + (int64_t)(ka + A * kb) * I) =
-                            f32x2{cr[u][bm][v] * scale, ci[u][bm][v] * scale};
-                    }
-            }
-        }
-        __syncthreads();
-    }
-}
-
-// ------------------------------------------------------------------------------------------
 // Twiddle multiply (memory-bound).  The tensor [outer][A][B][inner] is walked as a matrix whose
 // twiddle depends on the row only (inner > 1: rows = outer*A*B, columns = inner, factor
 // Tw[row % (A*B)]) or on the column only (inner == 1: rows = outer, columns = A*B, factor
@@ -1449,25 +1206,10 @@ hipError_t launch_fft_z(const float2* in, float2* out, int64_t nrows, int A, int
     return hipErrorInvalidValue;
 }
 
-namespace {
-template <int A, int B, int NW, int MINW, int WGS_PER_CU>
-hipError_t launch_fft_s_inst(const float2* in, float2* out, int64_t O, int64_t I, const DeviceMatrix& FA,
-                             const DeviceMatrix& FB, const float2* Tw, float scale, int conj,
-                             hipStream_t stream)
-{
-    const int64_t ntiles = O * (I / 16);
-    const int64_t resident = 256 * WGS_PER_CU;
-    const int64_t blocks = ntiles < resident ? ntiles : resident;
-    hipLaunchKernelGGL((k_fft_s<A, B, NW, MINW>), grid_for(blocks), dim3(NW * 64), 0, stream, in, out, O, I, FA, FB,
-                       Tw, scale, conj);
-    return hipGetLastError();
-}
-}  // namespace
-
+// Strided axes: every fused kernel lives in dft3d_fft_reg.hip / dft3d_fft_nested.hip.
 bool fft_s_supported(int A, int B, int64_t I)
 {
-    if (I % 16 != 0) return false;
-    return (A == 16 && B == 16) || (A == 16 && B == 32) || (A == 32 && B == 32) || fft_sr_supported(A, B, I);
+    return fft_sr_supported(A, B, I);
 }
 
 hipError_t launch_fft_s(const float2* in, float2* out, int64_t O, int64_t I, int A, int B,
@@ -1475,13 +1217,8 @@ hipError_t launch_fft_s(const float2* in, float2* out, int64_t O, int64_t I, int
                         int conj, hipStream_t stream)
 {
     if (O <= 0 || I <= 0) return hipSuccess;
-    if (fft_sr_supported(A, B, I)) return launch_fft_sr(in, out, O, I, A, B, FA, FB, Tw, scale, conj, stream);
-    if (A == 16 && B == 16) return launch_fft_s_inst<16, 16, 4, 2, 2>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
-    if (A == 16 && B == 32) return launch_fft_s_inst<16, 32, 4, 2, 2>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
-    if (A == 32 && B == 32) return launch_fft_s_inst<32, 32, 8, 2, 1>(in, out, O, I, FA, FB, Tw, scale, conj, stream);
-    return hipErrorInvalidValue;
+    return launch_fft_sr(in, out, O, I, A, B, FA, FB, Tw, scale, conj, stream);
 }
-
 
 hipError_t launch_copy(const void* in, void* out, size_t bytes, int variant, hipStream_t stream)
 {

@@ -470,7 +470,10 @@ def test_fft_fused_axis_kernel(dft, shape, split):
                                          ((2048, 3, 32), (16, 1, 1)), ((2048, 2, 4112), (16, 1, 1)),
                                          # 1024 = 16 x (4*16), against 32 x 32 by default
                                          ((1024, 1, 32), (16, 1, 1)), ((2, 1024, 48), (1, 16, 1)),
-                                         ((1024, 5, 1040), (16, 1, 1)), ((1024, 3, 1056), (16, 1, 1))])
+                                         ((1024, 5, 1040), (16, 1, 1)), ((1024, 3, 1056), (16, 1, 1)),
+                                         # 1024 = 32 x (2*16)
+                                         ((1024, 1, 32), (32, 1, 1)), ((2, 1024, 48), (1, 32, 1)),
+                                         ((1024, 3, 1056), (32, 1, 1))])
 def test_fft_fused_strided_axis_kernel(dft, shape, split):
     """The single-kernel x / y pass equals first stage + twiddle + second stage + re-ordering."""
     say(f"case fft fused strided axis {shape} split {split}")
