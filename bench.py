@@ -433,7 +433,8 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
     if kernel_note:
         roofline["kernel_note"] = kernel_note
     variant = ("+complex128" if c128 else "") + ("+bf16x3" if (opts.bf16x3 and form == dft.KDFT) else "") + \
-              ("+3m" if (opts.three_m and form == dft.KDFT) else "") + ("+unfused" if opts.unfused else "")
+              ("+3m" if (opts.three_m and form == dft.KDFT) else "") + ("+unfused" if opts.unfused else "") + \
+              ("+split" if (getattr(opts, "split_first", None) and form == dft.FFT) else "")
     roofline["traffic"] = measured_traffic(name + variant)
     if opts.three_m and form == dft.KDFT and not c128:
         roofline["complex_scheme"] = "3M"
