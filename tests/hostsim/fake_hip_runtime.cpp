@@ -302,7 +302,7 @@ hipError_t hipLaunchKernel(const void* func, dim3 grid, dim3 block, void** args,
         check_region(name, "matrix", a.M.re, (int64_t)2 * a.M.ld * a.M.rows * 4);
         if (starts("k_contract_bf16x3<"))
             check_region(name, "bf16 matrix planes", a.M.split, (int64_t)a.M.split_planes * a.M.split_ld * a.M.split_rows * 2);
-    } else if (starts("k_fft_sr<") || starts("k_fft_sw<") || starts("k_fft_ss<")) {
+    } else if (starts("k_fft_sr<")) {
         const FftStridedArgs& a = *(const FftStridedArgs*)args[0];
         const std::vector<long> t = template_ints(name);
         const int64_t N = t.size() >= 2 ? t[0] * t[1] : 0;
@@ -327,18 +327,12 @@ hipError_t hipLaunchKernel(const void* func, dim3 grid, dim3 block, void** args,
         L.src = *(const void* const*)args[0], L.dst = *(void* const*)args[1];
         L.src_bytes = L.dst_bytes = nrows * N * 8;
         if (N <= 0) fail(name + ": cannot read the split from the kernel name");
-    } else if (starts("k_fft_zr<") || starts("k_fft_zl<") || starts("k_fft_z<")) {
+    } else if (starts("k_fft_zr<") || starts("k_fft_z<")) {
         const std::vector<long> t = template_ints(name);
         const int64_t N = t.size() >= 2 ? t[0] * t[1] : 0;
         const int64_t nrows = *(const int64_t*)args[2];
         L.src = *(const void* const*)args[0], L.dst = *(void* const*)args[1];
         L.src_bytes = L.dst_bytes = nrows * N * 8;
-    } else if (starts("k_fft_s<")) {
-        const std::vector<long> t = template_ints(name);
-        const int64_t N = t.size() >= 2 ? t[0] * t[1] : 0;
-        const int64_t O = *(const int64_t*)args[2], I = *(const int64_t*)args[3];
-        L.src = *(const void* const*)args[0], L.dst = *(void* const*)args[1];
-        L.src_bytes = L.dst_bytes = O * N * I * 8;
     } else if (starts("k_kdft_small")) {
         const DeviceMatrix& Mx = *(const DeviceMatrix*)args[2];
         const DeviceMatrix& My = *(const DeviceMatrix*)args[3];
