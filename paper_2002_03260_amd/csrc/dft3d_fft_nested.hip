@@ -627,7 +627,7 @@ hipError_t configure_fft_nested_kernels()
     if (e == hipSuccess) e = configure_sn<1, 2, 4, 1>();
     if (e == hipSuccess) e = configure_sn<2, 4, 1, 1>();
     if (e == hipSuccess) e = configure_sn<2, 2, 2, 1>();
-    if (e == hipSuccess) e = configure_sn<2, 2, 1, 2>();
+    if (e == hipSuccess) e = configure_sn<2, 2, 1, 1>();
     return e;
 }
 
@@ -642,7 +642,7 @@ hipError_t launch_fft_sn(const FftStridedArgs& a, int A, int B, const DeviceMatr
     if (A == 32 && B == 64) return launch_sn_inst<2, 4, 1, 1>(a, FA, FB, Tw, scale, conj, stream);
     if (A == 32 && B == 32) {
         if (a.Zt % 2 == 0) return launch_sn_inst<2, 2, 2, 1>(a, FA, FB, Tw, scale, conj, stream);
-        return launch_sn_inst<2, 2, 1, 2>(a, FA, FB, Tw, scale, conj, stream);
+        return launch_sn_inst<2, 2, 1, 1>(a, FA, FB, Tw, scale, conj, stream);
     }
     // Wider tiles mean longer contiguous pieces per row (128 bytes per 16 columns) but one workgroup per CU
     // instead of two once the accumulators of N * columns outputs fill its registers.  Measured: 1024 points,
