@@ -403,6 +403,13 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
                     # the same on a strided axis: three real products in the first stage, four in the last
                     # (whose accumulators are the resident output tile)
                     flops = (6.0 * A + 8.0 * 16) * E
+            elif "stage1" in dom_name and A in (2, 4, 8) and not c128 and not opts.unfused:
+                # butterflies and twiddle in vector arithmetic: an element-wise, memory-bound pass
+                flops = 0.0
+            elif "stage2" in dom_name and A in (2, 4, 8) and B in (512, 1024, 2048) and not c128 and not opts.unfused:
+                # the B-point stage on the fused kernels (B = 16 x (C*16)): two 16-point matrix stages, three real
+                # products each on the contiguous axis, three and four on a strided one
+                flops = (6.0 * 32 if ax == 2 else 6.0 * 16 + 8.0 * 16) * E
             elif "stage1" in dom_name:
                 # strided stages with a 16 / 32 / 64 matrix run the three-product streaming kernel, and
                 # every stage of 128 points or more takes the three-product scheme

@@ -55,7 +55,7 @@ WORKLOADS = {
 # figure of the 2-D KDFT), given as a 3-D shape whose first axis has length 1.
 EXTRA_WORKLOADS = {
     "2d-8192": Workload("next_2d_8192", 6, (1, 8192, 8192), KDFT, "normal",
-                        splits=((1, 1), (64, 128), (64, 128))),
+                        splits=((1, 1), (4, 2048), (4, 2048))),
 }
 
 

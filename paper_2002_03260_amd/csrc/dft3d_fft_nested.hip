@@ -577,7 +577,104 @@ hipError_t launch_sn_inst(const FftStridedArgs& a, const DeviceMatrix& FA, const
     return hipGetLastError();
 }
 
+// ---- first stage of a split with a small first factor ----------------------------------------------
+// N = R * M with R = 2, 4 or 8 and the M-point second stage on one of the fused kernels above (8192 =
+// 4 * 2048): the first stage of Eq. 13 - 16, Z[k_a, j] = T[k_a, beta] * sum_l w_R^(k_a l) x[l, j] on the view
+// [O][R][I] (I = M * inner, beta = j / inner), is R-point butterflies on R values I elements apart plus one
+// complex multiplication: a memory-bound, element-wise pass.  A thread takes two neighbouring j (16-byte
+// accesses); the host checks that I is even and that the two share beta or are neighbours in it.
+// PERM: the input rows (innermost axis, nz = pA * pB points) still hold the result of a split pA x pB of that
+// axis as [k_a][k_b]; the pass reads position (z % pA) * pB + z / pA for column z, which is that axis'
+// re-ordering to natural order done on the way in (two 8-byte reads pB apart instead of one of 16 bytes).
+template <int R, bool SWAP, bool PERM>
+__global__ __launch_bounds__(256) void k_radix_tw(const float2* __restrict__ in, float2* __restrict__ out,
+                                                  int64_t npairs, uint32_t halfI, uint32_t inner, int B,
+                                                  const float2* __restrict__ Tw, uint32_t nz, uint32_t pA, uint32_t pB)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= npairs) return;
+    const int64_t o = t / halfI;
+    const uint32_t j = 2u * (uint32_t)(t - o * halfI);
+    const int64_t I = 2 * (int64_t)halfI;
+    const int64_t base = o * R * I + j;
+    f32x2 re[R], im[R];
+#pragma unroll
+    for (int l = 0; l < R; ++l) {
+        f32x4 v;
+        if constexpr (PERM) {
+            // j even and pA even: columns z and z + 1 share z / pA and sit pB apart in the input
+            const uint32_t z = j % nz;
+            const f32x2* src = reinterpret_cast<const f32x2*>(in + base + l * I) - z + ((z % pA) * pB + z / pA);
+            const f32x2 e0 = __builtin_nontemporal_load(src), e1 = __builtin_nontemporal_load(src + pB);
+            v = f32x4{e0.x, e0.y, e1.x, e1.y};
+        } else {
+            v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(in + base + l * I));
+        }
+        re[l] = SWAP ? f32x2{v.y, v.w} : f32x2{v.x, v.z};
+        im[l] = SWAP ? f32x2{v.x, v.z} : f32x2{v.y, v.w};
+    }
+    small_dft<R>(re, im);
+    if (Tw) {
+        const uint32_t b0 = j / inner, b1 = (j + 1) / inner;
+#pragma unroll
+        for (int k = 1; k < R; ++k) {                  // T[0, beta] = 1
+            const float2 w0 = Tw[(int64_t)k * B + b0], w1 = Tw[(int64_t)k * B + b1];
+            const f32x2 wr = {w0.x, w1.x}, wi = {w0.y, w1.y};
+            const f32x2 r = re[k], i = im[k];
+            re[k] = r * wr - i * wi;
+            im[k] = r * wi + i * wr;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const f32x4 v = SWAP ? f32x4{im[k].x, re[k].x, im[k].y, re[k].y} : f32x4{re[k].x, im[k].x, re[k].y, im[k].y};
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + base + k * I));
+    }
+}
+
+template <int R, bool PERM>
+hipError_t launch_radix_inst(const float2* in, float2* out, int64_t O, int64_t I, int64_t inner, int B, const float2* Tw,
+                             int conj, int64_t nz, int pA, int pB, hipStream_t stream)
+{
+    const int64_t npairs = O * (I / 2);
+    const int64_t blocks = (npairs + 255) / 256;
+    if (blocks >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+    if (conj)
+        hipLaunchKernelGGL((k_radix_tw<R, true, PERM>), dim3((unsigned)blocks), dim3(256), 0, stream, in, out, npairs,
+                           (uint32_t)(I / 2), (uint32_t)inner, B, Tw, (uint32_t)nz, (uint32_t)pA, (uint32_t)pB);
+    else
+        hipLaunchKernelGGL((k_radix_tw<R, false, PERM>), dim3((unsigned)blocks), dim3(256), 0, stream, in, out, npairs,
+                           (uint32_t)(I / 2), (uint32_t)inner, B, Tw, (uint32_t)nz, (uint32_t)pA, (uint32_t)pB);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+bool radix_stage_supported(int R, int64_t B, int64_t inner)
+{
+    // pairs of neighbouring elements of [B][inner]: in the same beta (inner even) or in neighbouring ones (inner 1)
+    return (R == 2 || R == 4 || R == 8) && B >= 1 && inner >= 1 && (B * inner) % 2 == 0 && (inner == 1 || inner % 2 == 0) &&
+           B * inner < (int64_t(1) << 32);
+}
+
+hipError_t launch_radix_twiddle(const float2* in, float2* out, int64_t O, int R, int64_t B, int64_t inner,
+                                const float2* Tw, int conj, int64_t nz, int pA, int pB, hipStream_t stream)
+{
+    if (O <= 0) return hipSuccess;
+    if (!radix_stage_supported(R, B, inner) || B >= (int64_t(1) << 31)) return hipErrorInvalidValue;
+    const int64_t I = B * inner;
+    if (pA > 1) {
+        // the permuted read works on whole rows of the innermost axis below the transformed one
+        if (nz < 2 || nz >= (int64_t(1) << 31) || inner % nz != 0 || pA % 2 != 0 || (int64_t)pA * pB != nz)
+            return hipErrorInvalidValue;
+        if (R == 2) return launch_radix_inst<2, true>(in, out, O, I, inner, (int)B, Tw, conj, nz, pA, pB, stream);
+        if (R == 4) return launch_radix_inst<4, true>(in, out, O, I, inner, (int)B, Tw, conj, nz, pA, pB, stream);
+        return launch_radix_inst<8, true>(in, out, O, I, inner, (int)B, Tw, conj, nz, pA, pB, stream);
+    }
+    if (R == 2) return launch_radix_inst<2, false>(in, out, O, I, inner, (int)B, Tw, conj, 1, 1, 1, stream);
+    if (R == 4) return launch_radix_inst<4, false>(in, out, O, I, inner, (int)B, Tw, conj, 1, 1, 1, stream);
+    return launch_radix_inst<8, false>(in, out, O, I, inner, (int)B, Tw, conj, 1, 1, 1, stream);
+}
 
 bool fft_zn_supported(int A, int B)
 {

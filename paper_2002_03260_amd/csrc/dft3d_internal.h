@@ -140,6 +140,14 @@ hipError_t launch_fft_zn(const float2* in, float2* out, int64_t nrows, int A, in
                          const DeviceMatrix& FA, const DeviceMatrix& FB, const float2* Tw, float scale,
                          int conj, hipStream_t stream);
 
+// First stage (+ twiddle unless Tw is null) of a split whose first factor R is 2, 4 or 8, on the view
+// [O][R][B][inner]: butterflies in vector arithmetic, one element-wise memory-bound pass.  With pA > 1 the
+// rows of the innermost tensor axis (nz = pA * pB points, inner a multiple of nz) are read through that axis'
+// re-ordering [k_a][k_b] -> k_a + pA * k_b, which then needs no pass of its own.
+bool radix_stage_supported(int R, int64_t B, int64_t inner);
+hipError_t launch_radix_twiddle(const float2* in, float2* out, int64_t O, int R, int64_t B, int64_t inner,
+                                const float2* Tw, int conj, int64_t nz, int pA, int pB, hipStream_t stream);
+
 // ---- fused strided-axis FFT-formulation pass ------------------------------------------------
 // Tensor viewed as [O][A*B][I]; one launch = both stages, twiddle and natural order along the
 // middle index.  I must be a multiple of 16; available for a fixed set of (A, B).

@@ -199,11 +199,37 @@ dft3d_status make_axis_matrix(int64_t n, const double* coords, DeviceMatrix* out
     return s;
 }
 
+// The twiddle table T[k_a * B + beta] = exp(-2 pi i k_a beta / (A B)) of an A x B split, on the device.
+dft3d_status upload_twiddle(int64_t A, int64_t B, float2** out)
+{
+    const size_t cnt = (size_t)(A * B);
+    std::vector<float> tr(cnt), ti(cnt);
+    dft3d_status s = dft3d_generate_twiddle(A, B, DFT3D_FORWARD, tr.data(), ti.data());
+    if (s != DFT3D_OK) return s;
+    std::vector<float2> tw(cnt);
+    for (size_t e = 0; e < cnt; ++e) tw[e] = make_float2(tr[e], ti[e]);
+    hipError_t e = hipMalloc((void**)out, cnt * sizeof(float2));
+    if (e != hipSuccess) {
+        *out = nullptr;
+        set_error("plan_create: hipMalloc of a twiddle table failed: %s", hipGetErrorString(e));
+        return DFT3D_ERR_ALLOC;
+    }
+    e = hipMemcpy(*out, tw.data(), cnt * sizeof(float2), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        set_error("plan_create: twiddle upload failed: %s", hipGetErrorString(e));
+        return DFT3D_ERR_HIP;
+    }
+    return DFT3D_OK;
+}
+
 int64_t default_split(int64_t n)
 {
     // 16 x (C*16), the split whose second factor the fused kernels split once more (2048: a third of the
     // matrix-core work of 32 x 64)
     if (n == 2048 || n == 1024) return 16;
+    // a radix-4 / radix-8 first stage in vector arithmetic, then 2048 points on the fused kernels
+    if (n == 8192) return 4;
+    if (n == 16384) return 8;
     if ((n & (n - 1)) == 0) {
         int lg = 0;
         while ((int64_t(1) << (lg + 1)) <= n) ++lg;
@@ -238,6 +264,12 @@ struct dft3d_plan_s {
     float2* Tw[3] = {nullptr, nullptr, nullptr};
     double* Tw64[3] = {nullptr, nullptr, nullptr};   // complex128 plans: the same table in fp64, (re, im) pairs
     int F_owner[3] = {0, 1, 2};
+    // FFT, first factor 2, 4 or 8 and a second factor B of 512, 1024 or 2048 points: the B-point second stage
+    // is run in the FFT formulation itself (Eq. 13 - 16 applied to it once more, B = A2 x B2) on the fused
+    // kernels, with the tables of that split; A2 = 0 where the second stage is the dense B x B contraction
+    int64_t A2[3] = {0, 0, 0}, B2[3] = {0, 0, 0};
+    DeviceMatrix FA2[3], FB2[3];
+    float2* Tw2[3] = {nullptr, nullptr, nullptr};
 
     void* workspace = nullptr;
     size_t workspace_bytes = 0;
@@ -381,14 +413,29 @@ hipError_t run_stage_c128(const DeviceMatrix& M, const void* in, void* out, int6
 }
 
 // FFT first stage on `axis`: view [outer][A][B*inner], contract the A index.
+// Whether the first stage of `axis` is the element-wise butterfly pass (2, 4 or 8 points).
+bool first_stage_is_radix(const dft3d_plan_s* p, int axis)
+{
+    return p->form == DFT3D_FFT && !p->complex128() && !(p->flags & DFT3D_FLAG_UNFUSED) &&
+           radix_stage_supported((int)p->A[axis], p->B[axis], p->inner(axis));
+}
+
+// unpermute_z: the input still has the z axis as [k_a][k_b] (its second stage ran without the re-ordering
+// pass); a first stage in butterflies reads through that permutation.
 hipError_t run_first_stage(const dft3d_plan_s* p, int axis, const float2* in, float2* out, int conj,
-                           int fuse_twiddle, hipStream_t st)
+                           int fuse_twiddle, hipStream_t st, bool unpermute_z = false)
 {
     if (p->complex128()) {
         const int64_t I = p->B[axis] * p->inner(axis);
         return run_stage_c128(p->FA[axis], in, out, p->outer(axis), I, 1, (int64_t)p->FA[axis].K * I, 0, I,
                               fuse_twiddle ? p->Tw64[axis] : nullptr, (int)p->B[axis], p->inner(axis), 1.0, conj, st);
     }
+    // 2, 4 or 8 points: butterflies in a memory-bound element-wise pass (the UNFUSED exhibit keeps the contraction)
+    if (first_stage_is_radix(p, axis))
+        return launch_radix_twiddle(in, out, p->outer(axis), (int)p->A[axis], p->B[axis], p->inner(axis),
+                                    fuse_twiddle ? p->Tw[axis] : nullptr, conj, p->n[2], unpermute_z ? (int)p->A[2] : 1,
+                                    unpermute_z ? (int)p->B[2] : 1, st);
+    if (unpermute_z) return hipErrorInvalidValue;
     ContractArgs a{};
     a.X = in;
     a.Y = out;
@@ -408,6 +455,17 @@ hipError_t run_first_stage(const dft3d_plan_s* p, int axis, const float2* in, fl
     return launch_contract(a, st);
 }
 
+// Whether the second stage of `axis` runs on a fused kernel with the split B = A2 x B2 (the UNFUSED exhibit
+// keeps the dense contraction).
+bool second_stage_nested(const dft3d_plan_s* p, int axis, int reorder)
+{
+    if (!p->A2[axis] || (p->flags & DFT3D_FLAG_UNFUSED)) return false;
+    const int A2 = (int)p->A2[axis], B2 = (int)p->B2[axis];
+    if (axis == 2) return !reorder && fft_zn_supported(A2, B2);
+    const int64_t inner = p->inner(axis);
+    return fft_sn_supported(A2, B2, inner) && p->A[axis] * inner <= (int64_t(1) << 23);
+}
+
 // FFT second stage on `axis`: view [outer*A][B][inner], contract the B index; with reorder the
 // result (k_a, k_b) lands at natural position k_a + A*k_b of the axis.
 hipError_t run_second_stage(const dft3d_plan_s* p, int axis, const float2* in, float2* out, int conj,
@@ -419,6 +477,25 @@ hipError_t run_second_stage(const dft3d_plan_s* p, int axis, const float2* in, f
         const double sc = conj ? 1.0 / (double)p->n[axis] : 1.0;
         return run_stage_c128(p->FB[axis], in, out, p->outer(axis) * A, inner, A, A * B * inner,
                               reorder ? inner : B * inner, reorder ? A * inner : inner, nullptr, 1, 1, sc, conj, st);
+    }
+    if (second_stage_nested(p, axis, reorder)) {
+        const int A2 = (int)p->A2[axis], B2 = (int)p->B2[axis];
+        if (axis == 2)     // rows of B contiguous points, [outer * A] of them; the result stays [k_a][k2]
+            return launch_fft_zn(in, out, p->outer(axis) * A, A2, B2, p->FA2[axis], p->FB2[axis], p->Tw2[axis], scale,
+                                 conj, st);
+        // view [outer][k_a][beta][inner] -> [outer][k2][k_a][inner] (re-ordered) or [outer][k_a][k2][inner]
+        FftStridedArgs f{};
+        f.X = in;
+        f.Y = out;
+        f.O = p->outer(axis);
+        f.Yn = A;
+        f.Zt = inner / 16;
+        f.inO = f.outO = A * B * inner;
+        f.inY = B * inner;
+        f.inN = inner;
+        f.outY = reorder ? inner : B * inner;
+        f.outN = reorder ? A * inner : inner;
+        return launch_fft_sr_ex(f, A2, B2, p->FA2[axis], p->FB2[axis], p->Tw2[axis], scale, conj, st);
     }
     ContractArgs a{};
     a.X = in;
@@ -730,6 +807,11 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
                 p->FB[j] = p->FB[i];
                 p->Tw[j] = p->Tw[i];
                 p->Tw64[j] = p->Tw64[i];
+                p->A2[j] = p->A2[i];
+                p->B2[j] = p->B2[i];
+                p->FA2[j] = p->FA2[i];
+                p->FB2[j] = p->FB2[i];
+                p->Tw2[j] = p->Tw2[i];
                 continue;
             }
             const bool c128 = (flags & DFT3D_FLAG_COMPLEX128) != 0;
@@ -757,23 +839,16 @@ static dft3d_status plan_create_impl(dft3d_plan* plan, int64_t nx, int64_t ny, i
                     break;
                 }
             }
-            const size_t cnt = (size_t)(p->A[j] * p->B[j]);
-            std::vector<float> tr(cnt), ti(cnt);
-            s = dft3d_generate_twiddle(p->A[j], p->B[j], DFT3D_FORWARD, tr.data(), ti.data());
+            s = upload_twiddle(p->A[j], p->B[j], &p->Tw[j]);
             if (s != DFT3D_OK) break;
-            std::vector<float2> tw(cnt);
-            for (size_t e = 0; e < cnt; ++e) tw[e] = make_float2(tr[e], ti[e]);
-            hipError_t e = hipMalloc((void**)&p->Tw[j], cnt * sizeof(float2));
-            if (e != hipSuccess) {
-                set_error("plan_create: hipMalloc of a twiddle table failed: %s", hipGetErrorString(e));
-                s = DFT3D_ERR_ALLOC;
-                break;
-            }
-            e = hipMemcpy(p->Tw[j], tw.data(), cnt * sizeof(float2), hipMemcpyHostToDevice);
-            if (e != hipSuccess) {
-                set_error("plan_create: twiddle upload failed: %s", hipGetErrorString(e));
-                s = DFT3D_ERR_HIP;
-                break;
+            const int64_t Bj = p->B[j];
+            if (!c128 && (A == 2 || A == 4 || A == 8) && (Bj == 512 || Bj == 1024 || Bj == 2048)) {
+                p->A2[j] = 16;
+                p->B2[j] = Bj / 16;
+                s = make_axis_matrix(p->A2[j], nullptr, &p->FA2[j]);
+                if (s == DFT3D_OK) s = make_axis_matrix(p->B2[j], nullptr, &p->FB2[j]);
+                if (s == DFT3D_OK) s = upload_twiddle(p->A2[j], p->B2[j], &p->Tw2[j]);
+                if (s != DFT3D_OK) break;
             }
         }
     }
@@ -944,6 +1019,9 @@ dft3d_status dft3d_plan_destroy(dft3d_plan p)
             free_matrix(p->FB[j]);
             if (p->Tw[j]) (void)hipFree(p->Tw[j]);
             if (p->Tw64[j]) (void)hipFree(p->Tw64[j]);
+            free_matrix(p->FA2[j]);
+            free_matrix(p->FB2[j]);
+            if (p->Tw2[j]) (void)hipFree(p->Tw2[j]);
         }
     }
     delete p;
@@ -1225,11 +1303,21 @@ dft3d_status exec_with_workspace(dft3d_plan p, const void* in, void* out, int di
     const bool zfused = !unfused && z_axis_fusable(p);
     bool sfused[2] = {!unfused && strided_axis_fusable(p, 0), !unfused && strided_axis_fusable(p, 1)};
     bool skip[3] = {!unfused && p->n[0] == 1, !unfused && p->n[1] == 1, !unfused && p->n[2] == 1};
+    // The re-ordering pass of a z axis without a fused kernel is saved when the pass right after its second
+    // stage is a first stage in butterflies (y, or x when y takes no pass): that pass reads through the
+    // permutation.  (Not for complex128 plans, whose first stages are contractions.)
+    bool allow_zfold = true;
+    auto z_folds_into = [&]() {
+        if (!allow_zfold || p->form != DFT3D_FFT || unfused || zfused || skip[2] || p->x_first) return -1;
+        const int next = !skip[1] ? 1 : (!skip[0] ? 0 : -1);
+        if (next < 0 || sfused[next] || !first_stage_is_radix(p, next) || p->A[2] % 2 != 0 || p->A[2] < 2) return -1;
+        return next;
+    };
     auto count_passes = [&]() {
         if (p->form != DFT3D_FFT) return 3 - (int)skip[0] - (int)skip[1] - (int)skip[2];
         if (unfused) return 10;
         int c = 0;
-        if (!skip[2]) c += zfused ? 1 : 3;
+        if (!skip[2]) c += zfused ? 1 : (z_folds_into() >= 0 ? 2 : 3);
         for (int axis = 0; axis < 2; ++axis)
             if (!skip[axis]) c += sfused[axis] ? 1 : 2;
         return c;
@@ -1241,8 +1329,9 @@ dft3d_status exec_with_workspace(dft3d_plan p, const void* in, void* out, int di
     }
     if (clobber && (npass % 2 == 0)) {
         // ping-ponging between in and out needs an odd pass count: try, one at a time, keeping the
-        // identity pass(es) of a length-1 axis or splitting a fused strided axis into its two stages
-        bool* knobs[5] = {&skip[2], &skip[1], &skip[0], &sfused[1], &sfused[0]};
+        // re-ordering pass of the z axis, the identity pass(es) of a length-1 axis, or splitting a fused strided
+        // axis into its two stages
+        bool* knobs[6] = {&allow_zfold, &skip[2], &skip[1], &skip[0], &sfused[1], &sfused[0]};
         for (bool* knob : knobs) {
             if (!*knob) continue;
             *knob = false;
@@ -1273,6 +1362,7 @@ dft3d_status exec_with_workspace(dft3d_plan p, const void* in, void* out, int di
     };
 
     hipError_t e = hipSuccess;
+    const int zfold = z_folds_into();      // (after the pass structure is final)
     if (p->form == DFT3D_KDFT) {
         for (int axis = 2; axis >= 0 && e == hipSuccess; --axis) {
             if (skip[axis]) continue;
@@ -1301,7 +1391,7 @@ dft3d_status exec_with_workspace(dft3d_plan p, const void* in, void* out, int di
                 continue;
             }
             mark(0);
-            e = run_first_stage(p, axis, src, dst, conj, unfused ? 0 : 1, st);
+            e = run_first_stage(p, axis, src, dst, conj, unfused ? 0 : 1, st, axis == zfold);
             advance();
             if (unfused && e == hipSuccess) {
                 mark(0);
@@ -1315,7 +1405,7 @@ dft3d_status exec_with_workspace(dft3d_plan p, const void* in, void* out, int di
             e = run_second_stage(p, axis, src, dst, conj, axis_scale(p, axis, direction), fold, st);
             advance();
         }
-        if (e == hipSuccess && !zfused && !skip[2]) {
+        if (e == hipSuccess && !zfused && !skip[2] && zfold < 0) {
             mark(0);
             e = run_reorder(p, unfused ? 7 : 4, src, dst, st);
             advance();

@@ -246,6 +246,11 @@ int main()
         {{32, 2048, 16}, DFT3D_FFT, 0, false, {0, 0, 0}},
         {{1, 8192, 8192}, DFT3D_KDFT, 0, false, {0, 0, 0}},
         {{1, 8192, 8192}, DFT3D_FFT, DFT3D_FLAG_CLOBBER_INPUT, false, {0, 0, 0}},
+        // first factor 2, 4 or 8 in vector arithmetic, second factor on the fused kernels
+        {{1, 8192, 8192}, DFT3D_FFT, 0, false, {0, 0, 0}},
+        {{1, 16384, 16384}, DFT3D_FFT, 0, false, {0, 0, 0}},
+        {{8, 4096, 1024}, DFT3D_FFT, 0, false, {2, 2, 2}},
+        {{4096, 3, 4112}, DFT3D_FFT, 0, false, {8, 1, 2}},
     };
     for (const Case& c : named) {
         const int np = run_case(c);
@@ -284,6 +289,7 @@ int main()
     steps_case(36, 20, 48, 0);
     steps_case(512, 3, 48, 0);
     steps_case(2, 2048, 32, 0);
+    steps_case(4, 8192, 16, 0);
     steps_case(64, 32, 128, DFT3D_FLAG_COMPLEX128);
     points_case(false);
     points_case(true);

@@ -333,6 +333,15 @@ hipError_t hipLaunchKernel(const void* func, dim3 grid, dim3 block, void** args,
         const int64_t nrows = *(const int64_t*)args[2];
         L.src = *(const void* const*)args[0], L.dst = *(void* const*)args[1];
         L.src_bytes = L.dst_bytes = nrows * N * 8;
+    } else if (starts("k_radix_tw<")) {
+        // element-wise first stage on [O][R][I]: args in, out, pairs (= O * I / 2), I / 2, ..
+        const std::vector<long> t = template_ints(name);
+        const int64_t R = t.size() >= 1 ? t[0] : 0;
+        const int64_t npairs = *(const int64_t*)args[2];
+        L.src = *(const void* const*)args[0], L.dst = *(void* const*)args[1];
+        L.src_bytes = L.dst_bytes = npairs * 2 * R * 8;
+        if (R != 2 && R != 4 && R != 8) fail(name + ": cannot read the radix from the kernel name");
+        if ((uint64_t)grid.x * 256 < (uint64_t)npairs) fail(name + ": grid does not cover the tensor");
     } else if (starts("k_kdft_small")) {
         const DeviceMatrix& Mx = *(const DeviceMatrix*)args[2];
         const DeviceMatrix& My = *(const DeviceMatrix*)args[3];

@@ -393,7 +393,11 @@ def test_generated_matrix_on_device_equals_host_generator(dft):
 FFT_CASES = [((16, 16, 16), None), ((8, 12, 30), (2, 3, 5)), ((64, 32, 128), None),
              ((36, 20, 48), (6, 4, 8)), ((32, 32, 512), (4, 8, 16)), ((6, 5, 7), (3, 1, 7)),
              # strided stages with 16 / 32 / 64-point matrices and inner extents that are multiples of 16
-             ((4, 2048, 16), None), ((2, 4096, 16), (0, 64, 0)), ((512, 3, 48), (16, 0, 0)), ((1024, 1, 80), (16, 0, 0))]
+             ((4, 2048, 16), None), ((2, 4096, 16), (0, 64, 0)), ((512, 3, 48), (16, 0, 0)), ((1024, 1, 80), (16, 0, 0)),
+             # first factor 2, 4 or 8 (butterflies in an element-wise pass), second factor of 512, 1024 or 2048 points
+             # on the fused kernels: 8192 = 4 x 2048 by default
+             ((2, 1024, 32), (0, 2, 0)), ((1024, 2, 16), (2, 0, 0)), ((3, 2, 4096), (0, 0, 2)), ((2, 3, 8192), None),
+             ((8192, 1, 16), None), ((1, 4096, 48), (0, 8, 0)), ((2, 2, 8192), (0, 0, 8)), ((1, 8192, 64), (0, 4, 16))]
 
 
 @pytest.mark.parametrize("shape,split", FFT_CASES)
@@ -506,6 +510,24 @@ def test_fft_exec_matches_oracle(dft, shape, split, flags):
         assert np.array_equal(to_host(xd), x), "input must be left intact"
         gotb = to_host(p.exec(xd, direction=dft.BACKWARD))
         assert report(f"fft exec backward {shape}", gotb, orc.dft3d(x, sign=orc.BACKWARD)) <= TOL
+
+
+@pytest.mark.parametrize("shape,split", [((2, 1024, 1024), (0, 2, 2)), ((1, 4096, 1024), (0, 8, 2)),
+                                         ((1024, 1, 1024), (2, 0, 2)), ((1, 1024, 4096), (0, 2, 8)),
+                                         ((4, 16, 4096), (2, 2, 4))])
+@pytest.mark.parametrize("flags", [0, 1])
+def test_fft_first_factor_in_butterflies_exec(dft, shape, split, flags):
+    """Splits R x M with R = 2, 4, 8: where the z axis and the axis transformed after it both start with the
+    butterfly pass, the second one reads through the z re-ordering (one pass fewer); with CLOBBER_INPUT the
+    pass count has to stay odd."""
+    say(f"case fft radix exec {shape} split {split} flags {flags}")
+    x = wl.draw_complex(shape, "normal", 5100 + sum(shape))
+    want = orc.dft3d(x)
+    with dft.Plan(shape, dft.FFT, split=split, flags=flags) as p:
+        got = to_host(p.exec(to_dev(x)))
+        assert report(f"fft radix exec {shape}", got, want) <= TOL
+        gotb = to_host(p.exec(to_dev(x), direction=dft.BACKWARD))
+        assert report(f"fft radix exec backward {shape}", gotb, orc.dft3d(x, sign=orc.BACKWARD)) <= TOL
 
 
 @pytest.mark.parametrize("shape", [(1, 96, 160), (1, 1, 256), (1, 256, 1), (40, 1, 48), (1, 1, 1), (1, 256, 512)])
