@@ -94,7 +94,11 @@ typedef enum { DFT3D_FORWARD = -1, DFT3D_BACKWARD = 1 } dft3d_direction;
  * dft3d_plan_create_ex additionally takes
  *   split     NULL, or three first-stage lengths A (0 = choose); A must divide the axis length.
  *             Default: A = 2^floor(log2(N)/2) for powers of two, else the divisor pair closest
- *             to sqrt(N) with A <= B.  (512 -> 16*32, 2048 -> 32*64.)
+ *             to sqrt(N) with A <= B (512 -> 16*32), except 1024 -> 16*64, 2048 -> 16*128 and, on
+ *             complex64 plans without DFT3D_FLAG_UNFUSED, 4096 -> 4*1024, 8192 -> 4*2048,
+ *             16384 -> 8*2048 (see dft3d_fft_first_stage; a strided axis only when the extent inside
+ *             it is a multiple of 16, the z axis at 4096 points only when the axis transformed next
+ *             takes such a split too: otherwise 64*64, 64*128, 128*128).
  *   flags     DFT3D_FLAG_* bits
  * Errors: INVALID_ARG (NULL plan pointer, size < 1 or > 2^24, bad split, unknown formulation or flag,
  * a coordinate that is not finite),
@@ -219,7 +223,10 @@ dft3d_status dft3d_mode_contract(dft3d_plan plan, int axis, const void* in, void
 
 /* FFT, first stage on `axis` (Eq. 16, then the twiddle if fuse_twiddle != 0):
  *   out[k_a*B + beta] = T * sum_l exp(-+2 pi i k_a l / A) in[B*l + beta],
- *   T = exp(-+2 pi i beta k_a / N) if fuse_twiddle else 1.  Valid on FFT plans. */
+ *   T = exp(-+2 pi i beta k_a / N) if fuse_twiddle else 1.  Valid on FFT plans.
+ * A first factor of 2, 4 or 8 is evaluated as butterflies in vector arithmetic (an element-wise,
+ * memory-bound pass) on complex64 plans without DFT3D_FLAG_UNFUSED; every other one as a contraction
+ * with the A x A matrix on the matrix cores. */
 dft3d_status dft3d_fft_first_stage(dft3d_plan plan, int axis, const void* in, void* out,
                                    int direction, int fuse_twiddle, void* stream);
 
@@ -231,7 +238,13 @@ dft3d_status dft3d_fft_phase(dft3d_plan plan, int axis, const void* in, void* ou
 /* FFT, second stage on `axis` (the matrix part of Eq. 15's phase adjustment):
  *   W[k_a, k_b] = sum_beta exp(-+2 pi i k_b beta / B) in[k_a*B + beta]
  * stored at slot k_a*B + k_b, or, if reorder != 0, in natural order at k_a + A*k_b.
- * BACKWARD also scales by 1/N_axis. */
+ * BACKWARD also scales by 1/N_axis.
+ * With A = 2, 4 or 8 and B = 512, 1024 or 2048 (complex64, no DFT3D_FLAG_UNFUSED; x and y: extent inside
+ * the axis a multiple of 16; z: reorder = 0) the B-point sums are evaluated by the fused kernel of
+ * dft3d_fft_axis for B = 16 x (B/16), i.e. Eq. 13 - 16 applied to the second stage once more; otherwise as a
+ * contraction with the B x B matrix.  dft3d_exec runs such an axis in two passes, and where the z axis and
+ * the axis transformed after it both have such a split, the first stage of the second one reads its input
+ * through the z re-ordering, which then takes no pass of its own. */
 dft3d_status dft3d_fft_second_stage(dft3d_plan plan, int axis, const void* in, void* out,
                                     int direction, int reorder, void* stream);
 
