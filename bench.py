@@ -600,7 +600,15 @@ def run_all(args, opts, mods):
         log(name)
         r = measure(name, k, wu, 0.3 if args.settle is None else args.settle, opts, mods, want_parity=parity_on)
         table[name] = table_entry(r)
+    # the paper's two-dimensional size (8192 x 8192, the 2-D strong-scaling figure of Section V): not one of the
+    # five configurations, reported beside them
+    two_d = {}
+    for name, k, wu in (("2d-8192-kdft", 10, 2), ("2d-8192-fft", 100, 10)):
+        log(name)
+        r = measure(name, k, wu, 0.3 if args.settle is None else args.settle, opts, mods, want_parity=parity_on)
+        two_d[name] = table_entry(r)
     head["configs"] = {k: table[k] for k in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5-kdft", "cfg5-fft")}
+    head["two_dimensional"] = two_d
     head["variants"] = variants
     head["paper_context"] = PAPER_CONTEXT
     if not args.no_cpu_baseline:
