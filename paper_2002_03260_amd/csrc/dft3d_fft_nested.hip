@@ -15,6 +15,10 @@
 // of the plan of an A x B split: FA is its first-stage matrix, T its twiddle table,
 // w_B^(k_c beta) = FB[k_c, beta] and F16[k_b, beta] = FB[C*k_b, beta].
 //
+// Longer axes (4096, 8192, 16384 points) put a first factor of 2, 4 or 8 in front: its stage is butterflies
+// and a twiddle in one element-wise pass (k_radix_tw, at the end of this file) and its second stage is one
+// of the transforms above.
+//
 // BACKWARD runs the forward transform on data with real and imaginary parts exchanged, and exchanges
 // them again in the result: with s(z) = i * conj(z), DFT(s(x)) = s(IDFT(x)).  The exchange is a choice
 // of register names, so the inverse costs exactly what the forward transform costs.
