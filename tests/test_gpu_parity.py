@@ -571,7 +571,7 @@ def test_kdft_and_fft_agree(dft):
     assert r <= 2 * TOL
 
 
-@pytest.mark.parametrize("variant", ["fp32", "3M", "BF16X3", "BF16X3+3M", "FFT", "FFT-nested", "small"])
+@pytest.mark.parametrize("variant", ["fp32", "3M", "BF16X3", "BF16X3+3M", "FFT", "FFT-nested", "FFT-radix", "small"])
 def test_power_of_two_scaling_is_exact(dft, variant):
     """exec(2^s x) must equal 2^s exec(x) bit for bit (s = -60, +60): scaling by a power of two
     commutes with every rounding of every path unless the path hides an assumption on the range of
@@ -579,11 +579,12 @@ def test_power_of_two_scaling_is_exact(dft, variant):
     import torch
 
     # ("FFT-nested": 512 and 1024 points run the kernels that split the second factor once more, with their
-    # butterflies in vector arithmetic)
-    shape = {"small": (32, 32, 32), "FFT-nested": (16, 512, 1024)}.get(variant, (128, 256, 128))
+    # butterflies in vector arithmetic; "FFT-radix": 8192 = 4 x 2048 with the first factor as a butterfly pass,
+    # and the y axis (8 x 8) reading through the z re-ordering)
+    shape = {"small": (32, 32, 32), "FFT-nested": (16, 512, 1024), "FFT-radix": (1, 64, 8192)}.get(variant, (128, 256, 128))
     form = dft.FFT if variant.startswith("FFT") else dft.KDFT
     flags = {"fp32": 0, "3M": dft.FLAG_3M, "BF16X3": dft.FLAG_BF16X3, "BF16X3+3M": dft.FLAG_BF16X3 | dft.FLAG_3M,
-             "FFT": 0, "FFT-nested": 0, "small": 0}[variant]
+             "FFT": 0, "FFT-nested": 0, "FFT-radix": 0, "small": 0}[variant]
     say(f"case scaling {variant} {shape}")
     x = wl.draw_complex(shape, "normal", 9100)
     with dft.Plan(shape, form, flags=flags) as p:
@@ -598,14 +599,14 @@ def test_power_of_two_scaling_is_exact(dft, variant):
             assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), f"{variant}: scaling by 2^{s} is not exact"
 
 
-@pytest.mark.parametrize("variant", ["fp32", "3M", "BF16X3", "BF16X3+3M", "FFT", "FFT-nested"])
+@pytest.mark.parametrize("variant", ["fp32", "3M", "BF16X3", "BF16X3+3M", "FFT", "FFT-nested", "FFT-radix"])
 def test_input_magnitudes_spanning_eighty_binades(dft, variant):
     """Every element carries its own power-of-two factor 2^e, e uniform in [-40, 40]: the result is
     dominated by the large elements and must still meet the tolerance against the oracle."""
-    shape = (16, 512, 1024) if variant == "FFT-nested" else (128, 128, 256)
+    shape = {"FFT-nested": (16, 512, 1024), "FFT-radix": (1, 64, 8192)}.get(variant, (128, 128, 256))
     form = dft.FFT if variant.startswith("FFT") else dft.KDFT
     flags = {"fp32": 0, "3M": dft.FLAG_3M, "BF16X3": dft.FLAG_BF16X3, "BF16X3+3M": dft.FLAG_BF16X3 | dft.FLAG_3M,
-             "FFT": 0, "FFT-nested": 0}[variant]
+             "FFT": 0, "FFT-nested": 0, "FFT-radix": 0}[variant]
     say(f"case wide magnitudes {variant} {shape}")
     rng = np.random.default_rng(9200)
     e = rng.integers(-40, 41, size=shape)
