@@ -68,8 +68,8 @@ typedef enum { DFT3D_FORWARD = -1, DFT3D_BACKWARD = 1 } dft3d_direction;
                                        Every byte count below doubles (16 bytes per element).  KDFT plans,
                                        and FFT plans as staged passes (first stage with the twiddle in its
                                        epilogue, second stage, re-ordering: no fused axis kernels, no
-                                       dft3d_fft_phase / dft3d_fft_axis).  Not combined with 3M / BF16X3 /
-                                       UNFUSED; not offered for point plans */
+                                       dft3d_fft_phase / dft3d_fft_axis), and point plans.  Not combined with
+                                       3M / BF16X3 / UNFUSED */
 #define DFT3D_FLAG_ADJOINT 32u      /* KDFT: the plan applies the conjugate transpose of the transform its
                                        other arguments describe, out = (M_x (x) M_y (x) M_z)^H in: from
                                        integer frequencies back to the (nonuniform) samples, the operation
@@ -123,7 +123,8 @@ dft3d_status dft3d_plan_create_ex(dft3d_plan* plan, int64_t nx, int64_t ny, int6
  *   zx,zy,zz  HOST arrays of 2*k? doubles, (re, im) of each point; points must be non-zero.  NULL =
  *             that axis uses the N-th roots of unity (then k? must equal n?).
  *   flags     DFT3D_FLAG_3M and / or DFT3D_FLAG_ADJOINT (then the roles of n? and k? swap: input
- *             kx x ky x kz, output nx x ny x nz, matrices V_j^H), or 0
+ *             kx x ky x kz, output nx x ny x nz, matrices V_j^H), DFT3D_FLAG_COMPLEX128 (complex128
+ *             tensors, the Vandermonde matrices kept in fp64; not together with 3M), or 0
  * exec needs a workspace of dft3d_plan_workspace_bytes = 8*(nx*ny*kz + nx*ky*kz) bytes (the two
  * intermediates; ADJOINT: 8*(kx*ky*nz + kx*ny*nz)).  dft3d_mode_contract on such a plan reads a tensor whose axes after `axis`
  * already have their output length and writes one whose `axis` has length k (order z, y, x).

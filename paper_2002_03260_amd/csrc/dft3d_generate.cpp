@@ -109,15 +109,15 @@ extern "C" dft3d_status dft3d_generate_twiddle(int64_t A, int64_t B, int directi
     return DFT3D_OK;
 }
 
-extern "C" dft3d_status dft3d_generate_points_matrix(int64_t k, int64_t n, const double* z, float* re,
-                                                     float* im)
+namespace dft3d {
+// V[r, j] = z_r^{-j} in fp64 (Eq. 3 as printed): modulus by exp/log, phase through the exactly reduced
+// fraction of a turn (so points on the unit circle keep unit modulus).
+dft3d_status generate_points_matrix_f64(int64_t k, int64_t n, const double* z, double* re, double* im)
 {
     if (k < 1 || n < 1 || !z || !re || !im) {
         set_error("dft3d_generate_points_matrix: invalid argument");
         return DFT3D_ERR_INVALID_ARG;
     }
-    // V[r, j] = z_r^{-j} = |z_r|^{-j} exp(-i j arg z_r): modulus by exp/log, phase through the
-    // exactly reduced fraction of a turn (so points on the unit circle keep unit modulus)
     for (int64_t r = 0; r < k; ++r) {
         const double zr = z[2 * r], zi = z[2 * r + 1];
         const double mod = std::hypot(zr, zi);
@@ -131,14 +131,36 @@ extern "C" dft3d_status dft3d_generate_points_matrix(int64_t k, int64_t n, const
             double cr, ci;
             unit_root_turns((double)j * turns, DFT3D_FORWARD, &cr, &ci);
             const double m = (lnmod == 0.0) ? 1.0 : std::exp(-(double)j * lnmod);
-            const float fr = (float)(m * cr), fi = (float)(m * ci);
-            if (!std::isfinite(fr) || !std::isfinite(fi)) {
-                set_error("dft3d_generate_points_matrix: entry (%lld, %lld) overflows fp32", (long long)r, (long long)j);
+            re[r * n + j] = m * cr;
+            im[r * n + j] = m * ci;
+            if (!std::isfinite(re[r * n + j]) || !std::isfinite(im[r * n + j])) {
+                set_error("dft3d_generate_points_matrix: entry (%lld, %lld) overflows", (long long)r, (long long)j);
                 return DFT3D_ERR_INVALID_ARG;
             }
-            re[r * n + j] = fr;
-            im[r * n + j] = fi;
         }
+    }
+    return DFT3D_OK;
+}
+}  // namespace dft3d
+
+extern "C" dft3d_status dft3d_generate_points_matrix(int64_t k, int64_t n, const double* z, float* re,
+                                                     float* im)
+{
+    if (k < 1 || n < 1 || !z || !re || !im) {
+        set_error("dft3d_generate_points_matrix: invalid argument");
+        return DFT3D_ERR_INVALID_ARG;
+    }
+    std::vector<double> dre((size_t)(k * n)), dim((size_t)(k * n));
+    const dft3d_status s = dft3d::generate_points_matrix_f64(k, n, z, dre.data(), dim.data());
+    if (s != DFT3D_OK) return s;
+    for (int64_t e = 0; e < k * n; ++e) {
+        const float fr = (float)dre[(size_t)e], fi = (float)dim[(size_t)e];
+        if (!std::isfinite(fr) || !std::isfinite(fi)) {
+            set_error("dft3d_generate_points_matrix: entry (%lld, %lld) overflows fp32", (long long)(e / n), (long long)(e % n));
+            return DFT3D_ERR_INVALID_ARG;
+        }
+        re[e] = fr;
+        im[e] = fi;
     }
     return DFT3D_OK;
 }

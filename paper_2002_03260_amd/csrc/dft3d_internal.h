@@ -200,6 +200,8 @@ hipError_t launch_copy(const void* in, void* out, size_t bytes, int variant, hip
 // exp(sign * 2 pi i * t) for t = p/q reduced exactly (uniform) or a real number of turns.
 void unit_root_ratio(int64_t p, int64_t q, int sign, double* re, double* im);
 void unit_root_turns(double t, int sign, double* re, double* im);
+// K x N matrix of Eq. 3 as printed for K evaluation points z (re, im pairs), in fp64.
+dft3d_status generate_points_matrix_f64(int64_t k, int64_t n, const double* z, double* re, double* im);
 
 void set_error(const char* fmt, ...);
 

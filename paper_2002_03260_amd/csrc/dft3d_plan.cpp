@@ -983,9 +983,13 @@ static dft3d_status plan_create_points_impl(dft3d_plan* plan, int64_t nx, int64_
             return DFT3D_ERR_INVALID_ARG;
         }
     }
-    if (flags & ~(DFT3D_FLAG_3M | DFT3D_FLAG_ADJOINT)) {
-        set_error("plan_create_points: only DFT3D_FLAG_3M and DFT3D_FLAG_ADJOINT are accepted");
+    if (flags & ~(DFT3D_FLAG_3M | DFT3D_FLAG_ADJOINT | DFT3D_FLAG_COMPLEX128)) {
+        set_error("plan_create_points: only DFT3D_FLAG_3M, DFT3D_FLAG_ADJOINT and DFT3D_FLAG_COMPLEX128 are accepted");
         return DFT3D_ERR_INVALID_ARG;
+    }
+    if ((flags & DFT3D_FLAG_COMPLEX128) && (flags & DFT3D_FLAG_3M)) {
+        set_error("plan_create_points: COMPLEX128 is not combined with 3M");
+        return DFT3D_ERR_UNSUPPORTED;
     }
     const bool adjoint = (flags & DFT3D_FLAG_ADJOINT) != 0;
     if (ky * kz >= (int64_t(1) << 31) || nx * ny >= (int64_t(1) << 31) ||
@@ -1011,6 +1015,17 @@ static dft3d_status plan_create_points_impl(dft3d_plan* plan, int64_t nx, int64_
                  : dft3d_generate_matrix(n[j], nullptr, DFT3D_FORWARD, re.data(), im.data());
         if (s == DFT3D_OK && adjoint) conjugate_transpose(re, im, k[j], n[j]);
         if (s == DFT3D_OK) s = upload_matrix(re, im, (int)p->k[j], (int)p->n[j], &p->M[j]);
+        if (s == DFT3D_OK && (flags & DFT3D_FLAG_COMPLEX128)) {
+            // the fp64 planes come from the fp64 entries, not from their fp32 roundings
+            std::vector<double> dre((size_t)(k[j] * n[j])), dim((size_t)(k[j] * n[j]));
+            if (z[j]) s = generate_points_matrix_f64(k[j], n[j], z[j], dre.data(), dim.data());
+            else
+                for (int64_t r = 0; r < n[j]; ++r)
+                    for (int64_t c = 0; c < n[j]; ++c)
+                        unit_root_ratio(r * c, n[j], DFT3D_FORWARD, &dre[(size_t)(r * n[j] + c)], &dim[(size_t)(r * n[j] + c)]);
+            if (s == DFT3D_OK && adjoint) conjugate_transpose(dre, dim, k[j], n[j]);
+            if (s == DFT3D_OK) s = upload_f64(dre, dim, (int)p->k[j], (int)p->n[j], &p->M[j]);
+        }
     }
     if (s != DFT3D_OK) return s;      // (the guard frees the plan)
     guard.p = nullptr;
@@ -1054,7 +1069,7 @@ size_t dft3d_plan_workspace_bytes(dft3d_plan p)
     if (!p) return 0;
     if (single_launch(p)) return 0;
     if (p->points)   // two intermediates of different shapes: after mode z and after mode y
-        return (size_t)(p->stage_out_elements(2) + p->stage_out_elements(1)) * 8;
+        return (size_t)(p->stage_out_elements(2) + p->stage_out_elements(1)) * p->elem_bytes();
     if (p->flags & DFT3D_FLAG_CLOBBER_INPUT) return 0;
     if (p->ws_pitch) return (size_t)(p->n[0] * p->n[1] * p->ws_pitch) * p->elem_bytes();
     return (size_t)p->elements() * p->elem_bytes();
@@ -1270,13 +1285,14 @@ dft3d_status exec_with_workspace(dft3d_plan p, const void* in, void* out, int di
             return DFT3D_ERR_INVALID_ARG;
         }
         const uintptr_t w = (uintptr_t)workspace, a = (uintptr_t)in, b = (uintptr_t)out;
-        const uintptr_t abytes = (uintptr_t)p->elements() * 8, bbytes = (uintptr_t)p->out_elements() * 8;
+        const uintptr_t abytes = (uintptr_t)p->elements() * p->elem_bytes(), bbytes = (uintptr_t)p->out_elements() * p->elem_bytes();
         if ((w < a + abytes && a < w + need) || (w < b + bbytes && b < w + need)) {
             set_error("%s: the workspace overlaps in or out", who);
             return DFT3D_ERR_INVALID_ARG;
         }
+        // (complex128 plans: the pointers are only passed through, an element is two float2)
         float2* w1 = (float2*)workspace;
-        float2* w2 = w1 + p->stage_out_elements(2);
+        float2* w2 = w1 + p->stage_out_elements(2) * (int64_t)(p->elem_bytes() / 8);
         hipStream_t pst = (hipStream_t)stream;
         hipError_t pe = run_mode(p, 2, (const float2*)in, w1, 0, 1.0f, pst);
         if (pe == hipSuccess) pe = run_mode(p, 1, w1, w2, 0, 1.0f, pst);

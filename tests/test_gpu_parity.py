@@ -273,6 +273,41 @@ def test_kdft_complex128(dft, shape):
         assert report(f"kdft complex128 clobber {shape}", got, want) <= TOL_F64
 
 
+@pytest.mark.parametrize("shape,ks,adjoint", [((6, 10, 12), (4, 10, 20), False), ((40, 33, 70), (33, 50, 70), False),
+                                              ((64, 48, 40), (80, 48, 130), True)])
+def test_kdft_complex128_evaluation_points(dft, shape, ks, adjoint):
+    """DFT3D_FLAG_COMPLEX128 on a plan of arbitrary evaluation points (Eq. 1 - 3 as printed, rectangular
+    Vandermonde matrices kept in fp64), and on its conjugate transpose."""
+    import torch
+
+    say(f"case complex128 points {shape} -> {ks} adjoint={adjoint}")
+    rng = np.random.default_rng(8400 + sum(shape))
+    points = []
+    for j in range(3):
+        if ks[j] == shape[j] and j == 1:
+            points.append(None)                 # this axis keeps the roots of unity
+        else:
+            radius = np.exp(rng.uniform(-0.3, 0.3, ks[j]) / shape[j])        # |z|^-n stays within e^(+-0.3)
+            points.append(radius * np.exp(2j * np.pi * rng.random(ks[j])))
+    Ms = [orc.dft_matrix(shape[j]) if points[j] is None else orc.points_matrix(points[j], shape[j]) for j in range(3)]
+    flags = dft.FLAG_COMPLEX128 | (dft.FLAG_ADJOINT if adjoint else 0)
+    with dft.Plan(shape, dft.KDFT, points=points, flags=flags) as p:
+        if adjoint:
+            y = wl.draw_complex128(tuple(ks), 8401)
+            want = y
+            for axis in (2, 1, 0):
+                want = orc.mode_contract(np.ascontiguousarray(Ms[axis].conj().T), want, axis)
+            got = p.exec(torch.from_numpy(y).to("cuda")).cpu().numpy()
+        else:
+            x = wl.draw_complex128(shape, 8402)
+            want = x
+            for axis in (2, 1, 0):
+                want = orc.mode_contract(Ms[axis], want, axis)
+            got = p.exec(torch.from_numpy(x).to("cuda")).cpu().numpy()
+        assert got.dtype == np.complex128 and got.shape == want.shape
+        assert report(f"complex128 points {shape}->{ks}", got, want) <= TOL_F64
+
+
 def test_kdft_complex128_nonuniform(dft):
     import torch
 
