@@ -106,6 +106,54 @@ def test_2d_8192_sampled_outputs(dft):
     assert abs(e_out / e_in - 1) <= 1e-5
 
 
+def _oracle_rows_and_columns_2d(x, k2s, k3s):
+    """Whole output rows X[0, k2, :] and columns X[0, :, k3] of a 2-D transform (shape 1 x n2 x n3) from the
+    oracle's own mode products: the sampled axis is reduced with the matching matrix rows only, the other
+    axis is transformed in full."""
+    n2, n3 = x.shape[1], x.shape[2]
+    rows = orc.mode_contract(orc.dft_matrix(n2, ks=np.asarray(k2s, dtype=np.int64)), x, 1)     # (1, |k2s|, n3)
+    rows = orc.mode_contract(orc.dft_matrix(n3), rows, 2)
+    cols = orc.mode_contract(orc.dft_matrix(n3, ks=np.asarray(k3s, dtype=np.int64)), x, 2)     # (1, n2, |k3s|)
+    cols = orc.mode_contract(orc.dft_matrix(n2), cols, 1)
+    return rows, cols
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("n", [8192, 16384])
+def test_2d_fft_whole_rows_and_columns(dft, n):
+    """2-D FFT formulation at n x n with the default split (8192 = 4 x 2048, 16384 = 8 x 2048: butterfly
+    first stage, fused second stage, the z re-ordering read through by the y pass): three whole output rows
+    and three whole output columns against the oracle, forward; then the round trip through BACKWARD."""
+    import torch
+
+    shape = (1, n, n)
+    say(f"case 2-D FFT rows and columns {shape}: drawing input")
+    x = wl.draw_complex(shape, "normal", 200203260 + n)
+    xd = torch.from_numpy(x).to("cuda")
+    k2s, k3s = [0, 4097 % n, n - 1], [5, n // 2, n - 3]
+    with dft.Plan(shape, dft.FFT) as p:
+        say(f"  splits {[p.split(a) for a in range(3)]}")
+        assert p.split(1)[0] in (4, 8) and p.split(2)[0] in (4, 8)
+        out = p.exec(xd)
+        torch.cuda.synchronize()
+        got_rows = out[:, k2s, :].cpu().numpy()
+        got_cols = out[:, :, k3s].cpu().numpy()
+        back = p.exec(out, direction=dft.BACKWARD)
+        torch.cuda.synchronize()
+        rt = (torch.linalg.vector_norm((back - xd).to(torch.complex128)) /
+              torch.linalg.vector_norm(xd.to(torch.complex128))).item()
+        del back, out
+    say(f"  gpu done; oracle rows {k2s} and columns {k3s}")
+    rows, cols = _oracle_rows_and_columns_2d(x, k2s, k3s)
+    for name, got, want in (("rows", got_rows, rows), ("columns", got_cols, cols)):
+        r = rel_l2(got, want)
+        m = np.max(np.abs(got - want)) / np.sqrt(np.mean(np.abs(want) ** 2))
+        say(f"[parity] 2-D FFT {n} {name} ({want.size} outputs): relL2={r:.3e} max|err|/rms={m:.3e}")
+        assert r <= TOL and m <= 1e-4
+    say(f"[parity] 2-D FFT {n} round trip: relL2={rt:.3e}")
+    assert rt <= TOL
+
+
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("shape", [(2048, 256, 256), (2048, 512, 512)])
 def test_fft_x_first_plan_sampled(dft, shape):
