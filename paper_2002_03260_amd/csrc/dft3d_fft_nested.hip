@@ -378,25 +378,36 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
     const int pb = wave >> 1, ph = wave & 1;
     const unsigned ld_lane = (unsigned)(B * lq) * (unsigned)inN + (unsigned)l16;
     f32x2 xs[CP][NS1][CH];
-    auto request = [&](int slot) {                     // of the tile at rq
-        const float2* src = X + ((int64_t)rq.o * a.inO + (int64_t)rq.y * a.inY + (int64_t)rq.zt * (16 * CH)) +
-                            (int64_t)(4 * slot + pb + 16 * ph) * inN;
+    const float2* rsrc = X;                             // base of the slot being requested
+    auto request_base = [&](int slot) {                // of the tile at rq
+        rsrc = X + ((int64_t)rq.o * a.inO + (int64_t)rq.y * a.inY + (int64_t)rq.zt * (16 * CH)) +
+               (int64_t)(4 * slot + pb + 16 * ph) * inN;
+    };
+    auto request_step = [&](int s) {                   // the registers of k-step s
 #pragma unroll
         for (int cp = 0; cp < CP; ++cp)
 #pragma unroll
-            for (int s = 0; s < NS1; ++s)
+            for (int cg = 0; cg < CH; ++cg)              // neighbouring 128-byte pieces of the same rows
+                xs[cp][s][cg] = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(
+                    &(rsrc + (int64_t)(4 * B * s + 32 * cp) * inN + 16 * cg)[ld_lane]));
+    };
+    auto request = [&](int slot) {
+        request_base(slot);
 #pragma unroll
-                for (int cg = 0; cg < CH; ++cg)          // neighbouring 128-byte pieces of the same rows
-                    xs[cp][s][cg] = __builtin_nontemporal_load(reinterpret_cast<const f32x2*>(
-                        &(src + (int64_t)(4 * B * s + 32 * cp) * inN + 16 * cg)[ld_lane]));
+        for (int s = 0; s < NS1; ++s) request_step(s);
     };
     // Requests past the last slot are not skipped: they re-read the last tile (every access in bounds) and
     // the producer step that uses them writes a ring buffer nobody reads.  With unconditional loads the
     // compiler can count how many younger requests may be in flight when the registers are used.
-    auto request_slot = [&](int64_t g) {               // called with g = 0, 1, 2, .. in this order
+    auto request_begin = [&](int64_t g) {              // called with g = 0, 1, 2, .. in this order
         const int slot = (int)(g & 3);
         if (slot == 0 && g != 0 && g < G) advance(rq);
-        request(slot);
+        request_base(slot);
+    };
+    auto request_slot = [&](int64_t g) {
+        request_begin(g);
+#pragma unroll
+        for (int s = 0; s < NS1; ++s) request_step(s);
     };
 
     // accumulators: [k_a = KW*wave + j % KW, column group j / KW][k_c], register v = k_b = 4*lq + v
@@ -425,28 +436,37 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
                     p2[cg][cp][ab] = p1[cg][cp][ab];
                     p3[cg][cp][ab] = p1[cg][cp][ab];
                 }
+        // The registers of a k-step are free as soon as its matrix instructions have been issued, and the
+        // request for the next slot goes out step by step between them.
+        request_begin(g_next);
 #pragma unroll
-        for (int ab = 0; ab < NAB; ++ab)
+        for (int sq = 0; sq < NS1 / 4; ++sq) {
+            f32x4 fr[NAB], fi[NAB], fs[NAB];
 #pragma unroll
-            for (int sq = 0; sq < NS1 / 4; ++sq) {
+            for (int ab = 0; ab < NAB; ++ab) {
                 const f32x4* t = faT + ((ab * (NS1 / 4) + sq) * 3) * 64 + lane;
-                const f32x4 fr = t[0], fi = t[64], fs = t[128];
-#pragma unroll
-                for (int s4 = 0; s4 < 4; ++s4)
-#pragma unroll
-                    for (int cg = 0; cg < CH; ++cg)
-#pragma unroll
-                        for (int cp = 0; cp < CP; ++cp) {
-                            const f32x2 x = xs[cp][4 * sq + s4][cg];
-                            const float xr = SWAP ? x.y : x.x, xi = SWAP ? x.x : x.y;
-                            p1[cg][cp][ab] = mfma(fr[s4], xr, p1[cg][cp][ab]);
-                            p2[cg][cp][ab] = mfma(fi[s4], xi, p2[cg][cp][ab]);
-                            p3[cg][cp][ab] = mfma(fs[s4], xr + xi, p3[cg][cp][ab]);
-                        }
+                fr[ab] = t[0], fi[ab] = t[64], fs[ab] = t[128];
             }
-        __builtin_amdgcn_sched_barrier(0);
-        request_slot(g_next);
-        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+#pragma unroll
+                for (int cg = 0; cg < CH; ++cg)
+#pragma unroll
+                    for (int cp = 0; cp < CP; ++cp) {
+                        const f32x2 x = xs[cp][4 * sq + s4][cg];
+                        const float xr = SWAP ? x.y : x.x, xi = SWAP ? x.x : x.y;
+#pragma unroll
+                        for (int ab = 0; ab < NAB; ++ab) {
+                            p1[cg][cp][ab] = mfma(fr[ab][s4], xr, p1[cg][cp][ab]);
+                            p2[cg][cp][ab] = mfma(fi[ab][s4], xi, p2[cg][cp][ab]);
+                            p3[cg][cp][ab] = mfma(fs[ab][s4], xr + xi, p3[cg][cp][ab]);
+                        }
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+                request_step(4 * sq + s4);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
         const int beta = 4 * slot + pb;
 #pragma unroll
         for (int cg = 0; cg < CH; ++cg)
