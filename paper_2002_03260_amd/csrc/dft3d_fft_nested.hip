@@ -412,14 +412,17 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
 
     // accumulators: [k_a = KW*wave + j % KW, column group j / KW][k_c], register v = k_b = 4*lq + v
     f32x4 wr[KW * CH][C], wi[KW * CH][C];
-    auto clear_acc = [&]() {
+    constexpr int KH = KW / 2;                         // k_a of this wave per half of a tile (all column groups)
+    auto clear_half = [&](int h) {
 #pragma unroll
-        for (int j = 0; j < KW * CH; ++j)
+        for (int cg = 0; cg < CH; ++cg)
 #pragma unroll
-            for (int kc = 0; kc < C; ++kc) {
-                wr[j][kc] = f32x4{0.f, 0.f, 0.f, 0.f};
-                wi[j][kc] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
+            for (int ja = h * KH; ja < (h + 1) * KH; ++ja)
+#pragma unroll
+                for (int kc = 0; kc < C; ++kc) {
+                    wr[KW * cg + ja][kc] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    wi[KW * cg + ja][kc] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
     };
 
     // ---- producer: slot `slot` (0..3) of the tile whose data sits in xs -> ring buffer `buf`; then the
@@ -546,12 +549,13 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
         }
     };
 
-    auto store_tile = [&]() {                          // the tile at st
+    // Half h of this wave's k_a (accumulator sets j = KW * column group + k_a % KW) of the tile at position p.
+    auto store_half = [&](int h, const Pos& p) {
         // rows k_a + A*k_c + A*C*k_b with k_b = 4*lq + v; the lane part needs 64 bits at N = 2048
-        float2* dst = Y + ((int64_t)st.o * a.outO + (int64_t)st.y * a.outY + (int64_t)st.zt * (16 * CH)) +
+        float2* dst = Y + ((int64_t)p.o * a.outO + (int64_t)p.y * a.outY + (int64_t)p.zt * (16 * CH)) +
                       ((int64_t)(A * C * 4 * lq) * outN + l16);
 #pragma unroll
-        for (int ja = 0; ja < KW; ++ja)
+        for (int ja = h * KH; ja < (h + 1) * KH; ++ja)
 #pragma unroll
             for (int kc = 0; kc < C; ++kc)
 #pragma unroll
@@ -568,21 +572,32 @@ __global__ __launch_bounds__(512, 2 * WPC) void k_fft_sn(FftStridedArgs a, Devic
     // Slots are numbered g = 0, 1, .. across the tiles of this workgroup.  One barrier per slot: before it
     // every wave has written slot g into ring buffer g % 2 and finished reading that buffer for slot g - 2;
     // after it the producer step of slot g + 1 and the consumer step of slot g run.
-    clear_acc();
+    // A finished tile is stored in two halves a slot apart: the first right after its last consumer step,
+    // the second after the next producer step, whose requests then queue behind half as many stores (the
+    // counter a wave waits on retires loads and stores in issue order).
+    clear_half(0);
+    clear_half(1);
     request_slot(0);
     __syncthreads();                                   // tables
     produce(0, 0, 1);
+    Pos done = st;                                     // tile whose second half is still in the accumulators
     for (int64_t g = 0; g < G; ++g) {
         __syncthreads();
         const int slot = (int)(g & 3), buf = (int)(g & 1);
         produce((slot + 1) & 3, buf ^ 1, g + 2);
+        if (slot == 0 && g != 0) {
+            store_half(1, done);
+            clear_half(1);
+        }
         consume(slot, buf);
         if (slot == 3) {
-            store_tile();
-            clear_acc();
+            store_half(0, st);
+            clear_half(0);
+            done = st;
             advance(st);
         }
     }
+    store_half(1, done);
 }
 
 template <int NAB, int C, int CH, int WPC>
