@@ -285,6 +285,28 @@ int main()
     }
     printf("sweep: %d plans run, %d combinations refused, %ld checks, %d failed\n", ran, refused, g_checked, g_failed);
 
+    // ---- seeded sweep over FFT plans with long axes: fused kernels, butterfly first stages, the z re-ordering
+    // read by the next pass, explicit splits, CLOBBER_INPUT's odd pass count
+    {
+        const int64_t lpool[] = {1, 2, 16, 48, 256, 512, 1024, 2048, 4096, 8192};
+        const int64_t spool[] = {0, 0, 0, 2, 4, 8, 16, 32};
+        int lran = 0;
+        for (int it = 0; it < 70; ++it) {
+            Case c{};
+            for (int j = 0; j < 3; ++j) c.n[j] = lpool[rng() % 10];
+            if (c.n[0] * c.n[1] * c.n[2] > (int64_t)1 << 33 || c.n[1] * c.n[2] >= (int64_t)1 << 31) continue;
+            c.form = DFT3D_FFT;
+            if (rng() % 100 < 35) c.flags |= DFT3D_FLAG_CLOBBER_INPUT;
+            else if (rng() % 100 < 10) c.flags |= DFT3D_FLAG_UNFUSED;
+            for (int j = 0; j < 3; ++j) {
+                const int64_t a = spool[rng() % 8];
+                c.split[j] = (a && c.n[j] % a == 0) ? a : 0;
+            }
+            if (run_case(c) >= 0) ++lran;
+        }
+        printf("long-axis sweep: %d plans run, %ld checks, %d failed\n", lran, g_checked, g_failed);
+    }
+
     steps_case(64, 32, 128, 0);
     steps_case(36, 20, 48, 0);
     steps_case(512, 3, 48, 0);
