@@ -175,6 +175,19 @@ def parity_entry(desc, got, want):
 
 def resolve(name, wl, dft):
     """(workload, formulation) of a --workload name."""
+    if name.startswith("shape:"):
+        # any other size, e.g. shape:1024x1024x1024:fft or shape:1x4096x4096:fft:0,64,64 (first factors, 0 = the
+        # library's default) or shape:384x384x384:kdft -- N(0,1) input, not one of the named configurations
+        parts = name.split(":")
+        shape = tuple(int(v) for v in parts[1].split("x"))
+        form = dft.FFT if (len(parts) > 2 and parts[2] == "fft") else dft.KDFT
+        splits = None
+        if len(parts) > 3:
+            first = [int(v) for v in parts[3].split(",")]
+            splits = tuple((a, n // a) if a > 0 else (0, 0) for a, n in zip(first, shape))
+        if len(shape) != 3 or min(shape) < 1:
+            raise SystemExit("bench.py: shape:NXxNYxNZ[:fft|kdft[:a,b,c]]")
+        return wl.Workload("shape_" + parts[1], 7, shape, form, "normal", splits=splits), form, True
     if name.startswith("cfg5") or name.startswith("2d-8192"):
         form = dft.FFT if name.endswith("fft") else dft.KDFT
         w = wl.WORKLOADS["cfg5"] if name.startswith("cfg5") else wl.EXTRA_WORKLOADS["2d-8192"]
@@ -210,6 +223,8 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
             raise SystemExit("bench.py: a complex128 tensor of this workload, its output and the workspace do not fit one GPU")
         flags = dft.FLAG_COMPLEX128
     plan = dft.Plan(w.shape, form, coords=coords, split=split, flags=flags)
+    if form == dft.FFT:
+        splits = tuple(plan.split(ax) for ax in range(3))      # (what the plan chose where none was named)
     if buffers is not None:
         x, out, ws = buffers
         if plan.workspace_bytes():
@@ -370,6 +385,10 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
         elif npass == 3:
             # (plans with 2048 points along x run the x pass first)
             pass_names = [f"{'xyz'[ax]}_fused_axis" for ax in plan.axis_order()]
+        if w.name.startswith("shape_") and not (npass == 3 and min(w.shape) > 1):
+            # an ad-hoc size: the pass structure is the plan's business; the passes are numbered and the slowest
+            # one is priced by its bytes only
+            pass_names = [f"pass{i}" for i in range(npass)]
         dom = max(range(npass), key=lambda i: pass_ms[i])
         dom_ms = pass_ms[dom]
         dom_name = pass_names[dom] if dom < len(pass_names) else f"pass{dom}"
@@ -625,7 +644,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="all",
                     help="all (default: headline cfg5-kdft = KDFT 2048^3 plus a table of every configuration), "
-                         "or one of cfg1..cfg4, cfg5-kdft, cfg5-fft, 2d-8192-kdft, 2d-8192-fft, copy")
+                         "or one of cfg1..cfg4, cfg5-kdft, cfg5-fft, 2d-8192-kdft, 2d-8192-fft, copy, "
+                         "or shape:NXxNYxNZ:fft|kdft[:first factors] for any other size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true", help="skip the oracle samples of the default run")
     ap.add_argument("--parity", action="store_true", help="single workload: add the oracle sample")
