@@ -158,7 +158,12 @@ dft3d_status dft3d_plan_set_workspace(dft3d_plan plan, void* dev, size_t bytes);
  * dft3d_mode_contract (Eq. 11, one mode product): writes a NUL-terminated name such as
  * "k_contract_s", "k_contract_c (3M)", "k_contract_bf16x3", "k_contract_sr", "k_contract_f64" or
  * "k_kdft_small" (the single launch that runs all three modes) into name[len].  Lets a caller see
- * whether a flag such as DFT3D_FLAG_BF16X3 takes effect for a shape.  Host only, launches nothing. */
+ * whether a flag such as DFT3D_FLAG_BF16X3 takes effect for a shape.  Host only, launches nothing.
+ * On an FFT plan the name says how dft3d_exec transforms the axis (Eq. 13 - 16): "fused" (one pass),
+ * "butterflies + fused second stage" (first factor 2, 4 or 8: two passes), "butterflies + second stage",
+ * "first stage + second stage" (matrix stages: two passes), "first stage, twiddle pass, second stage"
+ * (DFT3D_FLAG_UNFUSED) or "identity" (length 1); a z axis that is not "fused" also needs its re-ordering, a pass
+ * of its own unless the pass after it is a butterfly pass and reads through it. */
 dft3d_status dft3d_plan_mode_kernel(dft3d_plan plan, int axis, char* name, size_t len);
 
 /* First-stage / second-stage lengths chosen for an axis (0, 1 or 2) of an FFT plan. */

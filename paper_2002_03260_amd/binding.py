@@ -243,7 +243,8 @@ class Plan:
         return tuple(int(v) for v in order)
 
     def mode_kernel(self, axis: int) -> str:
-        """Name of the kernel family that contracts mode ``axis`` of this KDFT plan."""
+        """Name of the kernel family that contracts mode ``axis`` of a KDFT plan; for an FFT plan, how
+        exec transforms the axis ("fused", "butterflies + fused second stage", ...)."""
         buf = ctypes.create_string_buffer(64)
         _check(self._lib.dft3d_plan_mode_kernel(self._h, axis, buf, len(buf)))
         return buf.value.decode()

@@ -1122,7 +1122,19 @@ dft3d_status dft3d_plan_mode_kernel(dft3d_plan p, int axis, char* name, size_t l
         set_error("plan_mode_kernel: invalid argument");
         return DFT3D_ERR_INVALID_ARG;
     }
-    if (p->form != DFT3D_KDFT) { set_error("plan_mode_kernel: not a KDFT plan"); return DFT3D_ERR_UNSUPPORTED; }
+    if (p->form != DFT3D_KDFT) {
+        // FFT plan: how dft3d_exec transforms this axis (before CLOBBER_INPUT's adjustments of the pass count)
+        const char* how;
+        if (p->flags & DFT3D_FLAG_UNFUSED) how = "first stage, twiddle pass, second stage";
+        else if (p->n[axis] == 1) how = "identity";
+        else if (axis == 2 ? z_axis_fusable(p) : strided_axis_fusable(p, axis)) how = "fused";
+        else if (first_stage_is_radix(p, axis) && second_stage_nested(p, axis, axis != 2))
+            how = "butterflies + fused second stage";
+        else if (first_stage_is_radix(p, axis)) how = "butterflies + second stage";
+        else how = "first stage + second stage";
+        snprintf(name, len, "%s", how);
+        return DFT3D_OK;
+    }
     const char* k = single_launch(p) ? "k_kdft_small"
                     : p->complex128() ? "k_contract_f64"
                                       : contract_kernel_name(mode_args(p, axis, nullptr, nullptr, 0, 1.0f));

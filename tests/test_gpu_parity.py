@@ -382,8 +382,21 @@ def test_plan_reports_the_kernel_of_each_mode(dft):
     with dft.Plan((64, 64, 64), dft.KDFT, flags=dft.FLAG_COMPLEX128) as p:
         assert p.mode_kernel(1) == "k_contract_f64"
     with dft.Plan((64, 64, 64), dft.FFT) as p:
-        with pytest.raises(dft.Dft3dError):
-            p.mode_kernel(0)
+        assert p.mode_kernel(0) == "butterflies + second stage"           # 64 = 8 x 8 (FFT plans: how the axis runs)
+
+
+def test_fft_plan_reports_how_each_axis_runs(dft):
+    with dft.Plan((512, 48, 1024), dft.FFT) as p:
+        assert p.mode_kernel(0) == "fused" and p.mode_kernel(2) == "fused"
+        assert p.mode_kernel(1) == "first stage + second stage"          # 48 = 6 x 8
+    with dft.Plan((1, 8192, 8192), dft.FFT) as p:
+        assert p.mode_kernel(0) == "identity"
+        assert p.mode_kernel(1) == p.mode_kernel(2) == "butterflies + fused second stage"
+    with dft.Plan((8, 8192, 24), dft.FFT) as p:
+        assert p.mode_kernel(0) == "butterflies + second stage"           # 8 = 2 x 4
+        assert p.mode_kernel(1) == "first stage + second stage"           # inner extent 24: 8192 = 64 x 128
+    with dft.Plan((16, 16, 16), dft.FFT, flags=dft.FLAG_UNFUSED) as p:
+        assert p.mode_kernel(1) == "first stage, twiddle pass, second stage"
 
 
 def test_kdft_clobber_input(dft):
