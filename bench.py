@@ -225,6 +225,7 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
     plan = dft.Plan(w.shape, form, coords=coords, split=split, flags=flags)
     if form == dft.FFT:
         splits = tuple(plan.split(ax) for ax in range(3))      # (what the plan chose where none was named)
+    axis_passes = [plan.mode_kernel(ax) for ax in range(3)]   # kernel family (KDFT) / pass structure (FFT) per axis
     if buffers is not None:
         x, out, ws = buffers
         if plan.workspace_bytes():
@@ -504,6 +505,7 @@ def measure(name, steps, warmup, settle_s, opts, mods, buffers=None, want_parity
             "shape": list(w.shape), "input": f"{'complex128' if c128 else 'complex64'}, iid {w.dist}, seed {w.seed}",
             "nonuniform": w.nonuniform,
             "split": [list(s) for s in splits] if (form == dft.FFT and splits) else None,
+            "axes_xyz": axis_passes,
         },
         "roofline": roofline,
     }
