@@ -398,3 +398,53 @@ def test_cfg5_kdft_flag_variants_sampled(dft, cfg5, variant):
     assert rk <= 2 * TOL
     del out
     torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(600)
+def test_fft_long_axis_plans_against_library_fft(dft):
+    """Seeded random FFT plans with axes of up to 8192 points, explicit first factors and flags (every pass
+    structure: fused axes, butterfly first stages, the z re-ordering read by the next pass, matrix stages,
+    CLOBBER_INPUT's odd pass count, UNFUSED).  These shapes are too large for the fp64 oracle, so this is a
+    cross-check against the library FFT of the tensor framework on the same device tensor (fp64 copy), not a
+    parity claim: what it guards is the pass structure, whose every kernel has its own parity test."""
+    import torch
+
+    rng = np.random.default_rng(20020326)
+    lpool = [1, 2, 16, 48, 256, 512, 1024, 2048, 4096, 8192]
+    spool = [0, 0, 0, 2, 4, 8, 16, 32]
+    ran, worst = 0, 0.0
+    for it in range(60):
+        shape = tuple(int(rng.choice(lpool)) for _ in range(3))
+        E = int(np.prod(shape))
+        u = rng.random()
+        flags = dft.FLAG_CLOBBER_INPUT if u < 0.35 else (dft.FLAG_UNFUSED if u < 0.45 else 0)
+        split = tuple(int(a) if (a and n % a == 0) else 0 for a, n in zip(rng.choice(spool, 3), shape))
+        backward = bool(rng.random() < 0.3)
+        if E > (1 << 27) or E < 2:
+            continue
+        say(f"case long-axis plan {it}: {shape} split {split} flags {flags} backward {backward}")
+        x = torch.randn(shape, dtype=torch.complex64, device="cuda")
+        try:
+            x64 = x.to(torch.complex128)
+            ref = torch.fft.ifftn(x64) if backward else torch.fft.fftn(x64)
+        except RuntimeError as e:
+            pytest.skip(f"no library FFT on this box: {e}")
+        try:
+            plan = dft.Plan(shape, dft.FFT, split=split if any(split) else None, flags=flags)
+        except dft.Dft3dError as e:
+            assert e.status_name == "DFT3D_ERR_UNSUPPORTED", e
+            continue
+        with plan as p:
+            try:
+                got = p.exec(x.clone(), direction=dft.BACKWARD if backward else dft.FORWARD)
+            except dft.Dft3dError as e:
+                assert e.status_name == "DFT3D_ERR_UNSUPPORTED", e
+                continue
+            torch.cuda.synchronize()
+            r = (torch.linalg.vector_norm(got.to(torch.complex128) - ref) / torch.linalg.vector_norm(ref)).item()
+        assert r <= TOL, f"{shape} split {split} flags {flags} backward {backward}: relL2 {r:.3e}"
+        worst, ran = max(worst, r), ran + 1
+        del x, x64, ref, got
+    say(f"[cross-check] {ran} long-axis FFT plans against the library FFT: worst relL2 {worst:.3e}")
+    assert ran >= 30
+
